@@ -1,0 +1,174 @@
+/*
+ * bolt.h -- C ABI of the MI355X (gfx950) implementation of Bolt's hardware-native kernel family
+ * (arxiv 2110.15238): FP16 GEMM and implicit-GEMM NHWC conv2d with fused bias + activation
+ * epilogues, persistent back-to-back (b2b) GEMM / conv fusion, channel padding, and the
+ * light-weight profiler that picks template parameters per shape.
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers to IEEE binary16 data unless stated otherwise.
+ *     They are borrowed: the library never allocates, frees or keeps them.  Base pointers must be
+ *     16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls enqueue work and
+ *     return; they do not synchronise (bolt_tune does, it has to read timers).
+ *   - `workspace` is a device buffer of at least bolt_workspace_bytes(...) bytes (may be NULL when
+ *     that is 0).
+ *   - The return value is the only error channel.  Descriptors are validated before anything is
+ *     launched, so every error except BOLT_ERR_LAUNCH can be produced without a GPU.
+ *   - Accumulation is FP32 on the matrix cores; the epilogue runs in FP32 and converts once to
+ *     FP16 with round-to-nearest-even.
+ *   - Alignment (Section 3.2.3, "Kernel padding"): 128-bit accesses need every channel count,
+ *     reduction length and leading dimension to be a multiple of 8, else BOLT_ERR_ALIGNMENT;
+ *     pad with bolt_pad_channels_nhwc first.
+ */
+#ifndef BOLT_H_
+#define BOLT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BOLT_OK = 0,
+  BOLT_ERR_INVALID_ARG = 1,     /* null pointer, non-positive size, unknown enum value        */
+  BOLT_ERR_UNSUPPORTED = 2,     /* no compiled template instance can run this problem          */
+  BOLT_ERR_ALIGNMENT = 3,       /* a size / leading dimension / pointer breaks the 8-half rule */
+  BOLT_ERR_WORKSPACE = 4,       /* workspace missing or too small                              */
+  BOLT_ERR_LAUNCH = 5,          /* the HIP runtime reported an error                           */
+  BOLT_ERR_ILLEGAL_FUSION = 6   /* the two ops cannot be fused (Section 3.1.1 preconditions)   */
+} bolt_status;
+
+/* Epilogue activations (Section 3.1 pattern (i); Section 3.3 lists ReLU, GELU, Hardswish, Softplus). */
+typedef enum {
+  BOLT_ACT_NONE = 0,
+  BOLT_ACT_RELU = 1,
+  BOLT_ACT_GELU = 2,       /* 0.5 v (1 + erf(v / sqrt 2)) */
+  BOLT_ACT_HARDSWISH = 3,  /* v * clamp(v + 3, 0, 6) / 6   */
+  BOLT_ACT_SOFTPLUS = 4    /* log(1 + exp v)               */
+} bolt_act;
+
+typedef enum { BOLT_OP_GEMM = 0, BOLT_OP_CONV2D = 1, BOLT_OP_B2B_GEMM = 2, BOLT_OP_B2B_CONV = 3 } bolt_op;
+
+/* Storage of a GEMM's second operand. */
+typedef enum {
+  BOLT_LAYOUT_KN = 0, /* B[k][n] at B[k*ldb + n]: row-major K x N                      */
+  BOLT_LAYOUT_NK = 1  /* B[k][n] at B[n*ldb + k]: N x K, reduction index contiguous     */
+} bolt_layout;
+
+/* How a b2b kernel keeps the first op's output tile on chip (Section 3.1.1). */
+typedef enum {
+  BOLT_B2B_RF = 0,  /* register-file resident: each wave owns whole rows of D0            */
+  BOLT_B2B_LDS = 1  /* LDS resident: D0 tile staged through LDS and shared between waves   */
+} bolt_b2b_mode;
+
+/*
+ * The searched template parameters (Section 3.2.2: threadblock / warp / instruction shapes,
+ * swizzling functor, stages, ...).  kernel_id selects a compiled instance of the op's table
+ * (0 <= kernel_id < bolt_num_instances(op)); kernel_id = -1 (or a NULL config) lets the library
+ * choose by a built-in rule.  swizzle and split_k are run-time knobs and are honoured as given
+ * (0 is read as "off"); the remaining fields describe the instance and are filled in by
+ * bolt_tune / bolt_instance_config, ignored on input.
+ */
+typedef struct {
+  int32_t kernel_id;
+  int32_t tile_m, tile_n, tile_k; /* workgroup tile                                              */
+  int32_t waves_m, waves_n;       /* wave grid inside the workgroup (64-lane wavefronts)          */
+  int32_t mfma_shape;             /* 32 = v_mfma_f32_32x32x16_f16                                 */
+  int32_t stages;                 /* LDS buffers in the operand pipeline                          */
+  int32_t swizzle;                /* 0: n-tile fastest; g>0: XCD-aware remap, bands of g m-tiles  */
+  int32_t split_k;                /* >1: K split over workgroups, FP32 partials in the workspace  */
+  int32_t b2b_mode;               /* bolt_b2b_mode, b2b ops only                                  */
+} bolt_config;
+
+/* D[M x N] = act(alpha * A[M x K] . B[K x N] + beta * bias[N])   (Eq. 1 with C0 = broadcast bias) */
+typedef struct {
+  int32_t M, N, K;
+  int32_t lda, ldb, ldd; /* in elements; A and D are row-major                                   */
+  float alpha, beta;
+  int32_t act;           /* bolt_act                                                              */
+  int32_t b_layout;      /* bolt_layout                                                           */
+} bolt_gemm_desc;
+
+/* y[N,P,Q,K] = act(alpha * conv(x[N,H,W,C], w[K,R,S,C]) + beta * bias[K]); cross-correlation,
+ * zero padding, P = (H + 2 pad_h - R) / stride_h + 1 (floor), Q likewise; dilation 1, groups 1. */
+typedef struct {
+  int32_t N, H, W, C;
+  int32_t K, R, S;
+  int32_t stride_h, stride_w, pad_h, pad_w;
+  float alpha, beta;
+  int32_t act; /* bolt_act */
+} bolt_conv_desc;
+
+/* GEMM + fused epilogue (Section 2.2 tiling; Section 3.1 epilogue fusion patterns (i)-(iii)).
+ * A: M x K (lda), B per desc->b_layout (ldb), bias: N halves or NULL (beta term skipped),
+ * D: M x N (ldd).  Requires K, N, lda, ldb, ldd multiples of 8. */
+bolt_status bolt_gemm_epilogue(const bolt_gemm_desc* desc, const void* A, const void* B, const void* bias, void* D,
+                               const bolt_config* config, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Implicit-GEMM NHWC forward convolution + fused epilogue (Section 3.2.3: NHWC only; workloads of
+ * Section 4.1.1).  x: N*H*W*C, w: K*R*S*C, bias: K halves or NULL, y: N*P*Q*K.  Requires C and K
+ * multiples of 8. */
+bolt_status bolt_conv2d_fprop_nhwc(const bolt_conv_desc* desc, const void* x, const void* w, const void* bias,
+                                   void* y, const bolt_config* config, void* workspace, size_t workspace_bytes,
+                                   void* stream);
+
+/* Persistent back-to-back GEMM (Eq. 1-2, Section 3.1.1): D0 = act0(alpha0 A0.W0 + beta0 b0) is
+ * rounded to FP16 and stays on chip; D1 = act1(alpha1 D0.W1 + beta1 b1) is the only output.
+ * Legal only if g1->M == g0->M and g1->K == g0->N (else BOLT_ERR_ILLEGAL_FUSION).  Threadblock
+ * residence: the workgroup tile spans all of N0 and N1, so N0 <= 128, N1 <= 256 and both weight
+ * matrices must fit in LDS next to the streaming tiles (else BOLT_ERR_UNSUPPORTED).
+ * g0->ldd and g1->lda are ignored (D0 is never stored). */
+bolt_status bolt_b2b_gemm(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1, const void* A0, const void* W0,
+                          const void* b0, const void* W1, const void* b1, void* D1, const bolt_config* config,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* Persistent back-to-back convolution: c0 is any supported conv, c1 must be 1x1, stride 1, no
+ * padding, with c1->C == c0->K and c1's input extent equal to c0's output extent
+ * (N, P0, Q0) (else BOLT_ERR_ILLEGAL_FUSION).  Same residence limits as bolt_b2b_gemm with
+ * N0 = c0->K, N1 = c1->K. */
+bolt_status bolt_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc* c1, const void* x, const void* w0,
+                          const void* b0, const void* w1, const void* b1, void* y, const bolt_config* config,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* Light-weight profiler (Section 3.2.2): runs every compiled instance that is legal for the given
+ * problem (and a few split-K / swizzle settings) on the caller's real buffers, times them with
+ * HIP events and returns the fastest.  ptrs holds the device pointers of the op call in call order:
+ *   GEMM  {A, B, bias, D}            CONV     {x, w, bias, y}
+ *   B2B_GEMM {A0, W0, b0, W1, b1, D1}  B2B_CONV {x, w0, b0, w1, b1, y}
+ * desc1 is NULL for single ops.  The output buffer is overwritten.  Synchronises the stream.
+ * best_ms (may be NULL) receives the mean time per launch of the winner, n_tried (may be NULL) the
+ * number of candidates timed.  Results are cached per (op, shape) for the life of the process. */
+bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const void* const* ptrs, void* workspace,
+                      size_t workspace_bytes, void* stream, bolt_config* best, float* best_ms, int32_t* n_tried);
+
+/* dst[p, 0:C] = src[p, 0:C], dst[p, C:C_padded] = 0 for p < pixels (Section 3.2.3, Kernel
+ * padding).  C_padded >= C, C_padded % 8 == 0. src and dst must not overlap. */
+bolt_status bolt_pad_channels_nhwc(const void* src, void* dst, int64_t pixels, int32_t C, int32_t C_padded,
+                                   void* stream);
+
+/* Workspace bytes the op needs with this config (0 unless split_k > 1).  With config NULL: an
+ * upper bound over everything bolt_tune may try for this problem. */
+size_t bolt_workspace_bytes(bolt_op op, const void* desc0, const void* desc1, const bolt_config* config);
+
+/* Validation only: the status the op call would return before launching anything (no GPU needed). */
+bolt_status bolt_check(bolt_op op, const void* desc0, const void* desc1, const bolt_config* config);
+
+const char* bolt_status_string(bolt_status s);
+
+/* Number of compiled template instances of an op, and the description of instance kernel_id. */
+int32_t bolt_num_instances(bolt_op op);
+bolt_status bolt_instance_config(bolt_op op, int32_t kernel_id, bolt_config* out);
+/* Whether instance kernel_id can run the described problem (1) or not (0). */
+int32_t bolt_instance_supports(bolt_op op, int32_t kernel_id, const void* desc0, const void* desc1);
+
+/* Measured roofline denominators: runs an MFMA-only loop (returns sustained FP16 TFLOP/s) or a
+ * streaming copy of `bytes` bytes between two halves of `buffer` (returns GB/s, read + write). */
+bolt_status bolt_probe_mfma_peak(int32_t iterations, void* stream, float* tflops);
+bolt_status bolt_probe_copy_bandwidth(void* buffer, size_t bytes, int32_t repeats, void* stream, float* gbps);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BOLT_H_ */

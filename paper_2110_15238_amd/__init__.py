@@ -1,0 +1,24 @@
+"""MI355X-native Bolt hot path: FP16 MFMA GEMM / implicit-GEMM conv with fused epilogues,
+persistent back-to-back fusion, channel padding and the light-weight tuner, behind libbolt.so.
+
+The Python layer only marshals arguments; importing it fails if the HIP library is not built.
+"""
+from . import binding
+from .binding import (ACT, LAYOUT_KN, LAYOUT_NK, OP_B2B_CONV, OP_B2B_GEMM, OP_CONV2D, OP_GEMM, BoltConfig, BoltError,
+                      ConvDesc, GemmDesc, TuneResult, conv_desc, conv_out_hw, gemm_desc)
+
+# the C ABI's entry points under their own names
+bolt_gemm_epilogue = binding.gemm_epilogue
+bolt_conv2d_fprop_nhwc = binding.conv2d_fprop_nhwc
+bolt_b2b_gemm = binding.b2b_gemm
+bolt_b2b_conv = binding.b2b_conv
+bolt_tune = binding.tune
+bolt_pad_channels_nhwc = binding.pad_channels_nhwc
+bolt_workspace_bytes = binding.workspace_bytes
+bolt_check = binding.check
+bolt_status_string = binding.status_string
+bolt_num_instances = binding.num_instances
+bolt_instance_config = binding.instance_config
+bolt_instance_supports = binding.instance_supports
+bolt_probe_mfma_peak = binding.probe_mfma_peak
+bolt_probe_copy_bandwidth = binding.probe_copy_bandwidth

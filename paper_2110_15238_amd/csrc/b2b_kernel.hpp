@@ -1,0 +1,416 @@
+// Persistent back-to-back GEMM / conv kernels (Section 3.1.1 of the paper).
+//
+//   D0 = act0(alpha0 * X . W0 + beta0 * b0)   rounded to FP16, never written to global memory
+//   D1 = act1(alpha1 * D0 . W1 + beta1 * b1)
+//
+// Threadblock residence: a workgroup tile covers BM rows and ALL columns of both ops (N0T >= N0,
+// N1T >= N1 are compile-time upper bounds; missing weight rows are zero-filled).  Both weight
+// matrices are loaded into LDS once per workgroup (160 KB of LDS per CU makes that possible for
+// the memory-bound shapes fusion targets) and the workgroup then walks over row tiles
+// persistently, streaming only activations.
+//
+//   b2b_rf_kernel  (RF-resident fusion): waves split the tile along M only, so a wave owns whole
+//     rows of D0.  The MFMA computes the transposed product, hence a lane's accumulators are runs
+//     of 4 consecutive D0 columns of ONE row: exactly a B-operand fragment of the second MFMA up
+//     to a permutation of the reduction index, which is applied to the W1 fragment reads instead.
+//     The epilogue of op0 is done on those registers; D0 never leaves the register file.
+//   b2b_lds_kernel (LDS-resident fusion): waves tile op0 in 2-D; the FP16 D0 tile is stored to LDS
+//     in the swizzled operand layout and re-read as the activation operand of op1 by a different
+//     2-D wave tiling, which lifts the "wave tile N = N" restriction.
+#pragma once
+#include "bolt_device.hpp"
+#include "tile_loaders.hpp"
+
+namespace bolt {
+
+struct B2bParams {
+  const half_t* X;
+  const half_t* W0;
+  const half_t* b0;
+  const half_t* W1;
+  const half_t* b1;
+  half_t* Y;
+  int M, N0, K0, N1;
+  int ldx, ldw0, ldw1, ldy;
+  float alpha0, beta0, alpha1, beta1;
+  int act0, act1;
+  int tiles_m;
+  ConvGeom cg;  // XMODE 1 only (geometry of op0)
+};
+
+template <int N0T>
+struct B2bK1 {
+  static constexpr int KB1 = N0T < 64 ? N0T : 64;  // K-tile width of op1's LDS operands
+  static constexpr int NKT1 = N0T / KB1;
+};
+
+// Loads W0 as [nk0][N0T][BK] and W1 as [N0T/KB1][N1T][KB1] into LDS (all threads, then barrier).
+template <int BK, int NT, int N0T, int N1T, int WMODE>
+__device__ __forceinline__ void b2b_preload_weights(const B2bParams& p, half_t* W0s, half_t* W1s, int tid) {
+  constexpr int KB1 = B2bK1<N0T>::KB1;
+  const int nk0 = (p.K0 + BK - 1) / BK;
+  {
+    WTileLoader<N0T, BK, NT, WMODE> wl;
+    wl.init(p.W0, p.ldw0, p.N0, p.K0, 0, tid);
+    for (int kt = 0; kt < nk0; ++kt) {
+      wl.load(kt);
+      wl.store(W0s + kt * N0T * BK);
+    }
+  }
+  {
+    WTileLoader<N1T, KB1, NT, WMODE> wl;
+    wl.init(p.W1, p.ldw1, p.N1, p.N0, 0, tid);
+#pragma unroll
+    for (int kt = 0; kt < B2bK1<N0T>::NKT1; ++kt) {
+      wl.load(kt);
+      wl.store(W1s + kt * N1T * KB1);
+    }
+  }
+  __syncthreads();
+}
+
+// Epilogue of op1 for accumulators in the transposed MFMA layout, direct 8-byte stores.
+template <int FN, int FM>
+__device__ __forceinline__ void b2b_store_tile(const B2bParams& p, floatx16 (&acc)[FN][FM], int mrow, int ncol) {
+#pragma unroll
+  for (int a = 0; a < FN; ++a)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int n = ncol + a * 32 + q * 8;
+      if (n < p.N1) {
+        float bv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (p.b1) {
+          const half4 hb = *(const half4*)(p.b1 + n);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[e] = p.beta1 * (float)hb[e];
+        }
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+          const int m = mrow + b * 32;
+          if (m < p.M) {
+            half4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (half_t)apply_act(p.alpha1 * acc[a][b][q * 4 + e] + bv[e], p.act1);
+            *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
+          }
+        }
+      }
+    }
+}
+
+template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
+struct B2bRfTraits {
+  static constexpr int NT = 64 * NWAVES;
+  static constexpr int WTM = BM / NWAVES, FM = WTM / 32;
+  static constexpr int FN0 = N0T / 32, FN1 = N1T / 32;
+  static constexpr int NC1 = FN1 < 4 ? FN1 : 4;  // op1 accumulators live NC1 column fragments at a time
+  static_assert(WTM % 32 == 0 && N0T % 32 == 0 && N1T % 32 == 0 && FN1 % NC1 == 0, "tile shape");
+  static int lds_bytes(int K0) {
+    const int nk0 = (K0 + BK - 1) / BK;
+    return (nk0 * N0T * BK + N0T * N1T + 2 * BM * BK) * 2;
+  }
+};
+
+template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
+__global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) {
+  using T = B2bRfTraits<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE>;
+  constexpr int NT = T::NT, WTM = T::WTM, FM = T::FM, FN0 = T::FN0, FN1 = T::FN1, NC1 = T::NC1;
+  constexpr int KB1 = B2bK1<N0T>::KB1;
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  const int nk0 = (p.K0 + BK - 1) / BK;
+  half_t* W0s = lds;
+  half_t* W1s = W0s + nk0 * N0T * BK;
+  half_t* Xs = W1s + N0T * N1T;  // [2][BM*BK]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, l32 = lane & 31;
+  b2b_preload_weights<BK, NT, N0T, N1T, WMODE>(p, W0s, W1s, tid);
+
+  for (int tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
+    const int m0 = tile * BM;
+    XTileLoader<BM, BK, NT, XMODE> xl;
+    xl.init(p.X, p.ldx, p.M, p.K0, p.cg, m0, 0, tid);
+
+    floatx16 acc0[FN0][FM];
+#pragma unroll
+    for (int a = 0; a < FN0; ++a)
+#pragma unroll
+      for (int b = 0; b < FM; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc0[a][b][r] = 0.f;
+
+    // ---- op0 main loop: X streamed through a double-buffered LDS tile, W0 resident ----------
+    xl.load(0, p.cg);
+    xl.store(Xs);
+    __syncthreads();
+    for (int kt = 0; kt < nk0; ++kt) {
+      const int buf = kt & 1;
+      const bool more = kt + 1 < nk0;
+      if (more) xl.load(kt + 1, p.cg);
+      const half_t* xs = Xs + buf * BM * BK;
+      const half_t* ws = W0s + kt * N0T * BK;
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        half8 xf[FM], wf[FN0];
+        const int chunk = ks * 2 + g;
+#pragma unroll
+        for (int b = 0; b < FM; ++b) xf[b] = *(const half8*)(xs + lds_chunk_offset<BK>(wave * WTM + b * 32 + l32, chunk));
+#pragma unroll
+        for (int a = 0; a < FN0; ++a) wf[a] = *(const half8*)(ws + lds_chunk_offset<BK>(a * 32 + l32, chunk));
+#pragma unroll
+        for (int a = 0; a < FN0; ++a)
+#pragma unroll
+          for (int b = 0; b < FM; ++b) acc0[a][b] = mfma_32x32x16(wf[a], xf[b], acc0[a][b]);
+      }
+      if (more) xl.store(Xs + (buf ^ 1) * BM * BK);
+      __syncthreads();
+    }
+
+    // ---- epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 ------------
+    // Step t = 2a + h of op1 reduces over D0 columns [32a + 16h, 32a + 16h + 16).  Lane group g
+    // holds columns 32a+16h+4g+{0..3} (registers 8h..8h+3) and 32a+16h+8+4g+{0..3} (8h+4..8h+7).
+    half8 d0[FN0 * 2][FM];
+#pragma unroll
+    for (int a = 0; a < FN0; ++a)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int c0 = a * 32 + h * 16 + g * 4;
+        float bv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bv[e] = 0.f;
+        if (p.b0) {
+          if (c0 < p.N0) {
+            const half4 hb = *(const half4*)(p.b0 + c0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) bv[e] = p.beta0 * (float)hb[e];
+          }
+          if (c0 + 8 < p.N0) {
+            const half4 hb = *(const half4*)(p.b0 + c0 + 8);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) bv[4 + e] = p.beta0 * (float)hb[e];
+          }
+        }
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+          half8 d;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int col = c0 + (e < 4 ? e : e + 4);
+            const float v = apply_act(p.alpha0 * acc0[a][b][h * 8 + e] + bv[e], p.act0);
+            d[e] = col < p.N0 ? (half_t)v : (half_t)0.f;
+          }
+          d0[a * 2 + h][b] = d;
+        }
+      }
+
+    // ---- op1: W1 fragments from LDS with the matching reduction-index permutation ------------
+    const int mrow = m0 + wave * WTM + l32;
+#pragma unroll
+    for (int c1 = 0; c1 < FN1 / NC1; ++c1) {
+      floatx16 acc1[NC1][FM];
+#pragma unroll
+      for (int a = 0; a < NC1; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc1[a][b][r] = 0.f;
+#pragma unroll
+      for (int t = 0; t < FN0 * 2; ++t) {
+        const int kbase = t * 16;            // first D0 column of this step
+        const int kt1 = kbase / KB1;         // LDS k-tile of W1
+        const int chunk = (kbase % KB1) / 8; // chunk of columns kbase .. kbase+7 (then +1)
+        const half_t* ws = W1s + kt1 * N1T * KB1;
+#pragma unroll
+        for (int a = 0; a < NC1; ++a) {
+          const int row = (c1 * NC1 + a) * 32 + l32;
+          const half4 lo = *(const half4*)(ws + lds_chunk_offset<KB1>(row, chunk) + g * 4);
+          const half4 hi = *(const half4*)(ws + lds_chunk_offset<KB1>(row, chunk + 1) + g * 4);
+          const half8 wf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+          for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(wf, d0[t][b], acc1[a][b]);
+        }
+      }
+      b2b_store_tile<NC1, FM>(p, acc1, mrow, c1 * NC1 * 32 + g * 4);
+    }
+  }
+}
+
+template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE>
+struct B2bLdsTraits {
+  static constexpr int NT = 64 * WM0 * WN0;
+  static_assert(WM0 * WN0 == WM1 * WN1, "both wave grids use the same waves");
+  static constexpr int WTM0 = BM / WM0, WTN0 = N0T / WN0, FM0 = WTM0 / 32, FN0 = WTN0 / 32;
+  static constexpr int WTM1 = BM / WM1, WTN1 = N1T / WN1, FM1 = WTM1 / 32, FN1 = WTN1 / 32;
+  static_assert(WTM0 % 32 == 0 && WTN0 % 32 == 0 && WTM1 % 32 == 0 && WTN1 % 32 == 0, "tile shape");
+  static int lds_bytes(int K0) {
+    const int nk0 = (K0 + BK - 1) / BK;
+    return (nk0 * N0T * BK + N0T * N1T + 2 * BM * BK + BM * N0T) * 2;
+  }
+};
+
+template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE>
+__global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams p) {
+  using T = B2bLdsTraits<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>;
+  constexpr int NT = T::NT, FM0 = T::FM0, FN0 = T::FN0, FM1 = T::FM1, FN1 = T::FN1;
+  constexpr int WTM0 = T::WTM0, WTN0 = T::WTN0, WTM1 = T::WTM1, WTN1 = T::WTN1;
+  constexpr int KB1 = B2bK1<N0T>::KB1, NKT1 = B2bK1<N0T>::NKT1;
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  const int nk0 = (p.K0 + BK - 1) / BK;
+  half_t* W0s = lds;
+  half_t* W1s = W0s + nk0 * N0T * BK;
+  half_t* Xs = W1s + N0T * N1T;    // [2][BM*BK]
+  half_t* D0s = Xs + 2 * BM * BK;  // [NKT1][BM*KB1]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, l32 = lane & 31;
+  const int wm0 = wave % WM0, wn0 = wave / WM0;
+  const int wm1 = wave % WM1, wn1 = wave / WM1;
+  b2b_preload_weights<BK, NT, N0T, N1T, WMODE>(p, W0s, W1s, tid);
+
+  for (int tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
+    const int m0 = tile * BM;
+    XTileLoader<BM, BK, NT, XMODE> xl;
+    xl.init(p.X, p.ldx, p.M, p.K0, p.cg, m0, 0, tid);
+
+    floatx16 acc0[FN0][FM0];
+#pragma unroll
+    for (int a = 0; a < FN0; ++a)
+#pragma unroll
+      for (int b = 0; b < FM0; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc0[a][b][r] = 0.f;
+
+    xl.load(0, p.cg);
+    xl.store(Xs);
+    __syncthreads();
+    for (int kt = 0; kt < nk0; ++kt) {
+      const int buf = kt & 1;
+      const bool more = kt + 1 < nk0;
+      if (more) xl.load(kt + 1, p.cg);
+      const half_t* xs = Xs + buf * BM * BK;
+      const half_t* ws = W0s + kt * N0T * BK;
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        half8 xf[FM0], wf[FN0];
+        const int chunk = ks * 2 + g;
+#pragma unroll
+        for (int b = 0; b < FM0; ++b) xf[b] = *(const half8*)(xs + lds_chunk_offset<BK>(wm0 * WTM0 + b * 32 + l32, chunk));
+#pragma unroll
+        for (int a = 0; a < FN0; ++a) wf[a] = *(const half8*)(ws + lds_chunk_offset<BK>(wn0 * WTN0 + a * 32 + l32, chunk));
+#pragma unroll
+        for (int a = 0; a < FN0; ++a)
+#pragma unroll
+          for (int b = 0; b < FM0; ++b) acc0[a][b] = mfma_32x32x16(wf[a], xf[b], acc0[a][b]);
+      }
+      if (more) xl.store(Xs + (buf ^ 1) * BM * BK);
+      __syncthreads();
+    }
+
+    // ---- epilogue0 -> FP16 D0 tile in LDS, in the operand layout of op1 ----------------------
+    // (the last barrier of the loop above orders this after every read of the previous tile's D0s)
+#pragma unroll
+    for (int a = 0; a < FN0; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = wn0 * WTN0 + a * 32 + q * 8 + g * 4;
+        float bv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (p.b0 && col < p.N0) {
+          const half4 hb = *(const half4*)(p.b0 + col);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) bv[e] = p.beta0 * (float)hb[e];
+        }
+#pragma unroll
+        for (int b = 0; b < FM0; ++b) {
+          half4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float v = apply_act(p.alpha0 * acc0[a][b][q * 4 + e] + bv[e], p.act0);
+            o[e] = col < p.N0 ? (half_t)v : (half_t)0.f;
+          }
+          const int row = wm0 * WTM0 + b * 32 + l32;
+          *(half4*)(D0s + (col / KB1) * BM * KB1 + lds_chunk_offset<KB1>(row, (col % KB1) / 8) + (col & 4)) = o;
+        }
+      }
+    __syncthreads();
+
+    // ---- op1: both operands from LDS -----------------------------------------------------------
+    floatx16 acc1[FN1][FM1];
+#pragma unroll
+    for (int a = 0; a < FN1; ++a)
+#pragma unroll
+      for (int b = 0; b < FM1; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc1[a][b][r] = 0.f;
+#pragma unroll
+    for (int kt1 = 0; kt1 < NKT1; ++kt1) {
+      const half_t* xs = D0s + kt1 * BM * KB1;
+      const half_t* ws = W1s + kt1 * N1T * KB1;
+#pragma unroll
+      for (int ks = 0; ks < KB1 / 16; ++ks) {
+        half8 xf[FM1], wf[FN1];
+        const int chunk = ks * 2 + g;
+#pragma unroll
+        for (int b = 0; b < FM1; ++b) xf[b] = *(const half8*)(xs + lds_chunk_offset<KB1>(wm1 * WTM1 + b * 32 + l32, chunk));
+#pragma unroll
+        for (int a = 0; a < FN1; ++a) wf[a] = *(const half8*)(ws + lds_chunk_offset<KB1>(wn1 * WTN1 + a * 32 + l32, chunk));
+#pragma unroll
+        for (int a = 0; a < FN1; ++a)
+#pragma unroll
+          for (int b = 0; b < FM1; ++b) acc1[a][b] = mfma_32x32x16(wf[a], xf[b], acc1[a][b]);
+      }
+    }
+    b2b_store_tile<FN1, FM1>(p, acc1, m0 + wm1 * WTM1 + l32, wn1 * WTN1 + g * 4);
+  }
+}
+
+struct B2bInstance {
+  const char* name;
+  int mode;  // 0 RF-resident, 1 LDS-resident
+  int bm, bk, waves_m, waves_n, n0t, n1t, xmode, wmode, nthreads;
+  int (*lds_bytes)(int K0);
+  hipError_t (*launch)(const B2bParams&, int grid, int lds_bytes, hipStream_t);
+};
+
+template <typename KernT>
+hipError_t b2b_launch_common(KernT kern, bool& attr_set, const B2bParams& p, int grid, int nthreads, int lds_bytes,
+                             hipStream_t stream) {
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(nthreads), lds_bytes, stream, p);
+  return hipGetLastError();
+}
+
+template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
+hipError_t launch_b2b_rf(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
+  static bool attr_set = false;
+  return b2b_launch_common(b2b_rf_kernel<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE>, attr_set, p, grid, 64 * NWAVES,
+                           lds_bytes, stream);
+}
+
+template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE>
+hipError_t launch_b2b_lds(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
+  static bool attr_set = false;
+  return b2b_launch_common(b2b_lds_kernel<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>, attr_set, p, grid,
+                           64 * WM0 * WN0, lds_bytes, stream);
+}
+
+#define BOLT_B2B_RF_INSTANCE(BM, BK, NW, N0T, N1T, XMODE, WMODE)                                         \
+  {                                                                                                      \
+    "rf_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T, 0, BM, BK, NW, 1, N0T, N1T, XMODE, WMODE, 64 * NW,     \
+        &bolt::B2bRfTraits<BM, BK, NW, N0T, N1T, XMODE, WMODE>::lds_bytes,                                \
+        &bolt::launch_b2b_rf<BM, BK, NW, N0T, N1T, XMODE, WMODE>                                          \
+  }
+#define BOLT_B2B_LDS_INSTANCE(BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE)                          \
+  {                                                                                                      \
+    "lds_" #BM "x" #BK "_w" #WM0 "x" #WN0 "_" #WM1 "x" #WN1 "_n" #N0T "_" #N1T, 1, BM, BK, WM0, WN0, N0T, \
+        N1T, XMODE, WMODE, 64 * WM0 * WN0,                                                               \
+        &bolt::B2bLdsTraits<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>::lds_bytes,               \
+        &bolt::launch_b2b_lds<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>                         \
+  }
+
+}  // namespace bolt

@@ -1,0 +1,812 @@
+// Host side of the C ABI declared in include/bolt.h: descriptor validation, instance tables,
+// the built-in pick rule, the light-weight profiler (Section 3.2.2), and the small helper kernels
+// (channel padding, split-K reduction, roofline probes).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "../../include/bolt.h"
+#include "instances.hpp"
+
+namespace bolt {
+
+static constexpr int kNumCU = 256;            // MI355X compute units
+static constexpr int kLdsPerCU = 160 * 1024;  // bytes of LDS per compute unit / per workgroup
+static constexpr int kMaxSplitK = 8;
+
+// ------------------------------------------------------------------------------------------
+// helper kernels
+// ------------------------------------------------------------------------------------------
+
+// Sums split-K partials and applies the epilogue once.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial, const half_t* bias, half_t* Y,
+                                                            int M, int N, int ldy, int split_k, float alpha,
+                                                            float beta, int act) {
+  const int64_t quads = (int64_t)M * (N / 4);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < quads; i += (int64_t)gridDim.x * blockDim.x) {
+    const int m = (int)(i / (N / 4)), n = (int)(i % (N / 4)) * 4;
+    floatx4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int zz = 0; zz < split_k; ++zz) s += *(const floatx4*)(partial + ((int64_t)zz * M + m) * N + n);
+    half4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float v = alpha * s[e];
+      if (bias) v += beta * (float)bias[n + e];
+      o[e] = (half_t)apply_act(v, act);
+    }
+    *(half4*)(Y + (int64_t)m * ldy + n) = o;
+  }
+}
+
+// Kernel padding (Section 3.2.3): one thread writes one 16-byte chunk of the padded tensor.
+__global__ __launch_bounds__(256) void pad_channels_kernel(const half_t* src, half_t* dst, int64_t pixels, int C,
+                                                           int C8) {
+  const int chunks = C8 / 8;
+  const int64_t total = pixels * chunks;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t pix = i / chunks;
+    const int c0 = (int)(i - pix * chunks) * 8;
+    half8 v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (c0 + e < C) ? src[pix * C + c0 + e] : (half_t)0.f;
+    *(half8*)(dst + pix * C8 + c0) = v;
+  }
+}
+
+// MFMA-only loop: 4 independent accumulator chains per wave, no memory traffic.
+__global__ __launch_bounds__(256) void mfma_peak_kernel(float* sink, int iters) {
+  half8 a, b;
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (half_t)(0.001f * (threadIdx.x + e));
+    b[e] = (half_t)(0.002f * (threadIdx.x - e));
+  }
+  floatx16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  for (int i = 0; i < iters; ++i) {
+    c0 = mfma_32x32x16(a, b, c0);
+    c1 = mfma_32x32x16(a, b, c1);
+    c2 = mfma_32x32x16(a, b, c2);
+    c3 = mfma_32x32x16(a, b, c3);
+  }
+  float s = 0.f;
+  for (int e = 0; e < 16; ++e) s += c0[e] + c1[e] + c2[e] + c3[e];
+  if (s == 123.456f) sink[0] = s;  // keeps the loop alive; practically never true
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const floatx4* src, floatx4* dst, int64_t n16) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+// ------------------------------------------------------------------------------------------
+// instance tables
+// ------------------------------------------------------------------------------------------
+struct Tables {
+  std::vector<FpropInstance> gemm, conv;
+  std::vector<B2bInstance> b2b_gemm, b2b_conv;
+  Tables() {
+    register_gemm_kn_instances(gemm);
+    register_gemm_nk_instances(gemm);
+    register_conv_instances(conv);
+    register_b2b_gemm_instances(b2b_gemm);
+    register_b2b_conv_instances(b2b_conv);
+  }
+};
+static const Tables& tables() {
+  static Tables t;
+  return t;
+}
+
+static inline bool is_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline bool valid_act(int a) { return a >= BOLT_ACT_NONE && a <= BOLT_ACT_SOFTPLUS; }
+
+// ------------------------------------------------------------------------------------------
+// validation (no GPU needed)
+// ------------------------------------------------------------------------------------------
+static bolt_status check_gemm_desc(const bolt_gemm_desc* d) {
+  if (!d) return BOLT_ERR_INVALID_ARG;
+  if (d->M <= 0 || d->N <= 0 || d->K <= 0) return BOLT_ERR_INVALID_ARG;
+  if (!valid_act(d->act)) return BOLT_ERR_INVALID_ARG;
+  if (d->b_layout != BOLT_LAYOUT_KN && d->b_layout != BOLT_LAYOUT_NK) return BOLT_ERR_INVALID_ARG;
+  if (d->lda < d->K || d->ldd < d->N) return BOLT_ERR_INVALID_ARG;
+  if (d->b_layout == BOLT_LAYOUT_KN ? d->ldb < d->N : d->ldb < d->K) return BOLT_ERR_INVALID_ARG;
+  if ((d->N | d->K | d->lda | d->ldb | d->ldd) & 7) return BOLT_ERR_ALIGNMENT;
+  if (d->lda > (1 << 22) || d->ldb > (1 << 22) || d->ldd > (1 << 22)) return BOLT_ERR_UNSUPPORTED;
+  return BOLT_OK;
+}
+
+struct ConvDims {
+  int P, Q, M, Kg;
+};
+
+static bolt_status check_conv_desc(const bolt_conv_desc* d, ConvDims* out) {
+  if (!d) return BOLT_ERR_INVALID_ARG;
+  if (d->N <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0)
+    return BOLT_ERR_INVALID_ARG;
+  if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return BOLT_ERR_INVALID_ARG;
+  if (!valid_act(d->act)) return BOLT_ERR_INVALID_ARG;
+  if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return BOLT_ERR_INVALID_ARG;
+  if ((d->C | d->K) & 7) return BOLT_ERR_ALIGNMENT;
+  const int64_t P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
+  const int64_t Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+  const int64_t M = (int64_t)d->N * P * Q;
+  const int64_t Kg = (int64_t)d->R * d->S * d->C;
+  const int64_t in_elems = (int64_t)d->N * d->H * d->W * d->C;
+  // the kernels index tensors with 32-bit element offsets and pack window origins in 16 bits
+  if (d->H > 16384 || d->W > 16384 || d->pad_h > 8192 || d->pad_w > 8192) return BOLT_ERR_UNSUPPORTED;
+  if (in_elems >= (1ll << 31) || M * d->K >= (1ll << 31) || M >= (1ll << 30) || Kg >= (1 << 24))
+    return BOLT_ERR_UNSUPPORTED;
+  if (out) *out = {(int)P, (int)Q, (int)M, (int)Kg};
+  return BOLT_OK;
+}
+
+static ConvGeom make_geom(const bolt_conv_desc* d, const ConvDims& cd) {
+  ConvGeom g;
+  g.H = d->H; g.Wi = d->W; g.C = d->C; g.R = d->R; g.S = d->S; g.P = cd.P; g.Q = cd.Q;
+  g.stride_h = d->stride_h; g.stride_w = d->stride_w; g.pad_h = d->pad_h; g.pad_w = d->pad_w;
+  return g;
+}
+
+static bolt_status check_b2b_gemm(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1) {
+  if (!g0 || !g1) return BOLT_ERR_INVALID_ARG;
+  bolt_gemm_desc a = *g0, b = *g1;
+  a.ldd = a.N;  // D0 is never stored: its leading dimension is irrelevant
+  b.lda = b.K;
+  bolt_status s = check_gemm_desc(&a);
+  if (s != BOLT_OK) return s;
+  s = check_gemm_desc(&b);
+  if (s != BOLT_OK) return s;
+  if (g1->M != g0->M || g1->K != g0->N) return BOLT_ERR_ILLEGAL_FUSION;
+  if (g0->b_layout != g1->b_layout) return BOLT_ERR_UNSUPPORTED;
+  return BOLT_OK;
+}
+
+static bolt_status check_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc* c1, ConvDims* cd0) {
+  ConvDims d0, d1;
+  bolt_status s = check_conv_desc(c0, &d0);
+  if (s != BOLT_OK) return s;
+  s = check_conv_desc(c1, &d1);
+  if (s != BOLT_OK) return s;
+  if (c1->R != 1 || c1->S != 1 || c1->stride_h != 1 || c1->stride_w != 1 || c1->pad_h != 0 || c1->pad_w != 0)
+    return BOLT_ERR_ILLEGAL_FUSION;
+  if (c1->C != c0->K || c1->N != c0->N || c1->H != d0.P || c1->W != d0.Q) return BOLT_ERR_ILLEGAL_FUSION;
+  if (cd0) *cd0 = d0;
+  return BOLT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// single-op problems
+// ------------------------------------------------------------------------------------------
+struct FpropProblem {
+  FpropParams p;  // pointers filled in at launch
+  int xmode, wmode;
+};
+
+static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
+  if (in.xmode != pr.xmode || in.wmode != pr.wmode) return false;
+  if (in.lds_bytes > kLdsPerCU) return false;
+  // a tile more than half empty along N is never worth timing (64 is the narrowest tile family)
+  if (in.bn > 64 && in.bn / 2 >= pr.p.N) return false;
+  return true;
+}
+
+static void fprop_fill_config(const FpropInstance& in, int id, bolt_config* c) {
+  c->kernel_id = id;
+  c->tile_m = in.bm; c->tile_n = in.bn; c->tile_k = in.bk;
+  c->waves_m = in.waves_m; c->waves_n = in.waves_n;
+  c->mfma_shape = 32; c->stages = 2; c->b2b_mode = 0;
+}
+
+// Built-in pick rule: smallest estimated time under a crude model -- rounds of workgroups over
+// the compute units times the work of one tile, de-rated for small tiles (low FLOP per LDS byte).
+static int fprop_heuristic(const std::vector<FpropInstance>& tab, const FpropProblem& pr) {
+  int best = -1;
+  double best_cost = 0;
+  for (int i = 0; i < (int)tab.size(); ++i) {
+    const FpropInstance& in = tab[i];
+    if (!fprop_supports(in, pr)) continue;
+    const double tiles = (double)ceil_div(pr.p.M, in.bm) * ceil_div(pr.p.N, in.bn);
+    const int per_cu = std::max(1, std::min(kLdsPerCU / in.lds_bytes, 2048 / (64 * in.waves_m * in.waves_n) / 2));
+    const double rounds = std::ceil(tiles / (kNumCU * per_cu)) * per_cu;
+    const double wtm = (double)in.bm / in.waves_m, wtn = (double)in.bn / in.waves_n;
+    const double eff = 1.0 / (1.0 + 48.0 * (1.0 / wtm + 1.0 / wtn) / 2.0);
+    const double cost = rounds * (double)in.bm * in.bn / eff;
+    if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
+  }
+  return best;
+}
+
+static size_t splitk_bytes(int M, int N, int split_k) {
+  return split_k > 1 ? (size_t)split_k * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+// Launch one instance with run-time knobs.  Pointers in pr.p must be set.
+static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int swizzle, int split_k, void* ws,
+                                size_t ws_bytes, hipStream_t stream) {
+  FpropParams& p = pr.p;
+  p.tiles_m = ceil_div(p.M, in.bm);
+  p.tiles_n = ceil_div(p.N, in.bn);
+  p.swizzle = swizzle < 0 ? 0 : swizzle;
+  const int nk = ceil_div(p.K, in.bk);
+  split_k = std::max(1, std::min(std::min(split_k, kMaxSplitK), nk));
+  p.ktiles_per_split = ceil_div(nk, split_k);
+  split_k = ceil_div(nk, p.ktiles_per_split);  // no empty splits
+  p.split_k = split_k;
+  p.partial = nullptr;
+  if (split_k > 1) {
+    if (!ws || ws_bytes < splitk_bytes(p.M, p.N, split_k) || !is_aligned16(ws)) return BOLT_ERR_WORKSPACE;
+    p.partial = (float*)ws;
+  }
+  if ((int64_t)p.tiles_m * p.tiles_n >= (1ll << 31)) return BOLT_ERR_UNSUPPORTED;
+  if (in.launch(p, stream) != hipSuccess) return BOLT_ERR_LAUNCH;
+  if (split_k > 1) {
+    const int64_t quads = (int64_t)p.M * (p.N / 4);
+    const int blocks = (int)std::min<int64_t>((quads + 255) / 256, kNumCU * 8);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p.partial, p.bias, p.Y, p.M, p.N,
+                       p.ldy, split_k, p.alpha, p.beta, p.act);
+    if (hipGetLastError() != hipSuccess) return BOLT_ERR_LAUNCH;
+  }
+  return BOLT_OK;
+}
+
+static bolt_status make_gemm_problem(const bolt_gemm_desc* d, FpropProblem* pr) {
+  bolt_status s = check_gemm_desc(d);
+  if (s != BOLT_OK) return s;
+  std::memset(pr, 0, sizeof(*pr));
+  pr->xmode = 0;
+  pr->wmode = d->b_layout == BOLT_LAYOUT_KN ? 1 : 0;
+  FpropParams& p = pr->p;
+  p.M = d->M; p.N = d->N; p.K = d->K;
+  p.ldx = d->lda; p.ldw = d->ldb; p.ldy = d->ldd;
+  p.alpha = d->alpha; p.beta = d->beta; p.act = d->act;
+  return BOLT_OK;
+}
+
+static bolt_status make_conv_problem(const bolt_conv_desc* d, FpropProblem* pr) {
+  ConvDims cd;
+  bolt_status s = check_conv_desc(d, &cd);
+  if (s != BOLT_OK) return s;
+  std::memset(pr, 0, sizeof(*pr));
+  pr->xmode = 1;
+  pr->wmode = 0;
+  FpropParams& p = pr->p;
+  p.M = cd.M; p.N = d->K; p.K = cd.Kg;
+  p.ldx = 0; p.ldw = cd.Kg; p.ldy = d->K;
+  p.alpha = d->alpha; p.beta = d->beta; p.act = d->act;
+  p.cg = make_geom(d, cd);
+  return BOLT_OK;
+}
+
+static bolt_status resolve_fprop(const std::vector<FpropInstance>& tab, const FpropProblem& pr,
+                                 const bolt_config* cfg, int* id, int* swizzle, int* split_k) {
+  *swizzle = cfg ? cfg->swizzle : 0;
+  *split_k = cfg && cfg->split_k > 1 ? cfg->split_k : 1;
+  if (*split_k > kMaxSplitK) return BOLT_ERR_INVALID_ARG;
+  if (cfg && cfg->kernel_id >= 0) {
+    if (cfg->kernel_id >= (int)tab.size()) return BOLT_ERR_INVALID_ARG;
+    if (!fprop_supports(tab[cfg->kernel_id], pr)) return BOLT_ERR_UNSUPPORTED;
+    *id = cfg->kernel_id;
+    return BOLT_OK;
+  }
+  if (cfg && cfg->kernel_id < -1) return BOLT_ERR_INVALID_ARG;
+  *id = fprop_heuristic(tab, pr);
+  return *id < 0 ? BOLT_ERR_UNSUPPORTED : BOLT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// back-to-back problems
+// ------------------------------------------------------------------------------------------
+struct B2bProblem {
+  B2bParams p;
+  int xmode, wmode;
+};
+
+static bool b2b_supports(const B2bInstance& in, const B2bProblem& pr) {
+  if (in.xmode != pr.xmode || in.wmode != pr.wmode) return false;
+  if (pr.p.N0 > in.n0t || pr.p.N1 > in.n1t) return false;
+  // threadblock residence with the tightest compiled bound: do not carry more than 2x padding
+  if ((in.n0t > 32 && in.n0t / 2 >= pr.p.N0) || (in.n1t > 32 && in.n1t / 2 >= pr.p.N1)) return false;
+  if (in.lds_bytes(pr.p.K0) > kLdsPerCU) return false;
+  return true;
+}
+
+static void b2b_fill_config(const B2bInstance& in, int id, bolt_config* c) {
+  c->kernel_id = id;
+  c->tile_m = in.bm; c->tile_n = in.n1t; c->tile_k = in.bk;
+  c->waves_m = in.waves_m; c->waves_n = in.waves_n;
+  c->mfma_shape = 32; c->stages = 2; c->swizzle = 0; c->split_k = 1; c->b2b_mode = in.mode;
+}
+
+static int b2b_heuristic(const std::vector<B2bInstance>& tab, const B2bProblem& pr) {
+  int best = -1;
+  double best_cost = 0;
+  for (int i = 0; i < (int)tab.size(); ++i) {
+    if (!b2b_supports(tab[i], pr)) continue;
+    const B2bInstance& in = tab[i];
+    const double tiles = ceil_div(pr.p.M, in.bm);
+    const double rounds = std::ceil(tiles / kNumCU);
+    double cost = rounds * in.bm * (in.mode == 0 ? 1.0 : 1.1) * (double)in.n0t * in.n1t;
+    if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
+  }
+  return best;
+}
+
+static bolt_status b2b_launch(const B2bInstance& in, B2bProblem pr, hipStream_t stream) {
+  B2bParams& p = pr.p;
+  p.tiles_m = ceil_div(p.M, in.bm);
+  const int lds = in.lds_bytes(p.K0);
+  if (lds > kLdsPerCU) return BOLT_ERR_UNSUPPORTED;
+  const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / in.nthreads));
+  const int grid = std::min(p.tiles_m, kNumCU * per_cu);
+  if (in.launch(p, grid, lds, stream) != hipSuccess) return BOLT_ERR_LAUNCH;
+  return BOLT_OK;
+}
+
+static bolt_status make_b2b_gemm_problem(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1, B2bProblem* pr) {
+  bolt_status s = check_b2b_gemm(g0, g1);
+  if (s != BOLT_OK) return s;
+  std::memset(pr, 0, sizeof(*pr));
+  pr->xmode = 0;
+  pr->wmode = g0->b_layout == BOLT_LAYOUT_KN ? 1 : 0;
+  B2bParams& p = pr->p;
+  p.M = g0->M; p.N0 = g0->N; p.K0 = g0->K; p.N1 = g1->N;
+  p.ldx = g0->lda; p.ldw0 = g0->ldb; p.ldw1 = g1->ldb; p.ldy = g1->ldd;
+  p.alpha0 = g0->alpha; p.beta0 = g0->beta; p.act0 = g0->act;
+  p.alpha1 = g1->alpha; p.beta1 = g1->beta; p.act1 = g1->act;
+  return BOLT_OK;
+}
+
+static bolt_status make_b2b_conv_problem(const bolt_conv_desc* c0, const bolt_conv_desc* c1, B2bProblem* pr) {
+  ConvDims cd;
+  bolt_status s = check_b2b_conv(c0, c1, &cd);
+  if (s != BOLT_OK) return s;
+  std::memset(pr, 0, sizeof(*pr));
+  pr->xmode = 1;
+  pr->wmode = 0;
+  B2bParams& p = pr->p;
+  p.M = cd.M; p.N0 = c0->K; p.K0 = cd.Kg; p.N1 = c1->K;
+  p.ldx = 0; p.ldw0 = cd.Kg; p.ldw1 = c1->C; p.ldy = c1->K;
+  p.alpha0 = c0->alpha; p.beta0 = c0->beta; p.act0 = c0->act;
+  p.alpha1 = c1->alpha; p.beta1 = c1->beta; p.act1 = c1->act;
+  p.cg = make_geom(c0, cd);
+  return BOLT_OK;
+}
+
+static bolt_status resolve_b2b(const std::vector<B2bInstance>& tab, const B2bProblem& pr, const bolt_config* cfg,
+                               int* id) {
+  if (cfg && cfg->kernel_id >= 0) {
+    if (cfg->kernel_id >= (int)tab.size()) return BOLT_ERR_INVALID_ARG;
+    if (!b2b_supports(tab[cfg->kernel_id], pr)) return BOLT_ERR_UNSUPPORTED;
+    *id = cfg->kernel_id;
+    return BOLT_OK;
+  }
+  if (cfg && cfg->kernel_id < -1) return BOLT_ERR_INVALID_ARG;
+  *id = b2b_heuristic(tab, pr);
+  return *id < 0 ? BOLT_ERR_UNSUPPORTED : BOLT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// profiler
+// ------------------------------------------------------------------------------------------
+struct TuneKey {
+  int op;
+  std::string bytes;
+  bool operator<(const TuneKey& o) const { return op != o.op ? op < o.op : bytes < o.bytes; }
+};
+struct TuneVal {
+  bolt_config cfg;
+  float ms;
+  int tried;
+};
+static std::map<TuneKey, TuneVal>& tune_cache() {
+  static std::map<TuneKey, TuneVal> c;
+  return c;
+}
+static std::mutex& tune_mutex() {
+  static std::mutex m;
+  return m;
+}
+
+struct Candidate {
+  int id, swizzle, split_k;
+  float ms;
+};
+
+// Mean milliseconds per launch of `fn` over `reps` back-to-back launches (after `warm` untimed).
+template <typename F>
+static bolt_status time_launches(F&& fn, int warm, int reps, hipStream_t stream, hipEvent_t e0, hipEvent_t e1,
+                                 float* ms) {
+  for (int i = 0; i < warm; ++i) {
+    bolt_status s = fn();
+    if (s != BOLT_OK) return s;
+  }
+  if (hipEventRecord(e0, stream) != hipSuccess) return BOLT_ERR_LAUNCH;
+  for (int i = 0; i < reps; ++i) {
+    bolt_status s = fn();
+    if (s != BOLT_OK) return s;
+  }
+  if (hipEventRecord(e1, stream) != hipSuccess) return BOLT_ERR_LAUNCH;
+  if (hipEventSynchronize(e1) != hipSuccess) return BOLT_ERR_LAUNCH;
+  float t = 0.f;
+  if (hipEventElapsedTime(&t, e0, e1) != hipSuccess) return BOLT_ERR_LAUNCH;
+  *ms = t / reps;
+  return BOLT_OK;
+}
+
+template <typename RunF>
+static bolt_status tune_candidates(std::vector<Candidate>& cands, RunF&& run, hipStream_t stream, Candidate* best,
+                                   int* tried) {
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return BOLT_ERR_LAUNCH;
+  bolt_status status = BOLT_OK;
+  int n_ok = 0;
+  // pass 1: a short timing of every candidate
+  for (auto& c : cands) {
+    bolt_status s = time_launches([&] { return run(c); }, 2, 5, stream, e0, e1, &c.ms);
+    if (s == BOLT_ERR_LAUNCH) { status = s; break; }
+    if (s != BOLT_OK) { c.ms = -1.f; continue; }
+    ++n_ok;
+  }
+  if (status == BOLT_OK && n_ok == 0) status = BOLT_ERR_UNSUPPORTED;
+  if (status == BOLT_OK) {
+    std::vector<Candidate*> order;
+    for (auto& c : cands) if (c.ms >= 0.f) order.push_back(&c);
+    std::sort(order.begin(), order.end(), [](Candidate* a, Candidate* b) { return a->ms < b->ms; });
+    // pass 2: the few fastest again, longer
+    const int finalists = std::min<int>(4, (int)order.size());
+    Candidate* win = nullptr;
+    for (int i = 0; i < finalists && status == BOLT_OK; ++i) {
+      Candidate* c = order[i];
+      bolt_status s = time_launches([&] { return run(*c); }, 3, 30, stream, e0, e1, &c->ms);
+      if (s != BOLT_OK) { status = s; break; }
+      if (!win || c->ms < win->ms) win = c;
+    }
+    if (status == BOLT_OK) { *best = *win; *tried = n_ok; }
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  return status;
+}
+
+static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>& tab, const FpropProblem& pr,
+                                               size_t ws_bytes, bool have_ws) {
+  std::vector<Candidate> out;
+  for (int i = 0; i < (int)tab.size(); ++i) {
+    const FpropInstance& in = tab[i];
+    if (!fprop_supports(in, pr)) continue;
+    const int tiles_m = ceil_div(pr.p.M, in.bm), tiles_n = ceil_div(pr.p.N, in.bn);
+    const int64_t tiles = (int64_t)tiles_m * tiles_n;
+    const int nk = ceil_div(pr.p.K, in.bk);
+    const int swz[2] = {0, 4};
+    const int nswz = (tiles_n > 1 && tiles_m > 1 && tiles >= 64) ? 2 : 1;
+    for (int s = 0; s < nswz; ++s) {
+      out.push_back({i, swz[s], 1, 0.f});
+    }
+    // split-K only when the grid cannot fill the chip and K is deep enough to share
+    for (int sk = 2; sk <= kMaxSplitK; sk *= 2) {
+      if (tiles * (sk / 2) >= kNumCU || nk < 2 * sk) break;
+      if (!have_ws || ws_bytes < splitk_bytes(pr.p.M, pr.p.N, sk)) break;
+      out.push_back({i, 0, sk, 0.f});
+    }
+  }
+  return out;
+}
+
+}  // namespace bolt
+
+// ==========================================================================================
+// C ABI
+// ==========================================================================================
+using namespace bolt;
+
+extern "C" {
+
+const char* bolt_status_string(bolt_status s) {
+  switch (s) {
+    case BOLT_OK: return "ok";
+    case BOLT_ERR_INVALID_ARG: return "invalid argument";
+    case BOLT_ERR_UNSUPPORTED: return "unsupported problem or configuration";
+    case BOLT_ERR_ALIGNMENT: return "size, leading dimension or pointer not aligned to 8 halves / 16 bytes";
+    case BOLT_ERR_WORKSPACE: return "workspace missing or too small";
+    case BOLT_ERR_LAUNCH: return "HIP runtime error";
+    case BOLT_ERR_ILLEGAL_FUSION: return "ops cannot be fused back to back";
+    default: return "unknown status";
+  }
+}
+
+int32_t bolt_num_instances(bolt_op op) {
+  switch (op) {
+    case BOLT_OP_GEMM: return (int32_t)tables().gemm.size();
+    case BOLT_OP_CONV2D: return (int32_t)tables().conv.size();
+    case BOLT_OP_B2B_GEMM: return (int32_t)tables().b2b_gemm.size();
+    case BOLT_OP_B2B_CONV: return (int32_t)tables().b2b_conv.size();
+    default: return 0;
+  }
+}
+
+bolt_status bolt_instance_config(bolt_op op, int32_t id, bolt_config* out) {
+  if (!out || id < 0 || id >= bolt_num_instances(op)) return BOLT_ERR_INVALID_ARG;
+  std::memset(out, 0, sizeof(*out));
+  out->split_k = 1;
+  switch (op) {
+    case BOLT_OP_GEMM: fprop_fill_config(tables().gemm[id], id, out); break;
+    case BOLT_OP_CONV2D: fprop_fill_config(tables().conv[id], id, out); break;
+    case BOLT_OP_B2B_GEMM: b2b_fill_config(tables().b2b_gemm[id], id, out); break;
+    case BOLT_OP_B2B_CONV: b2b_fill_config(tables().b2b_conv[id], id, out); break;
+    default: return BOLT_ERR_INVALID_ARG;
+  }
+  return BOLT_OK;
+}
+
+int32_t bolt_instance_supports(bolt_op op, int32_t id, const void* desc0, const void* desc1) {
+  if (id < 0 || id >= bolt_num_instances(op)) return 0;
+  FpropProblem fp;
+  B2bProblem bp;
+  switch (op) {
+    case BOLT_OP_GEMM:
+      return make_gemm_problem((const bolt_gemm_desc*)desc0, &fp) == BOLT_OK && fprop_supports(tables().gemm[id], fp);
+    case BOLT_OP_CONV2D:
+      return make_conv_problem((const bolt_conv_desc*)desc0, &fp) == BOLT_OK && fprop_supports(tables().conv[id], fp);
+    case BOLT_OP_B2B_GEMM:
+      return make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp) == BOLT_OK &&
+             b2b_supports(tables().b2b_gemm[id], bp);
+    case BOLT_OP_B2B_CONV:
+      return make_b2b_conv_problem((const bolt_conv_desc*)desc0, (const bolt_conv_desc*)desc1, &bp) == BOLT_OK &&
+             b2b_supports(tables().b2b_conv[id], bp);
+    default: return 0;
+  }
+}
+
+bolt_status bolt_check(bolt_op op, const void* desc0, const void* desc1, const bolt_config* config) {
+  FpropProblem fp;
+  B2bProblem bp;
+  int id, swz, sk;
+  bolt_status s;
+  switch (op) {
+    case BOLT_OP_GEMM:
+      s = make_gemm_problem((const bolt_gemm_desc*)desc0, &fp);
+      return s != BOLT_OK ? s : resolve_fprop(tables().gemm, fp, config, &id, &swz, &sk);
+    case BOLT_OP_CONV2D:
+      s = make_conv_problem((const bolt_conv_desc*)desc0, &fp);
+      return s != BOLT_OK ? s : resolve_fprop(tables().conv, fp, config, &id, &swz, &sk);
+    case BOLT_OP_B2B_GEMM:
+      s = make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp);
+      return s != BOLT_OK ? s : resolve_b2b(tables().b2b_gemm, bp, config, &id);
+    case BOLT_OP_B2B_CONV:
+      s = make_b2b_conv_problem((const bolt_conv_desc*)desc0, (const bolt_conv_desc*)desc1, &bp);
+      return s != BOLT_OK ? s : resolve_b2b(tables().b2b_conv, bp, config, &id);
+    default: return BOLT_ERR_INVALID_ARG;
+  }
+}
+
+size_t bolt_workspace_bytes(bolt_op op, const void* desc0, const void* desc1, const bolt_config* config) {
+  (void)desc1;
+  FpropProblem fp;
+  bolt_status s;
+  if (op == BOLT_OP_GEMM) s = make_gemm_problem((const bolt_gemm_desc*)desc0, &fp);
+  else if (op == BOLT_OP_CONV2D) s = make_conv_problem((const bolt_conv_desc*)desc0, &fp);
+  else return 0;
+  if (s != BOLT_OK) return 0;
+  if (config) return splitk_bytes(fp.p.M, fp.p.N, std::min<int>(config->split_k, kMaxSplitK));
+  // upper bound for tuning: split-K is only tried while the output is small
+  size_t need = 0;
+  for (int sk = 2; sk <= kMaxSplitK; sk *= 2) {
+    const int64_t min_tiles = (int64_t)ceil_div(fp.p.M, 256) * ceil_div(fp.p.N, 256);
+    if (min_tiles * (sk / 2) >= kNumCU) break;
+    need = splitk_bytes(fp.p.M, fp.p.N, sk);
+  }
+  return need;
+}
+
+bolt_status bolt_gemm_epilogue(const bolt_gemm_desc* desc, const void* A, const void* B, const void* bias, void* D,
+                               const bolt_config* config, void* workspace, size_t workspace_bytes, void* stream) {
+  FpropProblem pr;
+  bolt_status s = make_gemm_problem(desc, &pr);
+  if (s != BOLT_OK) return s;
+  if (!A || !B || !D) return BOLT_ERR_INVALID_ARG;
+  if (!is_aligned16(A) || !is_aligned16(B) || !is_aligned16(D) || (bias && !is_aligned16(bias))) return BOLT_ERR_ALIGNMENT;
+  int id, swz, sk;
+  s = resolve_fprop(tables().gemm, pr, config, &id, &swz, &sk);
+  if (s != BOLT_OK) return s;
+  pr.p.X = (const half_t*)A; pr.p.W = (const half_t*)B; pr.p.bias = (const half_t*)bias; pr.p.Y = (half_t*)D;
+  return fprop_launch(tables().gemm[id], pr, swz, sk, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+bolt_status bolt_conv2d_fprop_nhwc(const bolt_conv_desc* desc, const void* x, const void* w, const void* bias,
+                                   void* y, const bolt_config* config, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  FpropProblem pr;
+  bolt_status s = make_conv_problem(desc, &pr);
+  if (s != BOLT_OK) return s;
+  if (!x || !w || !y) return BOLT_ERR_INVALID_ARG;
+  if (!is_aligned16(x) || !is_aligned16(w) || !is_aligned16(y) || (bias && !is_aligned16(bias))) return BOLT_ERR_ALIGNMENT;
+  int id, swz, sk;
+  s = resolve_fprop(tables().conv, pr, config, &id, &swz, &sk);
+  if (s != BOLT_OK) return s;
+  pr.p.X = (const half_t*)x; pr.p.W = (const half_t*)w; pr.p.bias = (const half_t*)bias; pr.p.Y = (half_t*)y;
+  return fprop_launch(tables().conv[id], pr, swz, sk, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+bolt_status bolt_b2b_gemm(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1, const void* A0, const void* W0,
+                          const void* b0, const void* W1, const void* b1, void* D1, const bolt_config* config,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  B2bProblem pr;
+  bolt_status s = make_b2b_gemm_problem(g0, g1, &pr);
+  if (s != BOLT_OK) return s;
+  if (!A0 || !W0 || !W1 || !D1) return BOLT_ERR_INVALID_ARG;
+  if (!is_aligned16(A0) || !is_aligned16(W0) || !is_aligned16(W1) || !is_aligned16(D1) ||
+      (b0 && !is_aligned16(b0)) || (b1 && !is_aligned16(b1)))
+    return BOLT_ERR_ALIGNMENT;
+  int id;
+  s = resolve_b2b(tables().b2b_gemm, pr, config, &id);
+  if (s != BOLT_OK) return s;
+  B2bParams& p = pr.p;
+  p.X = (const half_t*)A0; p.W0 = (const half_t*)W0; p.b0 = (const half_t*)b0;
+  p.W1 = (const half_t*)W1; p.b1 = (const half_t*)b1; p.Y = (half_t*)D1;
+  return b2b_launch(tables().b2b_gemm[id], pr, (hipStream_t)stream);
+}
+
+bolt_status bolt_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc* c1, const void* x, const void* w0,
+                          const void* b0, const void* w1, const void* b1, void* y, const bolt_config* config,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  B2bProblem pr;
+  bolt_status s = make_b2b_conv_problem(c0, c1, &pr);
+  if (s != BOLT_OK) return s;
+  if (!x || !w0 || !w1 || !y) return BOLT_ERR_INVALID_ARG;
+  if (!is_aligned16(x) || !is_aligned16(w0) || !is_aligned16(w1) || !is_aligned16(y) ||
+      (b0 && !is_aligned16(b0)) || (b1 && !is_aligned16(b1)))
+    return BOLT_ERR_ALIGNMENT;
+  int id;
+  s = resolve_b2b(tables().b2b_conv, pr, config, &id);
+  if (s != BOLT_OK) return s;
+  B2bParams& p = pr.p;
+  p.X = (const half_t*)x; p.W0 = (const half_t*)w0; p.b0 = (const half_t*)b0;
+  p.W1 = (const half_t*)w1; p.b1 = (const half_t*)b1; p.Y = (half_t*)y;
+  return b2b_launch(tables().b2b_conv[id], pr, (hipStream_t)stream);
+}
+
+bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const void* const* ptrs, void* workspace,
+                      size_t workspace_bytes, void* stream_v, bolt_config* best, float* best_ms, int32_t* n_tried) {
+  if (!desc0 || !ptrs || !best) return BOLT_ERR_INVALID_ARG;
+  hipStream_t stream = (hipStream_t)stream_v;
+  const bool single = op == BOLT_OP_GEMM || op == BOLT_OP_CONV2D;
+  const bool is_b2b = op == BOLT_OP_B2B_GEMM || op == BOLT_OP_B2B_CONV;
+  if (!single && !is_b2b) return BOLT_ERR_INVALID_ARG;
+  if (is_b2b && !desc1) return BOLT_ERR_INVALID_ARG;
+  const size_t dsz = (op == BOLT_OP_GEMM || op == BOLT_OP_B2B_GEMM) ? sizeof(bolt_gemm_desc) : sizeof(bolt_conv_desc);
+  TuneKey key{(int)op, std::string((const char*)desc0, dsz)};
+  if (is_b2b) key.bytes.append((const char*)desc1, dsz);
+
+  bolt_status s;
+  FpropProblem fp;
+  B2bProblem bp;
+  if (op == BOLT_OP_GEMM) s = make_gemm_problem((const bolt_gemm_desc*)desc0, &fp);
+  else if (op == BOLT_OP_CONV2D) s = make_conv_problem((const bolt_conv_desc*)desc0, &fp);
+  else if (op == BOLT_OP_B2B_GEMM) s = make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp);
+  else s = make_b2b_conv_problem((const bolt_conv_desc*)desc0, (const bolt_conv_desc*)desc1, &bp);
+  if (s != BOLT_OK) return s;
+  const int nptr = single ? 4 : 6;
+  for (int i = 0; i < nptr; ++i) {
+    const bool optional = single ? (i == 2) : (i == 2 || i == 4);
+    if (!ptrs[i] && !optional) return BOLT_ERR_INVALID_ARG;
+    if (ptrs[i] && !is_aligned16(ptrs[i])) return BOLT_ERR_ALIGNMENT;
+  }
+
+  {
+    std::lock_guard<std::mutex> lock(tune_mutex());
+    auto it = tune_cache().find(key);
+    if (it != tune_cache().end()) {
+      *best = it->second.cfg;
+      if (best_ms) *best_ms = it->second.ms;
+      if (n_tried) *n_tried = it->second.tried;
+      return BOLT_OK;
+    }
+  }
+
+  Candidate win{};
+  int tried = 0;
+  bolt_config cfg;
+  std::memset(&cfg, 0, sizeof(cfg));
+  if (single) {
+    const auto& tab = op == BOLT_OP_GEMM ? tables().gemm : tables().conv;
+    fp.p.X = (const half_t*)ptrs[0]; fp.p.W = (const half_t*)ptrs[1];
+    fp.p.bias = (const half_t*)ptrs[2]; fp.p.Y = (half_t*)ptrs[3];
+    const bool have_ws = workspace && is_aligned16(workspace);
+    std::vector<Candidate> cands = fprop_candidates(tab, fp, workspace_bytes, have_ws);
+    if (cands.empty()) return BOLT_ERR_UNSUPPORTED;
+    s = tune_candidates(cands, [&](const Candidate& c) {
+      return fprop_launch(tab[c.id], fp, c.swizzle, c.split_k, workspace, workspace_bytes, stream);
+    }, stream, &win, &tried);
+    if (s != BOLT_OK) return s;
+    fprop_fill_config(tab[win.id], win.id, &cfg);
+    cfg.swizzle = win.swizzle;
+    cfg.split_k = win.split_k;
+  } else {
+    const auto& tab = op == BOLT_OP_B2B_GEMM ? tables().b2b_gemm : tables().b2b_conv;
+    B2bParams& p = bp.p;
+    p.X = (const half_t*)ptrs[0]; p.W0 = (const half_t*)ptrs[1]; p.b0 = (const half_t*)ptrs[2];
+    p.W1 = (const half_t*)ptrs[3]; p.b1 = (const half_t*)ptrs[4]; p.Y = (half_t*)ptrs[5];
+    std::vector<Candidate> cands;
+    for (int i = 0; i < (int)tab.size(); ++i)
+      if (b2b_supports(tab[i], bp)) cands.push_back({i, 0, 1, 0.f});
+    if (cands.empty()) return BOLT_ERR_UNSUPPORTED;
+    s = tune_candidates(cands, [&](const Candidate& c) { return b2b_launch(tab[c.id], bp, stream); }, stream, &win,
+                        &tried);
+    if (s != BOLT_OK) return s;
+    b2b_fill_config(tab[win.id], win.id, &cfg);
+  }
+  *best = cfg;
+  if (best_ms) *best_ms = win.ms;
+  if (n_tried) *n_tried = tried;
+  std::lock_guard<std::mutex> lock(tune_mutex());
+  tune_cache()[key] = TuneVal{cfg, win.ms, tried};
+  return BOLT_OK;
+}
+
+bolt_status bolt_pad_channels_nhwc(const void* src, void* dst, int64_t pixels, int32_t C, int32_t C_padded,
+                                   void* stream) {
+  if (!src || !dst || pixels < 0 || C <= 0 || C_padded < C) return BOLT_ERR_INVALID_ARG;
+  if (C_padded & 7) return BOLT_ERR_ALIGNMENT;
+  if (!is_aligned16(dst)) return BOLT_ERR_ALIGNMENT;
+  if (pixels == 0) return BOLT_OK;
+  const int64_t total = pixels * (C_padded / 8);
+  const int blocks = (int)std::min<int64_t>((total + 255) / 256, kNumCU * 16);
+  hipLaunchKernelGGL(pad_channels_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const half_t*)src,
+                     (half_t*)dst, pixels, C, C_padded);
+  return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+}
+
+bolt_status bolt_probe_mfma_peak(int32_t iterations, void* stream_v, float* tflops) {
+  if (iterations <= 0 || !tflops) return BOLT_ERR_INVALID_ARG;
+  hipStream_t stream = (hipStream_t)stream_v;
+  float* sink = nullptr;
+  if (hipMalloc(&sink, 256) != hipSuccess) return BOLT_ERR_LAUNCH;
+  hipEvent_t e0, e1;
+  (void)hipEventCreate(&e0);
+  (void)hipEventCreate(&e1);
+  const int blocks = kNumCU * 2;  // 8 waves per CU: 2 per SIMD
+  float ms = 0.f;
+  bolt_status s = time_launches([&] {
+    hipLaunchKernelGGL(mfma_peak_kernel, dim3(blocks), dim3(256), 0, stream, sink, iterations);
+    return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+  }, 1, 3, stream, e0, e1, &ms);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  (void)hipFree(sink);
+  if (s != BOLT_OK) return s;
+  const double flop = (double)blocks * 4 /*waves*/ * iterations * 4.0 * (2.0 * 32 * 32 * 16);
+  *tflops = (float)(flop / (ms * 1e-3) / 1e12);
+  return BOLT_OK;
+}
+
+bolt_status bolt_probe_copy_bandwidth(void* buffer, size_t bytes, int32_t repeats, void* stream_v, float* gbps) {
+  if (!buffer || bytes < 64 || repeats <= 0 || !gbps) return BOLT_ERR_INVALID_ARG;
+  if (!is_aligned16(buffer)) return BOLT_ERR_ALIGNMENT;
+  hipStream_t stream = (hipStream_t)stream_v;
+  const int64_t n16 = (int64_t)(bytes / 2 / 16);
+  const floatx4* src = (const floatx4*)buffer;
+  floatx4* dst = (floatx4*)buffer + n16;
+  hipEvent_t e0, e1;
+  (void)hipEventCreate(&e0);
+  (void)hipEventCreate(&e1);
+  float ms = 0.f;
+  const int blocks = (int)std::min<int64_t>((n16 + 255) / 256, kNumCU * 32);
+  bolt_status s = time_launches([&] {
+    hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, stream, src, dst, n16);
+    return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+  }, 1, repeats, stream, e0, e1, &ms);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (s != BOLT_OK) return s;
+  *gbps = (float)(2.0 * n16 * 16 / (ms * 1e-3) / 1e9);
+  return BOLT_OK;
+}
+
+}  // extern "C"

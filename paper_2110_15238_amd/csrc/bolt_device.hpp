@@ -1,0 +1,87 @@
+// Device-side building blocks shared by every kernel template of the library (gfx950 / CDNA4).
+//
+// Vocabulary (Section 2.2 / Figure 2 of the paper, mapped to CDNA4): threadblock tile -> workgroup
+// tile, warp tile -> wave tile (64 lanes), tensor-core instruction -> v_mfma_f32_32x32x16_f16,
+// shared memory -> LDS, register file -> VGPR/AGPR.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bolt {
+
+typedef _Float16 half_t;
+typedef half_t half2v __attribute__((ext_vector_type(2)));
+typedef half_t half4 __attribute__((ext_vector_type(4)));
+typedef half_t half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2, ACT_HARDSWISH = 3, ACT_SOFTPLUS = 4 };
+
+// One matrix-core instruction: D(32x32) += A(32x16) * B(16x32), FP16 inputs, FP32 accumulate.
+// Lane l supplies A[i = l%32][k = 8*(l/32) .. +7] and B[k = 8*(l/32) .. +7][j = l%32];
+// it receives D[i = 8*(r/4) + 4*(l/32) + r%4][j = l%32] in accumulator register r (0..15).
+__device__ __forceinline__ floatx16 mfma_32x32x16(half8 a, half8 b, floatx16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+// LDS operand tiles are [rows][BK] halves, K contiguous, addressed in 16-byte chunks of 8 halves.
+// The chunk index is XOR-swizzled by the row so that (a) the 8 lanes of a fragment read that
+// touch 8 consecutive rows at one logical chunk and (b) the 8 lanes of a transposing store that
+// touch rows 8 apart at one logical chunk both spread over all banks.
+template <int BK>
+__device__ __forceinline__ int lds_chunk_offset(int row, int chunk) {
+  static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
+  if constexpr (BK == 32) {
+    int line = row >> 1;
+    int g = ((row & 1) << 2) | chunk;
+    g ^= (line ^ (line >> 3)) & 7;
+    return line * 64 + (g << 3);
+  } else {
+    return row * BK + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 3);
+  }
+}
+
+// The transcendental activations are kept out of line so that the fully unrolled epilogues stay
+// small; ReLU and "none" cost one compare.
+__device__ __attribute__((noinline)) float apply_act_slow(float v, int act) {
+  switch (act) {
+    case ACT_GELU: return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+    case ACT_HARDSWISH: {
+      float t = fminf(fmaxf(v + 3.f, 0.f), 6.f);
+      return v * t * (1.f / 6.f);
+    }
+    case ACT_SOFTPLUS: return v > 0.f ? v + log1pf(__expf(-v)) : log1pf(__expf(v));
+    default: return v;
+  }
+}
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == ACT_RELU) return v > 0.f ? v : 0.f;
+  if (act > ACT_RELU) return apply_act_slow(v, act);
+  return v;
+}
+
+// Workgroup id -> output tile.  mode 0: n-tile fastest.  mode g > 0: ids are first regrouped so
+// that the ids one XCD receives (hardware deals consecutive ids round-robin over 8 XCDs, each with
+// a private L2) are consecutive, then walked in bands of g m-tiles x all n-tiles.
+__device__ __forceinline__ void tile_of_workgroup(int bid, int tiles_m, int tiles_n, int mode, int& tm, int& tn) {
+  if (mode <= 0) {
+    tm = bid / tiles_n;
+    tn = bid - tm * tiles_n;
+    return;
+  }
+  const int total = tiles_m * tiles_n;
+  const int xcd = bid & 7, idx = bid >> 3;
+  const int per = total >> 3, rem = total & 7;
+  int pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  const int width = mode * tiles_n;
+  const int group = pid / width;
+  const int first_m = group * mode;
+  const int gsz = (tiles_m - first_m) < mode ? (tiles_m - first_m) : mode;
+  const int in_group = pid - group * width;
+  tm = first_m + in_group % gsz;
+  tn = in_group / gsz;
+}
+
+}  // namespace bolt

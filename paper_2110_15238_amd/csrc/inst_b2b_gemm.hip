@@ -1,0 +1,18 @@
+// Back-to-back GEMM instances: row-major activations, row-major [K][N] weights.
+#include "instances.hpp"
+namespace bolt {
+// RF(BM, BK, waves, N0T, N1T)  /  LDS(BM, BK, WM0, WN0, WM1, WN1, N0T, N1T)
+#define RF(BM, BK, NW, N0T, N1T) BOLT_B2B_RF_INSTANCE(BM, BK, NW, N0T, N1T, 0, 1)
+#define LD(BM, BK, A, B, C, D, N0T, N1T) BOLT_B2B_LDS_INSTANCE(BM, BK, A, B, C, D, N0T, N1T, 0, 1)
+void register_b2b_gemm_instances(std::vector<B2bInstance>& v) {
+  static const B2bInstance table[] = {
+      RF(128, 64, 4, 32, 32),   RF(128, 64, 4, 32, 128), RF(128, 64, 4, 64, 32),  RF(128, 64, 4, 64, 64),
+      RF(128, 64, 4, 64, 128),  RF(256, 64, 4, 64, 128), RF(64, 64, 2, 64, 128),  RF(128, 64, 4, 64, 256),
+      RF(128, 64, 4, 128, 64),  RF(128, 64, 4, 128, 128),
+      LD(64, 64, 2, 2, 2, 2, 64, 128),  LD(128, 64, 4, 1, 2, 2, 64, 128), LD(64, 64, 2, 2, 2, 2, 64, 64),
+      LD(64, 64, 2, 1, 2, 1, 64, 32),   LD(64, 64, 2, 1, 2, 1, 32, 32),   LD(64, 64, 2, 1, 1, 2, 32, 128),
+      LD(128, 64, 2, 2, 2, 2, 128, 64), LD(128, 64, 2, 2, 2, 2, 128, 128), LD(128, 64, 4, 1, 2, 2, 64, 256),
+  };
+  for (const auto& t : table) v.push_back(t);
+}
+}  // namespace bolt

@@ -1,0 +1,8 @@
+// Implicit-GEMM NHWC convolution instances (weights KRSC).
+#include "instances.hpp"
+namespace bolt {
+void register_conv_instances(std::vector<FpropInstance>& v) {
+  static const FpropInstance table[] = {BOLT_FPROP_TILE_LIST(BOLT_FPROP_INSTANCE, 1, 0)};
+  for (const auto& t : table) v.push_back(t);
+}
+}  // namespace bolt

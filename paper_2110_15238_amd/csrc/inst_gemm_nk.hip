@@ -1,0 +1,8 @@
+// GEMM instances, B stored [N][K] (reduction index contiguous).
+#include "instances.hpp"
+namespace bolt {
+void register_gemm_nk_instances(std::vector<FpropInstance>& v) {
+  static const FpropInstance table[] = {BOLT_FPROP_TILE_LIST(BOLT_FPROP_INSTANCE, 0, 0)};
+  for (const auto& t : table) v.push_back(t);
+}
+}  // namespace bolt

@@ -1,0 +1,43 @@
+// The per-architecture list of template instances the profiler searches over (Section 3.2.2):
+// a few tens of (workgroup tile, wave grid, K depth) combinations chosen by the hardware rules
+// the paper states, restated for a CDNA4 compute unit:
+//   - within the register budget (512 VGPR+AGPR per lane at one wave per SIMD) prefer large wave
+//     tiles, they raise the FLOP per LDS byte;
+//   - 4 or 8 waves per workgroup (1 or 2 per SIMD of the 4-SIMD compute unit);
+//   - small problems need small workgroup tiles so that at least 256 workgroups exist.
+// Each instance is compiled once into the library; tuning only runs them.
+#pragma once
+#include <vector>
+
+#include "b2b_kernel.hpp"
+#include "fprop_kernel.hpp"
+
+// X(BM, BN, BK, WAVES_M, WAVES_N)
+#define BOLT_FPROP_TILE_LIST(X, XMODE, WMODE) \
+  X(256, 256, 64, 2, 2, XMODE, WMODE),        \
+  X(256, 256, 64, 2, 4, XMODE, WMODE),        \
+  X(256, 128, 64, 2, 2, XMODE, WMODE),        \
+  X(256, 128, 64, 4, 2, XMODE, WMODE),        \
+  X(128, 256, 64, 2, 2, XMODE, WMODE),        \
+  X(128, 256, 64, 2, 4, XMODE, WMODE),        \
+  X(128, 128, 64, 2, 2, XMODE, WMODE),        \
+  X(128, 128, 32, 2, 2, XMODE, WMODE),        \
+  X(256, 64, 64, 4, 1, XMODE, WMODE),         \
+  X(256, 64, 64, 4, 2, XMODE, WMODE),         \
+  X(128, 64, 64, 4, 1, XMODE, WMODE),         \
+  X(128, 64, 64, 2, 2, XMODE, WMODE),         \
+  X(64, 128, 64, 2, 2, XMODE, WMODE),         \
+  X(64, 256, 64, 1, 4, XMODE, WMODE),         \
+  X(64, 64, 64, 2, 2, XMODE, WMODE),          \
+  X(64, 64, 64, 2, 1, XMODE, WMODE),          \
+  X(32, 64, 64, 1, 2, XMODE, WMODE),          \
+  X(64, 32, 64, 2, 1, XMODE, WMODE)
+
+namespace bolt {
+// Each function appends its instances in a fixed order; kernel_id is the index in the op's table.
+void register_gemm_kn_instances(std::vector<FpropInstance>& v);
+void register_gemm_nk_instances(std::vector<FpropInstance>& v);
+void register_conv_instances(std::vector<FpropInstance>& v);
+void register_b2b_gemm_instances(std::vector<B2bInstance>& v);
+void register_b2b_conv_instances(std::vector<B2bInstance>& v);
+}  // namespace bolt

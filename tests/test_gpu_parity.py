@@ -1,0 +1,487 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Bound for floating point: |gpu - oracle| <= 1e-2 * (1 + |oracle|).  Integer-valued cases (every
+partial sum exactly representable) must agree bit for bit.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import ref
+from util import assert_bit_equal, assert_close, dev, host
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def bolt():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2110_15238_amd as b
+    return b
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------------------------------------
+# GEMM
+# ---------------------------------------------------------------------------------------------
+def _run_gemm(bolt, A, B, bias, act="relu", alpha=1.0, beta=1.0, layout="kn", config=None, workspace=None):
+    M, K = A.shape
+    N = B.shape[1]
+    if layout == "kn":
+        Bd, lay = dev(B), bolt.LAYOUT_KN
+    else:
+        Bd, lay = dev(np.ascontiguousarray(B.T)), bolt.LAYOUT_NK
+    d = bolt.gemm_desc(M, N, K, alpha=alpha, beta=beta, act=act, b_layout=lay)
+    D = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_gemm_epilogue(d, dev(A), Bd, dev(bias), D, config, workspace)
+    torch.cuda.synchronize()
+    return host(D), d
+
+
+def test_config1_gemm_bias_relu(bolt):
+    t = wl.config1()
+    want = ref.gemm(t["A"], t["B"], t["bias"])
+    got, _ = _run_gemm(bolt, t["A"], t["B"], t["bias"])
+    assert_close(got, want, "config1 heuristic")
+    got, _ = _run_gemm(bolt, t["A"], t["B"], t["bias"], layout="nk")
+    assert_close(got, want, "config1 NK layout")
+
+
+@pytest.mark.parametrize("layout", ["kn", "nk"])
+def test_gemm_every_instance_ragged_shapes(bolt, layout):
+    # M, N, K chosen to give 1, 2 and 3 K-loop trips at BK = 64 / 32, ragged tiles in M and N
+    shapes = [(200, 136, 64), (333, 72, 128), (97, 264, 200), (1, 8, 8), (520, 320, 72)]
+    nk_off = bolt.bolt_num_instances(bolt.OP_GEMM) // 2
+    for (M, N, K) in shapes:
+        A = wl.uniform_fp16(101, 0, (M, K), -1, 1)
+        B = wl.uniform_fp16(101, 1, (K, N), -1, 1)
+        bias = wl.uniform_fp16(101, 2, (N,), -1, 1)
+        want = ref.gemm(A, B, bias)
+        d = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_KN if layout == "kn" else bolt.LAYOUT_NK)
+        ran = 0
+        for kid in range(bolt.bolt_num_instances(bolt.OP_GEMM)):
+            if not bolt.bolt_instance_supports(bolt.OP_GEMM, kid, d):
+                continue
+            _say("gemm %s shape %s instance %d" % (layout, (M, N, K), kid))
+            got, _ = _run_gemm(bolt, A, B, bias, layout=layout, config={"kernel_id": kid})
+            assert_close(got, want, "gemm %s %s instance %d" % (layout, (M, N, K), kid))
+            ran += 1
+        assert ran >= 3
+    assert nk_off > 0
+
+
+@pytest.mark.parametrize("layout", ["kn", "nk"])
+def test_gemm_integer_inputs_bit_exact(bolt, layout):
+    M, N, K = 300, 136, 128
+    A = wl.integer_fp16(102, 0, (M, K), -2, 2)
+    B = wl.integer_fp16(102, 1, (K, N), -2, 2)
+    bias = wl.integer_fp16(102, 2, (N,), -2, 2)
+    want = ref.gemm(A, B, bias, act="none")
+    d = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_KN if layout == "kn" else bolt.LAYOUT_NK)
+    for kid in range(bolt.bolt_num_instances(bolt.OP_GEMM)):
+        if bolt.bolt_instance_supports(bolt.OP_GEMM, kid, d):
+            _say("gemm int %s instance %d" % (layout, kid))
+            got, _ = _run_gemm(bolt, A, B, bias, act="none", layout=layout, config={"kernel_id": kid})
+            assert_bit_equal(got, want, "gemm integer instance %d" % kid)
+
+
+def test_gemm_alpha_beta_activations_and_no_bias(bolt):
+    M, N, K = 130, 72, 96
+    A = wl.uniform_fp16(103, 0, (M, K), -1, 1)
+    B = wl.uniform_fp16(103, 1, (K, N), -1, 1)
+    bias = wl.uniform_fp16(103, 2, (N,), -1, 1)
+    for act in ["none", "relu", "gelu", "hardswish", "softplus"]:
+        want = ref.gemm(A, B, bias, alpha=0.5, beta=2.0, act=act)
+        got, _ = _run_gemm(bolt, A, B, bias, act=act, alpha=0.5, beta=2.0)
+        assert_close(got, want, "gemm act " + act)
+    want = ref.gemm(A, B, None, act="relu")
+    got, _ = _run_gemm(bolt, A, B, None, act="relu")
+    assert_close(got, want, "gemm without bias")
+
+
+def test_gemm_split_k_and_swizzle(bolt):
+    M, N, K = 384, 256, 1024
+    A = wl.uniform_fp16(104, 0, (M, K), -1, 1)
+    B = wl.uniform_fp16(104, 1, (K, N), -1, 1)
+    bias = wl.uniform_fp16(104, 2, (N,), -1, 1)
+    want = ref.gemm(A, B, bias)
+    ws = torch.empty(8 * M * N, dtype=torch.float32, device="cuda")
+    d = bolt.gemm_desc(M, N, K)
+    kids = [k for k in range(bolt.bolt_num_instances(bolt.OP_GEMM)) if bolt.bolt_instance_supports(bolt.OP_GEMM, k, d)]
+    for kid in kids[:6]:
+        for split_k in (2, 3, 8):
+            _say("gemm split_k=%d instance %d" % (split_k, kid))
+            got, _ = _run_gemm(bolt, A, B, bias, config={"kernel_id": kid, "split_k": split_k}, workspace=ws)
+            assert_close(got, want, "split_k=%d instance %d" % (split_k, kid))
+        for swz in (1, 4, 7):
+            got, _ = _run_gemm(bolt, A, B, bias, config={"kernel_id": kid, "swizzle": swz})
+            assert_close(got, want, "swizzle=%d instance %d" % (swz, kid))
+    # a missing workspace is an error, not a silent fallback
+    with pytest.raises(bolt.BoltError) as e:
+        _run_gemm(bolt, A, B, bias, config={"kernel_id": kids[0], "split_k": 4})
+    assert e.value.status == 4
+
+
+def test_gemm_leading_dimensions(bolt):
+    M, N, K, lda, ldb, ldd = 70, 40, 48, 64, 56, 72
+    A = wl.uniform_fp16(105, 0, (M, lda), -1, 1)
+    B = wl.uniform_fp16(105, 1, (K, ldb), -1, 1)
+    bias = wl.uniform_fp16(105, 2, (N,), -1, 1)
+    want = ref.gemm(A[:, :K], B[:, :N], bias)
+    d = bolt.gemm_desc(M, N, K, lda=lda, ldb=ldb, ldd=ldd)
+    D = torch.zeros((M, ldd), dtype=torch.float16, device="cuda")
+    bolt.bolt_gemm_epilogue(d, dev(A), dev(B), dev(bias), D)
+    torch.cuda.synchronize()
+    got = host(D)
+    assert_close(got[:, :N], want, "gemm with leading dimensions")
+    assert not got[:, N:].any(), "columns beyond N were written"
+
+
+# ---------------------------------------------------------------------------------------------
+# convolution
+# ---------------------------------------------------------------------------------------------
+def _run_conv(bolt, x, w, bias, stride, pad, act="relu", config=None, workspace=None, alpha=1.0, beta=1.0):
+    N, H, W, Cc = x.shape
+    K, R, S, _ = w.shape
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad, alpha=alpha, beta=beta, act=act)
+    P, Q = bolt.conv_out_hw(d)
+    y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_conv2d_fprop_nhwc(d, dev(x), dev(w), dev(bias), y, config, workspace)
+    torch.cuda.synchronize()
+    return host(y), d
+
+
+CONV_SWEEP = [
+    # N H W C K R S stride pad
+    (2, 12, 12, 8, 16, 3, 3, 1, 1),
+    (1, 17, 13, 24, 40, 3, 3, 2, 1),
+    (2, 23, 23, 8, 64, 7, 7, 2, 3),
+    (3, 9, 11, 64, 72, 1, 1, 1, 0),
+    (2, 14, 14, 64, 128, 1, 1, 2, 0),
+    (1, 10, 9, 16, 24, 5, 3, (1, 2), (2, 0)),
+    (1, 6, 6, 136, 8, 3, 3, 1, 1),
+    (1, 5, 5, 8, 8, 5, 5, 1, 0),
+]
+
+
+@pytest.mark.parametrize("case", CONV_SWEEP)
+def test_conv_every_instance_shape_sweep(bolt, case):
+    N, H, W, Cc, K, R, S, stride, pad = case
+    x = wl.uniform_fp16(201, 0, (N, H, W, Cc), -1, 1)
+    w = wl.uniform_fp16(201, 1, (K, R, S, Cc), -1, 1)
+    bias = wl.uniform_fp16(201, 2, (K,), -1, 1)
+    want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_CONV2D)):
+        if not bolt.bolt_instance_supports(bolt.OP_CONV2D, kid, d):
+            continue
+        _say("conv case %s instance %d" % (case, kid))
+        got, _ = _run_conv(bolt, x, w, bias, stride, pad, config={"kernel_id": kid})
+        assert_close(got, want, "conv %s instance %d" % (case, kid))
+        ran += 1
+    assert ran >= 3
+
+
+def test_conv_integer_inputs_bit_exact(bolt):
+    N, H, W, Cc, K, R, S, stride, pad = 2, 13, 11, 8, 24, 3, 3, 1, 1
+    x = wl.integer_fp16(202, 0, (N, H, W, Cc), -2, 2)
+    w = wl.integer_fp16(202, 1, (K, R, S, Cc), -2, 2)
+    bias = wl.integer_fp16(202, 2, (K,), -2, 2)
+    for act in ("none", "relu"):
+        want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad, act=act)
+        d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
+        for kid in range(bolt.bolt_num_instances(bolt.OP_CONV2D)):
+            if bolt.bolt_instance_supports(bolt.OP_CONV2D, kid, d):
+                got, _ = _run_conv(bolt, x, w, bias, stride, pad, act=act, config={"kernel_id": kid})
+                assert_bit_equal(got, want, "conv integer instance %d act %s" % (kid, act))
+
+
+def test_conv_identity_1x1_returns_input_exactly(bolt):
+    x = wl.uniform_fp16(203, 0, (2, 9, 7, 64), -1, 1)
+    w = np.zeros((64, 1, 1, 64), np.float16)
+    for k in range(64):
+        w[k, 0, 0, k] = 1.0
+    got, _ = _run_conv(bolt, x, w, None, 1, 0, act="none")
+    assert_bit_equal(got, x, "identity 1x1")
+
+
+def test_conv_split_k(bolt):
+    N, H, W, Cc, K, R, S, stride, pad = 1, 7, 7, 128, 64, 3, 3, 1, 1
+    x = wl.uniform_fp16(204, 0, (N, H, W, Cc), -1, 1)
+    w = wl.normal_fp16(204, 1, (K, R, S, Cc), 0.05)
+    bias = wl.uniform_fp16(204, 2, (K,), -1, 1)
+    want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
+    ws = torch.empty(8 * 49 * K, dtype=torch.float32, device="cuda")
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
+    for kid in range(bolt.bolt_num_instances(bolt.OP_CONV2D)):
+        if bolt.bolt_instance_supports(bolt.OP_CONV2D, kid, d):
+            for sk in (2, 5, 8):
+                _say("conv split_k=%d instance %d" % (sk, kid))
+                got, _ = _run_conv(bolt, x, w, bias, stride, pad, config={"kernel_id": kid, "split_k": sk}, workspace=ws)
+                assert_close(got, want, "conv split_k=%d instance %d" % (sk, kid))
+
+
+def test_config2_conv_small_batch_full_compare(bolt):
+    t = wl.config2(batch=2)
+    want = ref.conv2d_nhwc(t["x"], t["w"], t["bias"], stride=1, pad=1)
+    got, _ = _run_conv(bolt, t["x"], t["w"], t["bias"], 1, 1)
+    assert_close(got, want, "config2 at batch 2")
+
+
+def _sample_idx(total, count, seed):
+    rng = np.random.default_rng(seed)
+    idx = rng.integers(0, total, size=count)
+    edge = np.array([0, total - 1])
+    return np.unique(np.concatenate([idx, edge]))
+
+
+def test_config2_conv_full_size_tuned_sampled(bolt):
+    t = wl.config2()
+    s = wl.CONFIG2_SHAPE
+    d = bolt.conv_desc(s.N, s.H, s.W, s.C, s.K, s.R, s.S, s.stride, s.pad)
+    x, w, b = dev(t["x"]), dev(t["w"]), dev(t["bias"])
+    y = torch.full((s.N, s.P, s.Q, s.K), float("nan"), dtype=torch.float16, device="cuda")
+    ws_bytes = bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d)
+    ws = torch.empty(max(ws_bytes, 16) // 4, dtype=torch.float32, device="cuda")
+    res = bolt.bolt_tune(bolt.OP_CONV2D, d, None, [x, w, b, y], ws)
+    _say("config2 tuned: %s %.4f ms, %d tried" % (res.config.as_dict(), res.ms, res.tried))
+    assert res.tried >= 3 and res.ms > 0
+    y.fill_(float("nan"))
+    bolt.bolt_conv2d_fprop_nhwc(d, x, w, b, y, res.config, ws)
+    torch.cuda.synchronize()
+    got = host(y).reshape(-1)
+    assert np.all(np.isfinite(got))
+    idx = _sample_idx(got.size, 20000, 1)
+    want = ref.conv2d_nhwc_at(t["x"], t["w"], idx, t["bias"], stride=1, pad=1)
+    assert_close(got[idx], want, "config2 full size, tuned, sampled")
+
+
+# ---------------------------------------------------------------------------------------------
+# channel padding
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("C,C8", [(3, 8), (46, 48), (8, 8), (174, 176), (1, 16)])
+def test_pad_channels_bit_exact(bolt, C, C8):
+    x = wl.uniform_fp16(301, 0, (3, 5, 7, C), -1, 1)
+    want = ref.pad_channels(x, C8)
+    dst = torch.full((3, 5, 7, C8), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_pad_channels_nhwc(dev(x), dst, C8)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(dst), want, "pad %d -> %d" % (C, C8))
+
+
+def test_padded_stem_conv_matches_unpadded_oracle(bolt):
+    # C = 3 padded to 8 on the GPU; the oracle runs the original 3-channel problem
+    N, H, W, K = 2, 30, 30, 64
+    x = wl.uniform_fp16(302, 0, (N, H, W, 3), -1, 1)
+    w = wl.normal_fp16(302, 1, (K, 7, 7, 3), 0.1)
+    bias = wl.uniform_fp16(302, 2, (K,), -1, 1)
+    want = ref.conv2d_nhwc(x, w, bias, stride=2, pad=3)
+    xp = torch.empty((N, H, W, 8), dtype=torch.float16, device="cuda")
+    wp = torch.empty((K, 7, 7, 8), dtype=torch.float16, device="cuda")
+    bolt.bolt_pad_channels_nhwc(dev(x), xp, 8)
+    bolt.bolt_pad_channels_nhwc(dev(w), wp, 8)
+    d = bolt.conv_desc(N, H, W, 8, K, 7, 7, 2, 3)
+    P, Q = bolt.conv_out_hw(d)
+    y = torch.empty((N, P, Q, K), dtype=torch.float16, device="cuda")
+    bolt.bolt_conv2d_fprop_nhwc(d, xp, wp, dev(bias), y)
+    torch.cuda.synchronize()
+    assert_close(host(y), want, "padded stem")
+
+
+# ---------------------------------------------------------------------------------------------
+# back-to-back GEMM
+# ---------------------------------------------------------------------------------------------
+def _run_b2b_gemm(bolt, t, config=None, act0="relu", act1="relu"):
+    M, K0 = t["A"].shape
+    N0, N1 = t["W0"].shape[1], t["W1"].shape[1]
+    g0 = bolt.gemm_desc(M, N0, K0, act=act0)
+    g1 = bolt.gemm_desc(M, N1, N0, act=act1)
+    D1 = torch.full((M, N1), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_b2b_gemm(g0, g1, dev(t["A"]), dev(t["W0"]), dev(t["b0"]), dev(t["W1"]), dev(t["b1"]), D1, config)
+    torch.cuda.synchronize()
+    return host(D1), g0, g1
+
+
+def test_config3_b2b_gemm_every_instance(bolt):
+    t = wl.config3()
+    want = ref.b2b_gemm(t["A"], t["W0"], t["b0"], t["W1"], t["b1"])
+    g0 = bolt.gemm_desc(16384, 64, 256)
+    g1 = bolt.gemm_desc(16384, 128, 64)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_GEMM)):
+        if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM, kid, g0, g1):
+            _say("config3 b2b gemm instance %d %s" % (kid, bolt.bolt_instance_config(bolt.OP_B2B_GEMM, kid).as_dict()))
+            got, _, _ = _run_b2b_gemm(bolt, t, {"kernel_id": kid})
+            assert_close(got, want, "config3 instance %d" % kid)
+            ran += 1
+    assert ran >= 2
+    got, _, _ = _run_b2b_gemm(bolt, t)
+    assert_close(got, want, "config3 heuristic")
+
+
+B2B_GEMM_SHAPES = [  # M, K0, N0, N1 (ragged M, every compiled (N0T, N1T) family, K0 tails)
+    (1000, 72, 64, 128), (333, 256, 64, 16), (515, 256, 128, 64), (700, 96, 32, 96), (129, 8, 8, 8),
+    (260, 200, 64, 256), (100, 64, 24, 72), (64, 128, 128, 128),
+]
+
+
+@pytest.mark.parametrize("shape", B2B_GEMM_SHAPES)
+def test_b2b_gemm_shapes_every_instance(bolt, shape):
+    M, K0, N0, N1 = shape
+    t = dict(A=wl.uniform_fp16(401, 0, (M, K0), -0.5, 0.5), W0=wl.uniform_fp16(401, 1, (K0, N0), -0.5, 0.5),
+             b0=wl.uniform_fp16(401, 2, (N0,), -0.5, 0.5), W1=wl.uniform_fp16(401, 3, (N0, N1), -0.5, 0.5),
+             b1=wl.uniform_fp16(401, 4, (N1,), -0.5, 0.5))
+    want = ref.b2b_gemm(t["A"], t["W0"], t["b0"], t["W1"], t["b1"])
+    g0, g1 = bolt.gemm_desc(M, N0, K0), bolt.gemm_desc(M, N1, N0)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_GEMM)):
+        if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM, kid, g0, g1):
+            _say("b2b gemm %s instance %d" % (shape, kid))
+            got, _, _ = _run_b2b_gemm(bolt, t, {"kernel_id": kid})
+            assert_close(got, want, "b2b gemm %s instance %d" % (shape, kid))
+            ran += 1
+    assert ran >= 1, "no instance for %s" % (shape,)
+
+
+def test_b2b_gemm_integer_bit_exact(bolt):
+    M, K0, N0, N1 = 300, 64, 64, 128
+    t = dict(A=wl.integer_fp16(402, 0, (M, K0), -1, 1), W0=wl.integer_fp16(402, 1, (K0, N0), -1, 1),
+             b0=wl.integer_fp16(402, 2, (N0,), -2, 2), W1=wl.integer_fp16(402, 3, (N0, N1), -1, 1),
+             b1=wl.integer_fp16(402, 4, (N1,), -2, 2))
+    # every partial sum is an integer below 2^24, exact in FP32 and in double, so both sides round the
+    # same exact value to FP16: the results must be identical
+    want = ref.b2b_gemm(t["A"], t["W0"], t["b0"], t["W1"], t["b1"], act1="none")
+    g0, g1 = bolt.gemm_desc(M, N0, K0), bolt.gemm_desc(M, N1, N0, act="none")
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_GEMM)):
+        if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM, kid, g0, g1):
+            got, _, _ = _run_b2b_gemm(bolt, t, {"kernel_id": kid}, act1="none")
+            assert_bit_equal(got, want, "b2b gemm integer instance %d" % kid)
+
+
+# ---------------------------------------------------------------------------------------------
+# back-to-back conv
+# ---------------------------------------------------------------------------------------------
+def _run_b2b_conv(bolt, t, stride, pad, config=None):
+    N, H, W, Cc = t["x"].shape
+    K0, R, S, _ = t["w0"].shape
+    K1 = t["w1"].shape[0]
+    c0 = bolt.conv_desc(N, H, W, Cc, K0, R, S, stride, pad)
+    P, Q = bolt.conv_out_hw(c0)
+    c1 = bolt.conv_desc(N, P, Q, K0, K1, 1, 1, 1, 0)
+    y = torch.full((N, P, Q, K1), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_b2b_conv(c0, c1, dev(t["x"]), dev(t["w0"]), dev(t["b0"]), dev(t["w1"]), dev(t["b1"]), y, config)
+    torch.cuda.synchronize()
+    return host(y), c0, c1
+
+
+def test_config4_b2b_conv_small_batch_every_instance(bolt):
+    t = wl.config4(batch=2)
+    want = ref.b2b_conv(t["x"], t["w0"], t["b0"], t["w1"], t["b1"], stride=1, pad=1)
+    c0 = bolt.conv_desc(2, 56, 56, 64, 64, 3, 3, 1, 1)
+    c1 = bolt.conv_desc(2, 56, 56, 64, 256, 1, 1, 1, 0)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_CONV)):
+        if bolt.bolt_instance_supports(bolt.OP_B2B_CONV, kid, c0, c1):
+            _say("config4 b2b conv instance %d %s" % (kid, bolt.bolt_instance_config(bolt.OP_B2B_CONV, kid).as_dict()))
+            got, _, _ = _run_b2b_conv(bolt, t, 1, 1, {"kernel_id": kid})
+            assert_close(got, want, "config4 (batch 2) instance %d" % kid)
+            ran += 1
+    assert ran >= 2
+
+
+def test_config4_b2b_conv_full_size_tuned_sampled_rows(bolt):
+    t = wl.config4()
+    c0 = bolt.conv_desc(32, 56, 56, 64, 64, 3, 3, 1, 1)
+    c1 = bolt.conv_desc(32, 56, 56, 64, 256, 1, 1, 1, 0)
+    x, w0, b0, w1, b1 = (dev(t[k]) for k in ("x", "w0", "b0", "w1", "b1"))
+    y = torch.full((32, 56, 56, 256), float("nan"), dtype=torch.float16, device="cuda")
+    res = bolt.bolt_tune(bolt.OP_B2B_CONV, c0, c1, [x, w0, b0, w1, b1, y])
+    _say("config4 tuned: %s %.4f ms, %d tried" % (res.config.as_dict(), res.ms, res.tried))
+    y.fill_(float("nan"))
+    bolt.bolt_b2b_conv(c0, c1, x, w0, b0, w1, b1, y, res.config)
+    torch.cuda.synchronize()
+    got = host(y).reshape(-1, 256)
+    assert np.all(np.isfinite(got))
+    rows = _sample_idx(got.shape[0], 300, 2)
+    want = ref.b2b_conv_rows(t["x"], t["w0"], t["b0"], t["w1"], t["b1"], rows, stride=1, pad=1)
+    assert_close(got[rows], want, "config4 full size, tuned, sampled rows")
+
+
+B2B_CONV_SHAPES = [  # N H W C K0 stride K1
+    (2, 20, 20, 8, 48, 2, 48), (1, 15, 17, 48, 48, 1, 48), (2, 12, 12, 64, 64, 2, 64), (1, 9, 9, 16, 32, 1, 32),
+    (1, 11, 11, 24, 128, 1, 128),
+]
+
+
+@pytest.mark.parametrize("shape", B2B_CONV_SHAPES)
+def test_b2b_conv_shapes_every_instance(bolt, shape):
+    N, H, W, Cc, K0, stride, K1 = shape
+    t = dict(x=wl.uniform_fp16(501, 0, (N, H, W, Cc), -1, 1), w0=wl.normal_fp16(501, 1, (K0, 3, 3, Cc), (2.0 / (9 * Cc)) ** 0.5),
+             b0=wl.uniform_fp16(501, 2, (K0,), -1, 1), w1=wl.normal_fp16(501, 3, (K1, 1, 1, K0), (2.0 / K0) ** 0.5),
+             b1=wl.uniform_fp16(501, 4, (K1,), -1, 1))
+    want = ref.b2b_conv(t["x"], t["w0"], t["b0"], t["w1"], t["b1"], stride=stride, pad=1)
+    c0 = bolt.conv_desc(N, H, W, Cc, K0, 3, 3, stride, 1)
+    P, Q = bolt.conv_out_hw(c0)
+    c1 = bolt.conv_desc(N, P, Q, K0, K1, 1, 1, 1, 0)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_CONV)):
+        if bolt.bolt_instance_supports(bolt.OP_B2B_CONV, kid, c0, c1):
+            _say("b2b conv %s instance %d" % (shape, kid))
+            got, _, _ = _run_b2b_conv(bolt, t, stride, 1, {"kernel_id": kid})
+            assert_close(got, want, "b2b conv %s instance %d" % (shape, kid))
+            ran += 1
+    assert ran >= 1, "no instance for %s" % (shape,)
+
+
+# ---------------------------------------------------------------------------------------------
+# config 5: every distinct ResNet-50 layer shape at full size, tuned, sampled outputs
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("index", list(range(23)))
+def test_config5_layer_full_size_tuned_sampled(bolt, index):
+    shape, cnt, t = wl.config5_layer(index)
+    x_log, w_log, bias = t["x"], t["w"], t["bias"]
+    x, w = dev(x_log), dev(w_log)
+    if shape.c_logical:
+        xp = torch.empty(x_log.shape[:-1] + (shape.C,), dtype=torch.float16, device="cuda")
+        wp = torch.empty(w_log.shape[:-1] + (shape.C,), dtype=torch.float16, device="cuda")
+        bolt.bolt_pad_channels_nhwc(x, xp, shape.C)
+        bolt.bolt_pad_channels_nhwc(w, wp, shape.C)
+        x, w = xp, wp
+    d = bolt.conv_desc(shape.N, shape.H, shape.W, shape.C, shape.K, shape.R, shape.S, shape.stride, shape.pad)
+    y = torch.full((shape.N, shape.P, shape.Q, shape.K), float("nan"), dtype=torch.float16, device="cuda")
+    ws_bytes = bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d)
+    ws = torch.empty(max(ws_bytes, 16) // 4, dtype=torch.float32, device="cuda")
+    b = dev(bias)
+    res = bolt.bolt_tune(bolt.OP_CONV2D, d, None, [x, w, b, y], ws)
+    _say("layer %d %s: %s %.4f ms (%d tried) %.1f TFLOP/s" %
+         (index, shape, res.config.as_dict(), res.ms, res.tried, shape.flops / res.ms / 1e9))
+    y.fill_(float("nan"))
+    bolt.bolt_conv2d_fprop_nhwc(d, x, w, b, y, res.config, ws)
+    torch.cuda.synchronize()
+    got = host(y).reshape(-1)
+    assert np.all(np.isfinite(got)), "unwritten or non-finite outputs"
+    idx = _sample_idx(got.size, 4000, 10 + index)
+    want = ref.conv2d_nhwc_at(x_log, w_log, idx, bias, stride=shape.stride, pad=shape.pad)
+    assert_close(got[idx], want, "config5 layer %d" % index)
+
+
+def test_tune_is_cached_and_probes_run(bolt):
+    M, N, K = 512, 256, 256
+    A, B = dev(wl.uniform_fp16(601, 0, (M, K), -1, 1)), dev(wl.uniform_fp16(601, 1, (K, N), -1, 1))
+    D = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    d = bolt.gemm_desc(M, N, K)
+    r1 = bolt.bolt_tune(bolt.OP_GEMM, d, None, [A, B, None, D])
+    r2 = bolt.bolt_tune(bolt.OP_GEMM, d, None, [A, B, None, D])
+    assert r1.config.as_dict() == r2.config.as_dict() and r1.ms == r2.ms
+    peak = bolt.bolt_probe_mfma_peak(2000)
+    buf = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    bw = bolt.bolt_probe_copy_bandwidth(buf, 3)
+    _say("MFMA loop %.0f TFLOP/s, copy %.0f GB/s" % (peak, bw))
+    assert peak > 100 and bw > 500

@@ -1,0 +1,143 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/bolt.h declares, and its
+descriptor validation returns the documented status for each kind of bad input (no kernel runs)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2110_15238_amd", "libbolt.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libbolt.so not built (run __graft_entry__.build())")
+
+OK, INVALID, UNSUPPORTED, ALIGNMENT, WORKSPACE, LAUNCH, ILLEGAL = range(7)
+
+
+@pytest.fixture(scope="module")
+def bolt():
+    import paper_2110_15238_amd as b
+    return b
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "bolt.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(bolt_[a-z0-9_]+)\s*\(", header))
+    assert {"bolt_gemm_epilogue", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune"} <= declared
+    lib = ctypes.CDLL(LIB)
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+
+
+def test_binding_lists_the_same_symbols(bolt):
+    header = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "bolt.h")).read(), flags=re.S)
+    declared = set(re.findall(r"\b(bolt_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(bolt.binding.EXPORTED)
+    for name in declared:
+        assert hasattr(bolt, name), name
+
+
+def test_struct_layouts_match_header(bolt):
+    assert ctypes.sizeof(bolt.BoltConfig) == 44
+    assert ctypes.sizeof(bolt.GemmDesc) == 40
+    assert ctypes.sizeof(bolt.ConvDesc) == 56
+
+
+def test_instance_tables(bolt):
+    for op in (bolt.OP_GEMM, bolt.OP_CONV2D, bolt.OP_B2B_GEMM, bolt.OP_B2B_CONV):
+        n = bolt.bolt_num_instances(op)
+        assert 10 <= n <= 64  # "tens" of instances per op
+        for i in range(n):
+            c = bolt.bolt_instance_config(op, i).as_dict()
+            assert c["kernel_id"] == i and c["tile_m"] % 32 == 0 and c["tile_n"] % 32 == 0
+            assert c["waves_m"] * c["waves_n"] in (2, 4, 8)
+    with pytest.raises(bolt.BoltError):
+        bolt.bolt_instance_config(bolt.OP_GEMM, 10 ** 6)
+
+
+def test_gemm_validation(bolt):
+    G, chk = bolt.gemm_desc, bolt.bolt_check
+    assert chk(bolt.OP_GEMM, G(256, 256, 256)) == OK
+    assert chk(bolt.OP_GEMM, G(1, 8, 8)) == OK
+    assert chk(bolt.OP_GEMM, G(0, 8, 8)) == INVALID
+    assert chk(bolt.OP_GEMM, G(8, 8, -8)) == INVALID
+    assert chk(bolt.OP_GEMM, G(256, 250, 256)) == ALIGNMENT        # N not a multiple of 8
+    assert chk(bolt.OP_GEMM, G(256, 256, 100)) == ALIGNMENT        # K not a multiple of 8
+    assert chk(bolt.OP_GEMM, G(256, 256, 256, lda=260)) == ALIGNMENT
+    assert chk(bolt.OP_GEMM, G(256, 256, 256, lda=128)) == INVALID  # lda < K
+    assert chk(bolt.OP_GEMM, G(256, 256, 256, ldd=8)) == INVALID
+    d = G(256, 256, 256)
+    d.act = 17
+    assert chk(bolt.OP_GEMM, d) == INVALID
+    d = G(256, 256, 256)
+    d.b_layout = 5
+    assert chk(bolt.OP_GEMM, d) == INVALID
+    assert chk(bolt.OP_GEMM, None) == INVALID
+    assert chk(bolt.OP_GEMM, G(64, 64, 64), None, {"kernel_id": 9999}) == INVALID
+    assert chk(bolt.OP_GEMM, G(64, 64, 64), None, {"kernel_id": -1, "split_k": 1000}) == INVALID
+    # an NK-layout instance cannot run a KN-layout problem
+    n = bolt.bolt_num_instances(bolt.OP_GEMM)
+    kn = [i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_GEMM, i, G(512, 512, 512))]
+    nk = [i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_GEMM, i, G(512, 512, 512, b_layout=bolt.LAYOUT_NK))]
+    assert kn and nk and not set(kn) & set(nk)
+    assert chk(bolt.OP_GEMM, G(512, 512, 512), None, {"kernel_id": nk[0]}) == UNSUPPORTED
+
+
+def test_conv_validation(bolt):
+    Cd, chk = bolt.conv_desc, bolt.bolt_check
+    assert chk(bolt.OP_CONV2D, Cd(32, 56, 56, 64, 64, 3, 3, 1, 1)) == OK
+    assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 3, 64, 7, 7, 2, 3)) == ALIGNMENT   # C = 3 must be padded to 8
+    assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 8, 64, 7, 7, 2, 3)) == OK
+    assert chk(bolt.OP_CONV2D, Cd(1, 8, 8, 8, 12, 3, 3, 1, 1)) == ALIGNMENT
+    assert chk(bolt.OP_CONV2D, Cd(1, 2, 2, 8, 8, 3, 3, 1, 0)) == INVALID            # filter larger than image
+    assert chk(bolt.OP_CONV2D, Cd(1, 8, 8, 8, 8, 3, 3, 0, 1)) == INVALID            # stride 0
+    assert chk(bolt.OP_CONV2D, Cd(1, 8, 8, 8, 8, 3, 3, 1, -1)) == INVALID
+    assert chk(bolt.OP_CONV2D, Cd(4096, 1024, 1024, 8, 8, 3, 3, 1, 1)) == UNSUPPORTED  # 32-bit offsets
+    assert bolt.conv_out_hw(Cd(1, 224, 224, 8, 64, 7, 7, 2, 3)) == (112, 112)
+
+
+def test_b2b_fusion_legality(bolt):
+    G, Cd, chk = bolt.gemm_desc, bolt.conv_desc, bolt.bolt_check
+    assert chk(bolt.OP_B2B_GEMM, G(16384, 64, 256), G(16384, 128, 64)) == OK
+    assert chk(bolt.OP_B2B_GEMM, G(16384, 64, 256), G(16000, 128, 64)) == ILLEGAL    # M must stay the same
+    assert chk(bolt.OP_B2B_GEMM, G(16384, 64, 256), G(16384, 128, 72)) == ILLEGAL    # K1 must equal N0
+    assert chk(bolt.OP_B2B_GEMM, G(16384, 64, 256), None) == INVALID
+    assert chk(bolt.OP_B2B_GEMM, G(16384, 512, 256), G(16384, 128, 512)) == UNSUPPORTED  # no tile spans N0 = 512
+    assert chk(bolt.OP_B2B_GEMM, G(16384, 128, 8192), G(16384, 64, 128)) == UNSUPPORTED  # W0 does not fit in LDS
+    c0 = Cd(32, 56, 56, 64, 64, 3, 3, 1, 1)
+    assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 64, 256, 1, 1, 1, 0)) == OK
+    assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 64, 256, 3, 3, 1, 1)) == ILLEGAL   # 2nd conv must be 1x1
+    assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 64, 256, 1, 1, 2, 0)) == ILLEGAL   # ... stride 1
+    assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 64, 256, 1, 1, 1, 1)) == ILLEGAL   # ... no padding
+    assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 128, 256, 1, 1, 1, 0)) == ILLEGAL  # C1 must equal K0
+    assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 28, 28, 64, 256, 1, 1, 1, 0)) == ILLEGAL   # extent must match
+    c0s = Cd(32, 56, 56, 64, 64, 3, 3, 2, 1)
+    assert chk(bolt.OP_B2B_CONV, c0s, Cd(32, 28, 28, 64, 64, 1, 1, 1, 0)) == OK
+
+
+def test_workspace_bytes(bolt):
+    d = bolt.conv_desc(32, 7, 7, 512, 512, 3, 3, 1, 1)
+    assert bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d, None, {"kernel_id": 0, "split_k": 4}) == 4 * 1568 * 512 * 4
+    assert bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d, None, {"kernel_id": 0, "split_k": 1}) == 0
+    assert bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d) >= 4 * 1568 * 512 * 4
+    big = bolt.conv_desc(32, 56, 56, 64, 64, 3, 3, 1, 1)
+    assert bolt.bolt_workspace_bytes(bolt.OP_CONV2D, big) == 0  # enough tiles: split-K is never tried
+
+
+def test_status_strings(bolt):
+    seen = {bolt.bolt_status_string(i) for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def test_null_pointers_are_rejected_before_any_launch(bolt):
+    lib = bolt.binding.raw()
+    d = bolt.gemm_desc(64, 64, 64)
+    assert lib.bolt_gemm_epilogue(ctypes.byref(d), None, None, None, None, None, None, 0, None) == INVALID
+    c = bolt.conv_desc(1, 8, 8, 8, 8, 3, 3, 1, 1)
+    assert lib.bolt_conv2d_fprop_nhwc(ctypes.byref(c), None, None, None, None, None, None, 0, None) == INVALID
+    assert lib.bolt_gemm_epilogue(ctypes.byref(d), 16, 32, None, 8, None, None, 0, None) == ALIGNMENT  # D misaligned
+    assert lib.bolt_pad_channels_nhwc(None, None, 4, 3, 8, None) == INVALID
+    assert lib.bolt_pad_channels_nhwc(16, 32, 4, 3, 7, None) == ALIGNMENT
+    assert lib.bolt_pad_channels_nhwc(16, 32, 4, 9, 8, None) == INVALID
+    assert lib.bolt_tune(0, None, None, None, None, 0, None, None, None, None) == INVALID
