@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Benchmark of the Bolt hot path on one MI355X.
+
+A "step" is one pass over the whole hot path on resident synthetic inputs:
+  config 1 (GEMM+bias+ReLU), config 2 (3x3 conv), config 3 (fused b2b GEMM), config 4 (fused b2b
+  conv) and config 5 (the 53 conv layers of a ResNet-50-shaped stack at batch 32, the stem's
+  input padded 3 -> 8 channels inside the step), every kernel with the template parameters
+  bolt_tune picked for its shape (tuning happens before the timed region).
+value = useful FP16 FLOPs of one step / time of one step, in TFLOP/s.
+
+Prints ONE JSON line.  Besides the contract fields it carries
+  roofline     -- the dominant kernel (the implicit-GEMM conv template over the 54 conv launches of
+                  a step): algorithmic FLOPs / average launch duration against the FP16 MFMA peak
+  cpu_baseline -- the CPU oracle timed on this machine's host cores on a bounded sample
+  shapes       -- per-shape TFLOP/s, fraction of MFMA / HBM roofline and the chosen template
+  b2b          -- fused vs unfused-pair time for configs 3 and 4
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X FP16 dense
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--reps", type=int, default=50, help="launches per shape for the per-shape table")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by batch with "
+              "no collective, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2110_15238_amd as bolt
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def empty(*shape):
+        return torch.empty(shape, dtype=torch.float16, device="cuda")
+
+    def timed(fn, reps):
+        """Mean ms per call of fn over reps back-to-back calls (events on the launch stream)."""
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")  # split-K workspace shared by all ops
+
+    # ------------------------------------------------------------------ build + tune every op
+    ops = []      # dicts: name, flops, bytes, run(), config
+    shapes_out = []
+
+    def add_conv(name, shape, t, count=1, in_step=True):
+        x, w = dev(t["x"]), dev(t["w"])
+        pad_fn = None
+        if shape.c_logical:
+            xp = empty(*(t["x"].shape[:-1] + (shape.C,)))
+            wp = empty(*(t["w"].shape[:-1] + (shape.C,)))
+            bolt.bolt_pad_channels_nhwc(w, wp, shape.C)     # weights are padded once, offline
+            x_src = x
+            pad_fn = lambda: bolt.bolt_pad_channels_nhwc(x_src, xp, shape.C)
+            pad_fn()
+            x, w = xp, wp
+        b = dev(t["bias"])
+        d = bolt.conv_desc(shape.N, shape.H, shape.W, shape.C, shape.K, shape.R, shape.S, shape.stride, shape.pad)
+        y = empty(shape.N, shape.P, shape.Q, shape.K)
+        res = bolt.bolt_tune(bolt.OP_CONV2D, d, None, [x, w, b, y], ws)
+        cfg = res.config
+        run = lambda: bolt.bolt_conv2d_fprop_nhwc(d, x, w, b, y, cfg, ws)
+        op = dict(name=name, kind="conv", flops=shape.flops, bytes=shape.bytes, run=run, count=count, cfg=cfg.as_dict(),
+                  pad=pad_fn, in_step=in_step, keep=(x, w, b, y, d))
+        ops.append(op)
+        return op
+
+    # config 1
+    t = wl.config1()
+    A1, B1, bias1, D1 = dev(t["A"]), dev(t["B"]), dev(t["bias"]), empty(256, 256)
+    g1 = bolt.gemm_desc(256, 256, 256)
+    cfg1 = bolt.bolt_tune(bolt.OP_GEMM, g1, None, [A1, B1, bias1, D1], ws).config
+    ops.append(dict(name="C1 gemm 256x256x256", kind="gemm", flops=2 * 256 ** 3, bytes=wl.GemmShape(256, 256, 256).bytes,
+                    run=lambda: bolt.bolt_gemm_epilogue(g1, A1, B1, bias1, D1, cfg1, ws), count=1, cfg=cfg1.as_dict(),
+                    pad=None, in_step=True))
+    # config 2
+    add_conv("C2 conv3x3 56x56 64->64", wl.CONFIG2_SHAPE, wl.config2())
+    # config 3: fused, and the unfused pair for the speedup
+    t = wl.config3()
+    A3, W0, b0, W1, b1 = (dev(t[k]) for k in ("A", "W0", "b0", "W1", "b1"))
+    D0u, D3, D3u = empty(16384, 64), empty(16384, 128), empty(16384, 128)
+    g30, g31 = bolt.gemm_desc(16384, 64, 256), bolt.gemm_desc(16384, 128, 64)
+    cfg3 = bolt.bolt_tune(bolt.OP_B2B_GEMM, g30, g31, [A3, W0, b0, W1, b1, D3]).config
+    cfg30 = bolt.bolt_tune(bolt.OP_GEMM, g30, None, [A3, W0, b0, D0u], ws).config
+    cfg31 = bolt.bolt_tune(bolt.OP_GEMM, g31, None, [D0u, W1, b1, D3u], ws).config
+    s30, s31 = wl.CONFIG3_SHAPE
+    fused_bytes3 = 2 * (16384 * 256 + 256 * 64 + 64 + 64 * 128 + 128 + 16384 * 128)
+    run3 = lambda: bolt.bolt_b2b_gemm(g30, g31, A3, W0, b0, W1, b1, D3, cfg3)
+
+    def run3u():
+        bolt.bolt_gemm_epilogue(g30, A3, W0, b0, D0u, cfg30, ws)
+        bolt.bolt_gemm_epilogue(g31, D0u, W1, b1, D3u, cfg31, ws)
+    ops.append(dict(name="C3 b2b gemm fused", kind="b2b_gemm", flops=s30.flops + s31.flops, bytes=fused_bytes3, run=run3,
+                    count=1, cfg=cfg3.as_dict(), pad=None, in_step=True))
+    # config 4
+    t = wl.config4()
+    x4, w40, b40, w41, b41 = (dev(t[k]) for k in ("x", "w0", "b0", "w1", "b1"))
+    c40 = bolt.conv_desc(32, 56, 56, 64, 64, 3, 3, 1, 1)
+    c41 = bolt.conv_desc(32, 56, 56, 64, 256, 1, 1, 1, 0)
+    y40u, y4, y4u = empty(32, 56, 56, 64), empty(32, 56, 56, 256), empty(32, 56, 56, 256)
+    cfg4 = bolt.bolt_tune(bolt.OP_B2B_CONV, c40, c41, [x4, w40, b40, w41, b41, y4]).config
+    cfg40 = bolt.bolt_tune(bolt.OP_CONV2D, c40, None, [x4, w40, b40, y40u], ws).config
+    cfg41 = bolt.bolt_tune(bolt.OP_CONV2D, c41, None, [y40u, w41, b41, y4u], ws).config
+    s40, s41 = wl.CONFIG4_SHAPES
+    fused_bytes4 = 2 * (x4.numel() + w40.numel() + w41.numel() + 64 + 256 + y4.numel())
+    run4 = lambda: bolt.bolt_b2b_conv(c40, c41, x4, w40, b40, w41, b41, y4, cfg4)
+
+    def run4u():
+        bolt.bolt_conv2d_fprop_nhwc(c40, x4, w40, b40, y40u, cfg40, ws)
+        bolt.bolt_conv2d_fprop_nhwc(c41, y40u, w41, b41, y4u, cfg41, ws)
+    ops.append(dict(name="C4 b2b conv fused", kind="b2b_conv", flops=s40.flops + s41.flops, bytes=fused_bytes4, run=run4,
+                    count=1, cfg=cfg4.as_dict(), pad=None, in_step=True))
+    # config 5
+    for i, (shape, cnt) in enumerate(wl.resnet50_layers(32)):
+        _, _, t = wl.config5_layer(i)
+        add_conv("C5 L%02d %dx%d %d->%d %dx%d/%d" % (i, shape.H, shape.W, shape.c_logical or shape.C, shape.K, shape.R,
+                                                    shape.S, shape.stride), shape, t, count=cnt)
+    torch.cuda.synchronize()
+
+    # ------------------------------------------------------------------ per-shape table
+    for op in ops:
+        ms = timed(op["run"], args.reps)
+        tfl = op["flops"] / ms / 1e9
+        gbs = op["bytes"] / ms / 1e6
+        t_mfma = op["flops"] / (MFMA_PEAK_TFLOPS * 1e9)   # ms
+        t_hbm = op["bytes"] / (HBM_PEAK_GBS * 1e6)        # ms
+        entry = dict(name=op["name"], ms=round(ms, 5), tflops=round(tfl, 2), pct_mfma_peak=round(100 * tfl / MFMA_PEAK_TFLOPS, 2),
+                     gbs=round(gbs, 1), pct_hbm_peak=round(100 * gbs / HBM_PEAK_GBS, 2),
+                     bound="mfma" if t_mfma >= t_hbm else "hbm", roofline_frac=round(max(t_mfma, t_hbm) / ms, 4),
+                     count=op["count"], config={k: op["cfg"][k] for k in ("kernel_id", "tile_m", "tile_n", "tile_k", "waves_m",
+                                                                         "waves_n", "swizzle", "split_k", "b2b_mode")})
+        if op["pad"] is not None:
+            pms = timed(op["pad"], args.reps)
+            entry["pad_ms"] = round(pms, 5)
+            entry["pad_cost_frac"] = round(pms / (pms + ms), 4)
+        op["ms"] = ms
+        shapes_out.append(entry)
+    ms3, ms3u = timed(run3, args.reps), timed(run3u, args.reps)
+    ms4, ms4u = timed(run4, args.reps), timed(run4u, args.reps)
+    b2b = dict(config3_gemm=dict(fused_ms=round(ms3, 5), unfused_ms=round(ms3u, 5), speedup=round(ms3u / ms3, 3)),
+               config4_conv=dict(fused_ms=round(ms4, 5), unfused_ms=round(ms4u, 5), speedup=round(ms4u / ms4, 3)))
+
+    # ------------------------------------------------------------------ the timed steps
+    conv_ops = [op for op in ops if op["kind"] == "conv"]
+    other_ops = [op for op in ops if op["kind"] != "conv"]
+    conv_launches = sum(op["count"] for op in conv_ops)
+    conv_flops = sum(op["flops"] * op["count"] for op in conv_ops)
+    step_flops = conv_flops + sum(op["flops"] for op in other_ops)
+
+    def step(ev=None):
+        for op in other_ops:
+            op["run"]()
+        for op in conv_ops:
+            if op["pad"] is not None:
+                op["pad"]()
+        if ev is not None:
+            ev[0].record(stream)
+        for op in conv_ops:
+            for _ in range(op["count"]):
+                op["run"]()
+        if ev is not None:
+            ev[1].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    conv_ms = sum(a.elapsed_time(b) for a, b in evs) / args.steps      # conv segment of a step
+    avg_launch_ms = conv_ms / conv_launches
+    achieved = conv_flops / conv_launches / (avg_launch_ms * 1e-3) / 1e12
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("fprop_conv_hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "FP16 TFLOP/s and % of MFMA peak per conv/GEMM shape; b2b fused vs unfused speedup",
+        "value": round(step_flops / (ms_per_step * 1e-3) / 1e12, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 (f32 accumulate)",
+        "data": "synthetic",
+        "config": {"workload": "one pass over configs 1-5: GEMM 256^3, conv3x3 56x56x64, fused b2b GEMM 16384x256x64x128, "
+                               "fused b2b conv 3x3->1x1 64->64->256, ResNet-50-shaped 53-conv stack at batch 32 (incl. stem "
+                               "channel pad 3->8); config 5 carries 96% of the FLOPs",
+                   "batch": 32, "step_gflop": round(step_flops / 1e9, 2)},
+        "roofline": {"bound": "mfma", "kernel": "bolt::fprop_kernel<..., XMODE=1> (implicit-GEMM conv, all tuned instances)",
+                     "achieved": round(achieved, 3), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
+                     "launches_per_step": conv_launches, "avg_launch_ms": round(avg_launch_ms, 5),
+                     "flops_per_launch": round(conv_flops / conv_launches)},
+        "b2b": b2b,
+        "shapes": shapes_out,
+    }
+    try:
+        out["probes"] = {"mfma_loop_tflops": round(bolt.bolt_probe_mfma_peak(20000), 1),
+                         "copy_gbs_1GiB": round(bolt.bolt_probe_copy_bandwidth(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"), 5), 1)}
+    except Exception as e:  # probes are context only
+        out["probes"] = {"error": str(e)}
+
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        t = wl.config2()
+        c0 = time.perf_counter()
+        ref.conv2d_nhwc(t["x"], t["w"], t["bias"], stride=1, pad=1)
+        dt = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(wl.CONFIG2_SHAPE.flops / dt / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": ref.num_threads(), "kind": "oracle",
+                               "sample": "config 2 in full (3x3 conv, N=32, 56x56, 64->64, 7.4 GFLOP), %.1f s" % dt}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
