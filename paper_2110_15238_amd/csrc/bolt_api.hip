@@ -116,7 +116,7 @@ static bolt_status check_gemm_desc(const bolt_gemm_desc* d) {
   if (d->lda < d->K || d->ldd < d->N) return BOLT_ERR_INVALID_ARG;
   if (d->b_layout == BOLT_LAYOUT_KN ? d->ldb < d->N : d->ldb < d->K) return BOLT_ERR_INVALID_ARG;
   if ((d->N | d->K | d->lda | d->ldb | d->ldd) & 7) return BOLT_ERR_ALIGNMENT;
-  if (d->lda > (1 << 22) || d->ldb > (1 << 22) || d->ldd > (1 << 22)) return BOLT_ERR_UNSUPPORTED;
+  if (d->lda > (1 << 21) || d->ldb > (1 << 21) || d->ldd > (1 << 21)) return BOLT_ERR_UNSUPPORTED;
   return BOLT_OK;
 }
 
@@ -137,9 +137,10 @@ static bolt_status check_conv_desc(const bolt_conv_desc* d, ConvDims* out) {
   const int64_t M = (int64_t)d->N * P * Q;
   const int64_t Kg = (int64_t)d->R * d->S * d->C;
   const int64_t in_elems = (int64_t)d->N * d->H * d->W * d->C;
-  // the kernels index tensors with 32-bit element offsets and pack window origins in 16 bits
+  // the kernels address the input through one buffer descriptor (< 2 GiB), index outputs with
+  // 32-bit element offsets and pack window origins in 16 bits
   if (d->H > 16384 || d->W > 16384 || d->pad_h > 8192 || d->pad_w > 8192) return BOLT_ERR_UNSUPPORTED;
-  if (in_elems >= (1ll << 31) || M * d->K >= (1ll << 31) || M >= (1ll << 30) || Kg >= (1 << 24))
+  if (in_elems >= (1ll << 30) || M * d->K >= (1ll << 31) || M >= (1ll << 30) || Kg >= (1 << 24))
     return BOLT_ERR_UNSUPPORTED;
   if (out) *out = {(int)P, (int)Q, (int)M, (int)Kg};
   return BOLT_OK;
@@ -199,7 +200,7 @@ static void fprop_fill_config(const FpropInstance& in, int id, bolt_config* c) {
   c->kernel_id = id;
   c->tile_m = in.bm; c->tile_n = in.bn; c->tile_k = in.bk;
   c->waves_m = in.waves_m; c->waves_n = in.waves_n;
-  c->mfma_shape = 32; c->stages = 2; c->b2b_mode = 0;
+  c->mfma_shape = 32; c->stages = in.stages; c->b2b_mode = 0;
 }
 
 // Built-in pick rule: smallest estimated time under a crude model -- rounds of workgroups over

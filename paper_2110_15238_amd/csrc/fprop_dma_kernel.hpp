@@ -1,0 +1,328 @@
+// Multi-stage GEMM / implicit-GEMM convolution kernel: operand tiles go global -> LDS directly
+// (buffer_load ... lds, 16 bytes per lane, no staging registers), NS tiles deep, so that the
+// latency of the loads for tile k+NS-1 is hidden behind the MFMA work on tiles k .. k+NS-2.
+// "Stages" is one of the searched template parameters of Section 3.2.2; everything else follows
+// the tiling of Section 2.2 as in fprop_kernel.hpp.  Both operands must be K-contiguous in memory
+// (conv: NHWC activations, KRSC weights; GEMM: A row-major, B stored [N][K]).
+//
+// Out-of-range rows, the K tail and zero-padding taps are not branched on: their lanes are given a
+// byte offset beyond the buffer descriptor's range, for which the hardware writes zeros to LDS.
+//
+// Epilogue (Section 3.1, patterns (i)-(iii)): scale, bias, activation and FP16 conversion on the
+// accumulator registers, then the FP16 tile is transposed through LDS so that every store
+// instruction writes whole 128-byte row segments.
+#pragma once
+#include "bolt_device.hpp"
+#include "fprop_kernel.hpp"
+
+namespace bolt {
+
+#define BOLT_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+static constexpr unsigned kInvalidOffset = 0x80000000u;  // beyond any descriptor range we create
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, bytes, 0x00020000);
+}
+
+// Workgroup barriers without the full fence of __syncthreads(): that fence would drain every
+// outstanding global load, including the prefetches that are meant to stay in flight.  The "memory"
+// clobber keeps the compiler from moving LDS accesses or direct-to-LDS loads across the barrier.
+//   barrier_after_loads<VM>: this wave's direct-to-LDS loads, except the VM newest, have landed.
+//   barrier_after_lds_writes: this wave's ds_write instructions have completed.
+template <int VM>
+__device__ __forceinline__ void barrier_after_loads() {
+  static_assert(VM >= 0 && VM < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(VM) : "memory");
+}
+__device__ __forceinline__ void barrier_after_lds_writes() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Swizzle used by the direct-to-LDS tiles: a lane's 16-byte slot in LDS is fixed by the hardware
+// (slot = lane), so the permutation is applied to which global chunk the lane fetches.  The chunk
+// index is XORed with row bits only, which keeps a lane's logical chunk the same for every row
+// group it serves.
+template <int BK>
+__device__ __forceinline__ int dma_swizzle(int row) {
+  return BK == 32 ? ((row >> 1) & 3) : (row & 7);
+}
+template <int BK>
+__device__ __forceinline__ int dma_chunk_offset(int row, int chunk) {
+  return row * BK + ((chunk ^ dma_swizzle<BK>(row)) << 3);
+}
+
+// One operand tile of ROWS x BK halves moved by NW waves; each load instruction of a wave fills
+// 1024 contiguous LDS bytes = RPI whole tile rows.
+template <int ROWS, int BK, int NW, int XMODE>
+struct DmaTileLoader {
+  static constexpr int CH = BK / 8;
+  static constexpr int RPI = 64 / CH;          // tile rows per instruction
+  static constexpr int NI = ROWS / RPI / NW;   // instructions per wave per tile
+  static_assert(BK == 32 || BK == 64, "BK");
+  static_assert(ROWS % (RPI * NW) == 0 && NI >= 1, "tile rows must split evenly over the waves");
+
+  __amdgpu_buffer_rsrc_t rsrc;
+  int xbase[XMODE == 1 ? NI : 1];
+  int xhw[XMODE == 1 ? NI : 1];
+  int cr, cs, cc;
+  int ld, rows_valid, K, wave, lrow, lc;
+
+  // GEMM-like source (XMODE 0): `base` points at row 0 of this tile, `bytes` is what remains of the
+  // tensor from there.  Conv source (XMODE 1): base/bytes describe the whole NHWC tensor.
+  __device__ __forceinline__ void init(const half_t* base, unsigned bytes, int ld_, int rows_valid_, int K_,
+                                       const ConvGeom& cg, int m0, int kt_begin, int wave_, int lane) {
+    rsrc = make_rsrc(base, bytes);
+    ld = ld_;
+    rows_valid = rows_valid_;
+    K = K_;
+    wave = wave_;
+    lrow = lane / CH;
+    lc = (lane % CH) ^ dma_swizzle<BK>(lrow);
+    cr = cs = cc = 0;
+    if constexpr (XMODE == 1) {
+      const int PQ = cg.P * cg.Q;
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int row = (j * NW + wave) * RPI + lrow;
+        if (row < rows_valid) {
+          const int m = m0 + row;
+          const int img = m / PQ, rem = m - img * PQ;
+          const int op = rem / cg.Q, oq = rem - op * cg.Q;
+          const int ih0 = op * cg.stride_h - cg.pad_h, iw0 = oq * cg.stride_w - cg.pad_w;
+          xbase[j] = ((img * cg.H + ih0) * cg.Wi + iw0) * cg.C;
+          xhw[j] = (int)(((unsigned)ih0 << 16) | ((unsigned)iw0 & 0xffffu));
+        } else {
+          xbase[j] = 0;
+          xhw[j] = (int)0x80008000u;
+        }
+      }
+      const int k = kt_begin * BK + lc * 8;
+      const int rs = k / cg.C;
+      cc = k - rs * cg.C;
+      cr = rs / cg.S;
+      cs = rs - cr * cg.S;
+    }
+  }
+
+  // Issue the loads of k-tile kt into the LDS tile at `dst` (conv mode: tiles in increasing order).
+  __device__ __forceinline__ void issue(int kt, half_t* dst, const ConvGeom& cg) {
+    const int k = kt * BK + lc * 8;
+    if constexpr (XMODE == 0) {
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int rb = (j * NW + wave) * RPI;
+        const int row = rb + lrow;
+        const unsigned off = (row < rows_valid && k < K) ? (unsigned)(row * ld + k) * 2u : kInvalidOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, BOLT_LDS_PTR(dst + rb * BK), 16, off, 0, 0, 0);
+      }
+    } else {
+      const int delta = (cr * cg.Wi + cs) * cg.C + cc;
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int rb = (j * NW + wave) * RPI;
+        const int ih = (xhw[j] >> 16) + cr, iw = (int)(short)(xhw[j] & 0xffff) + cs;
+        const bool ok = k < K && (unsigned)ih < (unsigned)cg.H && (unsigned)iw < (unsigned)cg.Wi;
+        const unsigned off = ok ? (unsigned)(xbase[j] + delta) * 2u : kInvalidOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, BOLT_LDS_PTR(dst + rb * BK), 16, off, 0, 0, 0);
+      }
+      cc += BK;
+      while (cc >= cg.C) {
+        cc -= cg.C;
+        if (++cs == cg.S) {
+          cs = 0;
+          ++cr;
+        }
+      }
+    }
+  }
+};
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS>
+struct FpropDmaTraits {
+  static constexpr int NW = WAVES_M * WAVES_N;
+  static constexpr int NT = 64 * NW;
+  static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  static constexpr int FM = WTM / 32, FN = WTN / 32;
+  static constexpr int STAGE_HALVES = (BM + BN) * BK;
+  static constexpr int PIPE_BYTES = NS * STAGE_HALVES * 2;
+  static constexpr int CTILE_BYTES = BM * BN * 2;
+  static constexpr int LDS_BYTES = PIPE_BYTES > CTILE_BYTES ? PIPE_BYTES : CTILE_BYTES;
+  static constexpr int CPR = BN / 8;            // 16-byte chunks per C-tile row
+  static constexpr int ROWS_PER_PASS = NT / CPR;
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+  static_assert(NS >= 2 && NS <= 4, "stages");
+  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+};
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const FpropParams p) {
+  using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS>;
+  constexpr int NW = T::NW, NT = T::NT, WTM = T::WTM, WTN = T::WTN, FM = T::FM, FN = T::FN;
+  constexpr int STAGE = T::STAGE_HALVES;
+  using XL = DmaTileLoader<BM, BK, NW, XMODE>;
+  using WL = DmaTileLoader<BN, BK, NW, 0>;
+  constexpr int L = XL::NI + WL::NI;  // load instructions per wave per k-tile
+  static_assert((NS - 2) * L < 64, "vmcnt range");
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int g = lane >> 5, l32 = lane & 31;
+  int tm, tn;
+  tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.swizzle, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int z = blockIdx.y;
+  const int nk_total = (p.K + BK - 1) / BK;
+  const int kt_begin = z * p.ktiles_per_split;
+  const int kt_end = (kt_begin + p.ktiles_per_split) < nk_total ? (kt_begin + p.ktiles_per_split) : nk_total;
+
+  XL xl;
+  WL wl;
+  if constexpr (XMODE == 0) {
+    const int64_t rem = ((int64_t)(p.M - m0 - 1) * p.ldx + p.K) * 2;
+    xl.init(p.X + (int64_t)m0 * p.ldx, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldx, p.M - m0, p.K, p.cg, m0,
+            kt_begin, wave, lane);
+  } else {
+    const int64_t bytes = (int64_t)p.cg.H * p.cg.Wi * p.cg.C * 2 * (int64_t)(p.M / (p.cg.P * p.cg.Q));
+    xl.init(p.X, (unsigned)bytes, 0, p.M - m0, p.K, p.cg, m0, kt_begin, wave, lane);
+  }
+  {
+    const int64_t rem = ((int64_t)(p.N - n0 - 1) * p.ldw + p.K) * 2;
+    wl.init(p.W + (int64_t)n0 * p.ldw, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldw, p.N - n0, p.K, p.cg, n0,
+            kt_begin, wave, lane);
+  }
+
+  floatx16 acc[FN][FM];
+#pragma unroll
+  for (int a = 0; a < FN; ++a)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  auto issue = [&](int kt, int stage) {
+    half_t* s = lds + stage * STAGE;
+    xl.issue(kt, s, p.cg);
+    wl.issue(kt, s + BM * BK, p.cg);
+  };
+  auto compute = [&](int stage) {
+    const half_t* xs = lds + stage * STAGE;
+    const half_t* ws = xs + BM * BK;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      half8 xf[FM], wf[FN];
+      const int chunk = ks * 2 + g;
+#pragma unroll
+      for (int b = 0; b < FM; ++b) xf[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
+#pragma unroll
+      for (int a = 0; a < FN; ++a) wf[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(wf[a], xf[b], acc[a][b]);
+    }
+  };
+
+  // ---- NS-deep pipeline: one barrier per k-tile ----------------------------------------------
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (kt_begin + s < kt_end) issue(kt_begin + s, s);
+  int stage = 0, fill = NS - 1;  // stage being consumed / stage the next issue goes to
+  for (int kt = kt_begin; kt < kt_end; ++kt) {
+    // loads of tiles newer than kt that may stay in flight: NS-2 tiles, fewer at the tail
+    // after the barrier tile kt has landed for every wave and everyone is done with tile kt-1
+    if (kt_end - 1 - kt >= NS - 2) barrier_after_loads<(NS - 2) * L>();
+    else barrier_after_loads<0>();
+    if (kt + NS - 1 < kt_end) issue(kt + NS - 1, fill);
+    compute(stage);
+    stage = stage + 1 == NS ? 0 : stage + 1;
+    fill = fill + 1 == NS ? 0 : fill + 1;
+  }
+
+  // ---- epilogue ---------------------------------------------------------------------------------
+  const int mrow = m0 + wm * WTM + l32;
+  const int ncol = n0 + wn * WTN + g * 4;
+  if (p.split_k > 1) {
+    float* dst = p.partial + (int64_t)z * p.M * p.N;
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int b = 0; b < FM; ++b)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int m = mrow + b * 32, n = ncol + a * 32 + q * 8;
+          if (m < p.M && n < p.N) {
+            floatx4 v = {acc[a][b][q * 4], acc[a][b][q * 4 + 1], acc[a][b][q * 4 + 2], acc[a][b][q * 4 + 3]};
+            *(floatx4*)(dst + (int64_t)m * p.N + n) = v;
+          }
+        }
+    return;
+  }
+
+  // registers -> FP16 C tile in LDS ([BM][BN], 16-byte chunks XOR-swizzled by row)
+  constexpr int CPR = T::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
+  barrier_after_lds_writes();  // every wave has finished reading the operand stages
+#pragma unroll
+  for (int a = 0; a < FN; ++a)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int nl = wn * WTN + a * 32 + q * 8 + g * 4;  // column inside the tile
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (p.bias && n0 + nl < p.N) {
+        const half4 hb = *(const half4*)(p.bias + n0 + nl);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bv[e] = p.beta * (float)hb[e];
+      }
+#pragma unroll
+      for (int b = 0; b < FM; ++b) {
+        half4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (half_t)apply_act(p.alpha * acc[a][b][q * 4 + e] + bv[e], p.act);
+        const int row = wm * WTM + b * 32 + l32;
+        *(half4*)(lds + row * BN + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) = o;
+      }
+    }
+  barrier_after_lds_writes();
+  // LDS -> global: each thread moves 16 bytes, consecutive threads cover consecutive row bytes
+  {
+    const int chunk = tid % CPR, r0 = tid / CPR;
+    const int n = n0 + chunk * 8;
+    if (n < p.N) {
+#pragma unroll
+      for (int i = 0; i < BM / T::ROWS_PER_PASS; ++i) {
+        const int row = r0 + i * T::ROWS_PER_PASS;
+        if (m0 + row < p.M) {
+          const half8 v = *(const half8*)(lds + row * BN + ((chunk ^ (row & CSW)) << 3));
+          *(half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n) = v;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS>
+hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
+  using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS>;
+  auto kern = fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid(p.tiles_m * p.tiles_n, p.split_k, 1);
+  hipLaunchKernelGGL(kern, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+  return hipGetLastError();
+}
+
+#define BOLT_FPROP_DMA_INSTANCE(BM, BN, BK, WM, WN, NS, XMODE)                                          \
+  {                                                                                                     \
+    "dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK, WM, WN, XMODE, 0, NS,               \
+        bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS>::LDS_BYTES,                                  \
+        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>                                           \
+  }
+
+}  // namespace bolt

@@ -168,6 +168,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_kernel(const Fpr
 struct FpropInstance {
   const char* name;
   int bm, bn, bk, waves_m, waves_n, xmode, wmode;
+  int stages;  // LDS operand buffers in flight
   int lds_bytes;
   hipError_t (*launch)(const FpropParams&, hipStream_t);
 };
@@ -189,7 +190,7 @@ hipError_t launch_fprop(const FpropParams& p, hipStream_t stream) {
 
 #define BOLT_FPROP_INSTANCE(BM, BN, BK, WM, WN, XMODE, WMODE)                                          \
   {                                                                                                    \
-    #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, WM, WN, XMODE, WMODE,                              \
+    #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, WM, WN, XMODE, WMODE, 2,                           \
         bolt::FpropTraits<BM, BN, BK, WM, WN, XMODE, WMODE>::LDS_BYTES,                                 \
         &bolt::launch_fprop<BM, BN, BK, WM, WN, XMODE, WMODE>                                           \
   }

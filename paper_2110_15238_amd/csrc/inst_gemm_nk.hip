@@ -2,7 +2,7 @@
 #include "instances.hpp"
 namespace bolt {
 void register_gemm_nk_instances(std::vector<FpropInstance>& v) {
-  static const FpropInstance table[] = {BOLT_FPROP_TILE_LIST(BOLT_FPROP_INSTANCE, 0, 0)};
+  static const FpropInstance table[] = {BOLT_FPROP_DMA_TILE_LIST(BOLT_FPROP_DMA_INSTANCE, 0)};
   for (const auto& t : table) v.push_back(t);
 }
 }  // namespace bolt

@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "b2b_kernel.hpp"
+#include "fprop_dma_kernel.hpp"
 #include "fprop_kernel.hpp"
 
 // X(BM, BN, BK, WAVES_M, WAVES_N)
@@ -32,6 +33,34 @@
   X(64, 64, 64, 2, 1, XMODE, WMODE),          \
   X(32, 64, 64, 1, 2, XMODE, WMODE),          \
   X(64, 32, 64, 2, 1, XMODE, WMODE)
+
+// X(BM, BN, BK, WAVES_M, WAVES_N, STAGES): direct-to-LDS multi-stage instances (K-contiguous operands)
+#define BOLT_FPROP_DMA_TILE_LIST(X, XMODE) \
+  X(256, 256, 64, 2, 2, 2, XMODE),         \
+  X(256, 256, 64, 2, 4, 2, XMODE),         \
+  X(256, 256, 32, 2, 2, 4, XMODE),         \
+  X(256, 256, 32, 2, 4, 3, XMODE),         \
+  X(256, 128, 64, 2, 2, 3, XMODE),         \
+  X(256, 128, 64, 4, 2, 3, XMODE),         \
+  X(256, 128, 32, 2, 2, 4, XMODE),         \
+  X(128, 256, 64, 2, 2, 3, XMODE),         \
+  X(128, 256, 64, 2, 4, 3, XMODE),         \
+  X(128, 128, 64, 2, 2, 3, XMODE),         \
+  X(128, 128, 64, 2, 2, 2, XMODE),         \
+  X(128, 128, 32, 2, 2, 4, XMODE),         \
+  X(256, 64, 64, 4, 1, 3, XMODE),          \
+  X(256, 64, 64, 4, 2, 3, XMODE),          \
+  X(128, 64, 64, 4, 1, 3, XMODE),          \
+  X(128, 64, 64, 2, 2, 3, XMODE),          \
+  X(128, 64, 64, 2, 2, 4, XMODE),          \
+  X(64, 128, 64, 2, 2, 3, XMODE),          \
+  X(64, 128, 64, 2, 2, 4, XMODE),          \
+  X(64, 256, 64, 1, 4, 3, XMODE),          \
+  X(64, 64, 64, 2, 2, 4, XMODE),           \
+  X(64, 64, 64, 2, 2, 3, XMODE),           \
+  X(64, 64, 64, 2, 1, 4, XMODE),           \
+  X(32, 64, 64, 1, 2, 4, XMODE),           \
+  X(64, 32, 64, 2, 1, 4, XMODE)
 
 namespace bolt {
 // Each function appends its instances in a fixed order; kernel_id is the index in the op's table.
