@@ -26,19 +26,18 @@ __device__ __forceinline__ floatx16 mfma_32x32x16(half8 a, half8 b, floatx16 c) 
 }
 
 // LDS operand tiles are [rows][BK] halves, K contiguous, addressed in 16-byte chunks of 8 halves.
-// The chunk index is XOR-swizzled by the row so that (a) the 8 lanes of a fragment read that
-// touch 8 consecutive rows at one logical chunk and (b) the 8 lanes of a transposing store that
-// touch rows 8 apart at one logical chunk both spread over all banks.
+// The LDS has 64 banks of 4 bytes; 128-bit accesses are served 16 lanes at a time, so 16 lanes
+// should land in 16 different 16-byte bank groups, bank group = (byte address / 16) mod 16.
+// The chunk index is XOR-swizzled by row bits so that (a) the 16 lanes of a fragment read, which
+// touch 16 consecutive rows at one logical chunk, are conflict-free and (b) the 16 lanes of a
+// transposing store, which touch rows 8 apart at one logical chunk, conflict only 2-way.
 template <int BK>
 __device__ __forceinline__ int lds_chunk_offset(int row, int chunk) {
-  static_assert(BK == 32 || BK == 64 || BK == 128, "BK");
+  static_assert(BK == 32 || BK == 64, "BK");
   if constexpr (BK == 32) {
-    int line = row >> 1;
-    int g = ((row & 1) << 2) | chunk;
-    g ^= (line ^ (line >> 3)) & 7;
-    return line * 64 + (g << 3);
+    return row * 32 + ((chunk ^ (((row >> 2) ^ (row >> 4)) & 3)) << 3);
   } else {
-    return row * BK + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 3);
+    return row * 64 + ((chunk ^ (((row >> 1) ^ (row >> 4)) & 7)) << 3);
   }
 }
 

@@ -29,23 +29,39 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, un
 // outstanding global load, including the prefetches that are meant to stay in flight.  The "memory"
 // clobber keeps the compiler from moving LDS accesses or direct-to-LDS loads across the barrier.
 //   barrier_after_loads<VM>: this wave's direct-to-LDS loads, except the VM newest, have landed.
+//   barrier_after_reads_and_loads<VM>: the same, and this wave's LDS reads have returned.
 //   barrier_after_lds_writes: this wave's ds_write instructions have completed.
+// The waits go through the s_waitcnt builtin so that the compiler's own wait-count bookkeeping
+// sees them (an asm wait would make it wait again, later and for more); the barrier itself is asm
+// with a "memory" clobber.  gfx9 s_waitcnt encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8].
+__device__ __forceinline__ void raw_barrier() { asm volatile("s_barrier" ::: "memory"); }
 template <int VM>
 __device__ __forceinline__ void barrier_after_loads() {
   static_assert(VM >= 0 && VM < 64, "vmcnt is a 6-bit counter");
-  asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(VM) : "memory");
+  __builtin_amdgcn_s_waitcnt((VM & 0xF) | ((VM >> 4) << 14) | 0x0F70);
+  raw_barrier();
+}
+template <int VM>
+__device__ __forceinline__ void barrier_after_reads_and_loads() {
+  static_assert(VM >= 0 && VM < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((VM & 0xF) | ((VM >> 4) << 14) | 0x0070);
+  raw_barrier();
 }
 __device__ __forceinline__ void barrier_after_lds_writes() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  raw_barrier();
 }
 
-// Swizzle used by the direct-to-LDS tiles: a lane's 16-byte slot in LDS is fixed by the hardware
-// (slot = lane), so the permutation is applied to which global chunk the lane fetches.  The chunk
-// index is XORed with row bits only, which keeps a lane's logical chunk the same for every row
-// group it serves.
+// Swizzle used by the direct-to-LDS tiles.  The LDS of this chip has 64 banks of 4 bytes and serves
+// a 128-bit read 16 lanes at a time, so the 16 lanes that read one logical chunk of 16 consecutive
+// rows must land in 16 different 16-byte bank groups.  A row is BK*2 bytes, so the bank group of
+// (row, chunk) is (row*CH + chunk) mod 16: XOR the chunk with the row bits above the ones that
+// already select the bank group.  A lane's 16-byte slot in LDS is fixed by the hardware
+// (slot = lane), so the permutation is applied to which global chunk the lane fetches; with an even
+// number of waves the XOR term is the same for every row group a lane serves.
 template <int BK>
 __device__ __forceinline__ int dma_swizzle(int row) {
-  return BK == 32 ? ((row >> 1) & 3) : (row & 7);
+  return BK == 32 ? ((row >> 2) & 3) : ((row >> 1) & 7);
 }
 template <int BK>
 __device__ __forceinline__ int dma_chunk_offset(int row, int chunk) {
@@ -61,6 +77,7 @@ struct DmaTileLoader {
   static constexpr int NI = ROWS / RPI / NW;   // instructions per wave per tile
   static_assert(BK == 32 || BK == 64, "BK");
   static_assert(ROWS % (RPI * NW) == 0 && NI >= 1, "tile rows must split evenly over the waves");
+  static_assert(NW % 2 == 0, "the swizzle term of a lane must not depend on the row group");
 
   __amdgpu_buffer_rsrc_t rsrc;
   int xbase[XMODE == 1 ? NI : 1];
@@ -78,7 +95,7 @@ struct DmaTileLoader {
     K = K_;
     wave = wave_;
     lrow = lane / CH;
-    lc = (lane % CH) ^ dma_swizzle<BK>(lrow);
+    lc = (lane % CH) ^ dma_swizzle<BK>(wave * RPI + lrow);  // same for every j because NW is even
     cr = cs = cc = 0;
     if constexpr (XMODE == 1) {
       const int PQ = cg.P * cg.Q;
@@ -163,7 +180,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
   using XL = DmaTileLoader<BM, BK, NW, XMODE>;
   using WL = DmaTileLoader<BN, BK, NW, 0>;
   constexpr int L = XL::NI + WL::NI;  // load instructions per wave per k-tile
-  static_assert((NS - 2) * L < 64, "vmcnt range");
+  static_assert((NS - 1) * L < 64, "vmcnt range");
 
   extern __shared__ __attribute__((aligned(16))) half_t lds[];
 
@@ -208,38 +225,58 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
     xl.issue(kt, s, p.cg);
     wl.issue(kt, s + BM * BK, p.cg);
   };
-  auto compute = [&](int stage) {
+  // Fragments are double-buffered in registers: the LDS reads of step ks+1 (or of the first step of
+  // the next tile) are in flight while the MFMAs of step ks execute, so the matrix pipe keeps
+  // working across the workgroup barrier that separates two k-tiles.
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "fragment double buffering alternates two register sets per tile");
+  half8 xf[2][FM], wf[2][FN];
+  auto read_frags = [&](int stage, int ks, half8 (&x)[FM], half8 (&w)[FN]) {
     const half_t* xs = lds + stage * STAGE;
     const half_t* ws = xs + BM * BK;
+    const int chunk = ks * 2 + g;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      half8 xf[FM], wf[FN];
-      const int chunk = ks * 2 + g;
+    for (int b = 0; b < FM; ++b) x[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
 #pragma unroll
-      for (int b = 0; b < FM; ++b) xf[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
-#pragma unroll
-      for (int a = 0; a < FN; ++a) wf[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
-#pragma unroll
-      for (int a = 0; a < FN; ++a)
-#pragma unroll
-        for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(wf[a], xf[b], acc[a][b]);
-    }
+    for (int a = 0; a < FN; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
   };
 
   // ---- NS-deep pipeline: one barrier per k-tile ----------------------------------------------
+  const int n_tiles = kt_end - kt_begin;
+  if (n_tiles > 0) {
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (kt_begin + s < kt_end) issue(kt_begin + s, s);
-  int stage = 0, fill = NS - 1;  // stage being consumed / stage the next issue goes to
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
-    // loads of tiles newer than kt that may stay in flight: NS-2 tiles, fewer at the tail
-    // after the barrier tile kt has landed for every wave and everyone is done with tile kt-1
-    if (kt_end - 1 - kt >= NS - 2) barrier_after_loads<(NS - 2) * L>();
+    for (int s = 0; s < NS; ++s)
+      if (s < n_tiles) issue(kt_begin + s, s);
+    if (n_tiles >= NS) barrier_after_loads<(NS - 1) * L>();
     else barrier_after_loads<0>();
-    if (kt + NS - 1 < kt_end) issue(kt + NS - 1, fill);
-    compute(stage);
-    stage = stage + 1 == NS ? 0 : stage + 1;
-    fill = fill + 1 == NS ? 0 : fill + 1;
+    read_frags(0, 0, xf[0], wf[0]);
+    int stage = 0;
+    for (int it = 0; it < n_tiles; ++it) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 1 < KS) {
+          read_frags(stage, ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
+        } else {
+          // end of tile `it`: this wave's reads of the tile are complete (lgkmcnt 0) and tile it+1 has
+          // landed (vmcnt); after the barrier that holds for every wave, so the stage just read
+          // can be refilled with tile it+NS while the last MFMAs of tile `it` are still to issue.
+          // After the last tile this runs once more unconditionally (the fragments it reads are
+          // never used): a branch here would make the compiler wait for the new reads before
+          // the MFMAs below.
+          __builtin_amdgcn_sched_barrier(0);  // keep the MFMAs of this step below the barrier
+          if (n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS - 2) * L>();
+          else barrier_after_reads_and_loads<0>();
+          if (it + NS < n_tiles) issue(kt_begin + it + NS, stage);
+          stage = stage + 1 == NS ? 0 : stage + 1;
+          read_frags(stage, 0, xf[0], wf[0]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int a = 0; a < FN; ++a)
+#pragma unroll
+          for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(wf[ks & 1][a], xf[ks & 1][b], acc[a][b]);
+      }
+    }
   }
 
   // ---- epilogue ---------------------------------------------------------------------------------
