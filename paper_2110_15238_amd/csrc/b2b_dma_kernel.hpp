@@ -1,0 +1,219 @@
+// Back-to-back fusion on top of the multi-stage direct-to-LDS main loop (Section 3.1.1,
+// RF-resident fusion).  One workgroup owns BM rows and all N0 and N1 columns (threadblock
+// residence); waves split the tile along M only, so the accumulators of op0, after the epilogue
+// of op0 and rounding to FP16, are re-used in registers as the activation operand of op1.
+//   op0: X (GEMM rows or implicit im2col) and W0 k-tiles stream through NS LDS stages;
+//   op1: W1 (all of it, [N1][N0] K-contiguous) is fetched to LDS once, at kernel start, so the
+//        second GEMM runs entirely out of registers and LDS;
+//   epilogue: D1 tile -> FP16 -> LDS -> 16-byte coalesced row stores.
+// Unlike stream_kernel.hpp this kernel is not persistent: 2 workgroups fit on a compute unit and
+// cover each other's prologue / epilogue.  K-contiguous weights only (conv KRSC, GEMM B as [N][K]).
+#pragma once
+#include "b2b_kernel.hpp"
+#include "fprop_dma_kernel.hpp"
+
+namespace bolt {
+
+template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
+struct B2bDmaTraits {
+  static constexpr int NT = 64 * NW;
+  static constexpr int WTM = BM / NW, FM = WTM / 32;
+  static constexpr int FN0 = N0T / 32, FN1 = N1T / 32;
+  static constexpr int KB1 = N0T < 64 ? N0T : 64, NKT1 = N0T / KB1;
+  static constexpr int STAGE_HALVES = (BM + N0T) * BK;
+  static constexpr int PIPE_BYTES = (NS * STAGE_HALVES + N0T * N1T) * 2;
+  static constexpr int CTILE_BYTES = BM * N1T * 2;
+  static constexpr int LDS_BYTES = PIPE_BYTES > CTILE_BYTES ? PIPE_BYTES : CTILE_BYTES;
+  static constexpr int CPR = N1T / 8;
+  static constexpr int ROWS_PER_PASS = NT / CPR;
+  static_assert(WTM % 32 == 0 && N0T % 32 == 0 && N1T % 32 == 0, "tile shape");
+  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  // waves per SIMD the register allocation must leave room for: as many workgroups as LDS admits
+  static constexpr int WGS_PER_CU = (160 * 1024) / LDS_BYTES < 1 ? 1 : (160 * 1024) / LDS_BYTES;
+  static constexpr int MIN_WAVES = (WGS_PER_CU * NW + 3) / 4 > 2 ? 2 : (WGS_PER_CU * NW + 3) / 4;
+  static int lds_bytes(int) { return LDS_BYTES; }
+};
+
+template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
+__global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::MIN_WAVES)) void b2b_dma_kernel(
+    const B2bParams p) {
+  using T = B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>;
+  constexpr int NT = T::NT, WTM = T::WTM, FM = T::FM, FN0 = T::FN0, FN1 = T::FN1;
+  constexpr int KB1 = T::KB1, NKT1 = T::NKT1, STAGE = T::STAGE_HALVES, KS = BK / 16;
+  using XL = DmaTileLoader<BM, BK, NW, XMODE>;
+  using WL = DmaTileLoader<N0T, BK, NW, 0>;
+  constexpr int L = XL::NI + WL::NI;
+  static_assert((NS - 1) * L < 64, "vmcnt range");
+  static_assert(KS % 2 == 0, "fragment double buffering");
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  half_t* W1s = lds + NS * STAGE;  // [NKT1][N1T*KB1]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int m0 = blockIdx.x * BM;
+  const int n_tiles = (p.K0 + BK - 1) / BK;
+
+  // W1 first: these are the oldest loads, any later wait for an operand tile covers them
+  {
+    DmaTileLoader<N1T, KB1, NW, 0> w1l;
+    const int64_t bytes = ((int64_t)(p.N1 - 1) * p.ldw1 + p.N0) * 2;
+    w1l.init(p.W1, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), p.ldw1, p.N1, p.N0, p.cg, 0, 0, wave, lane);
+#pragma unroll
+    for (int kt = 0; kt < NKT1; ++kt) w1l.issue(kt, W1s + kt * N1T * KB1, p.cg);
+  }
+  XL xl;
+  WL wl;
+  if constexpr (XMODE == 0) {
+    const int64_t rem = ((int64_t)(p.M - m0 - 1) * p.ldx + p.K0) * 2;
+    xl.init(p.X + (int64_t)m0 * p.ldx, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldx, p.M - m0, p.K0, p.cg, m0, 0,
+            wave, lane);
+  } else {
+    const int64_t bytes = (int64_t)p.cg.H * p.cg.Wi * p.cg.C * 2 * (int64_t)(p.M / (p.cg.P * p.cg.Q));
+    xl.init(p.X, (unsigned)bytes, 0, p.M - m0, p.K0, p.cg, m0, 0, wave, lane);
+  }
+  {
+    const int64_t bytes = ((int64_t)(p.N0 - 1) * p.ldw0 + p.K0) * 2;
+    wl.init(p.W0, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), p.ldw0, p.N0, p.K0, p.cg, 0, 0, wave, lane);
+  }
+
+  floatx16 acc0[FN0][FM];
+#pragma unroll
+  for (int a = 0; a < FN0; ++a)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc0[a][b][r] = 0.f;
+
+  auto issue = [&](int kt, int stage) {
+    half_t* s = lds + stage * STAGE;
+    xl.issue(kt, s, p.cg);
+    wl.issue(kt, s + BM * BK, p.cg);
+  };
+  half8 xf[2][FM], wf[2][FN0];
+  auto read_frags = [&](int stage, int ks, half8 (&x)[FM], half8 (&w)[FN0]) {
+    const half_t* xs = lds + stage * STAGE;
+    const half_t* ws = xs + BM * BK;
+    const int chunk = ks * 2 + g;
+#pragma unroll
+    for (int b = 0; b < FM; ++b) x[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wave * WTM + b * 32 + l32, chunk));
+#pragma unroll
+    for (int a = 0; a < FN0; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(a * 32 + l32, chunk));
+  };
+
+  // ---- op0: NS-deep pipeline, fragments double-buffered across the k-tile barrier -------------
+  {
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      if (s < n_tiles) issue(s, s);
+    if (n_tiles >= NS) barrier_after_loads<(NS - 1) * L>();
+    else barrier_after_loads<0>();
+    read_frags(0, 0, xf[0], wf[0]);
+    int stage = 0;
+    for (int it = 0; it < n_tiles; ++it) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 1 < KS) {
+          read_frags(stage, ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
+        } else {
+          __builtin_amdgcn_sched_barrier(0);
+          if (n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS - 2) * L>();
+          else barrier_after_reads_and_loads<0>();
+          if (it + NS < n_tiles) issue(it + NS, stage);
+          stage = stage + 1 == NS ? 0 : stage + 1;
+          read_frags(stage, 0, xf[0], wf[0]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int a = 0; a < FN0; ++a)
+#pragma unroll
+          for (int b = 0; b < FM; ++b) acc0[a][b] = mfma_32x32x16(wf[ks & 1][a], xf[ks & 1][b], acc0[a][b]);
+      }
+    }
+  }
+  // after the last k-tile every load, W1 included, has landed (the loop's final wait is vmcnt 0)
+
+  // ---- epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 ----------------
+  // Step t = 2a + h of op1 reduces over D0 columns [32a + 16h, 32a + 16h + 16).  Lane group g holds
+  // columns 32a+16h+4g+{0..3} (registers 8h..8h+3) and 32a+16h+8+4g+{0..3} (registers 8h+4..8h+7).
+  half8 d0[FN0 * 2][FM];
+  b2b_make_d0<FN0, FM>(p, acc0, d0, g);
+
+  // ---- op1: all N1 columns accumulate in registers; W1 fragments carry the matching permutation
+  floatx16 acc1[FN1][FM];
+#pragma unroll
+  for (int a = 0; a < FN1; ++a)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc1[a][b][r] = 0.f;
+#pragma unroll
+  for (int t = 0; t < FN0 * 2; ++t) {
+    const int kbase = t * 16;
+    const half_t* ws = W1s + (kbase / KB1) * N1T * KB1;
+    const int chunk = (kbase % KB1) / 8;
+#pragma unroll
+    for (int a = 0; a < FN1; ++a) {
+      const int row = a * 32 + l32;
+      const half4 lo = *(const half4*)(ws + dma_chunk_offset<KB1>(row, chunk) + g * 4);
+      const half4 hi = *(const half4*)(ws + dma_chunk_offset<KB1>(row, chunk + 1) + g * 4);
+      const half8 w1 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+      for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(w1, d0[t][b], acc1[a][b]);
+    }
+  }
+
+  // ---- epilogue1: registers -> FP16 D1 tile in LDS (over the dead stages and W1) -> global -----
+  constexpr int CPR = T::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
+  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
+  barrier_after_lds_writes();  // every wave is done reading W1 and the operand stages
+  auto tile_to_lds = [&](auto slow) {
+#pragma unroll
+    for (int a = 0; a < FN1; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = a * 32 + q * 8 + g * 4;
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+          const int row = wave * WTM + b * 32 + l32;
+          *(half4*)(lds + row * N1T + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
+              epilogue_quad<decltype(slow)::value>(acc1[a][b], q, nl, ep);
+        }
+      }
+  };
+  if (p.act1 > ACT_RELU) tile_to_lds(std::true_type{});
+  else tile_to_lds(std::false_type{});
+  barrier_after_lds_writes();
+  {
+    const int chunk = tid % CPR, r0 = tid / CPR;
+    const int n = chunk * 8;
+    if (n < p.N1) {
+#pragma unroll
+      for (int i = 0; i < BM / T::ROWS_PER_PASS; ++i) {
+        const int row = r0 + i * T::ROWS_PER_PASS;
+        if (m0 + row < p.M) {
+          const half8 v = *(const half8*)(lds + row * N1T + ((chunk ^ (row & CSW)) << 3));
+          *(half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n) = v;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
+hipError_t launch_b2b_dma(const B2bParams& p, int /*grid*/, int lds_bytes, hipStream_t stream) {
+  static bool attr_set = false;
+  return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS>, attr_set, p, p.tiles_m, 64 * NW, lds_bytes,
+                           stream);
+}
+
+// mode 0 = RF-resident fusion
+#define BOLT_B2B_DMA_INSTANCE(BM, BK, NW, N0T, N1T, NS, XMODE)                                            \
+  {                                                                                                       \
+    "b2bdma_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_s" #NS, 0, BM, BK, NW, 1, N0T, N1T, XMODE, 0, 64 * NW, \
+        NS, &bolt::B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::lds_bytes,                                \
+        &bolt::launch_b2b_dma<BM, BK, NW, N0T, N1T, XMODE, NS>                                             \
+  }
+
+}  // namespace bolt

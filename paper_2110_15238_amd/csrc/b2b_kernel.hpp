@@ -18,6 +18,8 @@
 //     in the swizzled operand layout and re-read as the activation operand of op1 by a different
 //     2-D wave tiling, which lifts the "wave tile N = N" restriction.
 #pragma once
+#include <type_traits>
+
 #include "bolt_device.hpp"
 #include "tile_loaders.hpp"
 
@@ -26,10 +28,11 @@ namespace bolt {
 struct B2bParams {
   const half_t* X;
   const half_t* W0;
-  const half_t* b0;
+  const half_t* b0;  // biases are never null inside the kernels (see EpilogueArgs)
   const half_t* W1;
   const half_t* b1;
   half_t* Y;
+  int b0_on, b1_on;
   int M, N0, K0, N1;
   int ldx, ldw0, ldw1, ldy;
   float alpha0, beta0, alpha1, beta1;
@@ -72,30 +75,53 @@ __device__ __forceinline__ void b2b_preload_weights(const B2bParams& p, half_t* 
 // Epilogue of op1 for accumulators in the transposed MFMA layout, direct 8-byte stores.
 template <int FN, int FM>
 __device__ __forceinline__ void b2b_store_tile(const B2bParams& p, floatx16 (&acc)[FN][FM], int mrow, int ncol) {
+  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
+  auto store_tile = [&](auto slow) {
 #pragma unroll
-  for (int a = 0; a < FN; ++a)
+    for (int a = 0; a < FN; ++a)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int n = ncol + a * 32 + q * 8;
-      if (n < p.N1) {
-        float bv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (p.b1) {
-          const half4 hb = *(const half4*)(p.b1 + n);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) bv[e] = p.beta1 * (float)hb[e];
-        }
+      for (int q = 0; q < 4; ++q) {
+        const int n = ncol + a * 32 + q * 8;
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
           const int m = mrow + b * 32;
-          if (m < p.M) {
-            half4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (half_t)apply_act(p.alpha1 * acc[a][b][q * 4 + e] + bv[e], p.act1);
-            *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
-          }
+          const half4 o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n, ep);
+          if (n < p.N1 && m < p.M) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
         }
       }
-    }
+  };
+  if (p.act1 > ACT_RELU) store_tile(std::true_type{});
+  else store_tile(std::false_type{});
+}
+
+// Epilogue of op0 in registers (RF-resident fusion): accumulators -> FP16 B-operand fragments of
+// op1.  Step t = 2a + h of op1 reduces over D0 columns [32a + 16h, 32a + 16h + 16): lane group g
+// holds columns 32a+16h+4g+{0..3} (accumulator quad 2h) and 32a+16h+8+4g+{0..3} (quad 2h+1), and the
+// W1 fragment reads apply the same permutation of the reduction index.  Columns >= N0 become 0.
+template <int FN0, int FM>
+__device__ __forceinline__ void b2b_make_d0(const B2bParams& p, const floatx16 (&acc0)[FN0][FM], half8 (&d0)[FN0 * 2][FM],
+                                            int g) {
+  const EpilogueArgs ep{p.b0, p.b0_on, p.N0, p.alpha0, p.beta0, p.act0};
+  auto make = [&](auto slow) {
+#pragma unroll
+    for (int a = 0; a < FN0; ++a)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int c0 = a * 32 + h * 16 + g * 4;
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+          half4 lo = epilogue_quad<decltype(slow)::value>(acc0[a][b], 2 * h, c0, ep);
+          half4 hi = epilogue_quad<decltype(slow)::value>(acc0[a][b], 2 * h + 1, c0 + 8, ep);
+          const half4 z = {0, 0, 0, 0};
+          if (c0 >= p.N0) lo = z;
+          if (c0 + 8 >= p.N0) hi = z;
+          const half8 d = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          d0[a * 2 + h][b] = d;
+        }
+      }
+  };
+  if (p.act0 > ACT_RELU) make(std::true_type{});
+  else make(std::false_type{});
 }
 
 template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
@@ -168,41 +194,8 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
     }
 
     // ---- epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 ------------
-    // Step t = 2a + h of op1 reduces over D0 columns [32a + 16h, 32a + 16h + 16).  Lane group g
-    // holds columns 32a+16h+4g+{0..3} (registers 8h..8h+3) and 32a+16h+8+4g+{0..3} (8h+4..8h+7).
     half8 d0[FN0 * 2][FM];
-#pragma unroll
-    for (int a = 0; a < FN0; ++a)
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int c0 = a * 32 + h * 16 + g * 4;
-        float bv[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) bv[e] = 0.f;
-        if (p.b0) {
-          if (c0 < p.N0) {
-            const half4 hb = *(const half4*)(p.b0 + c0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) bv[e] = p.beta0 * (float)hb[e];
-          }
-          if (c0 + 8 < p.N0) {
-            const half4 hb = *(const half4*)(p.b0 + c0 + 8);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) bv[4 + e] = p.beta0 * (float)hb[e];
-          }
-        }
-#pragma unroll
-        for (int b = 0; b < FM; ++b) {
-          half8 d;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int col = c0 + (e < 4 ? e : e + 4);
-            const float v = apply_act(p.alpha0 * acc0[a][b][h * 8 + e] + bv[e], p.act0);
-            d[e] = col < p.N0 ? (half_t)v : (half_t)0.f;
-          }
-          d0[a * 2 + h][b] = d;
-        }
-      }
+    b2b_make_d0<FN0, FM>(p, acc0, d0, g);
 
     // ---- op1: W1 fragments from LDS with the matching reduction-index permutation ------------
     const int mrow = m0 + wave * WTM + l32;
@@ -310,29 +303,27 @@ __global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams
 
     // ---- epilogue0 -> FP16 D0 tile in LDS, in the operand layout of op1 ----------------------
     // (the last barrier of the loop above orders this after every read of the previous tile's D0s)
+    {
+      const EpilogueArgs ep{p.b0, p.b0_on, p.N0, p.alpha0, p.beta0, p.act0};
+      auto d0_to_lds = [&](auto slow) {
 #pragma unroll
-    for (int a = 0; a < FN0; ++a)
+        for (int a = 0; a < FN0; ++a)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int col = wn0 * WTN0 + a * 32 + q * 8 + g * 4;
-        float bv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (p.b0 && col < p.N0) {
-          const half4 hb = *(const half4*)(p.b0 + col);
+          for (int q = 0; q < 4; ++q) {
+            const int col = wn0 * WTN0 + a * 32 + q * 8 + g * 4;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) bv[e] = p.beta0 * (float)hb[e];
-        }
-#pragma unroll
-        for (int b = 0; b < FM0; ++b) {
-          half4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float v = apply_act(p.alpha0 * acc0[a][b][q * 4 + e] + bv[e], p.act0);
-            o[e] = col < p.N0 ? (half_t)v : (half_t)0.f;
+            for (int b = 0; b < FM0; ++b) {
+              half4 o = epilogue_quad<decltype(slow)::value>(acc0[a][b], q, col, ep);
+              const half4 z = {0, 0, 0, 0};
+              if (col >= p.N0) o = z;
+              const int row = wm0 * WTM0 + b * 32 + l32;
+              *(half4*)(D0s + (col / KB1) * BM * KB1 + lds_chunk_offset<KB1>(row, (col % KB1) / 8) + (col & 4)) = o;
+            }
           }
-          const int row = wm0 * WTM0 + b * 32 + l32;
-          *(half4*)(D0s + (col / KB1) * BM * KB1 + lds_chunk_offset<KB1>(row, (col % KB1) / 8) + (col & 4)) = o;
-        }
-      }
+      };
+      if (p.act0 > ACT_RELU) d0_to_lds(std::true_type{});
+      else d0_to_lds(std::false_type{});
+    }
     __syncthreads();
 
     // ---- op1: both operands from LDS -----------------------------------------------------------
@@ -369,6 +360,7 @@ struct B2bInstance {
   const char* name;
   int mode;  // 0 RF-resident, 1 LDS-resident
   int bm, bk, waves_m, waves_n, n0t, n1t, xmode, wmode, nthreads;
+  int stages;
   int (*lds_bytes)(int K0);
   hipError_t (*launch)(const B2bParams&, int grid, int lds_bytes, hipStream_t);
 };
@@ -401,14 +393,14 @@ hipError_t launch_b2b_lds(const B2bParams& p, int grid, int lds_bytes, hipStream
 
 #define BOLT_B2B_RF_INSTANCE(BM, BK, NW, N0T, N1T, XMODE, WMODE)                                         \
   {                                                                                                      \
-    "rf_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T, 0, BM, BK, NW, 1, N0T, N1T, XMODE, WMODE, 64 * NW,     \
+    "rf_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T, 0, BM, BK, NW, 1, N0T, N1T, XMODE, WMODE, 64 * NW, 2,  \
         &bolt::B2bRfTraits<BM, BK, NW, N0T, N1T, XMODE, WMODE>::lds_bytes,                                \
         &bolt::launch_b2b_rf<BM, BK, NW, N0T, N1T, XMODE, WMODE>                                          \
   }
 #define BOLT_B2B_LDS_INSTANCE(BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE)                          \
   {                                                                                                      \
     "lds_" #BM "x" #BK "_w" #WM0 "x" #WN0 "_" #WM1 "x" #WN1 "_n" #N0T "_" #N1T, 1, BM, BK, WM0, WN0, N0T, \
-        N1T, XMODE, WMODE, 64 * WM0 * WN0,                                                               \
+        N1T, XMODE, WMODE, 64 * WM0 * WN0, 2,                                                            \
         &bolt::B2bLdsTraits<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>::lds_bytes,               \
         &bolt::launch_b2b_lds<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>                         \
   }

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -82,6 +84,17 @@ __global__ __launch_bounds__(256) void copy_kernel(const floatx4* src, floatx4* 
     dst[i] = src[i];
 }
 
+// Eight zero halves: what a kernel's bias pointer addresses when the caller gave no bias.
+__device__ __attribute__((aligned(16))) half_t g_zero_bias[8];
+
+static const half_t* zero_bias() {
+  static const half_t* ptr = [] {
+    void* q = nullptr;
+    return hipGetSymbolAddress(&q, HIP_SYMBOL(g_zero_bias)) == hipSuccess ? (const half_t*)q : nullptr;
+  }();
+  return ptr;
+}
+
 // ------------------------------------------------------------------------------------------
 // instance tables
 // ------------------------------------------------------------------------------------------
@@ -92,8 +105,12 @@ struct Tables {
     register_gemm_kn_instances(gemm);
     register_gemm_nk_instances(gemm);
     register_conv_instances(conv);
+    register_conv_stream_instances(conv);
     register_b2b_gemm_instances(b2b_gemm);
+    register_b2b_gemm_stream_instances(b2b_gemm);
     register_b2b_conv_instances(b2b_conv);
+    register_b2b_conv_stream_instances(b2b_conv);
+    register_b2b_conv_dma_instances(b2b_conv);
   }
 };
 static const Tables& tables() {
@@ -190,6 +207,12 @@ struct FpropProblem {
 
 static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
   if (in.xmode != pr.xmode || in.wmode != pr.wmode) return false;
+  if (in.stream_launch) {
+    // persistent weights-resident kernel: the tile spans all of N and the whole weight matrix
+    // must fit in LDS next to the activation stages
+    if (pr.p.N > in.n0t || (in.n0t > 32 && in.n0t / 2 >= pr.p.N)) return false;
+    return in.stream_lds_bytes(pr.p.K) <= kLdsPerCU;
+  }
   if (in.lds_bytes > kLdsPerCU) return false;
   // a tile more than half empty along N is never worth timing (64 is the narrowest tile family)
   if (in.bn > 64 && in.bn / 2 >= pr.p.N) return false;
@@ -212,7 +235,8 @@ static int fprop_heuristic(const std::vector<FpropInstance>& tab, const FpropPro
     const FpropInstance& in = tab[i];
     if (!fprop_supports(in, pr)) continue;
     const double tiles = (double)ceil_div(pr.p.M, in.bm) * ceil_div(pr.p.N, in.bn);
-    const int per_cu = std::max(1, std::min(kLdsPerCU / in.lds_bytes, 2048 / (64 * in.waves_m * in.waves_n) / 2));
+    const int lds = in.stream_launch ? in.stream_lds_bytes(pr.p.K) : in.lds_bytes;
+    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n) / 2));
     const double rounds = std::ceil(tiles / (kNumCU * per_cu)) * per_cu;
     const double wtm = (double)in.bm / in.waves_m, wtn = (double)in.bn / in.waves_n;
     const double eff = 1.0 / (1.0 + 48.0 * (1.0 / wtm + 1.0 / wtn) / 2.0);
@@ -230,6 +254,25 @@ static size_t splitk_bytes(int M, int N, int split_k) {
 static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int swizzle, int split_k, void* ws,
                                 size_t ws_bytes, hipStream_t stream) {
   FpropParams& p = pr.p;
+  p.bias_on = p.bias ? 1 : 0;
+  if (!p.bias) p.bias = zero_bias();
+  if (!p.bias) return BOLT_ERR_LAUNCH;
+  if (in.stream_launch) {
+    if (split_k > 1) return BOLT_ERR_UNSUPPORTED;
+    B2bParams q;
+    std::memset(&q, 0, sizeof(q));
+    q.X = p.X; q.W0 = p.W; q.b0 = p.bias; q.b0_on = p.bias_on; q.b1 = p.bias; q.b1_on = 0; q.Y = p.Y;
+    q.M = p.M; q.N0 = p.N; q.K0 = p.K; q.N1 = 0;
+    q.ldx = p.ldx; q.ldw0 = p.ldw; q.ldy = p.ldy;
+    q.alpha0 = p.alpha; q.beta0 = p.beta; q.act0 = p.act;
+    q.cg = p.cg;
+    q.tiles_m = ceil_div(p.M, in.bm);
+    const int lds = in.stream_lds_bytes(p.K);
+    if (lds > kLdsPerCU) return BOLT_ERR_UNSUPPORTED;
+    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n)));
+    const int grid = std::min(q.tiles_m, kNumCU * per_cu);
+    return in.stream_launch(q, grid, lds, stream) == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+  }
   p.tiles_m = ceil_div(p.M, in.bm);
   p.tiles_n = ceil_div(p.N, in.bn);
   p.swizzle = swizzle < 0 ? 0 : swizzle;
@@ -248,7 +291,8 @@ static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int sw
   if (split_k > 1) {
     const int64_t quads = (int64_t)p.M * (p.N / 4);
     const int blocks = (int)std::min<int64_t>((quads + 255) / 256, kNumCU * 8);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p.partial, p.bias, p.Y, p.M, p.N,
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p.partial,
+                       p.bias_on ? p.bias : (const half_t*)nullptr, p.Y, p.M, p.N,
                        p.ldy, split_k, p.alpha, p.beta, p.act);
     if (hipGetLastError() != hipSuccess) return BOLT_ERR_LAUNCH;
   }
@@ -320,7 +364,7 @@ static void b2b_fill_config(const B2bInstance& in, int id, bolt_config* c) {
   c->kernel_id = id;
   c->tile_m = in.bm; c->tile_n = in.n1t; c->tile_k = in.bk;
   c->waves_m = in.waves_m; c->waves_n = in.waves_n;
-  c->mfma_shape = 32; c->stages = 2; c->swizzle = 0; c->split_k = 1; c->b2b_mode = in.mode;
+  c->mfma_shape = 32; c->stages = in.stages; c->swizzle = 0; c->split_k = 1; c->b2b_mode = in.mode;
 }
 
 static int b2b_heuristic(const std::vector<B2bInstance>& tab, const B2bProblem& pr) {
@@ -339,6 +383,11 @@ static int b2b_heuristic(const std::vector<B2bInstance>& tab, const B2bProblem& 
 
 static bolt_status b2b_launch(const B2bInstance& in, B2bProblem pr, hipStream_t stream) {
   B2bParams& p = pr.p;
+  p.b0_on = p.b0 ? 1 : 0;
+  p.b1_on = p.b1 ? 1 : 0;
+  if (!p.b0) p.b0 = zero_bias();
+  if (!p.b1) p.b1 = zero_bias();
+  if (!p.b0 || !p.b1) return BOLT_ERR_LAUNCH;
   p.tiles_m = ceil_div(p.M, in.bm);
   const int lds = in.lds_bytes(p.K0);
   if (lds > kLdsPerCU) return BOLT_ERR_UNSUPPORTED;
@@ -439,6 +488,12 @@ static bolt_status time_launches(F&& fn, int warm, int reps, hipStream_t stream,
   return BOLT_OK;
 }
 
+// BOLT_TUNE_LOG=1 in the environment prints every candidate's time to stderr.
+static bool tune_log_enabled() {
+  static const bool on = [] { const char* e = std::getenv("BOLT_TUNE_LOG"); return e && e[0] && e[0] != '0'; }();
+  return on;
+}
+
 template <typename RunF>
 static bolt_status tune_candidates(std::vector<Candidate>& cands, RunF&& run, hipStream_t stream, Candidate* best,
                                    int* tried) {
@@ -451,6 +506,8 @@ static bolt_status tune_candidates(std::vector<Candidate>& cands, RunF&& run, hi
     bolt_status s = time_launches([&] { return run(c); }, 2, 5, stream, e0, e1, &c.ms);
     if (s == BOLT_ERR_LAUNCH) { status = s; break; }
     if (s != BOLT_OK) { c.ms = -1.f; continue; }
+    if (tune_log_enabled())
+      std::fprintf(stderr, "[bolt_tune] pass1 id %d swizzle %d split_k %d: %.4f ms\n", c.id, c.swizzle, c.split_k, c.ms);
     ++n_ok;
   }
   if (status == BOLT_OK && n_ok == 0) status = BOLT_ERR_UNSUPPORTED;
@@ -483,6 +540,10 @@ static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>&
     const int tiles_m = ceil_div(pr.p.M, in.bm), tiles_n = ceil_div(pr.p.N, in.bn);
     const int64_t tiles = (int64_t)tiles_m * tiles_n;
     const int nk = ceil_div(pr.p.K, in.bk);
+    if (in.stream_launch) {
+      out.push_back({i, 0, 1, 0.f});
+      continue;
+    }
     const int swz[2] = {0, 4};
     const int nswz = (tiles_n > 1 && tiles_m > 1 && tiles >= 64) ? 2 : 1;
     for (int s = 0; s < nswz; ++s) {

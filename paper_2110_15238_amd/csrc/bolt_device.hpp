@@ -61,6 +61,39 @@ __device__ __forceinline__ float apply_act(float v, int act) {
   return v;
 }
 
+// Fused epilogue arithmetic (Section 3.1, patterns (i)-(iii)) for one quad of an accumulator
+// fragment: 4 consecutive columns n .. n+3 of one output row, registers 4q .. 4q+3.
+//   out = act(alpha * acc + beta * bias[n + e]),  converted to FP16 with round-to-nearest-even.
+// The caller never passes a null bias: without a bias the pointer addresses 8 zero halves and
+// bias_on is 0, which keeps the hot path free of branches (the loads can be scheduled early).
+// Columns beyond N read bias[0..3]; their results are never stored.
+// SLOW = false handles "none" and ReLU with a select; SLOW = true calls the transcendental
+// activations.  The choice between the two is ONE wave-uniform branch around a whole tile.
+struct EpilogueArgs {
+  const half_t* bias;
+  int bias_on, N;
+  float alpha, beta;
+  int act;
+};
+
+template <bool SLOW>
+__device__ __forceinline__ half4 epilogue_quad(const floatx16& acc, int q, int n, const EpilogueArgs& ep) {
+  const half4 hb = *(const half4*)(ep.bias + (n < ep.N ? n : 0) * ep.bias_on);
+  half4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    float v = ep.alpha * acc[q * 4 + e] + ep.beta * (float)hb[e];
+    if constexpr (SLOW) {
+      v = apply_act_slow(v, ep.act);
+    } else {
+      const float r = v > 0.f ? v : 0.f;
+      v = ep.act == ACT_RELU ? r : v;
+    }
+    o[e] = (half_t)v;
+  }
+  return o;
+}
+
 // Workgroup id -> output tile.  mode 0: n-tile fastest.  mode g > 0: ids are first regrouped so
 // that the ids one XCD receives (hardware deals consecutive ids round-robin over 8 XCDs, each with
 // a private L2) are consecutive, then walked in bands of g m-tiles x all n-tiles.

@@ -168,7 +168,7 @@ struct FpropDmaTraits {
   static constexpr int CPR = BN / 8;            // 16-byte chunks per C-tile row
   static constexpr int ROWS_PER_PASS = NT / CPR;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
-  static_assert(NS >= 2 && NS <= 4, "stages");
+  static_assert(NS >= 2 && NS <= 8, "stages");
   static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
 };
 
@@ -301,27 +301,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
 
   // registers -> FP16 C tile in LDS ([BM][BN], 16-byte chunks XOR-swizzled by row)
   constexpr int CPR = T::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
+  const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act};
   barrier_after_lds_writes();  // every wave has finished reading the operand stages
+  auto tile_to_lds = [&](auto slow) {
 #pragma unroll
-  for (int a = 0; a < FN; ++a)
+    for (int a = 0; a < FN; ++a)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int nl = wn * WTN + a * 32 + q * 8 + g * 4;  // column inside the tile
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (p.bias && n0 + nl < p.N) {
-        const half4 hb = *(const half4*)(p.bias + n0 + nl);
+      for (int q = 0; q < 4; ++q) {
+        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;  // column inside the tile
 #pragma unroll
-        for (int e = 0; e < 4; ++e) bv[e] = p.beta * (float)hb[e];
+        for (int b = 0; b < FM; ++b) {
+          const int row = wm * WTM + b * 32 + l32;
+          *(half4*)(lds + row * BN + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
+              epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
+        }
       }
-#pragma unroll
-      for (int b = 0; b < FM; ++b) {
-        half4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (half_t)apply_act(p.alpha * acc[a][b][q * 4 + e] + bv[e], p.act);
-        const int row = wm * WTM + b * 32 + l32;
-        *(half4*)(lds + row * BN + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) = o;
-      }
-    }
+  };
+  if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
+  else tile_to_lds(std::false_type{});
   barrier_after_lds_writes();
   // LDS -> global: each thread moves 16 bytes, consecutive threads cover consecutive row bytes
   {
@@ -359,7 +356,7 @@ hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
   {                                                                                                     \
     "dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK, WM, WN, XMODE, 0, NS,               \
         bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS>::LDS_BYTES,                                  \
-        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>                                           \
+        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>, 0, nullptr, nullptr                      \
   }
 
 }  // namespace bolt

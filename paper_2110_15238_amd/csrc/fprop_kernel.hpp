@@ -16,6 +16,8 @@
 // operand), so a lane ends up with 4 consecutive output channels of one output row: an 8-byte
 // store, and the layout the back-to-back kernels need to reuse accumulators as operands.
 #pragma once
+#include <type_traits>
+
 #include "bolt_device.hpp"
 #include "tile_loaders.hpp"
 
@@ -24,7 +26,8 @@ namespace bolt {
 struct FpropParams {
   const half_t* X;
   const half_t* W;
-  const half_t* bias;  // [N] or nullptr
+  const half_t* bias;  // [N]; never null inside the kernels: without a bias it addresses 8 zero halves
+  int bias_on;         // 1 with a bias, 0 without (multiplies the bias index)
   half_t* Y;           // [M][ldy]
   float* partial;      // split-K partial sums [split_k][M][N], or nullptr
   int M, N, K;
@@ -139,30 +142,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_kernel(const Fpr
         }
     return;
   }
+  const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act};
+  auto store_tile = [&](auto slow) {
 #pragma unroll
-  for (int a = 0; a < FN; ++a)
+    for (int a = 0; a < FN; ++a)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int n = ncol + a * 32 + q * 8;
-      if (n < p.N) {
-        float bv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (p.bias) {
-          const half4 hb = *(const half4*)(p.bias + n);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) bv[e] = p.beta * (float)hb[e];
-        }
+      for (int q = 0; q < 4; ++q) {
+        const int n = ncol + a * 32 + q * 8;
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
           const int m = mrow + b * 32;
-          if (m < p.M) {
-            half4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (half_t)apply_act(p.alpha * acc[a][b][q * 4 + e] + bv[e], p.act);
-            *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
-          }
+          const half4 o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n, ep);
+          if (n < p.N && m < p.M) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
         }
       }
-    }
+  };
+  if (p.act > ACT_RELU) store_tile(std::true_type{});
+  else store_tile(std::false_type{});
 }
 
 struct FpropInstance {
@@ -171,6 +167,11 @@ struct FpropInstance {
   int stages;  // LDS operand buffers in flight
   int lds_bytes;
   hipError_t (*launch)(const FpropParams&, hipStream_t);
+  // persistent weights-resident instances (stream_kernel.hpp): compiled width n0t, LDS need as a
+  // function of K, and their own launcher; null for the tiled kernels
+  int n0t;
+  int (*stream_lds_bytes)(int K);
+  hipError_t (*stream_launch)(const struct B2bParams&, int grid, int lds_bytes, hipStream_t);
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>
@@ -192,7 +193,7 @@ hipError_t launch_fprop(const FpropParams& p, hipStream_t stream) {
   {                                                                                                    \
     #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, WM, WN, XMODE, WMODE, 2,                           \
         bolt::FpropTraits<BM, BN, BK, WM, WN, XMODE, WMODE>::LDS_BYTES,                                 \
-        &bolt::launch_fprop<BM, BN, BK, WM, WN, XMODE, WMODE>                                           \
+        &bolt::launch_fprop<BM, BN, BK, WM, WN, XMODE, WMODE>, 0, nullptr, nullptr                      \
   }
 
 }  // namespace bolt

@@ -9,9 +9,11 @@
 #pragma once
 #include <vector>
 
+#include "b2b_dma_kernel.hpp"
 #include "b2b_kernel.hpp"
 #include "fprop_dma_kernel.hpp"
 #include "fprop_kernel.hpp"
+#include "stream_kernel.hpp"
 
 // X(BM, BN, BK, WAVES_M, WAVES_N)
 #define BOLT_FPROP_TILE_LIST(X, XMODE, WMODE) \
@@ -38,28 +40,34 @@
 #define BOLT_FPROP_DMA_TILE_LIST(X, XMODE) \
   X(256, 256, 64, 2, 2, 2, XMODE),         \
   X(256, 256, 64, 2, 4, 2, XMODE),         \
-  X(256, 256, 32, 2, 2, 4, XMODE),         \
   X(256, 256, 32, 2, 4, 3, XMODE),         \
+  X(256, 256, 32, 2, 4, 4, XMODE),         \
   X(256, 128, 64, 2, 2, 3, XMODE),         \
   X(256, 128, 64, 4, 2, 3, XMODE),         \
-  X(256, 128, 32, 2, 2, 4, XMODE),         \
+  X(256, 128, 32, 4, 2, 6, XMODE),         \
   X(128, 256, 64, 2, 2, 3, XMODE),         \
   X(128, 256, 64, 2, 4, 3, XMODE),         \
-  X(128, 128, 64, 2, 2, 3, XMODE),         \
+  X(128, 256, 32, 2, 4, 6, XMODE),         \
   X(128, 128, 64, 2, 2, 2, XMODE),         \
+  X(128, 128, 64, 2, 2, 3, XMODE),         \
+  X(128, 128, 64, 2, 2, 4, XMODE),         \
   X(128, 128, 32, 2, 2, 4, XMODE),         \
+  X(128, 128, 32, 2, 2, 8, XMODE),         \
   X(256, 64, 64, 4, 1, 3, XMODE),          \
   X(256, 64, 64, 4, 2, 3, XMODE),          \
   X(128, 64, 64, 4, 1, 3, XMODE),          \
   X(128, 64, 64, 2, 2, 3, XMODE),          \
-  X(128, 64, 64, 2, 2, 4, XMODE),          \
+  X(128, 64, 64, 2, 2, 6, XMODE),          \
   X(64, 128, 64, 2, 2, 3, XMODE),          \
-  X(64, 128, 64, 2, 2, 4, XMODE),          \
+  X(64, 128, 64, 2, 2, 6, XMODE),          \
   X(64, 256, 64, 1, 4, 3, XMODE),          \
-  X(64, 64, 64, 2, 2, 4, XMODE),           \
+  X(64, 256, 64, 1, 4, 4, XMODE),          \
   X(64, 64, 64, 2, 2, 3, XMODE),           \
+  X(64, 64, 64, 2, 2, 5, XMODE),           \
+  X(64, 64, 64, 2, 2, 8, XMODE),           \
   X(64, 64, 64, 2, 1, 4, XMODE),           \
   X(32, 64, 64, 1, 2, 4, XMODE),           \
+  X(32, 64, 64, 1, 2, 8, XMODE),           \
   X(64, 32, 64, 2, 1, 4, XMODE)
 
 namespace bolt {
@@ -67,6 +75,10 @@ namespace bolt {
 void register_gemm_kn_instances(std::vector<FpropInstance>& v);
 void register_gemm_nk_instances(std::vector<FpropInstance>& v);
 void register_conv_instances(std::vector<FpropInstance>& v);
+void register_conv_stream_instances(std::vector<FpropInstance>& v);
 void register_b2b_gemm_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_instances(std::vector<B2bInstance>& v);
+void register_b2b_gemm_stream_instances(std::vector<B2bInstance>& v);
+void register_b2b_conv_stream_instances(std::vector<B2bInstance>& v);
+void register_b2b_conv_dma_instances(std::vector<B2bInstance>& v);
 }  // namespace bolt
