@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--reps", type=int, default=50, help="launches per shape for the per-shape table")
+    ap.add_argument("--tune-cache", default=None, help="JSON file of tuned configs: loaded if present, else written")
+    ap.add_argument("--steps-only", action="store_true",
+                    help="profiling runs: only warm-up + timed steps (no per-shape table, no probes, no oracle)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by batch with "
@@ -72,6 +75,18 @@ def main():
 
     ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")  # split-K workspace shared by all ops
 
+    cache = {}
+    if args.tune_cache and os.path.exists(args.tune_cache):
+        cache = json.load(open(args.tune_cache))
+
+    def tuned(name, op, d0, d1, tensors, workspace=None):
+        """bolt_tune, or the config stored under `name` by an earlier run (profiling runs skip the search)."""
+        if name in cache:
+            return bolt.BoltConfig.from_dict(cache[name])
+        cfg = bolt.bolt_tune(op, d0, d1, tensors, workspace).config
+        cache[name] = cfg.as_dict()
+        return cfg
+
     # ------------------------------------------------------------------ build + tune every op
     ops = []      # dicts: name, flops, bytes, run(), config
     shapes_out = []
@@ -90,8 +105,7 @@ def main():
         b = dev(t["bias"])
         d = bolt.conv_desc(shape.N, shape.H, shape.W, shape.C, shape.K, shape.R, shape.S, shape.stride, shape.pad)
         y = empty(shape.N, shape.P, shape.Q, shape.K)
-        res = bolt.bolt_tune(bolt.OP_CONV2D, d, None, [x, w, b, y], ws)
-        cfg = res.config
+        cfg = tuned(name, bolt.OP_CONV2D, d, None, [x, w, b, y], ws)
         run = lambda: bolt.bolt_conv2d_fprop_nhwc(d, x, w, b, y, cfg, ws)
         op = dict(name=name, kind="conv", flops=shape.flops, bytes=shape.bytes, run=run, count=count, cfg=cfg.as_dict(),
                   pad=pad_fn, in_step=in_step, keep=(x, w, b, y, d))
@@ -102,7 +116,7 @@ def main():
     t = wl.config1()
     A1, B1, bias1, D1 = dev(t["A"]), dev(t["B"]), dev(t["bias"]), empty(256, 256)
     g1 = bolt.gemm_desc(256, 256, 256)
-    cfg1 = bolt.bolt_tune(bolt.OP_GEMM, g1, None, [A1, B1, bias1, D1], ws).config
+    cfg1 = tuned("C1", bolt.OP_GEMM, g1, None, [A1, B1, bias1, D1], ws)
     ops.append(dict(name="C1 gemm 256x256x256", kind="gemm", flops=2 * 256 ** 3, bytes=wl.GemmShape(256, 256, 256).bytes,
                     run=lambda: bolt.bolt_gemm_epilogue(g1, A1, B1, bias1, D1, cfg1, ws), count=1, cfg=cfg1.as_dict(),
                     pad=None, in_step=True))
@@ -113,9 +127,9 @@ def main():
     A3, W0, b0, W1, b1 = (dev(t[k]) for k in ("A", "W0", "b0", "W1", "b1"))
     D0u, D3, D3u = empty(16384, 64), empty(16384, 128), empty(16384, 128)
     g30, g31 = bolt.gemm_desc(16384, 64, 256), bolt.gemm_desc(16384, 128, 64)
-    cfg3 = bolt.bolt_tune(bolt.OP_B2B_GEMM, g30, g31, [A3, W0, b0, W1, b1, D3]).config
-    cfg30 = bolt.bolt_tune(bolt.OP_GEMM, g30, None, [A3, W0, b0, D0u], ws).config
-    cfg31 = bolt.bolt_tune(bolt.OP_GEMM, g31, None, [D0u, W1, b1, D3u], ws).config
+    cfg3 = tuned("C3 fused", bolt.OP_B2B_GEMM, g30, g31, [A3, W0, b0, W1, b1, D3])
+    cfg30 = tuned("C3 op0", bolt.OP_GEMM, g30, None, [A3, W0, b0, D0u], ws)
+    cfg31 = tuned("C3 op1", bolt.OP_GEMM, g31, None, [D0u, W1, b1, D3u], ws)
     s30, s31 = wl.CONFIG3_SHAPE
     fused_bytes3 = 2 * (16384 * 256 + 256 * 64 + 64 + 64 * 128 + 128 + 16384 * 128)
     run3 = lambda: bolt.bolt_b2b_gemm(g30, g31, A3, W0, b0, W1, b1, D3, cfg3)
@@ -131,9 +145,9 @@ def main():
     c40 = bolt.conv_desc(32, 56, 56, 64, 64, 3, 3, 1, 1)
     c41 = bolt.conv_desc(32, 56, 56, 64, 256, 1, 1, 1, 0)
     y40u, y4, y4u = empty(32, 56, 56, 64), empty(32, 56, 56, 256), empty(32, 56, 56, 256)
-    cfg4 = bolt.bolt_tune(bolt.OP_B2B_CONV, c40, c41, [x4, w40, b40, w41, b41, y4]).config
-    cfg40 = bolt.bolt_tune(bolt.OP_CONV2D, c40, None, [x4, w40, b40, y40u], ws).config
-    cfg41 = bolt.bolt_tune(bolt.OP_CONV2D, c41, None, [y40u, w41, b41, y4u], ws).config
+    cfg4 = tuned("C4 fused", bolt.OP_B2B_CONV, c40, c41, [x4, w40, b40, w41, b41, y4])
+    cfg40 = tuned("C4 op0", bolt.OP_CONV2D, c40, None, [x4, w40, b40, y40u], ws)
+    cfg41 = tuned("C4 op1", bolt.OP_CONV2D, c41, None, [y40u, w41, b41, y4u], ws)
     s40, s41 = wl.CONFIG4_SHAPES
     fused_bytes4 = 2 * (x4.numel() + w40.numel() + w41.numel() + 64 + 256 + y4.numel())
     run4 = lambda: bolt.bolt_b2b_conv(c40, c41, x4, w40, b40, w41, b41, y4, cfg4)
@@ -149,9 +163,12 @@ def main():
         add_conv("C5 L%02d %dx%d %d->%d %dx%d/%d" % (i, shape.H, shape.W, shape.c_logical or shape.C, shape.K, shape.R,
                                                     shape.S, shape.stride), shape, t, count=cnt)
     torch.cuda.synchronize()
+    if args.tune_cache and not os.path.exists(args.tune_cache):
+        os.makedirs(os.path.dirname(os.path.abspath(args.tune_cache)), exist_ok=True)
+        json.dump(cache, open(args.tune_cache, "w"))
 
     # ------------------------------------------------------------------ per-shape table
-    for op in ops:
+    for op in ([] if args.steps_only else ops):
         ms = timed(op["run"], args.reps)
         tfl = op["flops"] / ms / 1e9
         gbs = op["bytes"] / ms / 1e6
@@ -168,8 +185,11 @@ def main():
             entry["pad_cost_frac"] = round(pms / (pms + ms), 4)
         op["ms"] = ms
         shapes_out.append(entry)
-    ms3, ms3u = timed(run3, args.reps), timed(run3u, args.reps)
-    ms4, ms4u = timed(run4, args.reps), timed(run4u, args.reps)
+    if args.steps_only:
+        ms3 = ms3u = ms4 = ms4u = float("nan")
+    else:
+        ms3, ms3u = timed(run3, args.reps), timed(run3u, args.reps)
+        ms4, ms4u = timed(run4, args.reps), timed(run4u, args.reps)
     b2b = dict(config3_gemm=dict(fused_ms=round(ms3, 5), unfused_ms=round(ms3u, 5), speedup=round(ms3u / ms3, 3)),
                config4_conv=dict(fused_ms=round(ms4, 5), unfused_ms=round(ms4u, 5), speedup=round(ms4u / ms4, 3)))
 
@@ -209,10 +229,10 @@ def main():
     achieved = conv_flops / conv_launches / (avg_launch_ms * 1e-3) / 1e12
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")  # written from the rocprofv3 --pmc passes
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("fprop_conv_hbm_bytes_per_launch")
+            traffic = json.load(open(tpath)).get("conv_hbm_bytes_per_launch")
         except Exception:
             traffic = None
 
@@ -235,6 +255,9 @@ def main():
         "b2b": b2b,
         "shapes": shapes_out,
     }
+    if args.steps_only:
+        print(json.dumps(out))
+        return
     try:
         out["probes"] = {"mfma_loop_tflops": round(bolt.bolt_probe_mfma_peak(20000), 1),
                          "copy_gbs_1GiB": round(bolt.bolt_probe_copy_bandwidth(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"), 5), 1)}
