@@ -106,6 +106,7 @@ struct Tables {
     register_gemm_nk_instances(gemm);
     register_conv_instances(conv);
     register_conv_stream_instances(conv);
+    register_conv_halo_instances(conv);
     register_b2b_gemm_instances(b2b_gemm);
     register_b2b_gemm_stream_instances(b2b_gemm);
     register_b2b_conv_instances(b2b_conv);
@@ -213,6 +214,7 @@ static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
     if (pr.p.N > in.n0t || (in.n0t > 32 && in.n0t / 2 >= pr.p.N)) return false;
     return in.stream_lds_bytes(pr.p.K) <= kLdsPerCU;
   }
+  if (in.dyn_supports && (!in.dyn_supports(pr.p) || in.dyn_lds_bytes(pr.p) > kLdsPerCU)) return false;
   if (in.lds_bytes > kLdsPerCU) return false;
   // a tile more than half empty along N is never worth timing (64 is the narrowest tile family)
   if (in.bn > 64 && in.bn / 2 >= pr.p.N) return false;
@@ -235,8 +237,8 @@ static int fprop_heuristic(const std::vector<FpropInstance>& tab, const FpropPro
     const FpropInstance& in = tab[i];
     if (!fprop_supports(in, pr)) continue;
     const double tiles = (double)ceil_div(pr.p.M, in.bm) * ceil_div(pr.p.N, in.bn);
-    const int lds = in.stream_launch ? in.stream_lds_bytes(pr.p.K) : in.lds_bytes;
-    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n) / 2));
+    const int lds = in.stream_launch ? in.stream_lds_bytes(pr.p.K) : (in.dyn_lds_bytes ? in.dyn_lds_bytes(pr.p) : in.lds_bytes);
+    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n * std::max(1, in.kgroups)) / 2));
     const double rounds = std::ceil(tiles / (kNumCU * per_cu)) * per_cu;
     const double wtm = (double)in.bm / in.waves_m, wtn = (double)in.bn / in.waves_n;
     const double eff = 1.0 / (1.0 + 48.0 * (1.0 / wtm + 1.0 / wtn) / 2.0);
@@ -269,13 +271,14 @@ static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int sw
     q.tiles_m = ceil_div(p.M, in.bm);
     const int lds = in.stream_lds_bytes(p.K);
     if (lds > kLdsPerCU) return BOLT_ERR_UNSUPPORTED;
-    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n)));
+    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n * std::max(1, in.kgroups))));
     const int grid = std::min(q.tiles_m, kNumCU * per_cu);
     return in.stream_launch(q, grid, lds, stream) == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
   }
   p.tiles_m = ceil_div(p.M, in.bm);
   p.tiles_n = ceil_div(p.N, in.bn);
   p.swizzle = swizzle < 0 ? 0 : swizzle;
+  if (in.dyn_supports && split_k > 1) return BOLT_ERR_UNSUPPORTED;
   const int nk = ceil_div(p.K, in.bk);
   split_k = std::max(1, std::min(std::min(split_k, kMaxSplitK), nk));
   p.ktiles_per_split = ceil_div(nk, split_k);
@@ -335,6 +338,8 @@ static bolt_status resolve_fprop(const std::vector<FpropInstance>& tab, const Fp
   if (cfg && cfg->kernel_id >= 0) {
     if (cfg->kernel_id >= (int)tab.size()) return BOLT_ERR_INVALID_ARG;
     if (!fprop_supports(tab[cfg->kernel_id], pr)) return BOLT_ERR_UNSUPPORTED;
+    // the weights-resident and halo kernels have no split-K variant
+    if (*split_k > 1 && (tab[cfg->kernel_id].stream_launch || tab[cfg->kernel_id].dyn_supports)) return BOLT_ERR_UNSUPPORTED;
     *id = cfg->kernel_id;
     return BOLT_OK;
   }
@@ -540,7 +545,7 @@ static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>&
     const int tiles_m = ceil_div(pr.p.M, in.bm), tiles_n = ceil_div(pr.p.N, in.bn);
     const int64_t tiles = (int64_t)tiles_m * tiles_n;
     const int nk = ceil_div(pr.p.K, in.bk);
-    if (in.stream_launch) {
+    if (in.stream_launch || in.dyn_supports) {  // no split-K / swizzle variants for these
       out.push_back({i, 0, 1, 0.f});
       continue;
     }

@@ -1,0 +1,285 @@
+// Implicit-GEMM convolution for stride-1 "same" filters (output extent = input extent, e.g. the
+// 3x3 / pad 1 layers of Section 4.1.1), with the activation halo re-used out of LDS.
+//
+// The generic implicit-GEMM kernel streams an im2col k-tile per filter tap: a 3x3 filter fetches
+// every input pixel nine times through the L1/L2 path.  For stride 1 and "same" padding the
+// im2col row of output pixel m at tap (r, s) is simply input pixel m + (r - pad_h) * W + (s - pad_w)
+// in the flattened (n, h, w) pixel index, so a tile of BM consecutive output pixels needs the
+// contiguous pixel range [m0 - halo, m0 + BM + halo), halo = pad_h * W + pad_w, ONCE per 64-channel
+// chunk.  That range is loaded to LDS once and every tap reads its MFMA fragments from it at a
+// shifted row; taps that fall outside the image (zero padding, image boundaries inside the flat
+// range) are masked per lane.  Weights stream as before, one [BN x 64] k-tile per (tap, chunk).
+//
+// Everything else (transposed-product MFMA layout, 64-bank swizzle, direct-to-LDS loads with
+// hardware zero fill, NS-stage weight pipeline with one barrier per item, register double-buffered
+// fragments, LDS-staged coalesced epilogue) is shared with fprop_dma_kernel.hpp.
+#pragma once
+#include "fprop_dma_kernel.hpp"
+
+namespace bolt {
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI>
+struct ConvHaloTraits {
+  static constexpr int BK = 64;
+  static constexpr int NW = WAVES_M * WAVES_N;
+  static constexpr int NT = 64 * NW;
+  static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  static constexpr int FM = WTM / 32, FN = WTN / 32;
+  static constexpr int CPR = BN / 8;
+  static constexpr int ROWS_PER_PASS = NT / CPR;
+  static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  static_assert(BM >= 16 * XI, "surplus row groups map onto distinct real ones");
+  static_assert(NW % 2 == 0, "swizzle term of a lane must not depend on the row group");
+  // X parts of the next channel chunk are issued at the first T - NS + 1 taps of a chunk, XI
+  // instructions per wave each; the halo must fit in those.
+  static bool supports(const FpropParams& p) {
+    const ConvGeom& g = p.cg;
+    const int T = g.R * g.S;
+    if (g.stride_h != 1 || g.stride_w != 1 || g.P != g.H || g.Q != g.Wi) return false;
+    if (2 * g.pad_h != g.R - 1 || 2 * g.pad_w != g.S - 1) return false;
+    if (g.C % 64 != 0 || T > 32 || T < NS) return false;
+    const int hb8 = halo_rows(g);
+    return (T - NS + 1) * XI * NW * 8 >= hb8;
+  }
+  static int halo_rows(const ConvGeom& g) {  // LDS rows (pixels) of one halo buffer, multiple of 16
+    const int hb = BM + 2 * (g.pad_h * g.Wi + g.pad_w);
+    return (hb + 15) / 16 * 16;
+  }
+  static int lds_bytes(const FpropParams& p) {
+    const int nbuf = p.cg.C > 64 ? 2 : 1;
+    const int pipe = (nbuf * halo_rows(p.cg) * 64 + NS * BN * 64) * 2;
+    const int ctile = BM * BN * 2;
+    return pipe > ctile ? pipe : ctile;
+  }
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const FpropParams p) {
+  using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI>;
+  constexpr int BK = 64, NW = T_::NW, NT = T_::NT, WTM = T_::WTM, WTN = T_::WTN, FM = T_::FM, FN = T_::FN, KS = 4;
+  using WL = DmaTileLoader<BN, BK, NW, 0>;
+  static_assert(NS >= 2 && NS <= 4, "the wait selection below handles up to two issue points in flight");
+  static_assert((NS - 1) * (WL::NI + XI) < 64, "vmcnt range");
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  const ConvGeom& cg = p.cg;
+  const int taps = cg.R * cg.S;
+  const int nchunks = cg.C / 64;
+  const int halo = cg.pad_h * cg.Wi + cg.pad_w;
+  const int hb8 = (BM + 2 * halo + 15) / 16 * 16;  // an even number of 8-row groups
+  const int nbuf = nchunks > 1 ? 2 : 1;
+  half_t* Xh = lds;                 // [nbuf][hb8 * 64]
+  half_t* Ws = Xh + nbuf * hb8 * 64;  // [NS][BN * 64]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int g = lane >> 5, l32 = lane & 31;
+  int tm, tn;
+  tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.swizzle, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int total_px = p.M;  // stride 1, same padding: output pixels == input pixels
+  const int S_items = nchunks * taps;
+  const int xparts = (hb8 / 8 + XI * NW - 1) / (XI * NW);  // issue points that carry halo loads (<= taps - NS + 1)
+
+  // ---- loaders ---------------------------------------------------------------------------------
+  WL wl;
+  {
+    const int64_t rem = ((int64_t)(p.N - n0 - 1) * p.ldw + p.K) * 2;
+    wl.init(p.W + (int64_t)n0 * p.ldw, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldw, p.N - n0, p.K, cg, n0, 0, wave,
+            lane);
+  }
+  const __amdgpu_buffer_rsrc_t xrsrc = make_rsrc(p.X, (unsigned)((int64_t)total_px * cg.C * 2));
+  const int lrow = lane >> 3;
+  const int xlc = (lane & 7) ^ dma_swizzle<BK>(wave * 8 + lrow);  // logical chunk this lane fetches
+  // X part `part` (0 .. xparts-1) of channel chunk `chunk` into halo buffer `buf`: XI instructions,
+  // each filling 8 LDS rows per wave.  Row groups past the halo (only in the last part) re-load the
+  // last group: the instruction count of a part must not depend on the wave.
+  auto issue_x_part = [&](int chunk, int part, int buf) {
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+      int group = (part * XI + i) * NW + wave;  // group of 8 LDS rows
+      if (group * 8 >= hb8) group = hb8 / 8 - 2 * (1 + i) + (wave & 1);  // same parity: same swizzle term
+      const int row = group * 8 + lrow;
+      const int px = m0 - halo + row;
+      const bool ok = px >= 0 && px < total_px;
+      const unsigned off = ok ? (unsigned)(px * cg.C + chunk * 64 + xlc * 8) * 2u : kInvalidOffset;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, BOLT_LDS_PTR(Xh + buf * hb8 * 64 + group * 512), 16, off, 0, 0,
+                                               0);
+    }
+  };
+  // Issue point at the end of item (chunk ac, tap at_): first, at the first xparts taps of a chunk,
+  // one part of the NEXT chunk's halo into the buffer the previous chunk no longer reads; then the W
+  // tile of item u into `stage`.  The order matters: an X part is older than the first W tile that is
+  // waited for at the chunk boundary, so that wait covers it (vector memory operations retire in
+  // issue order).  Returns whether X loads were issued: the waits count instructions.
+  auto issue_w = [&](int u, int stage) {
+    const int uc = u / taps, ut = u - uc * taps;
+    wl.issue(ut * nchunks + uc, Ws + stage * BN * 64, cg);
+  };
+  auto issue_point = [&](int ac, int at_, int u, int stage) -> bool {
+    const bool with_x = at_ < xparts && ac + 1 < nchunks;  // wave-uniform
+    if (with_x) issue_x_part(ac + 1, at_, (ac + 1) & 1);
+    issue_w(u, stage);
+    return with_x;
+  };
+  // Waits until at most the loads of the `NS - 2` most recent issue points are in flight; xhist bit k
+  // says whether the issue point k+1 items ago carried X loads.
+  auto wait_and_barrier = [&](unsigned xhist) {
+    if constexpr (NS == 2) {
+      barrier_after_reads_and_loads<0>();
+    } else {
+      const int j = __builtin_popcount(xhist & ((1u << (NS - 2)) - 1u));
+      if (j == 0) barrier_after_reads_and_loads<(NS - 2) * WL::NI>();
+      else if (NS == 3 || j == 1) barrier_after_reads_and_loads<(NS - 2) * WL::NI + XI>();
+      else barrier_after_reads_and_loads<(NS - 2) * WL::NI + 2 * XI>();
+    }
+  };
+
+  // ---- per-lane validity of every tap for the FM output pixels this lane feeds -------------------
+  unsigned tapmask[FM];
+#pragma unroll
+  for (int b = 0; b < FM; ++b) {
+    const int m = m0 + wm * WTM + b * 32 + l32;
+    unsigned mask = 0;
+    if (m < p.M) {
+      const int hw = cg.H * cg.Wi;
+      const int rem = m - (m / hw) * hw;
+      const int op = rem / cg.Wi, oq = rem - op * cg.Wi;
+      for (int t = 0; t < taps; ++t) {
+        const int r = t / cg.S, s = t - r * cg.S;
+        const int ih = op + r - cg.pad_h, iw = oq + s - cg.pad_w;
+        if ((unsigned)ih < (unsigned)cg.H && (unsigned)iw < (unsigned)cg.Wi) mask |= 1u << t;
+      }
+    }
+    tapmask[b] = mask;
+  }
+
+  floatx16 acc[FN][FM];
+#pragma unroll
+  for (int a = 0; a < FN; ++a)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+  half8 xf[2][FM], wf[2][FN];
+  const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  // fragments of step ks of item (chunk buffer `buf`, tap row offset `toff`, tap index `tap`)
+  auto read_frags = [&](int buf, int toff, int tap, int stage, int ks, half8 (&x)[FM], half8 (&w)[FN]) {
+    const half_t* xs = Xh + buf * hb8 * 64;
+    const half_t* ws = Ws + stage * BN * 64;
+    const int chunk = ks * 2 + g;
+#pragma unroll
+    for (int b = 0; b < FM; ++b) {
+      const int row = wm * WTM + b * 32 + l32 + toff;
+      const half8 v = *(const half8*)(xs + dma_chunk_offset<BK>(row, chunk));
+      x[b] = (tapmask[b] >> tap) & 1u ? v : zero8;
+    }
+#pragma unroll
+    for (int a = 0; a < FN; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+  };
+
+  // ---- prologue: all of chunk 0's halo, then the first NS items ---------------------------------------
+  // (S_items >= taps >= NS is a condition of support)
+  for (int part = 0; part < xparts; ++part) issue_x_part(0, part, 0);
+#pragma unroll
+  for (int s = 0; s < NS; ++s) issue_w(s, s);
+  barrier_after_loads<(NS - 1) * WL::NI>();
+  read_frags(0, 0, 0, 0, 0, xf[0], wf[0]);
+
+  int stage = 0, chunk = 0, tap = 0;
+  unsigned xhist = 0;
+  for (int s = 0; s < S_items; ++s) {
+    const int r = tap / cg.S;
+    const int toff = r * cg.Wi + (tap - r * cg.S);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) {
+        read_frags(chunk & 1, toff, tap, stage, ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
+      } else {
+        // end of item s: item s+1's W tile (and, being older, every X part it may need) has landed
+        __builtin_amdgcn_sched_barrier(0);
+        if (S_items - 2 - s >= NS - 2) wait_and_barrier(xhist);
+        else barrier_after_reads_and_loads<0>();
+        bool with_x = false;
+        if (s + NS < S_items) with_x = issue_point(chunk, tap, s + NS, stage);
+        xhist = (xhist << 1) | (with_x ? 1u : 0u);
+        stage = stage + 1 == NS ? 0 : stage + 1;
+        if (++tap == taps) {
+          tap = 0;
+          ++chunk;
+        }
+        const int r1 = tap / cg.S;
+        read_frags(chunk & 1, r1 * cg.Wi + (tap - r1 * cg.S), tap, stage, 0, xf[0], wf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(wf[ks & 1][a], xf[ks & 1][b], acc[a][b]);
+    }
+  }
+
+  // ---- epilogue: registers -> FP16 C tile in LDS -> coalesced stores ---------------------------------
+  constexpr int CPR = T_::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
+  const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act};
+  barrier_after_lds_writes();
+  auto tile_to_lds = [&](auto slow) {
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+          const int row = wm * WTM + b * 32 + l32;
+          *(half4*)(lds + row * BN + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
+              epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
+        }
+      }
+  };
+  if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
+  else tile_to_lds(std::false_type{});
+  barrier_after_lds_writes();
+  {
+    const int chunk16 = tid % CPR, r0 = tid / CPR;
+    const int n = n0 + chunk16 * 8;
+    if (n < p.N) {
+#pragma unroll
+      for (int i = 0; i < BM / T_::ROWS_PER_PASS; ++i) {
+        const int row = r0 + i * T_::ROWS_PER_PASS;
+        if (m0 + row < p.M) {
+          const half8 v = *(const half8*)(lds + row * BN + ((chunk16 ^ (row & CSW)) << 3));
+          *(half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n) = v;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI>
+hipError_t launch_conv_halo(const FpropParams& p, hipStream_t stream) {
+  using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI>;
+  auto kern = conv_halo_kernel<BM, BN, WAVES_M, WAVES_N, NS, XI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid(p.tiles_m * p.tiles_n, 1, 1);
+  hipLaunchKernelGGL(kern, grid, dim3(T_::NT), T_::lds_bytes(p), stream, p);
+  return hipGetLastError();
+}
+
+#define BOLT_CONV_HALO_INSTANCE(BM, BN, WM, WN, NS, XI)                                                 \
+  {                                                                                                     \
+    "halo_" #BM "x" #BN "_w" #WM "x" #WN "_s" #NS "_x" #XI, BM, BN, 64, WM, WN, 1, 0, NS, 0,              \
+        &bolt::launch_conv_halo<BM, BN, WM, WN, NS, XI>, 0, nullptr, nullptr,                            \
+        &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI>::supports,                                         \
+        &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI>::lds_bytes                                         \
+  }
+
+}  // namespace bolt

@@ -19,6 +19,9 @@ namespace bolt {
 
 #define BOLT_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+#ifndef BOLT_FRAG_DEPTH
+#define BOLT_FRAG_DEPTH 4  // MFMAs a register set of fragments should feed
+#endif
 static constexpr unsigned kInvalidOffset = 0x80000000u;  // beyond any descriptor range we create
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
@@ -70,7 +73,8 @@ __device__ __forceinline__ int dma_chunk_offset(int row, int chunk) {
 
 // One operand tile of ROWS x BK halves moved by NW waves; each load instruction of a wave fills
 // 1024 contiguous LDS bytes = RPI whole tile rows.
-template <int ROWS, int BK, int NW, int XMODE>
+// KSTRIDE: how many k-tiles the conv cursor advances per issue (k-groups interleave the k-tiles).
+template <int ROWS, int BK, int NW, int XMODE, int KSTRIDE = 1>
 struct DmaTileLoader {
   static constexpr int CH = BK / 8;
   static constexpr int RPI = 64 / CH;          // tile rows per instruction
@@ -143,7 +147,7 @@ struct DmaTileLoader {
         const unsigned off = ok ? (unsigned)(xbase[j] + delta) * 2u : kInvalidOffset;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, BOLT_LDS_PTR(dst + rb * BK), 16, off, 0, 0, 0);
       }
-      cc += BK;
+      cc += BK * KSTRIDE;
       while (cc >= cg.C) {
         cc -= cg.C;
         if (++cs == cg.S) {
@@ -155,37 +159,48 @@ struct DmaTileLoader {
   }
 };
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS>
+// KG k-groups: KG sets of WAVES_M x WAVES_N waves work on the same output tile, set g on the k-tiles
+// g, g+KG, ...; the sets' accumulators are summed through LDS before the epilogue.  This multiplies
+// the waves in flight for problems whose tile count cannot fill the chip, without a second kernel.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1>
 struct FpropDmaTraits {
-  static constexpr int NW = WAVES_M * WAVES_N;
+  static constexpr int WPG = WAVES_M * WAVES_N;  // waves per k-group
+  static constexpr int NW = WPG * KG;
   static constexpr int NT = 64 * NW;
   static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   static constexpr int FM = WTM / 32, FN = WTN / 32;
-  static constexpr int STAGE_HALVES = (BM + BN) * BK;
+  static constexpr int GROUP_HALVES = (BM + BN) * BK;      // one k-tile of both operands
+  static constexpr int STAGE_HALVES = KG * GROUP_HALVES;   // one pipeline stage
   static constexpr int PIPE_BYTES = NS * STAGE_HALVES * 2;
   static constexpr int CTILE_BYTES = BM * BN * 2;
-  static constexpr int LDS_BYTES = PIPE_BYTES > CTILE_BYTES ? PIPE_BYTES : CTILE_BYTES;
+  static constexpr int REDUCE_BYTES = (KG - 1) * BM * BN * 4;
+  static constexpr int LDS_BYTES = (PIPE_BYTES > CTILE_BYTES ? PIPE_BYTES : CTILE_BYTES) > REDUCE_BYTES
+                                       ? (PIPE_BYTES > CTILE_BYTES ? PIPE_BYTES : CTILE_BYTES)
+                                       : REDUCE_BYTES;
   static constexpr int CPR = BN / 8;            // 16-byte chunks per C-tile row
-  static constexpr int ROWS_PER_PASS = NT / CPR;
+  static constexpr int STORE_THREADS = NT / CPR <= BM ? NT : BM * CPR;  // threads that move the C tile out
+  static constexpr int ROWS_PER_PASS = STORE_THREADS / CPR;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
   static_assert(NS >= 2 && NS <= 8, "stages");
-  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  static_assert(KG >= 1 && NT <= 1024, "workgroup size");
+  static_assert(STORE_THREADS % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
 };
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const FpropParams p) {
-  using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS>;
-  constexpr int NW = T::NW, NT = T::NT, WTM = T::WTM, WTN = T::WTN, FM = T::FM, FN = T::FN;
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(const FpropParams p) {
+  using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
+  constexpr int WPG = T::WPG, WTM = T::WTM, WTN = T::WTN, FM = T::FM, FN = T::FN;
   constexpr int STAGE = T::STAGE_HALVES;
-  using XL = DmaTileLoader<BM, BK, NW, XMODE>;
-  using WL = DmaTileLoader<BN, BK, NW, 0>;
+  using XL = DmaTileLoader<BM, BK, WPG, XMODE, KG>;
+  using WL = DmaTileLoader<BN, BK, WPG, 0, KG>;
   constexpr int L = XL::NI + WL::NI;  // load instructions per wave per k-tile
   static_assert((NS - 1) * L < 64, "vmcnt range");
 
   extern __shared__ __attribute__((aligned(16))) half_t lds[];
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kg = wave_all / WPG, wave = wave_all - kg * WPG;  // k-group, wave inside the group
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
   const int g = lane >> 5, l32 = lane & 31;
   int tm, tn;
@@ -193,23 +208,27 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
   const int m0 = tm * BM, n0 = tn * BN;
   const int z = blockIdx.y;
   const int nk_total = (p.K + BK - 1) / BK;
-  const int kt_begin = z * p.ktiles_per_split;
-  const int kt_end = (kt_begin + p.ktiles_per_split) < nk_total ? (kt_begin + p.ktiles_per_split) : nk_total;
+  const int kt_first = z * p.ktiles_per_split;
+  const int kt_end = (kt_first + p.ktiles_per_split) < nk_total ? (kt_first + p.ktiles_per_split) : nk_total;
+  // This group's k-tiles are kt_begin, kt_begin + KG, ...; every group runs the same number of
+  // pipeline steps (the barriers are shared), tiles at or past kt_end load zeros.
+  const int kt_begin = kt_first + kg;
+  const int k_limit = kt_end * BK < p.K ? kt_end * BK : p.K;
 
   XL xl;
   WL wl;
   if constexpr (XMODE == 0) {
     const int64_t rem = ((int64_t)(p.M - m0 - 1) * p.ldx + p.K) * 2;
-    xl.init(p.X + (int64_t)m0 * p.ldx, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldx, p.M - m0, p.K, p.cg, m0,
-            kt_begin, wave, lane);
+    xl.init(p.X + (int64_t)m0 * p.ldx, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldx, p.M - m0, k_limit, p.cg,
+            m0, kt_begin, wave, lane);
   } else {
     const int64_t bytes = (int64_t)p.cg.H * p.cg.Wi * p.cg.C * 2 * (int64_t)(p.M / (p.cg.P * p.cg.Q));
-    xl.init(p.X, (unsigned)bytes, 0, p.M - m0, p.K, p.cg, m0, kt_begin, wave, lane);
+    xl.init(p.X, (unsigned)bytes, 0, p.M - m0, k_limit, p.cg, m0, kt_begin, wave, lane);
   }
   {
     const int64_t rem = ((int64_t)(p.N - n0 - 1) * p.ldw + p.K) * 2;
-    wl.init(p.W + (int64_t)n0 * p.ldw, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldw, p.N - n0, p.K, p.cg, n0,
-            kt_begin, wave, lane);
+    wl.init(p.W + (int64_t)n0 * p.ldw, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldw, p.N - n0, k_limit, p.cg,
+            n0, kt_begin, wave, lane);
   }
 
   floatx16 acc[FN][FM];
@@ -220,42 +239,63 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
+  half_t* const lds_group = lds + kg * T::GROUP_HALVES;  // this k-group's part of every stage
   auto issue = [&](int kt, int stage) {
-    half_t* s = lds + stage * STAGE;
+    half_t* s = lds_group + stage * STAGE;
     xl.issue(kt, s, p.cg);
     wl.issue(kt, s + BM * BK, p.cg);
   };
-  // Fragments are double-buffered in registers: the LDS reads of step ks+1 (or of the first step of
-  // the next tile) are in flight while the MFMAs of step ks execute, so the matrix pipe keeps
-  // working across the workgroup barrier that separates two k-tiles.
+  // Fragments are double-buffered in registers in groups of G k-steps: the LDS reads of the next
+  // group (or of the first group of the next tile) are in flight while the MFMAs of the current one
+  // execute, so the matrix pipe keeps working across the workgroup barrier that separates two
+  // k-tiles.  A wave tile with few accumulators issues few MFMAs per k-step, too few to cover an LDS
+  // round trip, so it prefetches deeper: G k-steps hold about BOLT_FRAG_DEPTH MFMAs.
   constexpr int KS = BK / 16;
-  static_assert(KS % 2 == 0, "fragment double buffering alternates two register sets per tile");
-  half8 xf[2][FM], wf[2][FN];
-  auto read_frags = [&](int stage, int ks, half8 (&x)[FM], half8 (&w)[FN]) {
-    const half_t* xs = lds + stage * STAGE;
+  constexpr int G = FM * FN >= BOLT_FRAG_DEPTH ? 1 : (BOLT_FRAG_DEPTH / (FM * FN) < KS ? BOLT_FRAG_DEPTH / (FM * FN) : KS);
+  constexpr int NG = KS / G;  // fragment groups per k-tile
+  static_assert(KS % G == 0 && (NG == 1 || NG % 2 == 0), "register sets alternate per group");
+  half8 xf[2][G][FM], wf[2][G][FN];
+  auto read_group = [&](int stage, int grp, half8 (&x)[G][FM], half8 (&w)[G][FN]) {
+    const half_t* xs = lds_group + stage * STAGE;
     const half_t* ws = xs + BM * BK;
-    const int chunk = ks * 2 + g;
 #pragma unroll
-    for (int b = 0; b < FM; ++b) x[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
+    for (int k = 0; k < G; ++k) {
+      const int chunk = (grp * G + k) * 2 + g;
 #pragma unroll
-    for (int a = 0; a < FN; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+      for (int b = 0; b < FM; ++b)
+        x[k][b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+        w[k][a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+    }
+  };
+  auto mfma_group = [&](const half8 (&x)[G][FM], const half8 (&w)[G][FN]) {
+#pragma unroll
+    for (int k = 0; k < G; ++k)
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(w[k][a], x[k][b], acc[a][b]);
   };
 
   // ---- NS-deep pipeline: one barrier per k-tile ----------------------------------------------
-  const int n_tiles = kt_end - kt_begin;
+  const int n_tiles = (kt_end - kt_first + KG - 1) / KG;  // pipeline steps, the same for every k-group
   if (n_tiles > 0) {
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-      if (s < n_tiles) issue(kt_begin + s, s);
+      if (s < n_tiles) issue(kt_begin + s * KG, s);
     if (n_tiles >= NS) barrier_after_loads<(NS - 1) * L>();
     else barrier_after_loads<0>();
-    read_frags(0, 0, xf[0], wf[0]);
+    read_group(0, 0, xf[0], wf[0]);
     int stage = 0;
-    for (int it = 0; it < n_tiles; ++it) {
+    // One k-tile; `par` = register set that holds its first fragment group.
+    auto tile_body = [&](int it, auto par) {
+      constexpr int P = decltype(par)::value;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if (ks + 1 < KS) {
-          read_frags(stage, ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
+      for (int j = 0; j < NG; ++j) {
+        const int cur = (P + j) & 1, nxt = cur ^ 1;
+        if (j + 1 < NG) {
+          read_group(stage, j + 1, xf[nxt], wf[nxt]);
         } else {
           // end of tile `it`: this wave's reads of the tile are complete (lgkmcnt 0) and tile it+1 has
           // landed (vmcnt); after the barrier that holds for every wave, so the stage just read
@@ -263,18 +303,52 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
           // After the last tile this runs once more unconditionally (the fragments it reads are
           // never used): a branch here would make the compiler wait for the new reads before
           // the MFMAs below.
-          __builtin_amdgcn_sched_barrier(0);  // keep the MFMAs of this step below the barrier
+          __builtin_amdgcn_sched_barrier(0);  // keep the MFMAs of this group below the barrier
           if (n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS - 2) * L>();
           else barrier_after_reads_and_loads<0>();
-          if (it + NS < n_tiles) issue(kt_begin + it + NS, stage);
+          if (it + NS < n_tiles) issue(kt_begin + (it + NS) * KG, stage);
           stage = stage + 1 == NS ? 0 : stage + 1;
-          read_frags(stage, 0, xf[0], wf[0]);
+          read_group(stage, 0, xf[nxt], wf[nxt]);
           __builtin_amdgcn_sched_barrier(0);
         }
+        mfma_group(xf[cur], wf[cur]);
+      }
+    };
+    if constexpr (NG % 2 == 0) {
+      for (int it = 0; it < n_tiles; ++it) tile_body(it, std::integral_constant<int, 0>{});
+    } else {  // one group per tile: the register sets swap roles every tile
+      int it = 0;
+      for (; it + 1 < n_tiles; it += 2) {
+        tile_body(it, std::integral_constant<int, 0>{});
+        tile_body(it + 1, std::integral_constant<int, 1>{});
+      }
+      if (it < n_tiles) tile_body(it, std::integral_constant<int, 0>{});
+    }
+  }
+
+  // ---- k-groups: sum the accumulators through LDS, group 0 carries on ------------------------------
+  if constexpr (KG > 1) {
+    float* red = reinterpret_cast<float*>(lds);  // [KG-1][WPG][FN*FM*16][64 lanes]
+    barrier_after_lds_writes();                  // every wave has finished reading the operand stages
+    if (kg > 0) {
+      float* mine = red + ((kg - 1) * WPG + wave) * (FN * FM * 16 * 64) + lane;
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mine[((a * FM + b) * 16 + r) * 64] = acc[a][b][r];
+    }
+    barrier_after_lds_writes();
+    if (kg == 0) {
+      for (int o = 0; o < KG - 1; ++o) {  // fixed order: the result does not depend on timing
+        const float* theirs = red + (o * WPG + wave) * (FN * FM * 16 * 64) + lane;
 #pragma unroll
         for (int a = 0; a < FN; ++a)
 #pragma unroll
-          for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(wf[ks & 1][a], xf[ks & 1][b], acc[a][b]);
+          for (int b = 0; b < FM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] += theirs[((a * FM + b) * 16 + r) * 64];
       }
     }
   }
@@ -283,6 +357,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
   const int mrow = m0 + wm * WTM + l32;
   const int ncol = n0 + wn * WTN + g * 4;
   if (p.split_k > 1) {
+    if (kg > 0) return;  // (no barrier follows on this path)
     float* dst = p.partial + (int64_t)z * p.M * p.N;
 #pragma unroll
     for (int a = 0; a < FN; ++a)
@@ -317,11 +392,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
         }
       }
   };
-  if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
-  else tile_to_lds(std::false_type{});
+  if (kg == 0) {
+    if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
+    else tile_to_lds(std::false_type{});
+  }
   barrier_after_lds_writes();
   // LDS -> global: each thread moves 16 bytes, consecutive threads cover consecutive row bytes
-  {
+  if (tid < T::STORE_THREADS) {
     const int chunk = tid % CPR, r0 = tid / CPR;
     const int n = n0 + chunk * 8;
     if (n < p.N) {
@@ -337,10 +414,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_dma_kernel(const
   }
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1>
 hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
-  using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS>;
-  auto kern = fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS>;
+  using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
+  auto kern = fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
@@ -356,7 +433,16 @@ hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
   {                                                                                                     \
     "dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK, WM, WN, XMODE, 0, NS,               \
         bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS>::LDS_BYTES,                                  \
-        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>, 0, nullptr, nullptr                      \
+        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>, 0, nullptr, nullptr, nullptr, nullptr    \
+  }
+
+// The same kernel with KG k-groups (64 * WM * WN * KG threads).
+#define BOLT_FPROP_DMA_KG_INSTANCE(BM, BN, BK, WM, WN, NS, XMODE, KG)                                   \
+  {                                                                                                     \
+    "dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_kg" #KG, BM, BN, BK, WM, WN, XMODE, 0, NS,     \
+        bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS, KG>::LDS_BYTES,                              \
+        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS, KG>, 0, nullptr, nullptr, nullptr,        \
+        nullptr, KG                                                                                     \
   }
 
 }  // namespace bolt

@@ -172,6 +172,10 @@ struct FpropInstance {
   int n0t;
   int (*stream_lds_bytes)(int K);
   hipError_t (*stream_launch)(const struct B2bParams&, int grid, int lds_bytes, hipStream_t);
+  // instances whose legality / LDS need depends on the problem (conv_halo_kernel.hpp); null otherwise
+  bool (*dyn_supports)(const FpropParams&);
+  int (*dyn_lds_bytes)(const FpropParams&);
+  int kgroups;  // k-groups of waves per workgroup (0 or 1: none); threads = 64 * waves_m * waves_n * kgroups
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>
@@ -193,7 +197,7 @@ hipError_t launch_fprop(const FpropParams& p, hipStream_t stream) {
   {                                                                                                    \
     #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, WM, WN, XMODE, WMODE, 2,                           \
         bolt::FpropTraits<BM, BN, BK, WM, WN, XMODE, WMODE>::LDS_BYTES,                                 \
-        &bolt::launch_fprop<BM, BN, BK, WM, WN, XMODE, WMODE>, 0, nullptr, nullptr                      \
+        &bolt::launch_fprop<BM, BN, BK, WM, WN, XMODE, WMODE>, 0, nullptr, nullptr, nullptr, nullptr    \
   }
 
 }  // namespace bolt

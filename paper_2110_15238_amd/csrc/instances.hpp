@@ -11,6 +11,7 @@
 
 #include "b2b_dma_kernel.hpp"
 #include "b2b_kernel.hpp"
+#include "conv_halo_kernel.hpp"
 #include "fprop_dma_kernel.hpp"
 #include "fprop_kernel.hpp"
 #include "stream_kernel.hpp"
@@ -70,12 +71,24 @@
   X(32, 64, 64, 1, 2, 8, XMODE),           \
   X(64, 32, 64, 2, 1, 4, XMODE)
 
+// Tiles with k-groups: tile M, N, K, waves M, N, stages, x mode, k-groups.
+#define BOLT_FPROP_DMA_KG_TILE_LIST(X, XMODE) \
+  X(64, 64, 64, 2, 2, 2, XMODE, 2),           \
+  X(64, 64, 64, 2, 2, 3, XMODE, 2),           \
+  X(64, 64, 64, 2, 2, 2, XMODE, 4),           \
+  X(64, 128, 64, 2, 2, 2, XMODE, 2),          \
+  X(128, 64, 64, 2, 2, 2, XMODE, 2),          \
+  X(128, 128, 64, 2, 2, 2, XMODE, 2),         \
+  X(32, 64, 64, 1, 2, 3, XMODE, 2),           \
+  X(32, 64, 64, 1, 2, 2, XMODE, 4)
+
 namespace bolt {
 // Each function appends its instances in a fixed order; kernel_id is the index in the op's table.
 void register_gemm_kn_instances(std::vector<FpropInstance>& v);
 void register_gemm_nk_instances(std::vector<FpropInstance>& v);
 void register_conv_instances(std::vector<FpropInstance>& v);
 void register_conv_stream_instances(std::vector<FpropInstance>& v);
+void register_conv_halo_instances(std::vector<FpropInstance>& v);
 void register_b2b_gemm_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_instances(std::vector<B2bInstance>& v);
 void register_b2b_gemm_stream_instances(std::vector<B2bInstance>& v);

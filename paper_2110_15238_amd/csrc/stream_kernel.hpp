@@ -294,7 +294,7 @@ hipError_t launch_stream(const B2bParams& p, int grid, int lds_bytes, hipStream_
   {                                                                                                           \
     "stream_" #BM "x" #BK "_w" #NW "_n" #N0T "_s" #NS, BM, N0T, BK, NW, 1, XMODE, WMODE, NS, 0, nullptr, N0T,   \
         &bolt::StreamTraits<BM, BK, NW, N0T, 0, XMODE, WMODE, NS>::lds_bytes,                                  \
-        &bolt::launch_stream<BM, BK, NW, N0T, 0, XMODE, WMODE, NS>                                             \
+        &bolt::launch_stream<BM, BK, NW, N0T, 0, XMODE, WMODE, NS>, nullptr, nullptr                           \
   }
 
 }  // namespace bolt

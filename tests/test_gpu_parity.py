@@ -167,6 +167,12 @@ CONV_SWEEP = [
     (1, 10, 9, 16, 24, 5, 3, (1, 2), (2, 0)),
     (1, 6, 6, 136, 8, 3, 3, 1, 1),
     (1, 5, 5, 8, 8, 5, 5, 1, 0),
+    # stride 1, "same" padding, C % 64 == 0: also legal for the halo re-use kernels
+    (2, 12, 12, 64, 72, 3, 3, 1, 1),
+    (1, 9, 11, 128, 40, 3, 3, 1, 1),
+    (5, 5, 4, 64, 64, 3, 3, 1, 1),
+    (2, 7, 9, 192, 136, 5, 3, 1, (2, 1)),
+    (1, 30, 30, 64, 264, 3, 3, 1, 1),
 ]
 
 
@@ -220,12 +226,17 @@ def test_conv_split_k(bolt):
     want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
     ws = torch.empty(8 * 49 * K, dtype=torch.float32, device="cuda")
     d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
+    ran = 0
     for kid in range(bolt.bolt_num_instances(bolt.OP_CONV2D)):
         if bolt.bolt_instance_supports(bolt.OP_CONV2D, kid, d):
             for sk in (2, 5, 8):
+                if bolt.bolt_check(bolt.OP_CONV2D, d, None, {"kernel_id": kid, "split_k": sk}) == 2:  # BOLT_ERR_UNSUPPORTED
+                    continue  # instance has no split-K variant (reported before any launch)
+                ran += 1
                 _say("conv split_k=%d instance %d" % (sk, kid))
                 got, _ = _run_conv(bolt, x, w, bias, stride, pad, config={"kernel_id": kid, "split_k": sk}, workspace=ws)
                 assert_close(got, want, "conv split_k=%d instance %d" % (sk, kid))
+    assert ran >= 9
 
 
 def test_config2_conv_small_batch_full_compare(bolt):
