@@ -107,6 +107,7 @@ struct Tables {
     register_conv_instances(conv);
     register_conv_stream_instances(conv);
     register_conv_halo_instances(conv);
+    register_gemm_nk_instances(conv);  // for 1x1 / stride 1 / pad 0 filters
     register_b2b_gemm_instances(b2b_gemm);
     register_b2b_gemm_stream_instances(b2b_gemm);
     register_b2b_conv_instances(b2b_conv);
@@ -327,6 +328,12 @@ static bolt_status make_conv_problem(const bolt_conv_desc* d, FpropProblem* pr) 
   p.ldx = 0; p.ldw = cd.Kg; p.ldy = d->K;
   p.alpha = d->alpha; p.beta = d->beta; p.act = d->act;
   p.cg = make_geom(d, cd);
+  // A 1x1 filter with unit stride and no padding is a plain GEMM over the [N*H*W][C] pixel matrix:
+  // the GEMM instances (cheaper addressing than the implicit-GEMM gather) serve it.
+  if (d->R == 1 && d->S == 1 && d->stride_h == 1 && d->stride_w == 1 && d->pad_h == 0 && d->pad_w == 0) {
+    pr->xmode = 0;
+    p.ldx = d->C;
+  }
   return BOLT_OK;
 }
 
@@ -549,8 +556,8 @@ static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>&
       out.push_back({i, 0, 1, 0.f});
       continue;
     }
-    const int swz[2] = {0, 4};
-    const int nswz = (tiles_n > 1 && tiles_m > 1 && tiles >= 64) ? 2 : 1;
+    const int swz[3] = {0, 1, 4};
+    const int nswz = (tiles_n > 1 && tiles_m > 1 && tiles >= 64) ? 3 : 1;
     for (int s = 0; s < nswz; ++s) {
       out.push_back({i, swz[s], 1, 0.f});
     }
