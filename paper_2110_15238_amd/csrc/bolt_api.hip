@@ -217,6 +217,8 @@ static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
   }
   if (in.dyn_supports && (!in.dyn_supports(pr.p) || in.dyn_lds_bytes(pr.p) > kLdsPerCU)) return false;
   if (in.lds_bytes > kLdsPerCU) return false;
+  // single-stage instances hold exactly one k-tile per k-group
+  if (in.stages == 1 && ceil_div(pr.p.K, in.bk) > std::max(1, in.kgroups)) return false;
   // a tile more than half empty along N is never worth timing (64 is the narrowest tile family)
   if (in.bn > 64 && in.bn / 2 >= pr.p.N) return false;
   return true;
@@ -345,8 +347,10 @@ static bolt_status resolve_fprop(const std::vector<FpropInstance>& tab, const Fp
   if (cfg && cfg->kernel_id >= 0) {
     if (cfg->kernel_id >= (int)tab.size()) return BOLT_ERR_INVALID_ARG;
     if (!fprop_supports(tab[cfg->kernel_id], pr)) return BOLT_ERR_UNSUPPORTED;
-    // the weights-resident and halo kernels have no split-K variant
-    if (*split_k > 1 && (tab[cfg->kernel_id].stream_launch || tab[cfg->kernel_id].dyn_supports)) return BOLT_ERR_UNSUPPORTED;
+    // the weights-resident, halo and single-stage kernels have no split-K variant
+    if (*split_k > 1 && (tab[cfg->kernel_id].stream_launch || tab[cfg->kernel_id].dyn_supports ||
+                         tab[cfg->kernel_id].stages == 1))
+      return BOLT_ERR_UNSUPPORTED;
     *id = cfg->kernel_id;
     return BOLT_OK;
   }
@@ -562,7 +566,7 @@ static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>&
       out.push_back({i, swz[s], 1, 0.f});
     }
     // split-K only when the grid cannot fill the chip and K is deep enough to share
-    for (int sk = 2; sk <= kMaxSplitK; sk *= 2) {
+    for (int sk = 2; sk <= kMaxSplitK && in.stages != 1; sk *= 2) {
       if (tiles * (sk / 2) >= kNumCU || nk < 2 * sk) break;
       if (!have_ws || ws_bytes < splitk_bytes(pr.p.M, pr.p.N, sk)) break;
       out.push_back({i, 0, sk, 0.f});

@@ -181,7 +181,7 @@ struct FpropDmaTraits {
   static constexpr int STORE_THREADS = NT / CPR <= BM ? NT : BM * CPR;  // threads that move the C tile out
   static constexpr int ROWS_PER_PASS = STORE_THREADS / CPR;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
-  static_assert(NS >= 2 && NS <= 8, "stages");
+  static_assert(NS >= 1 && NS <= 8, "stages (NS == 1: problems of a single k-tile per k-group only)");
   static_assert(KG >= 1 && NT <= 1024, "workgroup size");
   static_assert(STORE_THREADS % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
 };
@@ -295,7 +295,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
       for (int j = 0; j < NG; ++j) {
         const int cur = (P + j) & 1, nxt = cur ^ 1;
         if (j + 1 < NG) {
+          // Fences keep the order "issue the next group's reads, then this group's MFMAs": left alone,
+          // the scheduler sinks each read to just before its first use and the MFMAs wait on LDS.
+          __builtin_amdgcn_sched_barrier(0);
           read_group(stage, j + 1, xf[nxt], wf[nxt]);
+          __builtin_amdgcn_sched_barrier(0);
         } else {
           // end of tile `it`: this wave's reads of the tile are complete (lgkmcnt 0) and tile it+1 has
           // landed (vmcnt); after the barrier that holds for every wave, so the stage just read
@@ -304,7 +308,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
           // never used): a branch here would make the compiler wait for the new reads before
           // the MFMAs below.
           __builtin_amdgcn_sched_barrier(0);  // keep the MFMAs of this group below the barrier
-          if (n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS - 2) * L>();
+          if (NS >= 2 && n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS >= 2 ? NS - 2 : 0) * L>();
           else barrier_after_reads_and_loads<0>();
           if (it + NS < n_tiles) issue(kt_begin + (it + NS) * KG, stage);
           stage = stage + 1 == NS ? 0 : stage + 1;

@@ -71,6 +71,17 @@
   X(32, 64, 64, 1, 2, 8, XMODE),           \
   X(64, 32, 64, 2, 1, 4, XMODE)
 
+// Single-stage tiles: the whole reduction is one k-tile (K <= tile K), so one operand buffer is
+// enough and several workgroups share a compute unit, which hides the load and store latencies
+// of these short-lived workgroups.
+#define BOLT_FPROP_DMA_1STAGE_TILE_LIST(X, XMODE) \
+  X(256, 128, 64, 4, 2, 1, XMODE),                \
+  X(128, 256, 64, 2, 4, 1, XMODE),                \
+  X(128, 128, 64, 2, 2, 1, XMODE),                \
+  X(128, 64, 64, 2, 2, 1, XMODE),                 \
+  X(64, 128, 64, 2, 2, 1, XMODE),                 \
+  X(64, 64, 64, 2, 2, 1, XMODE)
+
 // Tiles with k-groups: tile M, N, K, waves M, N, stages, x mode, k-groups.
 #define BOLT_FPROP_DMA_KG_TILE_LIST(X, XMODE) \
   X(64, 64, 64, 2, 2, 2, XMODE, 2),           \
