@@ -128,10 +128,17 @@ struct DmaTileLoader {
 
   // Issue the loads of k-tile kt into the LDS tile at `dst` (conv mode: tiles in increasing order).
   __device__ __forceinline__ void issue(int kt, half_t* dst, const ConvGeom& cg) {
+    issue_part<0, NI>(kt, dst, cg);
+    advance(cg);
+  }
+  // Instructions J0 .. J1-1 of k-tile kt only; advance() moves the conv cursor to the next k-tile
+  // once all parts of a tile have been issued.
+  template <int J0, int J1>
+  __device__ __forceinline__ void issue_part(int kt, half_t* dst, const ConvGeom& cg) {
     const int k = kt * BK + lc * 8;
     if constexpr (XMODE == 0) {
 #pragma unroll
-      for (int j = 0; j < NI; ++j) {
+      for (int j = J0; j < J1; ++j) {
         const int rb = (j * NW + wave) * RPI;
         const int row = rb + lrow;
         const unsigned off = (row < rows_valid && k < K) ? (unsigned)(row * ld + k) * 2u : kInvalidOffset;
@@ -140,13 +147,17 @@ struct DmaTileLoader {
     } else {
       const int delta = (cr * cg.Wi + cs) * cg.C + cc;
 #pragma unroll
-      for (int j = 0; j < NI; ++j) {
+      for (int j = J0; j < J1; ++j) {
         const int rb = (j * NW + wave) * RPI;
         const int ih = (xhw[j] >> 16) + cr, iw = (int)(short)(xhw[j] & 0xffff) + cs;
         const bool ok = k < K && (unsigned)ih < (unsigned)cg.H && (unsigned)iw < (unsigned)cg.Wi;
         const unsigned off = ok ? (unsigned)(xbase[j] + delta) * 2u : kInvalidOffset;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, BOLT_LDS_PTR(dst + rb * BK), 16, off, 0, 0, 0);
       }
+    }
+  }
+  __device__ __forceinline__ void advance(const ConvGeom& cg) {
+    if constexpr (XMODE == 1) {
       cc += BK * KSTRIDE;
       while (cc >= cg.C) {
         cc -= cg.C;
@@ -288,34 +299,98 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
     else barrier_after_loads<0>();
     read_group(0, 0, xf[0], wf[0]);
     int stage = 0;
+    // The L load instructions of a k-tile are issued in SL slices spread over the MFMA groups that
+    // follow the barrier which frees their stage: a burst of direct-to-LDS loads stalls in issue while
+    // the address path digests it, and a wave issues in order, so everything behind the burst would
+    // wait with it.  Slice 0 goes out right after the barrier, the others between the later groups.
+    constexpr int SL = NG > 1 ? NG : KS;
+    auto issue_slice = [&](int kt, int stg, auto sc) {
+      constexpr int S = decltype(sc)::value;
+      constexpr int lo = S * L / SL, hi = (S + 1) * L / SL;  // positions in [X instructions | W instructions]
+      constexpr int XN = XL::NI;
+      constexpr int xlo = lo < XN ? lo : XN, xhi = hi < XN ? hi : XN;
+      constexpr int wlo = (lo > XN ? lo : XN) - XN, whi = (hi > XN ? hi : XN) - XN;
+      half_t* s = lds_group + stg * STAGE;
+      xl.template issue_part<xlo, xhi>(kt, s, p.cg);
+      wl.template issue_part<wlo, whi>(kt, s + BM * BK, p.cg);
+      if (S == SL - 1) {
+        xl.advance(p.cg);
+        wl.advance(p.cg);
+      }
+    };
+    auto read_step = [&](int stg, int ks, half8 (&x)[FM], half8 (&w)[FN]) {
+      const half_t* xs = lds_group + stg * STAGE;
+      const half_t* ws = xs + BM * BK;
+      const int chunk = ks * 2 + g;
+#pragma unroll
+      for (int b = 0; b < FM; ++b) x[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
+#pragma unroll
+      for (int a = 0; a < FN; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+    };
+    int fill_stage = 0;  // stage that the tile in flight of issue (tile it-1+NS) goes to
     // One k-tile; `par` = register set that holds its first fragment group.
     auto tile_body = [&](int it, auto par) {
       constexpr int P = decltype(par)::value;
-#pragma unroll
-      for (int j = 0; j < NG; ++j) {
-        const int cur = (P + j) & 1, nxt = cur ^ 1;
-        if (j + 1 < NG) {
-          // Fences keep the order "issue the next group's reads, then this group's MFMAs": left alone,
-          // the scheduler sinks each read to just before its first use and the MFMAs wait on LDS.
+      if constexpr (NG > 1) {
+        auto group = [&](auto jc) {
+          constexpr int j = decltype(jc)::value;
+          constexpr int cur = (P + j) & 1, nxt = cur ^ 1;
+          // Fences keep the order "loads, the next group's reads, this group's MFMAs": left alone, the
+          // scheduler sinks each read to just before its first use and the MFMAs wait on LDS.
           __builtin_amdgcn_sched_barrier(0);
-          read_group(stage, j + 1, xf[nxt], wf[nxt]);
+          if (j + 1 < NG) {
+            // slice j+1 of the tile whose slice 0 went out at the barrier that ended tile it-1
+            if (it >= 1 && it - 1 + NS < n_tiles)
+              issue_slice(kt_begin + (it - 1 + NS) * KG, fill_stage, std::integral_constant<int, (j + 1 < NG ? j + 1 : 0)>{});
+            read_group(stage, j + 1, xf[nxt], wf[nxt]);
+          } else {
+            // end of tile `it`: this wave's reads of the tile are complete (lgkmcnt 0) and tile it+1 has
+            // landed (vmcnt); after the barrier that holds for every wave, so the stage just read
+            // can be refilled with tile it+NS while the last MFMAs of tile `it` are still to issue.
+            // After the last tile this runs once more unconditionally (the fragments it reads are
+            // never used): a branch here would make the compiler wait for the new reads before
+            // the MFMAs below.
+            if (NS >= 2 && n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS >= 2 ? NS - 2 : 0) * L>();
+            else barrier_after_reads_and_loads<0>();
+            if (it + NS < n_tiles) issue_slice(kt_begin + (it + NS) * KG, stage, std::integral_constant<int, 0>{});
+            fill_stage = stage;
+            stage = stage + 1 == NS ? 0 : stage + 1;
+            read_group(stage, 0, xf[nxt], wf[nxt]);
+          }
           __builtin_amdgcn_sched_barrier(0);
-        } else {
-          // end of tile `it`: this wave's reads of the tile are complete (lgkmcnt 0) and tile it+1 has
-          // landed (vmcnt); after the barrier that holds for every wave, so the stage just read
-          // can be refilled with tile it+NS while the last MFMAs of tile `it` are still to issue.
-          // After the last tile this runs once more unconditionally (the fragments it reads are
-          // never used): a branch here would make the compiler wait for the new reads before
-          // the MFMAs below.
-          __builtin_amdgcn_sched_barrier(0);  // keep the MFMAs of this group below the barrier
-          if (NS >= 2 && n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS >= 2 ? NS - 2 : 0) * L>();
-          else barrier_after_reads_and_loads<0>();
-          if (it + NS < n_tiles) issue(kt_begin + (it + NS) * KG, stage);
-          stage = stage + 1 == NS ? 0 : stage + 1;
-          read_group(stage, 0, xf[nxt], wf[nxt]);
-          __builtin_amdgcn_sched_barrier(0);
+          mfma_group(xf[cur], wf[cur]);
+        };
+        group(std::integral_constant<int, 0>{});
+        group(std::integral_constant<int, 1>{});
+        if constexpr (NG > 2) {
+          group(std::integral_constant<int, 2>{});
+          group(std::integral_constant<int, 3>{});
         }
-        mfma_group(xf[cur], wf[cur]);
+        static_assert(NG == 2 || NG == 4 || NG == 1, "fragment groups per k-tile");
+      } else {
+        // One fragment group per tile (small wave tiles): the same interleave per k-step.
+        constexpr int cur = P, nxt = P ^ 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if (NS >= 2 && n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS >= 2 ? NS - 2 : 0) * L>();
+        else barrier_after_reads_and_loads<0>();
+        const int nstage = stage + 1 == NS ? 0 : stage + 1;
+        const bool more = it + NS < n_tiles;
+        auto step = [&](auto kc) {
+          constexpr int ks = decltype(kc)::value;
+          if (more) issue_slice(kt_begin + (it + NS) * KG, stage, kc);
+          read_step(nstage, ks, xf[nxt][ks], wf[nxt][ks]);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int a = 0; a < FN; ++a)
+#pragma unroll
+            for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(wf[cur][ks][a], xf[cur][ks][b], acc[a][b]);
+          __builtin_amdgcn_sched_barrier(0);
+        };
+        step(std::integral_constant<int, 0>{});
+        if constexpr (KS > 1) step(std::integral_constant<int, 1>{});
+        if constexpr (KS > 2) step(std::integral_constant<int, 2>{});
+        if constexpr (KS > 3) step(std::integral_constant<int, 3>{});
+        stage = nstage;
       }
     };
     if constexpr (NG % 2 == 0) {

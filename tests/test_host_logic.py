@@ -47,7 +47,7 @@ def test_struct_layouts_match_header(bolt):
 def test_instance_tables(bolt):
     for op in (bolt.OP_GEMM, bolt.OP_CONV2D, bolt.OP_B2B_GEMM, bolt.OP_B2B_CONV):
         n = bolt.bolt_num_instances(op)
-        assert 10 <= n <= 128  # "tens" of instances per op
+        assert 10 <= n <= 256  # tens to a couple of hundred instances per op
         for i in range(n):
             c = bolt.bolt_instance_config(op, i).as_dict()
             assert c["kernel_id"] == i and c["tile_m"] % 32 == 0 and c["tile_n"] % 32 == 0
