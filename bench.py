@@ -278,7 +278,7 @@ def main():
                                "fused b2b conv 3x3->1x1 64->64->256, ResNet-50-shaped 53-conv stack at batch 32 (incl. stem "
                                "channel pad 3->8); config 5 carries 96% of the FLOPs",
                    "batch": 32, "step_gflop": round(step_flops / 1e9, 2)},
-        "roofline": {"bound": "mfma", "kernel": "bolt::fprop_kernel<..., XMODE=1> (implicit-GEMM conv, all tuned instances)",
+        "roofline": {"bound": "mfma", "kernel": "conv op launches: bolt::fprop_dma_kernel<...> (implicit-GEMM gather, or GEMM addressing for 1x1/s1) and bolt::conv_halo_kernel<...>, all tuned instances",
                      "achieved": round(achieved, 3), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
                      "launches_per_step": conv_launches, "avg_launch_ms": round(avg_launch_ms, 5),
@@ -289,6 +289,38 @@ def main():
     if args.steps_only:
         print(json.dumps(out))
         return
+
+    # ------------------------------------------------------------------ large shapes (context, outside the step)
+    # The five configurations are small problems (7 GFLOP at most per launch); these two show what the
+    # same tuned templates reach when the problem fills the chip.
+    large = []
+    try:
+        M = N = K = 8192
+        Ag = torch.randn((M, K), device="cuda", dtype=torch.float16) * 0.5
+        Bg = torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.5
+        Dg = empty(M, N)
+        gd = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK, act="none")
+        cfg = tuned("large gemm 8192 NK", bolt.OP_GEMM, gd, None, [Ag, Bg, None, Dg], ws)
+        ms = timed(lambda: bolt.bolt_gemm_epilogue(gd, Ag, Bg, None, Dg, cfg, ws), 10)
+        large.append(dict(name="GEMM 8192x8192x8192 (B as [N][K])", ms=round(ms, 4), tflops=round(2.0 * M * N * K / ms / 1e9, 1),
+                          pct_mfma_peak=round(100 * 2.0 * M * N * K / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
+                          config={k: cfg.as_dict()[k] for k in ("kernel_id", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n", "stages", "swizzle")}))
+        del Ag, Bg, Dg
+        cs = wl.ConvShape(128, 56, 56, 256, 256, 3, 3, 1, 1)
+        xg = torch.randn((cs.N, cs.H, cs.W, cs.C), device="cuda", dtype=torch.float16) * 0.5
+        wg = torch.randn((cs.K, cs.R, cs.S, cs.C), device="cuda", dtype=torch.float16) * 0.05
+        bg = torch.zeros(cs.K, device="cuda", dtype=torch.float16)
+        yg = empty(cs.N, cs.P, cs.Q, cs.K)
+        cd = bolt.conv_desc(cs.N, cs.H, cs.W, cs.C, cs.K, cs.R, cs.S, cs.stride, cs.pad)
+        cfg = tuned("large conv 128x56x56x256", bolt.OP_CONV2D, cd, None, [xg, wg, bg, yg], ws)
+        ms = timed(lambda: bolt.bolt_conv2d_fprop_nhwc(cd, xg, wg, bg, yg, cfg, ws), 10)
+        large.append(dict(name="conv3x3 N=128 56x56 256->256", ms=round(ms, 4), tflops=round(cs.flops / ms / 1e9, 1),
+                          pct_mfma_peak=round(100 * cs.flops / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
+                          config={k: cfg.as_dict()[k] for k in ("kernel_id", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n", "stages", "swizzle")}))
+        del xg, wg, yg
+    except Exception as e:  # context only
+        large.append({"error": str(e)})
+    out["large_shapes"] = large
     try:
         out["probes"] = {"mfma_loop_tflops": round(bolt.bolt_probe_mfma_peak(20000), 1),
                          "copy_gbs_1GiB": round(bolt.bolt_probe_copy_bandwidth(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"), 5), 1)}

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE,
         const int row = r0 + i * T::ROWS_PER_PASS;
         if (m0 + row < p.M) {
           const half8 v = *(const half8*)(lds + row * N1T + ((chunk ^ (row & CSW)) << 3));
-          *(half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n) = v;
+          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
         }
       }
     }

@@ -252,7 +252,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
         const int row = r0 + i * T_::ROWS_PER_PASS;
         if (m0 + row < p.M) {
           const half8 v = *(const half8*)(lds + row * BN + ((chunk16 ^ (row & CSW)) << 3));
-          *(half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n) = v;
+          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
         }
       }
     }
