@@ -48,7 +48,7 @@ struct ConvHaloTraits {
   }
   static int lds_bytes(const FpropParams& p) {
     const int nbuf = p.cg.C > 64 ? 2 : 1;
-    const int pipe = (nbuf * halo_rows(p.cg) * 64 + NS * BN * 64) * 2;
+    const int pipe = ((nbuf * halo_rows(p.cg) + 8) * 64 + NS * BN * 64) * 2;
     const int ctile = BM * BN * 2;
     return pipe > ctile ? pipe : ctile;
   }
@@ -69,8 +69,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
   const int halo = cg.pad_h * cg.Wi + cg.pad_w;
   const int hb8 = (BM + 2 * halo + 15) / 16 * 16;  // an even number of 8-row groups
   const int nbuf = nchunks > 1 ? 2 : 1;
-  half_t* Xh = lds;                 // [nbuf][hb8 * 64]
-  half_t* Ws = Xh + nbuf * hb8 * 64;  // [NS][BN * 64]
+  half_t* Xh = lds;                        // [nbuf][hb8 * 64], then one row of zeros
+  const int zero_row = nbuf * hb8;         // what a lane reads for a filter tap outside the image
+  half_t* Ws = Xh + (zero_row + 8) * 64;   // [NS][BN * 64]
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -114,14 +115,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
   // tile of item u into `stage`.  The order matters: an X part is older than the first W tile that is
   // waited for at the chunk boundary, so that wait covers it (vector memory operations retire in
   // issue order).  Returns whether X loads were issued: the waits count instructions.
-  auto issue_w = [&](int u, int stage) {
-    const int uc = u / taps, ut = u - uc * taps;
-    wl.issue(ut * nchunks + uc, Ws + stage * BN * 64, cg);
+  int w_tap = 0, w_chunk = 0;  // (tap, chunk) of the next W tile to fetch; its k-tile is tap * nchunks + chunk
+  auto issue_w = [&](int stage) {
+    wl.issue(w_tap * nchunks + w_chunk, Ws + stage * BN * 64, cg);
+    if (++w_tap == taps) {
+      w_tap = 0;
+      ++w_chunk;
+    }
   };
-  auto issue_point = [&](int ac, int at_, int u, int stage) -> bool {
+  auto issue_point = [&](int ac, int at_, int stage) -> bool {
     const bool with_x = at_ < xparts && ac + 1 < nchunks;  // wave-uniform
     if (with_x) issue_x_part(ac + 1, at_, (ac + 1) & 1);
-    issue_w(u, stage);
+    issue_w(stage);
     return with_x;
   };
   // Waits until at most the loads of the `NS - 2` most recent issue points are in flight; xhist bit k
@@ -147,14 +152,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
       const int hw = cg.H * cg.Wi;
       const int rem = m - (m / hw) * hw;
       const int op = rem / cg.Wi, oq = rem - op * cg.Wi;
-      for (int t = 0; t < taps; ++t) {
-        const int r = t / cg.S, s = t - r * cg.S;
-        const int ih = op + r - cg.pad_h, iw = oq + s - cg.pad_w;
-        if ((unsigned)ih < (unsigned)cg.H && (unsigned)iw < (unsigned)cg.Wi) mask |= 1u << t;
+      const int ih0 = op - cg.pad_h, iw0 = oq - cg.pad_w;
+      const int r_lo = ih0 < 0 ? -ih0 : 0, r_hi = cg.H - ih0 < cg.R ? cg.H - ih0 : cg.R;
+      const int s_lo = iw0 < 0 ? -iw0 : 0, s_hi = cg.Wi - iw0 < cg.S ? cg.Wi - iw0 : cg.S;
+      if (s_hi > s_lo) {
+        const unsigned rowbits = ((s_hi >= 32 ? 0u : 1u << s_hi) - 1u) & ~((1u << s_lo) - 1u);
+        for (int r = r_lo; r < r_hi; ++r) mask |= rowbits << (r * cg.S);
       }
     }
     tapmask[b] = mask;
   }
+  if (tid < 8) *(half8*)(Xh + zero_row * 64 + tid * 8) = half8{0, 0, 0, 0, 0, 0, 0, 0};
 
   floatx16 acc[FN][FM];
 #pragma unroll
@@ -164,62 +172,98 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-  half8 xf[2][FM], wf[2][FN];
-  const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-  // fragments of step ks of item (chunk buffer `buf`, tap row offset `toff`, tap index `tap`)
-  auto read_frags = [&](int buf, int toff, int tap, int stage, int ks, half8 (&x)[FM], half8 (&w)[FN]) {
-    const half_t* xs = Xh + buf * hb8 * 64;
+  // Fragments are double-buffered in registers in groups of G k-steps, as in fprop_dma_kernel.hpp.
+  constexpr int G = FM * FN >= BOLT_FRAG_DEPTH ? 1 : (BOLT_FRAG_DEPTH / (FM * FN) < KS ? BOLT_FRAG_DEPTH / (FM * FN) : KS);
+  constexpr int NG = KS / G;
+  static_assert(KS % G == 0 && (NG == 1 || NG % 2 == 0), "register sets alternate per group");
+  half8 xf[2][G][FM], wf[2][G][FN];
+  // LDS row (over both halo buffers) each of this lane's FM fragments reads for the item being read:
+  // its own pixel shifted by the tap, or the row of zeros where the tap falls outside the image.
+  int xrow[FM];
+  auto set_rows = [&](int buf, int toff, int tap) {
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+      xrow[b] = (tapmask[b] >> tap) & 1u ? buf * hb8 + wm * WTM + b * 32 + l32 + toff : zero_row;
+  };
+  auto read_group = [&](int stage, int grp, half8 (&x)[G][FM], half8 (&w)[G][FN]) {
     const half_t* ws = Ws + stage * BN * 64;
-    const int chunk = ks * 2 + g;
 #pragma unroll
-    for (int b = 0; b < FM; ++b) {
-      const int row = wm * WTM + b * 32 + l32 + toff;
-      const half8 v = *(const half8*)(xs + dma_chunk_offset<BK>(row, chunk));
-      x[b] = (tapmask[b] >> tap) & 1u ? v : zero8;
+    for (int k = 0; k < G; ++k) {
+      const int chunk = (grp * G + k) * 2 + g;
+#pragma unroll
+      for (int b = 0; b < FM; ++b) x[k][b] = *(const half8*)(Xh + dma_chunk_offset<BK>(xrow[b], chunk));
+#pragma unroll
+      for (int a = 0; a < FN; ++a) w[k][a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
     }
+  };
+  auto mfma_group = [&](const half8 (&x)[G][FM], const half8 (&w)[G][FN]) {
 #pragma unroll
-    for (int a = 0; a < FN; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+    for (int k = 0; k < G; ++k)
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(w[k][a], x[k][b], acc[a][b]);
   };
 
   // ---- prologue: all of chunk 0's halo, then the first NS items ---------------------------------------
   // (S_items >= taps >= NS is a condition of support)
   for (int part = 0; part < xparts; ++part) issue_x_part(0, part, 0);
 #pragma unroll
-  for (int s = 0; s < NS; ++s) issue_w(s, s);
-  barrier_after_loads<(NS - 1) * WL::NI>();
-  read_frags(0, 0, 0, 0, 0, xf[0], wf[0]);
+  for (int s = 0; s < NS; ++s) issue_w(s);
+  barrier_after_reads_and_loads<(NS - 1) * WL::NI>();  // lgkmcnt 0 too: the zero row's ds_write is done
+  set_rows(0, 0, 0);
+  read_group(0, 0, xf[0], wf[0]);
 
-  int stage = 0, chunk = 0, tap = 0;
+  int stage = 0;
+  int chunk = 0, tap = 0, fr = 0, fs = 0;  // item in progress: channel chunk, filter tap = fr * S + fs
   unsigned xhist = 0;
-  for (int s = 0; s < S_items; ++s) {
-    const int r = tap / cg.S;
-    const int toff = r * cg.Wi + (tap - r * cg.S);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) {
-        read_frags(chunk & 1, toff, tap, stage, ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
+  auto tile_body = [&](int s, auto par) {
+    constexpr int P = decltype(par)::value;
+    auto group = [&](auto jc) {
+      constexpr int j = decltype(jc)::value;
+      constexpr int cur = (P + j) & 1, nxt = cur ^ 1;
+      __builtin_amdgcn_sched_barrier(0);
+      if (j + 1 < NG) {
+        read_group(stage, j + 1, xf[nxt], wf[nxt]);
       } else {
         // end of item s: item s+1's W tile (and, being older, every X part it may need) has landed
-        __builtin_amdgcn_sched_barrier(0);
         if (S_items - 2 - s >= NS - 2) wait_and_barrier(xhist);
         else barrier_after_reads_and_loads<0>();
         bool with_x = false;
-        if (s + NS < S_items) with_x = issue_point(chunk, tap, s + NS, stage);
+        if (s + NS < S_items) with_x = issue_point(chunk, tap, stage);
         xhist = (xhist << 1) | (with_x ? 1u : 0u);
         stage = stage + 1 == NS ? 0 : stage + 1;
-        if (++tap == taps) {
-          tap = 0;
+        ++tap;
+        if (++fs == cg.S) {
+          fs = 0;
+          ++fr;
+        }
+        if (tap == taps) {
+          tap = fr = fs = 0;
           ++chunk;
         }
-        const int r1 = tap / cg.S;
-        read_frags(chunk & 1, r1 * cg.Wi + (tap - r1 * cg.S), tap, stage, 0, xf[0], wf[0]);
-        __builtin_amdgcn_sched_barrier(0);
+        set_rows(chunk < nchunks ? chunk & 1 : 0, fr * cg.Wi + fs, tap);  // (after the last item: never used)
+        read_group(stage, 0, xf[nxt], wf[nxt]);
       }
-#pragma unroll
-      for (int a = 0; a < FN; ++a)
-#pragma unroll
-        for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(wf[ks & 1][a], xf[ks & 1][b], acc[a][b]);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_group(xf[cur], wf[cur]);
+    };
+    group(std::integral_constant<int, 0>{});
+    if constexpr (NG > 1) group(std::integral_constant<int, 1>{});
+    if constexpr (NG > 2) {
+      group(std::integral_constant<int, 2>{});
+      group(std::integral_constant<int, 3>{});
     }
+  };
+  if constexpr (NG % 2 == 0) {
+    for (int s = 0; s < S_items; ++s) tile_body(s, std::integral_constant<int, 0>{});
+  } else {
+    int s = 0;
+    for (; s + 1 < S_items; s += 2) {
+      tile_body(s, std::integral_constant<int, 0>{});
+      tile_body(s + 1, std::integral_constant<int, 1>{});
+    }
+    if (s < S_items) tile_body(s, std::integral_constant<int, 0>{});
   }
 
   // ---- epilogue: registers -> FP16 C tile in LDS -> coalesced stores ---------------------------------
