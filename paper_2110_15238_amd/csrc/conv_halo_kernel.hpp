@@ -18,17 +18,21 @@
 
 namespace bolt {
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI>
+// KG k-groups: set g of WAVES_M x WAVES_N waves reduces over the 64-channel chunks g, g + KG, ... with
+// its own halo buffers and weight stages; the sets' accumulators are summed through LDS in a fixed
+// order before the epilogue (as in fprop_dma_kernel.hpp).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG = 1>
 struct ConvHaloTraits {
   static constexpr int BK = 64;
-  static constexpr int NW = WAVES_M * WAVES_N;
-  static constexpr int NT = 64 * NW;
+  static constexpr int NW = WAVES_M * WAVES_N;  // waves per k-group
+  static constexpr int NT = 64 * NW * KG;
   static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   static constexpr int FM = WTM / 32, FN = WTN / 32;
   static constexpr int CPR = BN / 8;
-  static constexpr int ROWS_PER_PASS = NT / CPR;
+  static constexpr int STORE_THREADS = NT / CPR <= BM ? NT : BM * CPR;
+  static constexpr int ROWS_PER_PASS = STORE_THREADS / CPR;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
-  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  static_assert(STORE_THREADS % CPR == 0 && BM % ROWS_PER_PASS == 0 && NT <= 1024, "C tile store mapping");
   static_assert(BM >= 16 * XI, "surplus row groups map onto distinct real ones");
   static_assert(NW % 2 == 0, "swizzle term of a lane must not depend on the row group");
   // X parts of the next channel chunk are issued at the first T - NS + 1 taps of a chunk, XI
@@ -38,25 +42,28 @@ struct ConvHaloTraits {
     const int T = g.R * g.S;
     if (g.stride_h != 1 || g.stride_w != 1 || g.P != g.H || g.Q != g.Wi) return false;
     if (2 * g.pad_h != g.R - 1 || 2 * g.pad_w != g.S - 1) return false;
-    if (g.C % 64 != 0 || T > 32 || T < NS) return false;
+    if (g.C % (64 * KG) != 0 || T > 32 || T < NS) return false;
     const int hb8 = halo_rows(g);
     return (T - NS + 1) * XI * NW * 8 >= hb8;
   }
-  static int halo_rows(const ConvGeom& g) {  // LDS rows (pixels) of one halo buffer, multiple of 16
+  static __host__ __device__ int halo_rows(const ConvGeom& g) {  // LDS rows (pixels) of one halo buffer, multiple of 16
     const int hb = BM + 2 * (g.pad_h * g.Wi + g.pad_w);
     return (hb + 15) / 16 * 16;
   }
+  static __host__ __device__ int group_halves(const ConvGeom& g) {  // LDS of one k-group: halo buffers, zero row, weight stages
+    const int nbuf = g.C > 64 * KG ? 2 : 1;
+    return (nbuf * halo_rows(g) + 8) * 64 + NS * BN * 64;
+  }
   static int lds_bytes(const FpropParams& p) {
-    const int nbuf = p.cg.C > 64 ? 2 : 1;
-    const int pipe = ((nbuf * halo_rows(p.cg) + 8) * 64 + NS * BN * 64) * 2;
-    const int ctile = BM * BN * 2;
-    return pipe > ctile ? pipe : ctile;
+    const int pipe = KG * group_halves(p.cg) * 2;
+    const int ctile = BM * BN * 2, reduce = (KG - 1) * BM * BN * 4;
+    return pipe > ctile ? (pipe > reduce ? pipe : reduce) : (ctile > reduce ? ctile : reduce);
   }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const FpropParams p) {
-  using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI>;
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG = 1>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(const FpropParams p) {
+  using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>;
   constexpr int BK = 64, NW = T_::NW, NT = T_::NT, WTM = T_::WTM, WTN = T_::WTN, FM = T_::FM, FN = T_::FN, KS = 4;
   using WL = DmaTileLoader<BN, BK, NW, 0>;
   static_assert(NS >= 2 && NS <= 4, "the wait selection below handles up to two issue points in flight");
@@ -65,16 +72,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
   extern __shared__ __attribute__((aligned(16))) half_t lds[];
   const ConvGeom& cg = p.cg;
   const int taps = cg.R * cg.S;
-  const int nchunks = cg.C / 64;
+  const int nchunks_all = cg.C / 64;      // 64-channel chunks of the input
+  const int nchunks = nchunks_all / KG;   // ... of which this k-group takes kg, kg + KG, ...
   const int halo = cg.pad_h * cg.Wi + cg.pad_w;
   const int hb8 = (BM + 2 * halo + 15) / 16 * 16;  // an even number of 8-row groups
   const int nbuf = nchunks > 1 ? 2 : 1;
-  half_t* Xh = lds;                        // [nbuf][hb8 * 64], then one row of zeros
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kg = wave_all / NW, wave = wave_all - kg * NW;
+  half_t* Xh = lds + kg * T_::group_halves(cg);  // [nbuf][hb8 * 64], then one row of zeros
   const int zero_row = nbuf * hb8;         // what a lane reads for a filter tap outside the image
   half_t* Ws = Xh + (zero_row + 8) * 64;   // [NS][BN * 64]
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
   const int g = lane >> 5, l32 = lane & 31;
   int tm, tn;
@@ -105,7 +114,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
       const int row = group * 8 + lrow;
       const int px = m0 - halo + row;
       const bool ok = px >= 0 && px < total_px;
-      const unsigned off = ok ? (unsigned)(px * cg.C + chunk * 64 + xlc * 8) * 2u : kInvalidOffset;
+      const unsigned off = ok ? (unsigned)(px * cg.C + (kg + chunk * KG) * 64 + xlc * 8) * 2u : kInvalidOffset;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, BOLT_LDS_PTR(Xh + buf * hb8 * 64 + group * 512), 16, off, 0, 0,
                                                0);
     }
@@ -117,7 +126,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
   // issue order).  Returns whether X loads were issued: the waits count instructions.
   int w_tap = 0, w_chunk = 0;  // (tap, chunk) of the next W tile to fetch; its k-tile is tap * nchunks + chunk
   auto issue_w = [&](int stage) {
-    wl.issue(w_tap * nchunks + w_chunk, Ws + stage * BN * 64, cg);
+    wl.issue(w_tap * nchunks_all + kg + w_chunk * KG, Ws + stage * BN * 64, cg);
     if (++w_tap == taps) {
       w_tap = 0;
       ++w_chunk;
@@ -162,7 +171,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
     }
     tapmask[b] = mask;
   }
-  if (tid < 8) *(half8*)(Xh + zero_row * 64 + tid * 8) = half8{0, 0, 0, 0, 0, 0, 0, 0};
+  if (wave == 0 && lane < 8) *(half8*)(Xh + zero_row * 64 + lane * 8) = half8{0, 0, 0, 0, 0, 0, 0, 0};
 
   floatx16 acc[FN][FM];
 #pragma unroll
@@ -266,6 +275,33 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
     if (s < S_items) tile_body(s, std::integral_constant<int, 0>{});
   }
 
+  // ---- k-groups: sum the accumulators through LDS, group 0 carries on ------------------------------
+  if constexpr (KG > 1) {
+    float* red = reinterpret_cast<float*>(lds);  // [KG-1][NW][FN*FM*16][64 lanes]
+    barrier_after_lds_writes();                  // every wave has finished reading halo and weight stages
+    if (kg > 0) {
+      float* mine = red + ((kg - 1) * NW + wave) * (FN * FM * 16 * 64) + lane;
+#pragma unroll
+      for (int a = 0; a < FN; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mine[((a * FM + b) * 16 + r) * 64] = acc[a][b][r];
+    }
+    barrier_after_lds_writes();
+    if (kg == 0) {
+      for (int o = 0; o < KG - 1; ++o) {  // fixed order: the result does not depend on timing
+        const float* theirs = red + (o * NW + wave) * (FN * FM * 16 * 64) + lane;
+#pragma unroll
+        for (int a = 0; a < FN; ++a)
+#pragma unroll
+          for (int b = 0; b < FM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] += theirs[((a * FM + b) * 16 + r) * 64];
+      }
+    }
+  }
+
   // ---- epilogue: registers -> FP16 C tile in LDS -> coalesced stores ---------------------------------
   constexpr int CPR = T_::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
   const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act};
@@ -284,10 +320,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
         }
       }
   };
-  if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
-  else tile_to_lds(std::false_type{});
+  if (kg == 0) {
+    if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
+    else tile_to_lds(std::false_type{});
+  }
   barrier_after_lds_writes();
-  {
+  if (tid < T_::STORE_THREADS) {
     const int chunk16 = tid % CPR, r0 = tid / CPR;
     const int n = n0 + chunk16 * 8;
     if (n < p.N) {
@@ -303,10 +341,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_halo_kernel(const
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG = 1>
 hipError_t launch_conv_halo(const FpropParams& p, hipStream_t stream) {
-  using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI>;
-  auto kern = conv_halo_kernel<BM, BN, WAVES_M, WAVES_N, NS, XI>;
+  using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>;
+  auto kern = conv_halo_kernel<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -324,6 +362,14 @@ hipError_t launch_conv_halo(const FpropParams& p, hipStream_t stream) {
         &bolt::launch_conv_halo<BM, BN, WM, WN, NS, XI>, 0, nullptr, nullptr,                            \
         &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI>::supports,                                         \
         &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI>::lds_bytes                                         \
+  }
+
+#define BOLT_CONV_HALO_KG_INSTANCE(BM, BN, WM, WN, NS, XI, KG)                                          \
+  {                                                                                                     \
+    "halo_" #BM "x" #BN "_w" #WM "x" #WN "_s" #NS "_x" #XI "_kg" #KG, BM, BN, 64, WM, WN, 1, 0, NS, 0,    \
+        &bolt::launch_conv_halo<BM, BN, WM, WN, NS, XI, KG>, 0, nullptr, nullptr,                        \
+        &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI, KG>::supports,                                     \
+        &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI, KG>::lds_bytes, KG                                 \
   }
 
 }  // namespace bolt

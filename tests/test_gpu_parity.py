@@ -173,6 +173,7 @@ CONV_SWEEP = [
     (5, 5, 4, 64, 64, 3, 3, 1, 1),
     (2, 7, 9, 192, 136, 5, 3, 1, (2, 1)),
     (1, 30, 30, 64, 264, 3, 3, 1, 1),
+    (2, 9, 10, 256, 72, 3, 3, 1, 1),   # four 64-channel chunks: the halo kernels' k-groups of 2 and 4
 ]
 
 
