@@ -1,0 +1,146 @@
+// Back-to-back fusion of a stride-1 "same" convolution (e.g. 3x3 / pad 1) with a 1x1 convolution
+// (Section 3.1.1, RF-resident fusion; the bottleneck pair of Section 4.1.2), on top of the halo
+// main loop of conv_halo_kernel.hpp: the activation halo of the first convolution is fetched to
+// LDS once per 64-channel chunk, its weights stream per filter tap, W1 is fetched once at kernel
+// start, and the accumulators of op0 become the activation operand of op1 in registers exactly
+// as in b2b_dma_kernel.hpp (waves split the tile along M only).
+#pragma once
+#include "b2b_kernel.hpp"
+#include "conv_halo_kernel.hpp"
+
+namespace bolt {
+
+template <int BM, int NW, int N0T, int N1T, int NS, int XI>
+struct B2bHaloTraits {
+  using Halo = ConvHaloTraits<BM, N0T, NW, 1, NS, XI, 1>;
+  static constexpr int NT = 64 * NW;
+  static constexpr int WTM = BM / NW, FM = WTM / 32;
+  static constexpr int FN0 = N0T / 32, FN1 = N1T / 32;
+  static constexpr int KB1 = N0T < 64 ? N0T : 64, NKT1 = N0T / KB1;
+  static constexpr int CPR = N1T / 8;
+  static constexpr int ROWS_PER_PASS = NT / CPR;
+  static_assert(WTM % 32 == 0 && N0T % 32 == 0 && N1T % 32 == 0, "tile shape");
+  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  static FpropParams as_fprop(const B2bParams& p) {  // the view of op0 that the halo legality rules read
+    FpropParams f{};
+    f.M = p.M; f.N = p.N0; f.K = p.K0; f.cg = p.cg;
+    return f;
+  }
+  static bool supports(const B2bParams& p) { return Halo::supports(as_fprop(p)); }
+  static int lds_bytes(const B2bParams& p) {
+    const int pipe = (Halo::group_halves(p.cg) + N0T * N1T) * 2;
+    const int ctile = BM * N1T * 2;
+    return pipe > ctile ? pipe : ctile;
+  }
+};
+
+template <int BM, int NW, int N0T, int N1T, int NS, int XI>
+__global__ __launch_bounds__(64 * NW, 2) void b2b_halo_kernel(const B2bParams p) {
+  using T = B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>;
+  constexpr int NT = T::NT, WTM = T::WTM, FM = T::FM, FN0 = T::FN0, FN1 = T::FN1;
+  constexpr int KB1 = T::KB1, NKT1 = T::NKT1;
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  half_t* W1s = lds + T::Halo::group_halves(p.cg);  // [NKT1][N1T * KB1], behind the halo buffers and W0 stages
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int m0 = blockIdx.x * BM;
+
+  // W1 first: these are the oldest loads, the main loop's first wait covers them
+  {
+    DmaTileLoader<N1T, KB1, NW, 0> w1l;
+    const int64_t bytes = ((int64_t)(p.N1 - 1) * p.ldw1 + p.N0) * 2;
+    w1l.init(p.W1, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), p.ldw1, p.N1, p.N0, p.cg, 0, 0, wave, lane);
+#pragma unroll
+    for (int kt = 0; kt < NKT1; ++kt) w1l.issue(kt, W1s + kt * N1T * KB1, p.cg);
+  }
+
+  floatx16 acc0[FN0][FM];
+  {
+    const HaloArgs h{p.X, p.W0, p.N0, p.M, p.K0, p.ldw0, p.cg, m0};
+    conv_halo_mainloop<BM, N0T, NW, 1, NS, XI, 1>(h, lds, acc0);
+  }
+
+  // ---- epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 ----------------
+  half8 d0[FN0 * 2][FM];
+  b2b_make_d0<FN0, FM>(p, acc0, d0, g);
+
+  // ---- op1: all N1 columns accumulate in registers; W1 fragments carry the matching permutation
+  floatx16 acc1[FN1][FM];
+#pragma unroll
+  for (int a = 0; a < FN1; ++a)
+#pragma unroll
+    for (int b = 0; b < FM; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc1[a][b][r] = 0.f;
+#pragma unroll
+  for (int t = 0; t < FN0 * 2; ++t) {
+    const int kbase = t * 16;
+    const half_t* ws = W1s + (kbase / KB1) * N1T * KB1;
+    const int chunk = (kbase % KB1) / 8;
+#pragma unroll
+    for (int a = 0; a < FN1; ++a) {
+      const int row = a * 32 + l32;
+      const half4 lo = *(const half4*)(ws + dma_chunk_offset<KB1>(row, chunk) + g * 4);
+      const half4 hi = *(const half4*)(ws + dma_chunk_offset<KB1>(row, chunk + 1) + g * 4);
+      const half8 w1 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+      for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(w1, d0[t][b], acc1[a][b]);
+    }
+  }
+
+  // ---- epilogue1: registers -> FP16 D1 tile in LDS (over the dead buffers and W1) -> global -----
+  constexpr int CPR = T::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
+  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
+  barrier_after_lds_writes();  // every wave is done reading W1, the halo and the weight stages
+  auto tile_to_lds = [&](auto slow) {
+#pragma unroll
+    for (int a = 0; a < FN1; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = a * 32 + q * 8 + g * 4;
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+          const int row = wave * WTM + b * 32 + l32;
+          *(half4*)(lds + row * N1T + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
+              epilogue_quad<decltype(slow)::value>(acc1[a][b], q, nl, ep);
+        }
+      }
+  };
+  if (p.act1 > ACT_RELU) tile_to_lds(std::true_type{});
+  else tile_to_lds(std::false_type{});
+  barrier_after_lds_writes();
+  {
+    const int chunk = tid % CPR, r0 = tid / CPR;
+    const int n = chunk * 8;
+    if (n < p.N1) {
+#pragma unroll
+      for (int i = 0; i < BM / T::ROWS_PER_PASS; ++i) {
+        const int row = r0 + i * T::ROWS_PER_PASS;
+        if (m0 + row < p.M) {
+          const half8 v = *(const half8*)(lds + row * N1T + ((chunk ^ (row & CSW)) << 3));
+          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int NW, int N0T, int N1T, int NS, int XI>
+hipError_t launch_b2b_halo(const B2bParams& p, int /*grid*/, int lds_bytes, hipStream_t stream) {
+  static bool attr_set = false;
+  return b2b_launch_common(b2b_halo_kernel<BM, NW, N0T, N1T, NS, XI>, attr_set, p, p.tiles_m, 64 * NW, lds_bytes, stream);
+}
+
+// mode 0 = RF-resident fusion; legality and LDS need depend on the geometry (dyn hooks)
+#define BOLT_B2B_HALO_INSTANCE(BM, NW, N0T, N1T, NS, XI)                                                  \
+  {                                                                                                       \
+    "b2bhalo_" #BM "_w" #NW "_n" #N0T "_" #N1T "_s" #NS "_x" #XI, 0, BM, 64, NW, 1, N0T, N1T, 1, 0, 64 * NW, \
+        NS, nullptr, &bolt::launch_b2b_halo<BM, NW, N0T, N1T, NS, XI>,                                     \
+        &bolt::B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::supports,                                          \
+        &bolt::B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::lds_bytes                                          \
+  }
+
+}  // namespace bolt

@@ -363,6 +363,9 @@ struct B2bInstance {
   int stages;
   int (*lds_bytes)(int K0);
   hipError_t (*launch)(const B2bParams&, int grid, int lds_bytes, hipStream_t);
+  // instances whose legality / LDS need depends on the geometry (b2b_halo_kernel.hpp); null otherwise
+  bool (*dyn_supports)(const B2bParams&);
+  int (*dyn_lds_bytes)(const B2bParams&);
 };
 
 template <typename KernT>

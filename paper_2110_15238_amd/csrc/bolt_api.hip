@@ -129,6 +129,7 @@ struct Tables {
     register_b2b_conv_instances(b2b_conv);
     register_b2b_conv_stream_instances(b2b_conv);
     register_b2b_conv_dma_instances(b2b_conv);
+    register_b2b_conv_halo_instances(b2b_conv);
   }
 };
 static const Tables& tables() {
@@ -399,6 +400,7 @@ static bool b2b_supports(const B2bInstance& in, const B2bProblem& pr) {
   if (pr.p.N0 > in.n0t || pr.p.N1 > in.n1t) return false;
   // threadblock residence with the tightest compiled bound: do not carry more than 2x padding
   if ((in.n0t > 32 && in.n0t / 2 >= pr.p.N0) || (in.n1t > 32 && in.n1t / 2 >= pr.p.N1)) return false;
+  if (in.dyn_supports) return in.dyn_supports(pr.p) && in.dyn_lds_bytes(pr.p) <= kLdsPerCU;
   if (in.lds_bytes(pr.p.K0) > kLdsPerCU) return false;
   return true;
 }
@@ -432,7 +434,7 @@ static bolt_status b2b_launch(const B2bInstance& in, B2bProblem pr, hipStream_t 
   if (!p.b1) p.b1 = zero_bias();
   if (!p.b0 || !p.b1) return BOLT_ERR_LAUNCH;
   p.tiles_m = ceil_div(p.M, in.bm);
-  const int lds = in.lds_bytes(p.K0);
+  const int lds = in.dyn_lds_bytes ? in.dyn_lds_bytes(p) : in.lds_bytes(p.K0);
   if (lds > kLdsPerCU) return BOLT_ERR_UNSUPPORTED;
   const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / in.nthreads));
   const int grid = std::min(p.tiles_m, kNumCU * per_cu);

@@ -46,13 +46,18 @@ struct ConvHaloTraits {
     const int hb8 = halo_rows(g);
     return (T - NS + 1) * XI * NW * 8 >= hb8;
   }
-  static __host__ __device__ int halo_rows(const ConvGeom& g) {  // LDS rows (pixels) of one halo buffer, multiple of 16
+  static __host__ __device__ int halo_rows(const ConvGeom& g) {  // LDS rows (pixels) of one halo buffer, multiple of 8
     const int hb = BM + 2 * (g.pad_h * g.Wi + g.pad_w);
-    return (hb + 15) / 16 * 16;
+    return (hb + 7) / 8 * 8;
+  }
+  // Rows from one halo buffer to the next: with two buffers the second starts on a 16-row boundary
+  // so that a row's swizzle term is the same in both.
+  static __host__ __device__ int buffer_stride(const ConvGeom& g) {
+    return g.C > 64 * KG ? (halo_rows(g) + 15) / 16 * 16 : halo_rows(g);
   }
   static __host__ __device__ int group_halves(const ConvGeom& g) {  // LDS of one k-group: halo buffers, zero row, weight stages
     const int nbuf = g.C > 64 * KG ? 2 : 1;
-    return (nbuf * halo_rows(g) + 8) * 64 + NS * BN * 64;
+    return (nbuf * buffer_stride(g) + 1) * 64 + NS * BN * 64;
   }
   static int lds_bytes(const FpropParams& p) {
     const int pipe = KG * group_halves(p.cg) * 2;
@@ -61,46 +66,57 @@ struct ConvHaloTraits {
   }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG = 1>
-__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(const FpropParams p) {
+// What the main loop needs to know about the problem (the single convolution and the fused pair share it).
+struct HaloArgs {
+  const half_t* X;  // NHWC input
+  const half_t* W;  // row 0 of this tile's weights, [w_rows][K] with leading dimension ldw
+  int w_rows;       // valid weight rows (output channels) from W on
+  int M, K, ldw;    // output pixels (= input pixels), R*S*C, weight leading dimension
+  ConvGeom cg;
+  int m0;           // first output pixel of the tile
+};
+
+// Prologue and main loop: on return acc holds this k-group's partial sums of the BM x BN tile and
+// every load has landed.  `lds` is the workgroup's dynamic LDS; k-group kg uses
+// [kg * group_halves, (kg + 1) * group_halves).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG>
+__device__ __forceinline__ void conv_halo_mainloop(const HaloArgs& h, half_t* lds,
+                                                   floatx16 (&acc)[BN / WAVES_N / 32][BM / WAVES_M / 32]) {
   using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>;
-  constexpr int BK = 64, NW = T_::NW, NT = T_::NT, WTM = T_::WTM, WTN = T_::WTN, FM = T_::FM, FN = T_::FN, KS = 4;
+  constexpr int BK = 64, NW = T_::NW, WTM = T_::WTM, WTN = T_::WTN, FM = T_::FM, FN = T_::FN, KS = 4;
   using WL = DmaTileLoader<BN, BK, NW, 0>;
   static_assert(NS >= 2 && NS <= 4, "the wait selection below handles up to two issue points in flight");
   static_assert((NS - 1) * (WL::NI + XI) < 64, "vmcnt range");
 
-  extern __shared__ __attribute__((aligned(16))) half_t lds[];
-  const ConvGeom& cg = p.cg;
+  const ConvGeom& cg = h.cg;
   const int taps = cg.R * cg.S;
   const int nchunks_all = cg.C / 64;      // 64-channel chunks of the input
   const int nchunks = nchunks_all / KG;   // ... of which this k-group takes kg, kg + KG, ...
   const int halo = cg.pad_h * cg.Wi + cg.pad_w;
-  const int hb8 = (BM + 2 * halo + 15) / 16 * 16;  // an even number of 8-row groups
+  const int hb8 = (BM + 2 * halo + 7) / 8 * 8;  // rows of one halo buffer
+  const int bstride = T_::buffer_stride(cg);     // rows between the two buffers
   const int nbuf = nchunks > 1 ? 2 : 1;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kg = wave_all / NW, wave = wave_all - kg * NW;
   half_t* Xh = lds + kg * T_::group_halves(cg);  // [nbuf][hb8 * 64], then one row of zeros
-  const int zero_row = nbuf * hb8;         // what a lane reads for a filter tap outside the image
-  half_t* Ws = Xh + (zero_row + 8) * 64;   // [NS][BN * 64]
+  const int zero_row = nbuf * bstride;     // what a lane reads for a filter tap outside the image
+  half_t* Ws = Xh + (zero_row + 1) * 64;   // [NS][BN * 64]
 
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
   const int g = lane >> 5, l32 = lane & 31;
-  int tm, tn;
-  tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.swizzle, tm, tn);
-  const int m0 = tm * BM, n0 = tn * BN;
-  const int total_px = p.M;  // stride 1, same padding: output pixels == input pixels
+  const int m0 = h.m0;
+  const int total_px = h.M;  // stride 1, same padding: output pixels == input pixels
   const int S_items = nchunks * taps;
   const int xparts = (hb8 / 8 + XI * NW - 1) / (XI * NW);  // issue points that carry halo loads (<= taps - NS + 1)
 
   // ---- loaders ---------------------------------------------------------------------------------
   WL wl;
   {
-    const int64_t rem = ((int64_t)(p.N - n0 - 1) * p.ldw + p.K) * 2;
-    wl.init(p.W + (int64_t)n0 * p.ldw, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldw, p.N - n0, p.K, cg, n0, 0, wave,
-            lane);
+    const int64_t rem = ((int64_t)(h.w_rows - 1) * h.ldw + h.K) * 2;
+    wl.init(h.W, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), h.ldw, h.w_rows, h.K, cg, 0, 0, wave, lane);
   }
-  const __amdgpu_buffer_rsrc_t xrsrc = make_rsrc(p.X, (unsigned)((int64_t)total_px * cg.C * 2));
+  const __amdgpu_buffer_rsrc_t xrsrc = make_rsrc(h.X, (unsigned)((int64_t)total_px * cg.C * 2));
   const int lrow = lane >> 3;
   const int xlc = (lane & 7) ^ dma_swizzle<BK>(wave * 8 + lrow);  // logical chunk this lane fetches
   // X part `part` (0 .. xparts-1) of channel chunk `chunk` into halo buffer `buf`: XI instructions,
@@ -110,13 +126,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(
 #pragma unroll
     for (int i = 0; i < XI; ++i) {
       int group = (part * XI + i) * NW + wave;  // group of 8 LDS rows
-      if (group * 8 >= hb8) group = hb8 / 8 - 2 * (1 + i) + (wave & 1);  // same parity: same swizzle term
+      if (group * 8 >= hb8) {  // the highest real groups of this wave's parity: same swizzle term
+        const int top = hb8 / 8 - 1;
+        group = top - ((top ^ wave) & 1) - 2 * i;
+      }
       const int row = group * 8 + lrow;
       const int px = m0 - halo + row;
       const bool ok = px >= 0 && px < total_px;
       const unsigned off = ok ? (unsigned)(px * cg.C + (kg + chunk * KG) * 64 + xlc * 8) * 2u : kInvalidOffset;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, BOLT_LDS_PTR(Xh + buf * hb8 * 64 + group * 512), 16, off, 0, 0,
-                                               0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, BOLT_LDS_PTR(Xh + buf * bstride * 64 + group * 512), 16, off, 0,
+                                               0, 0);
     }
   };
   // Issue point at the end of item (chunk ac, tap at_): first, at the first xparts taps of a chunk,
@@ -157,7 +176,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(
   for (int b = 0; b < FM; ++b) {
     const int m = m0 + wm * WTM + b * 32 + l32;
     unsigned mask = 0;
-    if (m < p.M) {
+    if (m < h.M) {
       const int hw = cg.H * cg.Wi;
       const int rem = m - (m / hw) * hw;
       const int op = rem / cg.Wi, oq = rem - op * cg.Wi;
@@ -173,7 +192,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(
   }
   if (wave == 0 && lane < 8) *(half8*)(Xh + zero_row * 64 + lane * 8) = half8{0, 0, 0, 0, 0, 0, 0, 0};
 
-  floatx16 acc[FN][FM];
 #pragma unroll
   for (int a = 0; a < FN; ++a)
 #pragma unroll
@@ -192,7 +210,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(
   auto set_rows = [&](int buf, int toff, int tap) {
 #pragma unroll
     for (int b = 0; b < FM; ++b)
-      xrow[b] = (tapmask[b] >> tap) & 1u ? buf * hb8 + wm * WTM + b * 32 + l32 + toff : zero_row;
+      xrow[b] = (tapmask[b] >> tap) & 1u ? buf * bstride + wm * WTM + b * 32 + l32 + toff : zero_row;
   };
   auto read_group = [&](int stage, int grp, half8 (&x)[G][FM], half8 (&w)[G][FN]) {
     const half_t* ws = Ws + stage * BN * 64;
@@ -273,6 +291,28 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(
       tile_body(s + 1, std::integral_constant<int, 1>{});
     }
     if (s < S_items) tile_body(s, std::integral_constant<int, 0>{});
+  }
+
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG = 1>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(const FpropParams p) {
+  using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>;
+  constexpr int NW = T_::NW, WTM = T_::WTM, WTN = T_::WTN, FM = T_::FM, FN = T_::FN;
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kg = wave_all / NW, wave = wave_all - kg * NW;
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int g = lane >> 5, l32 = lane & 31;
+  int tm, tn;
+  tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.swizzle, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  floatx16 acc[FN][FM];
+  {
+    const HaloArgs h{p.X, p.W + (int64_t)n0 * p.ldw, p.N - n0, p.M, p.K, p.ldw, p.cg, m0};
+    conv_halo_mainloop<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>(h, lds, acc);
   }
 
   // ---- k-groups: sum the accumulators through LDS, group 0 carries on ------------------------------

@@ -12,6 +12,7 @@
 #include "b2b_dma_kernel.hpp"
 #include "b2b_kernel.hpp"
 #include "conv_halo_kernel.hpp"
+#include "b2b_halo_kernel.hpp"
 #include "fprop_dma_kernel.hpp"
 #include "fprop_kernel.hpp"
 #include "stream_kernel.hpp"
@@ -105,4 +106,5 @@ void register_b2b_conv_instances(std::vector<B2bInstance>& v);
 void register_b2b_gemm_stream_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_stream_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_dma_instances(std::vector<B2bInstance>& v);
+void register_b2b_conv_halo_instances(std::vector<B2bInstance>& v);
 }  // namespace bolt
