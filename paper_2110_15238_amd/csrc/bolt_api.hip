@@ -4,7 +4,6 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -83,21 +82,6 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(float* sink, int iters) 
 __global__ __launch_bounds__(256) void copy_kernel(const floatx4* src, floatx4* dst, int64_t n16) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (int64_t)gridDim.x * blockDim.x)
     dst[i] = src[i];
-}
-
-// Tickets of the fused split-K: one word per output tile, zero between launches (the workgroup
-// that draws the last ticket of a tile resets it).  Launches take slots round-robin so that
-// launches overlapping on different streams do not share words.
-static constexpr int kCounterSlots = 16, kCounterTiles = 4096;
-__device__ unsigned g_splitk_counters[kCounterSlots * kCounterTiles];
-
-static unsigned* splitk_counters() {
-  static unsigned* ptr = [] {
-    void* q = nullptr;
-    return hipGetSymbolAddress(&q, HIP_SYMBOL(g_splitk_counters)) == hipSuccess ? (unsigned*)q : nullptr;
-  }();
-  static std::atomic<unsigned> next{0};
-  return ptr ? ptr + (size_t)(next.fetch_add(1) % kCounterSlots) * kCounterTiles : nullptr;
 }
 
 // Eight zero halves: what a kernel's bias pointer addresses when the caller gave no bias.
@@ -305,24 +289,13 @@ static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int sw
   split_k = ceil_div(nk, p.ktiles_per_split);  // no empty splits
   p.split_k = split_k;
   p.partial = nullptr;
-  p.counters = nullptr;
-  p.fused = 0;
   if (split_k > 1) {
-    if (!ws || !is_aligned16(ws)) return BOLT_ERR_WORKSPACE;
-    // in-kernel reduction where the instance has it, the tile count fits the ticket words and the
-    // workspace holds whole (padded) tiles; the two-kernel form otherwise
-    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    if (in.fused_splitk && tiles <= kCounterTiles &&
-        ws_bytes >= splitk_bytes(p.tiles_m * in.bm, p.tiles_n * in.bn, split_k)) {
-      p.counters = splitk_counters();
-      p.fused = p.counters ? 1 : 0;
-    }
-    if (!p.fused && ws_bytes < splitk_bytes(p.M, p.N, split_k)) return BOLT_ERR_WORKSPACE;
+    if (!ws || ws_bytes < splitk_bytes(p.M, p.N, split_k) || !is_aligned16(ws)) return BOLT_ERR_WORKSPACE;
     p.partial = (float*)ws;
   }
   if ((int64_t)p.tiles_m * p.tiles_n >= (1ll << 31)) return BOLT_ERR_UNSUPPORTED;
   if (in.launch(p, stream) != hipSuccess) return BOLT_ERR_LAUNCH;
-  if (split_k > 1 && !p.fused) {
+  if (split_k > 1) {
     const int64_t quads = (int64_t)p.M * (p.N / 4);
     const int blocks = (int)std::min<int64_t>((quads + 255) / 256, kNumCU * 8);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p.partial,
@@ -595,20 +568,10 @@ static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>&
       out.push_back({i, swz[s], 1, 0.f});
     }
     // split-K only when the grid cannot fill the chip and K is deep enough to share
-    if (in.fused_splitk) {
-      // reduced inside the kernel: cheap enough to try up to about three workgroups per CU
-      static const int sks[] = {2, 3, 4, 6, 8};
-      for (int sk : sks) {
-        if (tiles * sk > 3 * kNumCU || nk < 2 * sk) break;
-        if (!have_ws || ws_bytes < splitk_bytes(tiles_m * in.bm, tiles_n * in.bn, sk)) break;
-        out.push_back({i, 0, sk, 0.f});
-      }
-    } else {
-      for (int sk = 2; sk <= kMaxSplitK && in.stages != 1; sk *= 2) {
-        if (tiles * (sk / 2) >= kNumCU || nk < 2 * sk) break;
-        if (!have_ws || ws_bytes < splitk_bytes(pr.p.M, pr.p.N, sk)) break;
-        out.push_back({i, 0, sk, 0.f});
-      }
+    for (int sk = 2; sk <= kMaxSplitK && in.stages != 1; sk *= 2) {
+      if (tiles * (sk / 2) >= kNumCU || nk < 2 * sk) break;
+      if (!have_ws || ws_bytes < splitk_bytes(pr.p.M, pr.p.N, sk)) break;
+      out.push_back({i, 0, sk, 0.f});
     }
   }
   return out;
@@ -709,24 +672,13 @@ size_t bolt_workspace_bytes(bolt_op op, const void* desc0, const void* desc1, co
   else if (op == BOLT_OP_CONV2D) s = make_conv_problem((const bolt_conv_desc*)desc0, &fp);
   else return 0;
   if (s != BOLT_OK) return 0;
-  const std::vector<FpropInstance>& tab = op == BOLT_OP_GEMM ? tables().gemm : tables().conv;
-  if (config) {
-    const int sk = std::min<int>(config->split_k, kMaxSplitK);
-    size_t need = splitk_bytes(fp.p.M, fp.p.N, sk);
-    if (sk > 1 && config->kernel_id >= 0 && config->kernel_id < (int)tab.size() && tab[config->kernel_id].fused_splitk) {
-      // the in-kernel reduction stores whole tiles
-      const FpropInstance& in = tab[config->kernel_id];
-      need = std::max(need, splitk_bytes(ceil_div(fp.p.M, in.bm) * in.bm, ceil_div(fp.p.N, in.bn) * in.bn, sk));
-    }
-    return need;
-  }
-  // upper bound for tuning: split-K is only tried while the grid is small (see fprop_candidates)
+  if (config) return splitk_bytes(fp.p.M, fp.p.N, std::min<int>(config->split_k, kMaxSplitK));
+  // upper bound for tuning: split-K is only tried while the output is small
   size_t need = 0;
-  static const int sks[] = {2, 3, 4, 6, 8};
-  const int64_t min_tiles = (int64_t)ceil_div(fp.p.M, 256) * ceil_div(fp.p.N, 256);
-  for (int sk : sks) {
-    if (min_tiles * sk > 3 * kNumCU) break;
-    need = splitk_bytes(ceil_div(fp.p.M, 256) * 256, ceil_div(fp.p.N, 256) * 256, sk);
+  for (int sk = 2; sk <= kMaxSplitK; sk *= 2) {
+    const int64_t min_tiles = (int64_t)ceil_div(fp.p.M, 256) * ceil_div(fp.p.N, 256);
+    if (min_tiles * (sk / 2) >= kNumCU) break;
+    need = splitk_bytes(fp.p.M, fp.p.N, sk);
   }
   return need;
 }

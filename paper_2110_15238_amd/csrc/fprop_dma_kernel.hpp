@@ -435,65 +435,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
   // ---- epilogue ---------------------------------------------------------------------------------
   const int mrow = m0 + wm * WTM + l32;
   const int ncol = n0 + wn * WTN + g * 4;
-  if constexpr (KG == 1) {
-    if (p.split_k > 1 && p.fused) {
-      // Fused split-K: every split of this tile stores its accumulators, then takes a ticket; the
-      // split that draws the last ticket sums all partials in split order (so the result does not
-      // depend on which one was last) and carries on to the epilogue.  Partials travel between
-      // workgroups that may sit on different XCDs (private L2s), so they are stored and loaded with
-      // the system-coherent cache policy (write-through / no L2 hit); a device-scope fence instead
-      // would write back and invalidate a whole L2 per workgroup (measured: 2x slower kernels).
-      constexpr int PER_WAVE = FN * FM * 16 * 64;
-      constexpr int kCoherent = 0x11;  // sc0 | sc1: write through to / read from memory, past the L2s
-      const int tile_id = blockIdx.x;
-      const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-      // one descriptor per split: [tiles][NW][PER_WAVE] floats (the host checked the workspace size)
-      const unsigned split_bytes = (unsigned)(tiles * T::NW * PER_WAVE * 4);
-      const unsigned my_off = (unsigned)(((unsigned)tile_id * T::NW + wave) * PER_WAVE + lane * 4) * 4u;
-      {
-        const __amdgpu_buffer_rsrc_t mine = make_rsrc(p.partial + (int64_t)z * tiles * T::NW * PER_WAVE, split_bytes);
-#pragma unroll
-        for (int a = 0; a < FN; ++a)
-#pragma unroll
-          for (int b = 0; b < FM; ++b)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const floatx4 v = {acc[a][b][q * 4], acc[a][b][q * 4 + 1], acc[a][b][q * 4 + 2], acc[a][b][q * 4 + 3]};
-              __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4_t, v), mine,
-                                                     my_off + (unsigned)((a * FM + b) * 4 + q) * 1024u, 0, kCoherent);
-            }
-      }
-      unsigned* flag = reinterpret_cast<unsigned*>(lds);
-      __syncthreads();  // every wave's stores have completed (vmcnt 0), nobody reads the operand stages any more
-      if (tid == 0) *flag = atomicAdd(p.counters + tile_id, 1u);  // device-scope ticket
-      __syncthreads();
-      if (*flag != (unsigned)(p.split_k - 1)) return;
-      if (tid == 0) atomicExch(p.counters + tile_id, 0u);  // ready for the next launch
-#pragma unroll
-      for (int a = 0; a < FN; ++a)
-#pragma unroll
-        for (int b = 0; b < FM; ++b)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-      for (int zz = 0; zz < p.split_k; ++zz) {
-        const __amdgpu_buffer_rsrc_t theirs = make_rsrc(p.partial + (int64_t)zz * tiles * T::NW * PER_WAVE, split_bytes);
-#pragma unroll
-        for (int a = 0; a < FN; ++a)
-#pragma unroll
-          for (int b = 0; b < FM; ++b)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              const floatx4 v = __builtin_bit_cast(
-                  floatx4, __builtin_amdgcn_raw_buffer_load_b128(theirs, my_off + (unsigned)((a * FM + b) * 4 + q) * 1024u, 0,
-                                                                 kCoherent));
-#pragma unroll
-              for (int e = 0; e < 4; ++e) acc[a][b][q * 4 + e] += v[e];
-            }
-      }
-      __syncthreads();  // the flag word is part of the C tile below
-    }
-  }
-  if (p.split_k > 1 && !p.fused) {
+  if (p.split_k > 1) {
     if (kg > 0) return;  // (no barrier follows on this path)
     float* dst = p.partial + (int64_t)z * p.M * p.N;
 #pragma unroll
@@ -570,8 +512,7 @@ hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
   {                                                                                                     \
     "dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK, WM, WN, XMODE, 0, NS,               \
         bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS>::LDS_BYTES,                                  \
-        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>, 0, nullptr, nullptr, nullptr, nullptr,   \
-        1, (NS) > 1                                                                                      \
+        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>, 0, nullptr, nullptr, nullptr, nullptr    \
   }
 
 // The same kernel with KG k-groups (64 * WM * WN * KG threads).

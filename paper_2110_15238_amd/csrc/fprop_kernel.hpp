@@ -37,11 +37,6 @@ struct FpropParams {
   int tiles_m, tiles_n, swizzle;
   int split_k, ktiles_per_split;
   ConvGeom cg;  // XMODE 1 only
-  // Split-K reduced inside the kernel (fused != 0): `partial` holds [split_k][tiles][BM*BN] floats in
-  // the kernel's own register order and counters[tile] counts the splits of a tile that have
-  // stored theirs; the last one sums all of them in split order and runs the epilogue.
-  unsigned* counters;
-  int fused;
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>
@@ -181,7 +176,6 @@ struct FpropInstance {
   bool (*dyn_supports)(const FpropParams&);
   int (*dyn_lds_bytes)(const FpropParams&);
   int kgroups;  // k-groups of waves per workgroup (0 or 1: none); threads = 64 * waves_m * waves_n * kgroups
-  int fused_splitk;  // the kernel can reduce split-K partials itself (see FpropParams::fused)
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>

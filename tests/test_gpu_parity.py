@@ -111,7 +111,7 @@ def test_gemm_split_k_and_swizzle(bolt):
     B = wl.uniform_fp16(104, 1, (K, N), -1, 1)
     bias = wl.uniform_fp16(104, 2, (N,), -1, 1)
     want = ref.gemm(A, B, bias)
-    ws = torch.empty(8 * 512 * 256, dtype=torch.float32, device="cuda")  # whole (padded) tiles for the in-kernel reduction
+    ws = torch.empty(8 * M * N, dtype=torch.float32, device="cuda")
     d = bolt.gemm_desc(M, N, K)
     kids = [k for k in range(bolt.bolt_num_instances(bolt.OP_GEMM)) if bolt.bolt_instance_supports(bolt.OP_GEMM, k, d)]
     for kid in kids[:6]:
@@ -225,7 +225,7 @@ def test_conv_split_k(bolt):
     w = wl.normal_fp16(204, 1, (K, R, S, Cc), 0.05)
     bias = wl.uniform_fp16(204, 2, (K,), -1, 1)
     want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
-    ws = torch.empty(8 * 256 * 256, dtype=torch.float32, device="cuda")  # whole tiles of the largest instance
+    ws = torch.empty(8 * 49 * K, dtype=torch.float32, device="cuda")
     d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
     ran = 0
     for kid in range(bolt.bolt_num_instances(bolt.OP_CONV2D)):
@@ -238,53 +238,6 @@ def test_conv_split_k(bolt):
                 got, _ = _run_conv(bolt, x, w, bias, stride, pad, config={"kernel_id": kid, "split_k": sk}, workspace=ws)
                 assert_close(got, want, "conv split_k=%d instance %d" % (sk, kid))
     assert ran >= 9
-
-
-def test_fused_split_k_is_exact_repeatable_and_leaves_its_tickets_clear(bolt):
-    """Split-K reduced inside the kernel (the last workgroup of a tile sums the partials in split
-    order): integer inputs stay bit-exact, repeated launches agree bit for bit (fixed summation
-    order, ticket words back at zero), ragged tiles and every split count are covered, GEMM
-    addressing (1x1) and gather addressing (3x3) both."""
-    cases = [(2, 14, 14, 256, 136, 3, 3, 1, 1), (3, 7, 9, 512, 72, 1, 1, 1, 0), (1, 13, 13, 192, 264, 3, 3, 2, 1)]
-    for ci, (N, H, W, Cc, K, R, S, stride, pad) in enumerate(cases):
-        x = wl.integer_fp16(230 + ci, 0, (N, H, W, Cc), -2, 2)
-        w = wl.integer_fp16(230 + ci, 1, (K, R, S, Cc), -1, 1)
-        bias = wl.integer_fp16(230 + ci, 2, (K,), -3, 3)
-        want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
-        d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
-        ran = 0
-        for kid in range(bolt.bolt_num_instances(bolt.OP_CONV2D)):
-            if not bolt.bolt_instance_supports(bolt.OP_CONV2D, kid, d):
-                continue
-            for sk in (2, 3, 4, 6, 8):
-                cfg = {"kernel_id": kid, "split_k": sk}
-                if bolt.bolt_check(bolt.OP_CONV2D, d, None, cfg) != 0:
-                    continue
-                ws = torch.empty(max(bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d, None, cfg), 16), dtype=torch.uint8, device="cuda")
-                _say("fused split-K case %d instance %d split_k %d" % (ci, kid, sk))
-                got0, _ = _run_conv(bolt, x, w, bias, stride, pad, config=cfg, workspace=ws)
-                got1, _ = _run_conv(bolt, x, w, bias, stride, pad, config=cfg, workspace=ws)
-                assert_bit_equal(got0, want, "fused split-K case %d instance %d split_k %d" % (ci, kid, sk))
-                assert_bit_equal(got1, got0, "second launch, case %d instance %d split_k %d" % (ci, kid, sk))
-                ran += 1
-        assert ran >= 20
-    # non-integer data: two launches agree bit for bit (the summation order does not depend on timing)
-    N, H, W, Cc, K, R, S, stride, pad = 4, 14, 14, 256, 256, 3, 3, 1, 1
-    x = wl.uniform_fp16(240, 0, (N, H, W, Cc), -1, 1)
-    w = wl.normal_fp16(240, 1, (K, R, S, Cc), 0.03)
-    bias = wl.uniform_fp16(240, 2, (K,), -1, 1)
-    want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
-    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
-    kids = [k for k in range(bolt.bolt_num_instances(bolt.OP_CONV2D)) if bolt.bolt_instance_supports(bolt.OP_CONV2D, k, d)]
-    for kid in kids[:12]:
-        cfg = {"kernel_id": kid, "split_k": 4}
-        if bolt.bolt_check(bolt.OP_CONV2D, d, None, cfg) != 0:
-            continue
-        ws = torch.empty(max(bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d, None, cfg), 16), dtype=torch.uint8, device="cuda")
-        runs = [_run_conv(bolt, x, w, bias, stride, pad, config=cfg, workspace=ws)[0] for _ in range(3)]
-        assert_close(runs[0], want, "fused split-K instance %d" % kid)
-        assert_bit_equal(runs[1], runs[0], "repeat 1, instance %d" % kid)
-        assert_bit_equal(runs[2], runs[0], "repeat 2, instance %d" % kid)
 
 
 def test_config2_conv_small_batch_full_compare(bolt):
