@@ -209,7 +209,13 @@ struct FpropProblem {
 };
 
 static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
-  if (in.xmode != pr.xmode || in.wmode != pr.wmode) return false;
+  if (in.wmode != pr.wmode) return false;
+  if (in.xmode == 3) {
+    // filter-row gather: a whole filter row of one output pixel (S*C halves) fits one k-tile
+    if (pr.xmode != 1 || pr.p.cg.S * pr.p.cg.C > in.bk) return false;
+  } else if (in.xmode != pr.xmode) {
+    return false;
+  }
   if (in.stream_launch) {
     // persistent weights-resident kernel: the tile spans all of N and the whole weight matrix
     // must fit in LDS next to the activation stages
@@ -283,7 +289,7 @@ static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int sw
   p.tiles_n = ceil_div(p.N, in.bn);
   p.swizzle = swizzle < 0 ? 0 : swizzle;
   if (in.dyn_supports && split_k > 1) return BOLT_ERR_UNSUPPORTED;
-  const int nk = ceil_div(p.K, in.bk);
+  const int nk = in.xmode == 3 ? p.cg.R : ceil_div(p.K, in.bk);  // x mode 3: one k-tile per filter row
   split_k = std::max(1, std::min(std::min(split_k, kMaxSplitK), nk));
   p.ktiles_per_split = ceil_div(nk, split_k);
   split_k = ceil_div(nk, p.ktiles_per_split);  // no empty splits
@@ -557,7 +563,7 @@ static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>&
     if (!fprop_supports(in, pr)) continue;
     const int tiles_m = ceil_div(pr.p.M, in.bm), tiles_n = ceil_div(pr.p.N, in.bn);
     const int64_t tiles = (int64_t)tiles_m * tiles_n;
-    const int nk = ceil_div(pr.p.K, in.bk);
+    const int nk = in.xmode == 3 ? pr.p.cg.R : ceil_div(pr.p.K, in.bk);
     if (in.stream_launch || in.dyn_supports) {  // no split-K / swizzle variants for these
       out.push_back({i, 0, 1, 0.f});
       continue;

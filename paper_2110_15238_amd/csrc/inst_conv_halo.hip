@@ -14,5 +14,7 @@ void register_conv_halo_instances(std::vector<FpropInstance>& v) {
       HK(128, 64, 2, 2, 2, 2, 2), HK(128, 128, 2, 2, 2, 1, 2),
   };
   for (const auto& t : table) v.push_back(t);
+  static const FpropInstance rowgather[] = {BOLT_FPROP_DMA_ROWGATHER_TILE_LIST(BOLT_FPROP_DMA_INSTANCE)};
+  for (const auto& t : rowgather) v.push_back(t);
 }
 }  // namespace bolt

@@ -83,6 +83,18 @@
   X(64, 128, 64, 2, 2, 1, XMODE),                 \
   X(64, 64, 64, 2, 2, 1, XMODE)
 
+// Tiles for the filter-row gather of thin inputs (x mode 3): K is short (one k-tile per filter row)
+// and N is usually 64.
+#define BOLT_FPROP_DMA_ROWGATHER_TILE_LIST(X) \
+  X(256, 64, 64, 4, 1, 3, 3),                 \
+  X(256, 64, 64, 4, 2, 3, 3),                 \
+  X(128, 64, 64, 2, 2, 3, 3),                 \
+  X(128, 64, 64, 4, 1, 3, 3),                 \
+  X(128, 64, 64, 2, 2, 4, 3),                 \
+  X(64, 64, 64, 2, 2, 3, 3),                  \
+  X(128, 128, 64, 2, 2, 3, 3),                \
+  X(64, 128, 64, 2, 2, 3, 3)
+
 // Tiles with k-groups: tile M, N, K, waves M, N, stages, x mode, k-groups.
 #define BOLT_FPROP_DMA_KG_TILE_LIST(X, XMODE) \
   X(64, 64, 64, 2, 2, 2, XMODE, 2),           \
