@@ -45,8 +45,8 @@ def main():
                     help="profiling runs: only warm-up + timed steps (no per-shape table, no probes, no oracle)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by batch with "
-              "no collective, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path would shard by batch, "
+              "weights replicated, with no collective)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -527,7 +527,7 @@ static bolt_status tune_candidates(std::vector<Candidate>& cands, RunF&& run, hi
   int n_ok = 0;
   // pass 1: a short timing of every candidate
   for (auto& c : cands) {
-    bolt_status s = time_launches([&] { return run(c); }, 2, 5, stream, e0, e1, &c.ms);
+    bolt_status s = time_launches([&] { return run(c); }, 2, 8, stream, e0, e1, &c.ms);
     if (s == BOLT_ERR_LAUNCH) { status = s; break; }
     if (s != BOLT_OK) { c.ms = -1.f; continue; }
     if (tune_log_enabled())
@@ -540,11 +540,11 @@ static bolt_status tune_candidates(std::vector<Candidate>& cands, RunF&& run, hi
     for (auto& c : cands) if (c.ms >= 0.f) order.push_back(&c);
     std::sort(order.begin(), order.end(), [](Candidate* a, Candidate* b) { return a->ms < b->ms; });
     // pass 2: the few fastest again, longer
-    const int finalists = std::min<int>(4, (int)order.size());
+    const int finalists = std::min<int>(6, (int)order.size());
     Candidate* win = nullptr;
     for (int i = 0; i < finalists && status == BOLT_OK; ++i) {
       Candidate* c = order[i];
-      bolt_status s = time_launches([&] { return run(*c); }, 3, 30, stream, e0, e1, &c->ms);
+      bolt_status s = time_launches([&] { return run(*c); }, 3, 60, stream, e0, e1, &c->ms);
       if (s != BOLT_OK) { status = s; break; }
       if (!win || c->ms < win->ms) win = c;
     }
