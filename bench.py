@@ -258,6 +258,32 @@ def main():
     avg_launch_ms = conv_ms / conv_launches
     achieved = conv_flops / conv_launches / (avg_launch_ms * 1e-3) / 1e12
 
+    # Per-op times INSIDE a step (every op finds caches that the 56 other ops have just swept: the cold
+    # number that belongs beside the back-to-back one of the per-shape table).  Separate, untimed steps.
+    if not args.steps_only:
+        diag_steps = 5
+        marks = []
+        for _ in range(diag_steps):
+            row = []
+            for op in other_ops:
+                op["run"]()
+            for op in conv_ops:
+                if op["pad"] is not None:
+                    op["pad"]()
+            for op in conv_ops:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(op["count"]):
+                    op["run"]()
+                e1.record(stream)
+                row.append((e0, e1))
+            marks.append(row)
+        torch.cuda.synchronize()
+        by_name = {e["name"]: e for e in shapes_out}
+        for i, op in enumerate(conv_ops):
+            ms = sum(m[i][0].elapsed_time(m[i][1]) for m in marks) / diag_steps / op["count"]
+            by_name[op["name"]]["ms_in_step"] = round(ms, 5)
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")  # written from the rocprofv3 --pmc passes
     if os.path.exists(tpath):
@@ -294,18 +320,23 @@ def main():
     # The five configurations are small problems (7 GFLOP at most per launch); these two show what the
     # same tuned templates reach when the problem fills the chip.
     large = []
+    cfg_keys = ("kernel_id", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n", "stages", "swizzle")
     try:
-        M = N = K = 8192
-        Ag = torch.randn((M, K), device="cuda", dtype=torch.float16) * 0.5
-        Bg = torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.5
-        Dg = empty(M, N)
-        gd = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK, act="none")
-        cfg = tuned("large gemm 8192 NK", bolt.OP_GEMM, gd, None, [Ag, Bg, None, Dg], ws)
-        ms = timed(lambda: bolt.bolt_gemm_epilogue(gd, Ag, Bg, None, Dg, cfg, ws), 10)
-        large.append(dict(name="GEMM 8192x8192x8192 (B as [N][K])", ms=round(ms, 4), tflops=round(2.0 * M * N * K / ms / 1e9, 1),
-                          pct_mfma_peak=round(100 * 2.0 * M * N * K / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
-                          config={k: cfg.as_dict()[k] for k in ("kernel_id", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n", "stages", "swizzle")}))
-        del Ag, Bg, Dg
+        # 8192^3 and 4096^3 are ours (long enough for steady state); 1280 x 3072 x 768 is the FFN GEMM of
+        # the paper's epilogue-fusion experiment (Section 4.1.1)
+        for (M, N, K) in ((8192, 8192, 8192), (4096, 4096, 4096), (wl.EPILOGUE_GEMM.M, wl.EPILOGUE_GEMM.N, wl.EPILOGUE_GEMM.K)):
+            Ag = torch.randn((M, K), device="cuda", dtype=torch.float16) * 0.5
+            Bg = torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.5
+            biasg = torch.randn((N,), device="cuda", dtype=torch.float16)
+            Dg = empty(M, N)
+            gd = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK, act="relu")
+            cfg = tuned("large gemm %dx%dx%d NK" % (M, N, K), bolt.OP_GEMM, gd, None, [Ag, Bg, biasg, Dg], ws)
+            ms = timed(lambda: bolt.bolt_gemm_epilogue(gd, Ag, Bg, biasg, Dg, cfg, ws), 10 if M >= 8192 else 30)
+            large.append(dict(name="GEMM %dx%dx%d + bias + ReLU (B as [N][K])" % (M, N, K), ms=round(ms, 4),
+                              tflops=round(2.0 * M * N * K / ms / 1e9, 1),
+                              pct_mfma_peak=round(100 * 2.0 * M * N * K / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
+                              config={k: cfg.as_dict()[k] for k in cfg_keys}))
+            del Ag, Bg, Dg
         cs = wl.ConvShape(128, 56, 56, 256, 256, 3, 3, 1, 1)
         xg = torch.randn((cs.N, cs.H, cs.W, cs.C), device="cuda", dtype=torch.float16) * 0.5
         wg = torch.randn((cs.K, cs.R, cs.S, cs.C), device="cuda", dtype=torch.float16) * 0.05
@@ -316,16 +347,85 @@ def main():
         ms = timed(lambda: bolt.bolt_conv2d_fprop_nhwc(cd, xg, wg, bg, yg, cfg, ws), 10)
         large.append(dict(name="conv3x3 N=128 56x56 256->256", ms=round(ms, 4), tflops=round(cs.flops / ms / 1e9, 1),
                           pct_mfma_peak=round(100 * cs.flops / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
-                          config={k: cfg.as_dict()[k] for k in ("kernel_id", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n", "stages", "swizzle")}))
+                          config={k: cfg.as_dict()[k] for k in cfg_keys}))
         del xg, wg, yg
     except Exception as e:  # context only
         large.append({"error": str(e)})
     out["large_shapes"] = large
+
+    # ------------------------------------------------------------------ the paper's b2b tables (context)
+    # Tables 1 and 2 (Section 4.1.2): fused vs unfused on the paper's own shapes, random data.  Extents that
+    # are not multiples of 8 are padded with zeros first (Section 3.2.3), as a caller of the library must.
+    tables = []
+
+    def pad8(v):
+        return (v + 7) // 8 * 8
+
+    def rnd(*shape, scale=0.5):
+        return torch.randn(shape, device="cuda", dtype=torch.float16) * scale
+
+    for (M, N0, K0, N1) in wl.TABLE1_B2B_GEMM:
+        entry = dict(name="Table 1 b2b GEMM M=%d N0=%d K0=%d N1=%d" % (M, N0, K0, N1))
+        try:
+            n0, k0, n1 = pad8(N0), pad8(K0), pad8(N1)
+            A, W0, b0, W1, b1 = rnd(M, k0), rnd(k0, n0, scale=0.1), rnd(n0), rnd(n0, n1, scale=0.1), rnd(n1)
+            D0, D1, D1u = empty(M, n0), empty(M, n1), empty(M, n1)
+            g0, g1 = bolt.gemm_desc(M, n0, k0), bolt.gemm_desc(M, n1, n0)
+            if bolt.bolt_check(bolt.OP_B2B_GEMM, g0, g1) != 0:
+                # row-major weights of this size do not fit the weights-resident kernels: store them
+                # reduction-contiguous ([N][K]), which the multi-stage fused kernel streams
+                W0, W1 = rnd(n0, k0, scale=0.1), rnd(n1, n0, scale=0.1)
+                g0 = bolt.gemm_desc(M, n0, k0, b_layout=bolt.LAYOUT_NK)
+                g1 = bolt.gemm_desc(M, n1, n0, b_layout=bolt.LAYOUT_NK)
+                entry["weights"] = "[N][K]"
+            cf = tuned(entry["name"] + " fused", bolt.OP_B2B_GEMM, g0, g1, [A, W0, b0, W1, b1, D1])
+            c0 = tuned(entry["name"] + " op0", bolt.OP_GEMM, g0, None, [A, W0, b0, D0], ws)
+            c1 = tuned(entry["name"] + " op1", bolt.OP_GEMM, g1, None, [D0, W1, b1, D1u], ws)
+
+            def unfused():
+                bolt.bolt_gemm_epilogue(g0, A, W0, b0, D0, c0, ws)
+                bolt.bolt_gemm_epilogue(g1, D0, W1, b1, D1u, c1, ws)
+            mf = timed(lambda: bolt.bolt_b2b_gemm(g0, g1, A, W0, b0, W1, b1, D1, cf), args.reps)
+            mu = timed(unfused, args.reps)
+            entry.update(padded_to=[n0, k0, n1], fused_ms=round(mf, 5), unfused_ms=round(mu, 5), speedup=round(mu / mf, 3))
+        except bolt.BoltError as e:
+            entry["status"] = str(e)
+        tables.append(entry)
+    for (H, IC, OC0, st, OC1) in wl.TABLE2_B2B_CONV:
+        entry = dict(name="Table 2 b2b conv %dx%d IC=%d OC=%d stride %d -> 1x1 OC=%d" % (H, H, IC, OC0, st, OC1))
+        try:
+            ic = pad8(IC)
+            x, w0, b0, w1, b1 = rnd(32, H, H, ic), rnd(OC0, 3, 3, ic, scale=0.1), rnd(OC0), rnd(OC1, 1, 1, OC0, scale=0.1), rnd(OC1)
+            c0d = bolt.conv_desc(32, H, H, ic, OC0, 3, 3, st, 1)
+            P, Q = bolt.conv_out_hw(c0d)
+            c1d = bolt.conv_desc(32, P, Q, OC0, OC1, 1, 1, 1, 0)
+            y0, y1, y1u = empty(32, P, Q, OC0), empty(32, P, Q, OC1), empty(32, P, Q, OC1)
+            cf = tuned(entry["name"] + " fused", bolt.OP_B2B_CONV, c0d, c1d, [x, w0, b0, w1, b1, y1])
+            c0 = tuned(entry["name"] + " op0", bolt.OP_CONV2D, c0d, None, [x, w0, b0, y0], ws)
+            c1 = tuned(entry["name"] + " op1", bolt.OP_CONV2D, c1d, None, [y0, w1, b1, y1u], ws)
+
+            def unfused_c():
+                bolt.bolt_conv2d_fprop_nhwc(c0d, x, w0, b0, y0, c0, ws)
+                bolt.bolt_conv2d_fprop_nhwc(c1d, y0, w1, b1, y1u, c1, ws)
+            mf = timed(lambda: bolt.bolt_b2b_conv(c0d, c1d, x, w0, b0, w1, b1, y1, cf), args.reps)
+            mu = timed(unfused_c, args.reps)
+            entry.update(padded_ic=ic, fused_ms=round(mf, 5), unfused_ms=round(mu, 5), speedup=round(mu / mf, 3))
+            del x, y0, y1, y1u
+        except bolt.BoltError as e:
+            entry["status"] = str(e)
+        tables.append(entry)
+    out["paper_tables_b2b"] = tables
     try:
         out["probes"] = {"mfma_loop_tflops": round(bolt.bolt_probe_mfma_peak(20000), 1),
                          "copy_gbs_1GiB": round(bolt.bolt_probe_copy_bandwidth(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"), 5), 1)}
     except Exception as e:  # probes are context only
         out["probes"] = {"error": str(e)}
+
+    sustained = out["probes"].get("mfma_loop_tflops")
+    if sustained:
+        for e in out["large_shapes"]:
+            if "tflops" in e:
+                e["pct_mfma_sustained"] = round(100 * e["tflops"] / sustained, 2)  # vs the MFMA-only loop of this run
 
     if not args.no_cpu_baseline:
         from oracle import ref

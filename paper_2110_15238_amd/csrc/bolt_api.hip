@@ -110,6 +110,7 @@ struct Tables {
     register_gemm_nk_instances(conv);  // for 1x1 / stride 1 / pad 0 filters
     register_b2b_gemm_instances(b2b_gemm);
     register_b2b_gemm_stream_instances(b2b_gemm);
+    register_b2b_gemm_dma_instances(b2b_gemm);
     register_b2b_conv_instances(b2b_conv);
     register_b2b_conv_stream_instances(b2b_conv);
     register_b2b_conv_dma_instances(b2b_conv);

@@ -310,13 +310,16 @@ def test_padded_stem_conv_matches_unpadded_oracle(bolt):
 # ---------------------------------------------------------------------------------------------
 # back-to-back GEMM
 # ---------------------------------------------------------------------------------------------
-def _run_b2b_gemm(bolt, t, config=None, act0="relu", act1="relu"):
+def _run_b2b_gemm(bolt, t, config=None, act0="relu", act1="relu", layout="kn"):
     M, K0 = t["A"].shape
     N0, N1 = t["W0"].shape[1], t["W1"].shape[1]
-    g0 = bolt.gemm_desc(M, N0, K0, act=act0)
-    g1 = bolt.gemm_desc(M, N1, N0, act=act1)
+    lay = bolt.LAYOUT_KN if layout == "kn" else bolt.LAYOUT_NK
+    W0 = t["W0"] if layout == "kn" else np.ascontiguousarray(t["W0"].T)
+    W1 = t["W1"] if layout == "kn" else np.ascontiguousarray(t["W1"].T)
+    g0 = bolt.gemm_desc(M, N0, K0, act=act0, b_layout=lay)
+    g1 = bolt.gemm_desc(M, N1, N0, act=act1, b_layout=lay)
     D1 = torch.full((M, N1), float("nan"), dtype=torch.float16, device="cuda")
-    bolt.bolt_b2b_gemm(g0, g1, dev(t["A"]), dev(t["W0"]), dev(t["b0"]), dev(t["W1"]), dev(t["b1"]), D1, config)
+    bolt.bolt_b2b_gemm(g0, g1, dev(t["A"]), dev(W0), dev(t["b0"]), dev(W1), dev(t["b1"]), D1, config)
     torch.cuda.synchronize()
     return host(D1), g0, g1
 
@@ -358,6 +361,27 @@ def test_b2b_gemm_shapes_every_instance(bolt, shape):
             _say("b2b gemm %s instance %d" % (shape, kid))
             got, _, _ = _run_b2b_gemm(bolt, t, {"kernel_id": kid})
             assert_close(got, want, "b2b gemm %s instance %d" % (shape, kid))
+            ran += 1
+    assert ran >= 1, "no instance for %s" % (shape,)
+
+
+@pytest.mark.parametrize("shape", [(1000, 72, 64, 128), (515, 576, 128, 64), (700, 96, 32, 96), (260, 200, 64, 256),
+                                   (333, 256, 64, 16), (64, 128, 128, 128)])
+def test_b2b_gemm_reduction_contiguous_weights_every_instance(bolt, shape):
+    """Weights stored [N][K] (the multi-stage fused kernel; Table 1's K0 = 576, N0 = 128 row only runs here)."""
+    M, K0, N0, N1 = shape
+    t = dict(A=wl.uniform_fp16(403, 0, (M, K0), -0.5, 0.5), W0=wl.uniform_fp16(403, 1, (K0, N0), -0.5, 0.5),
+             b0=wl.uniform_fp16(403, 2, (N0,), -0.5, 0.5), W1=wl.uniform_fp16(403, 3, (N0, N1), -0.5, 0.5),
+             b1=wl.uniform_fp16(403, 4, (N1,), -0.5, 0.5))
+    want = ref.b2b_gemm(t["A"], t["W0"], t["b0"], t["W1"], t["b1"])
+    g0 = bolt.gemm_desc(M, N0, K0, b_layout=bolt.LAYOUT_NK)
+    g1 = bolt.gemm_desc(M, N1, N0, b_layout=bolt.LAYOUT_NK)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_GEMM)):
+        if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM, kid, g0, g1):
+            _say("b2b gemm [N][K] %s instance %d" % (shape, kid))
+            got, _, _ = _run_b2b_gemm(bolt, t, {"kernel_id": kid}, layout="nk")
+            assert_close(got, want, "b2b gemm [N][K] %s instance %d" % (shape, kid))
             ran += 1
     assert ran >= 1, "no instance for %s" % (shape,)
 
