@@ -415,6 +415,31 @@ def main():
             entry["status"] = str(e)
         tables.append(entry)
     out["paper_tables_b2b"] = tables
+
+    # ------------------------------------------------------------------ epilogue fusion (context)
+    # Section 4.1.1's experiment: GEMM 1280 x 3072 x 768 + bias + activation computed in the GEMM's epilogue,
+    # against the same tuned GEMM writing its plain result followed by a separate bias + activation pass.
+    epi = []
+    try:
+        g = wl.EPILOGUE_GEMM
+        Ae, Be, be = rnd(g.M, g.K), rnd(g.N, g.K, scale=0.1), rnd(g.N)
+        De, Du = empty(g.M, g.N), empty(g.M, g.N)
+        for act in ("relu", "gelu", "hardswish", "softplus"):
+            gf = bolt.gemm_desc(g.M, g.N, g.K, b_layout=bolt.LAYOUT_NK, act=act)
+            gn = bolt.gemm_desc(g.M, g.N, g.K, b_layout=bolt.LAYOUT_NK, act="none")
+            cf = tuned("epilogue gemm fused " + act, bolt.OP_GEMM, gf, None, [Ae, Be, be, De], ws)
+            cn = tuned("epilogue gemm plain", bolt.OP_GEMM, gn, None, [Ae, Be, None, Du], ws)
+
+            def unfused_e():
+                bolt.bolt_gemm_epilogue(gn, Ae, Be, None, Du, cn, ws)
+                bolt.bolt_bias_act(Du, be, 1.0, 1.0, act)
+            mf = timed(lambda: bolt.bolt_gemm_epilogue(gf, Ae, Be, be, De, cf, ws), args.reps)
+            mu = timed(unfused_e, args.reps)
+            epi.append(dict(name="GEMM %dx%dx%d + bias + %s" % (g.M, g.N, g.K, act), fused_ms=round(mf, 5),
+                            unfused_ms=round(mu, 5), speedup=round(mu / mf, 3)))
+    except Exception as e:  # context only
+        epi.append({"error": str(e)})
+    out["epilogue_fusion"] = epi
     try:
         out["probes"] = {"mfma_loop_tflops": round(bolt.bolt_probe_mfma_peak(20000), 1),
                          "copy_gbs_1GiB": round(bolt.bolt_probe_copy_bandwidth(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"), 5), 1)}

@@ -148,6 +148,14 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
 bolt_status bolt_pad_channels_nhwc(const void* src, void* dst, int64_t pixels, int32_t C, int32_t C_padded,
                                    void* stream);
 
+/* Stand-alone epilogue, in place: D[m, n] = act(alpha * D[m, n] + beta * bias[n]) for m < M, n < N,
+ * FP16 in and out, arithmetic in FP32.  This is the separate element-wise pass that epilogue fusion
+ * removes (Section 3.1; Section 4.1.1 measures the fused GEMM against GEMM followed by this pass);
+ * it exists so that the comparison can be made.  D: device, row-major, row stride ldd >= N;
+ * bias: device, N halves, or NULL (no bias term).  M == 0 is a no-op.  N % 8 == 0, ldd % 8 == 0, 16-byte aligned pointers. */
+bolt_status bolt_bias_act(void* D, const void* bias, int64_t M, int32_t N, int32_t ldd, float alpha, float beta,
+                          bolt_act act, void* stream);
+
 /* Workspace bytes the op needs with this config (0 unless split_k > 1).  With config NULL: an
  * upper bound over everything bolt_tune may try for this problem. */
 size_t bolt_workspace_bytes(bolt_op op, const void* desc0, const void* desc1, const bolt_config* config);

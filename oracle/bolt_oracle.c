@@ -99,6 +99,18 @@ static double epilogue(double s, float alpha, float beta, const uint16_t *bias, 
   return apply_act(v, act);
 }
 
+/* ---- stand-alone epilogue: out[m,n] = act(alpha * in[m,n] + beta * bias[n]) ----------------
+ * The un-fused baseline of the epilogue-fusion experiment (Section 4.1.1): the GEMM writes its
+ * FP16 result, a second pass reads it back, applies bias and activation, and rounds again. */
+void bolt_ref_bias_act(int64_t M, int64_t N, const uint16_t *in, int64_t ldi, const uint16_t *bias, float alpha,
+                       float beta, int act, uint16_t *out, int64_t ldo) {
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n)
+      out[m * ldo + n] = bolt_ref_double_to_half(
+          epilogue(bolt_ref_half_to_double(in[m * ldi + n]), alpha, beta, bias, (int)n, act));
+}
+
 /* ---- GEMM: D[m,n] = act(alpha * sum_k A[m,k] B[k,n] + beta * bias[n]) -------------------- */
 
 static double gemm_dot(const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb, int64_t m, int64_t n,

@@ -42,6 +42,8 @@ def lib():
         L.bolt_ref_half_to_double.argtypes = [C.c_uint16]
         L.bolt_ref_double_to_half.restype = C.c_uint16
         L.bolt_ref_double_to_half.argtypes = [C.c_double]
+        L.bolt_ref_bias_act.restype = None
+        L.bolt_ref_bias_act.argtypes = [_i64, _i64, _p, _i64, _p, _f32, _f32, _int, _p, _i64]
         L.bolt_ref_gemm.restype = None
         L.bolt_ref_gemm.argtypes = [_i64] * 3 + [_p, _i64, _p, _i64, _p, _f32, _f32, _int, _p, _i64]
         L.bolt_ref_gemm_at.restype = None
@@ -91,6 +93,16 @@ def out_hw(H, W, R, S, stride, pad):
     sh, sw = (stride, stride) if np.isscalar(stride) else stride
     ph, pw = (pad, pad) if np.isscalar(pad) else pad
     return (H + 2 * ph - R) // sh + 1, (W + 2 * pw - S) // sw + 1, sh, sw, ph, pw
+
+
+def bias_act(X, bias=None, alpha=1.0, beta=1.0, act="relu"):
+    """Stand-alone epilogue on an FP16 matrix: act(alpha * X + beta * bias) -> float16 (Section 4.1.1's un-fused baseline)."""
+    X = _h(X)
+    M, N = X.shape
+    bias = None if bias is None else _h(bias)
+    out = np.empty((M, N), np.float16)
+    lib().bolt_ref_bias_act(M, N, _ptr(X), N, _ptr(bias), alpha, beta, ACT[act], _ptr(out), N)
+    return out
 
 
 def gemm(A, B, bias=None, alpha=1.0, beta=1.0, act="relu"):

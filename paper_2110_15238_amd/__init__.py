@@ -14,6 +14,7 @@ bolt_b2b_gemm = binding.b2b_gemm
 bolt_b2b_conv = binding.b2b_conv
 bolt_tune = binding.tune
 bolt_pad_channels_nhwc = binding.pad_channels_nhwc
+bolt_bias_act = binding.bias_act
 bolt_workspace_bytes = binding.workspace_bytes
 bolt_check = binding.check
 bolt_status_string = binding.status_string

@@ -89,13 +89,15 @@ _lib.bolt_tune.argtypes = [C.c_int, _vp, _vp, C.POINTER(_vp), _vp, _sz, _vp, C.P
                            C.POINTER(C.c_float), C.POINTER(_i32)]
 _lib.bolt_pad_channels_nhwc.restype = C.c_int
 _lib.bolt_pad_channels_nhwc.argtypes = [_vp, _vp, C.c_int64, _i32, _i32, _vp]
+_lib.bolt_bias_act.restype = C.c_int
+_lib.bolt_bias_act.argtypes = [_vp, _vp, C.c_int64, _i32, _i32, C.c_float, C.c_float, C.c_int, _vp]
 _lib.bolt_probe_mfma_peak.restype = C.c_int
 _lib.bolt_probe_mfma_peak.argtypes = [_i32, _vp, C.POINTER(C.c_float)]
 _lib.bolt_probe_copy_bandwidth.restype = C.c_int
 _lib.bolt_probe_copy_bandwidth.argtypes = [_vp, _sz, _i32, _vp, C.POINTER(C.c_float)]
 
 EXPORTED = ["bolt_gemm_epilogue", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune",
-            "bolt_pad_channels_nhwc", "bolt_workspace_bytes", "bolt_check", "bolt_status_string",
+            "bolt_pad_channels_nhwc", "bolt_bias_act", "bolt_workspace_bytes", "bolt_check", "bolt_status_string",
             "bolt_num_instances", "bolt_instance_config", "bolt_instance_supports", "bolt_probe_mfma_peak",
             "bolt_probe_copy_bandwidth"]
 
@@ -240,6 +242,15 @@ def pad_channels_nhwc(src, dst, C_padded: int):
     _check(_lib.bolt_pad_channels_nhwc(_ptr(src), _ptr(dst), pixels, Cin, C_padded, _stream()),
            "bolt_pad_channels_nhwc")
     return dst
+
+
+def bias_act(D, bias=None, alpha: float = 1.0, beta: float = 1.0, act="relu"):
+    """In place on a 2-D FP16 tensor (row stride = its stride(0)): D = act(alpha * D + beta * bias)."""
+    M, N = D.shape
+    a = ACT[act] if isinstance(act, str) else int(act)
+    _check(_lib.bolt_bias_act(_ptr(D), _ptr(bias), M, N, D.stride(0) if M > 1 else N, alpha, beta, a, _stream()),
+           "bolt_bias_act")
+    return D
 
 
 def probe_mfma_peak(iterations: int = 20000) -> float:

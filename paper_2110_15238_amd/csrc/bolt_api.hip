@@ -60,6 +60,26 @@ __global__ __launch_bounds__(256) void pad_channels_kernel(const half_t* src, ha
   }
 }
 
+// Stand-alone epilogue (the un-fused baseline of Section 4.1.1): one thread rewrites one 16-byte
+// chunk of D in place, D = act(alpha * D + beta * bias[n]).  ldd and N are multiples of 8.
+__global__ __launch_bounds__(256) void bias_act_kernel(half_t* D, const half_t* bias, int64_t M, int N, int ldd,
+                                                       float alpha, float beta, int act) {
+  const int chunks = N / 8;
+  const int64_t total = M * chunks;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t m = i / chunks;
+    const int n0 = (int)(i - m * chunks) * 8;
+    half8* p = (half8*)(D + m * ldd + n0);
+    const half8 v = *p;
+    half8 b = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (bias) b = *(const half8*)(bias + n0);
+    half8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (half_t)apply_act(alpha * (float)v[e] + beta * (float)b[e], act);
+    *p = o;
+  }
+}
+
 // MFMA-only loop: 4 independent accumulator chains per wave, no memory traffic.
 __global__ __launch_bounds__(256) void mfma_peak_kernel(float* sink, int iters) {
   half8 a, b;
@@ -847,6 +867,19 @@ bolt_status bolt_pad_channels_nhwc(const void* src, void* dst, int64_t pixels, i
   const int blocks = (int)std::min<int64_t>((total + 255) / 256, kNumCU * 16);
   hipLaunchKernelGGL(pad_channels_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const half_t*)src,
                      (half_t*)dst, pixels, C, C_padded);
+  return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+}
+
+bolt_status bolt_bias_act(void* D, const void* bias, int64_t M, int32_t N, int32_t ldd, float alpha, float beta,
+                          bolt_act act, void* stream) {
+  if (M < 0 || N <= 0 || ldd < N || (M > 0 && !D)) return BOLT_ERR_INVALID_ARG;
+  if ((int)act < (int)BOLT_ACT_NONE || (int)act > (int)BOLT_ACT_SOFTPLUS) return BOLT_ERR_INVALID_ARG;
+  if ((N & 7) || (ldd & 7) || !is_aligned16(D) || (bias && !is_aligned16(bias))) return BOLT_ERR_ALIGNMENT;
+  if (M == 0) return BOLT_OK;
+  const int64_t total = M * (N / 8);
+  const int blocks = (int)std::min<int64_t>((total + 255) / 256, kNumCU * 16);
+  hipLaunchKernelGGL(bias_act_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (half_t*)D,
+                     (const half_t*)bias, M, N, ldd, alpha, beta, (int)act);
   return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
 }
 

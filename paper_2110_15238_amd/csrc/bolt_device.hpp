@@ -41,24 +41,70 @@ __device__ __forceinline__ int lds_chunk_offset(int row, int chunk) {
   }
 }
 
-// The transcendental activations are kept out of line so that the fully unrolled epilogues stay
-// small; ReLU and "none" cost one compare.
-__device__ __attribute__((noinline)) float apply_act_slow(float v, int act) {
+// Transcendental activations in FP32 with the hardware exp2 / log2 / rcp units.  Their relative error
+// (below 1e-5) is far under half an FP16 ulp (4.9e-4), the rounding the result gets anyway.
+//
+// GELU = v * Phi(v), Phi(v) = erfc(-v / sqrt 2) / 2.  With z = |v| / sqrt 2 and t = 1 / (1 + z / 2),
+// erfc(z) = t * Q(t) * exp(-z^2), where Q is a degree-7 polynomial fitted (Chebyshev nodes on t in
+// (0, 1], float64 scaled-erfc as the target) to 4.6e-6 relative error.  This form has no cancellation in
+// the negative tail, where 1 + erf(v / sqrt 2) would lose every digit.
+__device__ __forceinline__ float gelu_fast(float v) {
+  const float z = fabsf(v) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(1.f + 0.5f * z);
+  float q = 4.458448196e-02f;
+  q = q * t + -8.891160022e-02f;
+  q = q * t + -6.914768965e-02f;
+  q = q * t + 1.436112067e-01f;
+  q = q * t + 1.560333553e-01f;
+  q = q * t + 2.497963131e-01f;
+  q = q * t + 2.819394284e-01f;
+  q = q * t + 2.820960852e-01f;
+  const float h = 0.5f * t * q * __builtin_amdgcn_exp2f(z * z * -1.44269504088896340736f);  // erfc(z) / 2
+  return v * (v < 0.f ? h : 1.f - h);
+}
+
+// softplus = max(v, 0) + log1p(e), e = exp(-|v|) in (0, 1]: three series terms while e is small (the
+// sum 1 + e would round e away), the log2 unit otherwise.
+__device__ __forceinline__ float softplus_fast(float v) {
+  const float e = __builtin_amdgcn_exp2f(fabsf(v) * -1.44269504088896340736f);
+  const float series = e * (1.f + e * (-0.5f + e * 0.33333333333f));
+  const float direct = __builtin_amdgcn_logf(1.f + e) * 0.69314718055994530942f;
+  return fmaxf(v, 0.f) + (e < 0.015625f ? series : direct);
+}
+
+__device__ __forceinline__ float hardswish_fast(float v) {
+  return v * fminf(fmaxf(v + 3.f, 0.f), 6.f) * (1.f / 6.f);
+}
+
+// The fully unrolled epilogues call this once per 4 outputs; out of line so that they stay small.
+// act is wave-uniform: the switch is scalar branches.
+__device__ __attribute__((noinline)) floatx4 apply_act_slow4(floatx4 v, int act) {
   switch (act) {
-    case ACT_GELU: return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
-    case ACT_HARDSWISH: {
-      float t = fminf(fmaxf(v + 3.f, 0.f), 6.f);
-      return v * t * (1.f / 6.f);
-    }
-    case ACT_SOFTPLUS: return v > 0.f ? v + log1pf(__expf(-v)) : log1pf(__expf(v));
-    default: return v;
+    case ACT_GELU:
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = gelu_fast(v[e]);
+      break;
+    case ACT_HARDSWISH:
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = hardswish_fast(v[e]);
+      break;
+    case ACT_SOFTPLUS:
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = softplus_fast(v[e]);
+      break;
+    default: break;
   }
+  return v;
 }
 
 __device__ __forceinline__ float apply_act(float v, int act) {
-  if (act == ACT_RELU) return v > 0.f ? v : 0.f;
-  if (act > ACT_RELU) return apply_act_slow(v, act);
-  return v;
+  switch (act) {
+    case ACT_RELU: return v > 0.f ? v : 0.f;
+    case ACT_GELU: return gelu_fast(v);
+    case ACT_HARDSWISH: return hardswish_fast(v);
+    case ACT_SOFTPLUS: return softplus_fast(v);
+    default: return v;
+  }
 }
 
 // Fused epilogue arithmetic (Section 3.1, patterns (i)-(iii)) for one quad of an accumulator
@@ -80,17 +126,20 @@ template <bool SLOW>
 __device__ __forceinline__ half4 epilogue_quad(const floatx16& acc, int q, int n, const EpilogueArgs& ep) {
   const half4 hb = *(const half4*)(ep.bias + (n < ep.N ? n : 0) * ep.bias_on);
   half4 o;
+  floatx4 v;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    float v = ep.alpha * acc[q * 4 + e] + ep.beta * (float)hb[e];
-    if constexpr (SLOW) {
-      v = apply_act_slow(v, ep.act);
-    } else {
-      const float r = v > 0.f ? v : 0.f;
-      v = ep.act == ACT_RELU ? r : v;
+  for (int e = 0; e < 4; ++e) v[e] = ep.alpha * acc[q * 4 + e] + ep.beta * (float)hb[e];
+  if constexpr (SLOW) {
+    v = apply_act_slow4(v, ep.act);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float r = v[e] > 0.f ? v[e] : 0.f;
+      v[e] = ep.act == ACT_RELU ? r : v[e];
     }
-    o[e] = (half_t)v;
   }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (half_t)v[e];
   return o;
 }
 

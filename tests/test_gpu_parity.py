@@ -508,6 +508,36 @@ def test_config5_layer_full_size_tuned_sampled(bolt, index):
     assert_close(got[idx], want, "config5 layer %d" % index)
 
 
+@pytest.mark.parametrize("act", ["none", "relu", "gelu", "hardswish", "softplus"])
+def test_bias_act_standalone_epilogue(bolt, act):
+    # several grid strides plus a ragged last block; with and without a bias; also M = 1 and M = 0
+    for (M, N, seed) in [(1030, 136, 61), (1, 8, 62), (4099, 3072, 63)]:
+        _say(f"bias_act act={act} M={M} N={N}")
+        x = wl.uniform_fp16(seed, 0, (M, N), -6, 6)
+        b = wl.uniform_fp16(seed, 1, (N,), -2, 2)
+        for bias, alpha, beta in [(b, 0.75, -1.5), (None, 1.0, 1.0)]:
+            D = dev(x).clone()
+            bolt.bolt_bias_act(D, dev(bias), alpha, beta, act)
+            torch.cuda.synchronize()
+            assert_close(host(D), ref.bias_act(x, bias, alpha, beta, act), f"bias_act {act} {M}x{N}")
+    empty = torch.empty((0, 16), dtype=torch.float16, device="cuda")
+    bolt.bolt_bias_act(empty, None, 1.0, 1.0, act)
+
+
+def test_unfused_gemm_plus_bias_act_matches_fused_on_integers(bolt):
+    A = wl.integer_fp16(64, 0, (300, 72), -3, 3)
+    B = wl.integer_fp16(64, 1, (72, 136), -3, 3)
+    bias = wl.integer_fp16(64, 2, (136,), -4, 4)
+    fused, _ = _run_gemm(bolt, A, B, bias, act="relu")
+    d = bolt.gemm_desc(300, 136, 72, act="none")
+    D = torch.empty((300, 136), dtype=torch.float16, device="cuda")
+    bolt.bolt_gemm_epilogue(d, dev(A), dev(B), None, D)
+    bolt.bolt_bias_act(D, dev(bias), 1.0, 1.0, "relu")
+    torch.cuda.synchronize()
+    assert_bit_equal(host(D), fused, "unfused vs fused")
+    assert_bit_equal(fused, ref.gemm(A, B, bias), "fused vs oracle")
+
+
 def test_tune_is_cached_and_probes_run(bolt):
     M, N, K = 512, 256, 256
     A, B = dev(wl.uniform_fp16(601, 0, (M, K), -1, 1)), dev(wl.uniform_fp16(601, 1, (K, N), -1, 1))

@@ -140,4 +140,8 @@ def test_null_pointers_are_rejected_before_any_launch(bolt):
     assert lib.bolt_pad_channels_nhwc(None, None, 4, 3, 8, None) == INVALID
     assert lib.bolt_pad_channels_nhwc(16, 32, 4, 3, 7, None) == ALIGNMENT
     assert lib.bolt_pad_channels_nhwc(16, 32, 4, 9, 8, None) == INVALID
+    assert lib.bolt_bias_act(None, None, 4, 8, 8, 1.0, 1.0, 1, None) == INVALID
+    assert lib.bolt_bias_act(32, None, 4, 12, 16, 1.0, 1.0, 1, None) == ALIGNMENT
+    assert lib.bolt_bias_act(32, None, 4, 16, 8, 1.0, 1.0, 1, None) == INVALID    # ldd < N
+    assert lib.bolt_bias_act(32, None, 4, 8, 8, 1.0, 1.0, 9, None) == INVALID     # unknown activation
     assert lib.bolt_tune(0, None, None, None, None, 0, None, None, None, None) == INVALID

@@ -403,6 +403,38 @@ def test_activation_closed_forms(act):
     assert np.all(np.abs(got - want) <= 0.5 * ulp * (1 + 1e-6) + 1e-300)
 
 
+@pytest.mark.parametrize("act", ["none", "relu", "gelu", "hardswish", "softplus"])
+def test_bias_act_closed_forms_with_alpha_beta(act):
+    # the stand-alone epilogue pass (Section 4.1.1's un-fused baseline): every finite-range half in a
+    # column strip, per-column bias, alpha/beta exactly representable so the affine part is exact in fp64
+    M, N = 96, 16
+    x = wl.uniform_fp16(31, 0, (M, N), -6, 6)
+    b = wl.uniform_fp16(31, 1, (N,), -2, 2)
+    alpha, beta = 0.75, -1.5
+    got = ref.bias_act(x, b, alpha, beta, act).astype(np.float64)
+    t = alpha * x.astype(np.float64) + beta * b.astype(np.float64)[None, :]
+    want = {"none": t, "relu": np.maximum(t, 0), "gelu": 0.5 * t * (1 + np.vectorize(math.erf)(t / math.sqrt(2))),
+            "hardswish": t * np.clip(t + 3, 0, 6) / 6, "softplus": np.logaddexp(0, t)}[act]
+    ulp = np.spacing(np.abs(want).astype(np.float16)).astype(np.float64)
+    assert np.all(np.abs(got - want) <= 0.5 * ulp * (1 + 1e-6) + 1e-300)
+    # no bias pointer: the beta term vanishes; a transposed bias index would break the per-column check above
+    nb = ref.bias_act(x, None, alpha, 123.0, "none").astype(np.float64)
+    assert np.array_equal(nb, (alpha * x.astype(np.float64)).astype(np.float16).astype(np.float64))
+
+
+def test_unfused_epilogue_equals_fused_on_integer_inputs():
+    # with small integers nothing rounds, so GEMM(act none, no bias) followed by the stand-alone pass must
+    # reproduce the fused GEMM bit for bit
+    A = wl.integer_fp16(32, 0, (40, 24), -3, 3)
+    B = wl.integer_fp16(32, 1, (24, 16), -3, 3)
+    bias = wl.integer_fp16(32, 2, (16,), -4, 4)
+    fused = ref.gemm(A, B, bias, 1.0, 1.0, "relu")
+    plain = ref.gemm(A, B, None, 1.0, 1.0, "none")
+    assert np.array_equal(ref.bias_act(plain, bias, 1.0, 1.0, "relu"), fused)
+    assert np.array_equal(fused.astype(np.float64),
+                          np.maximum(A.astype(np.float64) @ B.astype(np.float64) + bias.astype(np.float64), 0))
+
+
 # --------------------------------------------------------------------------------------------
 # workload tables
 # --------------------------------------------------------------------------------------------
