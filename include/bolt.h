@@ -18,7 +18,10 @@
  *     FP16 with round-to-nearest-even.
  *   - Alignment (Section 3.2.3, "Kernel padding"): 128-bit accesses need every channel count,
  *     reduction length and leading dimension to be a multiple of 8, else BOLT_ERR_ALIGNMENT;
- *     pad with bolt_pad_channels_nhwc first.
+ *     pad with bolt_pad_channels_nhwc first.  The one exception is the input channel count of
+ *     bolt_conv2d_fprop_nhwc: an even C that is not a multiple of 8 is accepted and runs on slow
+ *     alignment-2 kernels (32-bit accesses), the "unpadded" case that Table 3 measures padding
+ *     against.  An odd C is BOLT_ERR_ALIGNMENT.
  */
 #ifndef BOLT_H_
 #define BOLT_H_
@@ -108,8 +111,8 @@ bolt_status bolt_gemm_epilogue(const bolt_gemm_desc* desc, const void* A, const 
                                const bolt_config* config, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Implicit-GEMM NHWC forward convolution + fused epilogue (Section 3.2.3: NHWC only; workloads of
- * Section 4.1.1).  x: N*H*W*C, w: K*R*S*C, bias: K halves or NULL, y: N*P*Q*K.  Requires C and K
- * multiples of 8. */
+ * Section 4.1.1).  x: N*H*W*C, w: K*R*S*C, bias: K halves or NULL, y: N*P*Q*K.  Requires K a
+ * multiple of 8 and C even; C a multiple of 8 for the fast (128-bit) kernels. */
 bolt_status bolt_conv2d_fprop_nhwc(const bolt_conv_desc* desc, const void* x, const void* w, const void* bias,
                                    void* y, const bolt_config* config, void* workspace, size_t workspace_bytes,
                                    void* stream);
@@ -144,7 +147,8 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
                       size_t workspace_bytes, void* stream, bolt_config* best, float* best_ms, int32_t* n_tried);
 
 /* dst[p, 0:C] = src[p, 0:C], dst[p, C:C_padded] = 0 for p < pixels (Section 3.2.3, Kernel
- * padding).  C_padded >= C, C_padded % 8 == 0. src and dst must not overlap. */
+ * padding).  C_padded >= C, C_padded % 8 == 0, pixels * C_padded < 2^34 (else BOLT_ERR_UNSUPPORTED).
+ * src and dst must not overlap. */
 bolt_status bolt_pad_channels_nhwc(const void* src, void* dst, int64_t pixels, int32_t C, int32_t C_padded,
                                    void* stream);
 

@@ -111,16 +111,31 @@ def raw():
     return _lib
 
 
-def _stream() -> int:
+_torch = None
+_raw_stream = None
+
+
+def _load_torch():
+    global _torch, _raw_stream
     import torch
+    _torch = torch
+    # the raw-handle query skips building a Stream object (about a microsecond per call)
+    _raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+    return torch
+
+
+def _stream() -> int:
+    torch = _torch or _load_torch()
+    if _raw_stream is not None:
+        return _raw_stream(torch.cuda.current_device())
     return int(torch.cuda.current_stream().cuda_stream)
 
 
 def _ptr(t) -> Optional[int]:
     if t is None:
         return None
-    import torch
-    assert t.is_cuda and t.dtype == torch.float16 and t.is_contiguous(), "expects contiguous CUDA float16 tensors"
+    torch = _torch or _load_torch()
+    assert t.is_cuda and t.dtype is torch.float16 and t.is_contiguous(), "expects contiguous CUDA float16 tensors"
     return t.data_ptr()
 
 

@@ -45,18 +45,28 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial
   }
 }
 
-// Kernel padding (Section 3.2.3): one thread writes one 16-byte chunk of the padded tensor.
-__global__ __launch_bounds__(256) void pad_channels_kernel(const half_t* src, half_t* dst, int64_t pixels, int C,
-                                                           int C8) {
+// Kernel padding (Section 3.2.3): one thread writes one 16-byte chunk of the padded tensor.  An even
+// channel count is read as 32-bit pairs (a pair never straddles the end of a pixel), an odd one half
+// by half.  The host guarantees pixels * C8 / 8 < 2^31.
+template <bool EVEN>
+__global__ __launch_bounds__(256) void pad_channels_kernel(const half_t* src, half_t* dst, int pixels, int C, int C8) {
   const int chunks = C8 / 8;
-  const int64_t total = pixels * chunks;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-    const int64_t pix = i / chunks;
-    const int c0 = (int)(i - pix * chunks) * 8;
+  const int total = pixels * chunks;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    const int pix = i / chunks;
+    const int c0 = (i - pix * chunks) * 8;
+    const half_t* s = src + (int64_t)pix * C + c0;
     half8 v;
+    if constexpr (EVEN) {
+      uintx4 u;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = (c0 + e < C) ? src[pix * C + c0 + e] : (half_t)0.f;
-    *(half8*)(dst + pix * C8 + c0) = v;
+      for (int e = 0; e < 4; ++e) u[e] = (c0 + 2 * e < C) ? *(const unsigned*)(s + 2 * e) : 0u;
+      v = __builtin_bit_cast(half8, u);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (c0 + e < C) ? s[e] : (half_t)0.f;
+    }
+    *(half8*)(dst + (int64_t)pix * C8 + c0) = v;
   }
 }
 
@@ -128,6 +138,7 @@ struct Tables {
     register_conv_stream_instances(conv);
     register_conv_halo_instances(conv);
     register_gemm_nk_instances(conv);  // for 1x1 / stride 1 / pad 0 filters
+    register_conv_align2_instances(conv);  // even channel counts that are not multiples of 8
     register_b2b_gemm_instances(b2b_gemm);
     register_b2b_gemm_stream_instances(b2b_gemm);
     register_b2b_gemm_dma_instances(b2b_gemm);
@@ -172,7 +183,8 @@ static bolt_status check_conv_desc(const bolt_conv_desc* d, ConvDims* out) {
   if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return BOLT_ERR_INVALID_ARG;
   if (!valid_act(d->act)) return BOLT_ERR_INVALID_ARG;
   if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return BOLT_ERR_INVALID_ARG;
-  if ((d->C | d->K) & 7) return BOLT_ERR_ALIGNMENT;
+  // C % 8 == 0 is the fast path (128-bit accesses); an even C runs on the alignment-2 instances
+  if ((d->K & 7) || (d->C & 1)) return BOLT_ERR_ALIGNMENT;
   const int64_t P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
   const int64_t Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
   const int64_t M = (int64_t)d->N * P * Q;
@@ -214,6 +226,7 @@ static bolt_status check_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc
   if (s != BOLT_OK) return s;
   s = check_conv_desc(c1, &d1);
   if (s != BOLT_OK) return s;
+  if (c0->C & 7) return BOLT_ERR_ALIGNMENT;  // the fused kernels have no alignment-2 form
   if (c1->R != 1 || c1->S != 1 || c1->stride_h != 1 || c1->stride_w != 1 || c1->pad_h != 0 || c1->pad_w != 0)
     return BOLT_ERR_ILLEGAL_FUSION;
   if (c1->C != c0->K || c1->N != c0->N || c1->H != d0.P || c1->W != d0.Q) return BOLT_ERR_ILLEGAL_FUSION;
@@ -364,6 +377,7 @@ static bolt_status make_conv_problem(const bolt_conv_desc* d, FpropProblem* pr) 
     pr->xmode = 0;
     p.ldx = d->C;
   }
+  if (d->C & 7) pr->xmode = pr->wmode = 2;  // alignment 2 (Section 3.2.3): the unpadded kernels
   return BOLT_OK;
 }
 
@@ -864,9 +878,12 @@ bolt_status bolt_pad_channels_nhwc(const void* src, void* dst, int64_t pixels, i
   if (!is_aligned16(dst)) return BOLT_ERR_ALIGNMENT;
   if (pixels == 0) return BOLT_OK;
   const int64_t total = pixels * (C_padded / 8);
+  if (total >= (1ll << 31)) return BOLT_ERR_UNSUPPORTED;
   const int blocks = (int)std::min<int64_t>((total + 255) / 256, kNumCU * 16);
-  hipLaunchKernelGGL(pad_channels_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const half_t*)src,
-                     (half_t*)dst, pixels, C, C_padded);
+  // 32-bit reads need an even channel count and a 4-byte aligned source
+  const bool even = !(C & 1) && !((uintptr_t)src & 3);
+  hipLaunchKernelGGL(even ? pad_channels_kernel<true> : pad_channels_kernel<false>, dim3(blocks), dim3(256), 0,
+                     (hipStream_t)stream, (const half_t*)src, (half_t*)dst, (int)pixels, C, C_padded);
   return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
 }
 

@@ -14,6 +14,7 @@ typedef half_t half2v __attribute__((ext_vector_type(2)));
 typedef half_t half4 __attribute__((ext_vector_type(4)));
 typedef half_t half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2, ACT_HARDSWISH = 3, ACT_SOFTPLUS = 4 };

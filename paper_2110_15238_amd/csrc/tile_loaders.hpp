@@ -3,8 +3,10 @@
 // Every operand tile lands in LDS as [rows][BK] halves with K contiguous and the 16-byte chunk
 // swizzle of lds_chunk_offset<BK>.  Global accesses are 128-bit (8 halves), which is why channel
 // counts and leading dimensions must be multiples of 8 ("alignment 8" of Section 3.2.3, Kernel
-// padding).  A tile is fetched into registers first (load) and written to LDS later (store) so the
-// fetch of tile k+1 overlaps the MFMA work on tile k.
+// padding); the alignment-2 modes fetch the same chunks as four 32-bit pairs and only need even
+// channel counts: they are the slow "unpadded" kernels that padding is measured against (Table 3).
+// A tile is fetched into registers first (load) and written to LDS later (store) so the fetch of
+// tile k+1 overlaps the MFMA work on tile k.
 #pragma once
 #include "bolt_device.hpp"
 
@@ -18,6 +20,8 @@ struct ConvGeom {
 //   XMODE 0: rows of a row-major matrix with leading dimension ld.
 //   XMODE 1: implicit im2col of an NHWC tensor: row m = (img, p, q), column k = (r, s, c); taps
 //            outside the image read as zero.  Needs C % 8 == 0 so a chunk never straddles a tap.
+//   XMODE 2: the same view for C % 2 == 0 (alignment 2): every pair of halves has its own tap,
+//            bounds test and 32-bit load.
 template <int ROWS, int BK, int NT, int XMODE>
 struct XTileLoader {
   static constexpr int CH = BK / 8;
@@ -26,8 +30,8 @@ struct XTileLoader {
   static_assert(ROWS % RP == 0 && PASSES >= 1, "tile rows must be a multiple of the rows one pass covers");
 
   half8 r[PASSES];
-  int xbase[XMODE == 1 ? PASSES : 1];
-  int xhw[XMODE == 1 ? PASSES : 1];
+  int xbase[XMODE != 0 ? PASSES : 1];
+  int xhw[XMODE != 0 ? PASSES : 1];
   int cr, cs, cc;
   const half_t* g;
   int ld, rows_valid, K, lc, lr;
@@ -79,12 +83,38 @@ struct XTileLoader {
         r[i] = (row < rows_valid && k < K) ? *(const half8*)(g + (int64_t)row * ld + k) : zero8;
       }
     } else {
-      const int delta = (cr * cg.Wi + cs) * cg.C + cc;
+      if constexpr (XMODE == 1) {
+        const int delta = (cr * cg.Wi + cs) * cg.C + cc;
 #pragma unroll
-      for (int i = 0; i < PASSES; ++i) {
-        const int ih = (xhw[i] >> 16) + cr, iw = (int)(short)(xhw[i] & 0xffff) + cs;
-        const bool ok = k < K && (unsigned)ih < (unsigned)cg.H && (unsigned)iw < (unsigned)cg.Wi;
-        r[i] = ok ? *(const half8*)(g + (xbase[i] + delta)) : zero8;
+        for (int i = 0; i < PASSES; ++i) {
+          const int ih = (xhw[i] >> 16) + cr, iw = (int)(short)(xhw[i] & 0xffff) + cs;
+          const bool ok = k < K && (unsigned)ih < (unsigned)cg.H && (unsigned)iw < (unsigned)cg.Wi;
+          r[i] = ok ? *(const half8*)(g + (xbase[i] + delta)) : zero8;
+        }
+      } else {
+        uintx4 v[PASSES];
+        int pr = cr, ps = cs, pc = cc;  // tap of the current pair
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int delta = (pr * cg.Wi + ps) * cg.C + pc;
+          const bool k_ok = k + 2 * j < K;
+#pragma unroll
+          for (int i = 0; i < PASSES; ++i) {
+            const int ih = (xhw[i] >> 16) + pr, iw = (int)(short)(xhw[i] & 0xffff) + ps;
+            const bool ok = k_ok && (unsigned)ih < (unsigned)cg.H && (unsigned)iw < (unsigned)cg.Wi;
+            v[i][j] = ok ? *(const unsigned*)(g + (xbase[i] + delta)) : 0u;
+          }
+          pc += 2;
+          if (pc >= cg.C) {  // C is even: a pair never straddles a tap
+            pc = 0;
+            if (++ps == cg.S) {
+              ps = 0;
+              ++pr;
+            }
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) r[i] = __builtin_bit_cast(half8, v[i]);
       }
       cc += BK;
       while (cc >= cg.C) {
@@ -107,17 +137,18 @@ struct XTileLoader {
 //   WMODE 0: source is [N][K] with leading dimension ld (K contiguous).
 //   WMODE 1: source is [K][N] with leading dimension ld (N contiguous): each thread fetches an
 //            8(k) x 8(n) block as 8 row chunks and writes its transpose as 8 column chunks.
+//   WMODE 2: as WMODE 0 with an even (not 8-divisible) ld and K: four 32-bit loads per chunk.
 template <int ROWS, int BK, int NT, int WMODE>
 struct WTileLoader {
   static constexpr int CH = BK / 8;
   static constexpr int RP = NT / CH;
-  static constexpr int PASSES = (ROWS + RP - 1) / RP;       // WMODE 0
+  static constexpr int PASSES = (ROWS + RP - 1) / RP;       // WMODE 0, 2
   static constexpr int NB = (BK / 8) * (ROWS / 8);          // WMODE 1: 8x8 blocks in the tile
   static constexpr int KP = (NB + NT - 1) / NT;
   static constexpr bool RAGGED0 = (ROWS % RP) != 0;
   static constexpr bool RAGGED1 = (NB % NT) != 0;
 
-  half8 r[WMODE == 0 ? PASSES : KP * 8];
+  half8 r[WMODE != 1 ? PASSES : KP * 8];
   const half_t* g;
   int ld, rows_valid, K, tid;
 
@@ -126,7 +157,7 @@ struct WTileLoader {
     K = K_;
     ld = ldw;
     rows_valid = N - n0;
-    g = (WMODE == 0) ? W + (int64_t)n0 * ldw : W + n0;
+    g = (WMODE != 1) ? W + (int64_t)n0 * ldw : W + n0;
   }
 
   __device__ __forceinline__ void load(int kt) {
@@ -139,6 +170,19 @@ struct WTileLoader {
         const int row = lr + i * RP;
         const bool ok = (!RAGGED0 || row < ROWS) && row < rows_valid && k < K;
         r[i] = ok ? *(const half8*)(g + (int64_t)row * ld + k) : zero8;
+      }
+    } else if constexpr (WMODE == 2) {
+      const int lc = tid % CH, lr = tid / CH;
+      const int k = kt * BK + lc * 8;
+#pragma unroll
+      for (int i = 0; i < PASSES; ++i) {
+        const int row = lr + i * RP;
+        const bool ok = (!RAGGED0 || row < ROWS) && row < rows_valid;
+        uintx4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          v[j] = (ok && k + 2 * j < K) ? *(const unsigned*)(g + (int64_t)row * ld + k + 2 * j) : 0u;
+        r[i] = __builtin_bit_cast(half8, v);
       }
     } else {
 #pragma unroll
@@ -156,7 +200,7 @@ struct WTileLoader {
   }
 
   __device__ __forceinline__ void store(half_t* dst) const {
-    if constexpr (WMODE == 0) {
+    if constexpr (WMODE != 1) {
       const int lc = tid % CH, lr = tid / CH;
 #pragma unroll
       for (int i = 0; i < PASSES; ++i) {

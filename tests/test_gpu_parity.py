@@ -196,6 +196,59 @@ def test_conv_every_instance_shape_sweep(bolt, case):
     assert ran >= 3
 
 
+# Even channel counts that are not multiples of 8 run on the alignment-2 instances (the unpadded side of
+# Table 3): that table's geometries at a small batch, plus C = 2, a strided 1x1 and non-square strides.
+ALIGN2_SWEEP = [(2,) + row[1:7] + (1, row[7]) for row in wl.TABLE3_PADDING] + [
+    (3, 9, 11, 2, 16, 3, 3, 1, 1),
+    (2, 14, 14, 46, 40, 1, 1, 2, 0),
+    (1, 10, 9, 10, 24, 5, 3, (1, 2), (2, 0)),
+    (1, 6, 6, 30, 72, 3, 3, 1, 1),
+    (1, 7, 7, 6, 8, 7, 7, 1, 3),
+]
+
+
+@pytest.mark.parametrize("case", ALIGN2_SWEEP)
+def test_conv_alignment2_every_instance(bolt, case):
+    N, H, W, Cc, K, R, S, stride, pad = case
+    x = wl.uniform_fp16(211, 0, (N, H, W, Cc), -1, 1)
+    w = wl.uniform_fp16(211, 1, (K, R, S, Cc), -1, 1)
+    bias = wl.uniform_fp16(211, 2, (K,), -1, 1)
+    want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_CONV2D)):
+        if not bolt.bolt_instance_supports(bolt.OP_CONV2D, kid, d):
+            continue
+        _say("align-2 conv case %s instance %d" % (case, kid))
+        got, _ = _run_conv(bolt, x, w, bias, stride, pad, config={"kernel_id": kid})
+        assert_close(got, want, "align-2 conv %s instance %d" % (case, kid))
+        ran += 1
+    assert ran >= 3
+    got, _ = _run_conv(bolt, x, w, bias, stride, pad)  # built-in pick rule
+    assert_close(got, want, "align-2 conv %s heuristic" % (case,))
+
+
+def test_conv_alignment2_integer_bit_exact_split_k_and_padding_equivalence(bolt):
+    N, H, W, Cc, K, R, S, stride, pad = 2, 10, 13, 46, 32, 5, 5, 1, 2
+    x = wl.integer_fp16(212, 0, (N, H, W, Cc), -2, 2)
+    w = wl.integer_fp16(212, 1, (K, R, S, Cc), -2, 2)
+    bias = wl.integer_fp16(212, 2, (K,), -3, 3)
+    want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
+    got, d = _run_conv(bolt, x, w, bias, stride, pad)
+    assert_bit_equal(got, want, "align-2 integer conv")
+    ws = torch.empty(bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d), dtype=torch.uint8, device="cuda")
+    kid = next(i for i in range(bolt.bolt_num_instances(bolt.OP_CONV2D)) if bolt.bolt_instance_supports(bolt.OP_CONV2D, i, d))
+    got, _ = _run_conv(bolt, x, w, bias, stride, pad, config={"kernel_id": kid, "split_k": 4}, workspace=ws)
+    assert_bit_equal(got, want, "align-2 integer conv, split-K 4")
+    # Table 3's two sides compute the same thing: unpadded on alignment 2 == padded to 48 on alignment 8
+    xp = torch.empty((N, H, W, 48), dtype=torch.float16, device="cuda")
+    wp = torch.empty((K, R, S, 48), dtype=torch.float16, device="cuda")
+    bolt.bolt_pad_channels_nhwc(dev(x), xp, 48)
+    bolt.bolt_pad_channels_nhwc(dev(w), wp, 48)
+    got_p, _ = _run_conv(bolt, host(xp), host(wp), bias, stride, pad)
+    assert_bit_equal(got_p, want, "padded integer conv")
+
+
 def test_conv_integer_inputs_bit_exact(bolt):
     N, H, W, Cc, K, R, S, stride, pad = 2, 13, 11, 8, 24, 3, 3, 1, 1
     x = wl.integer_fp16(202, 0, (N, H, W, Cc), -2, 2)

@@ -89,6 +89,15 @@ def test_conv_validation(bolt):
     assert chk(bolt.OP_CONV2D, Cd(32, 56, 56, 64, 64, 3, 3, 1, 1)) == OK
     assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 3, 64, 7, 7, 2, 3)) == ALIGNMENT   # C = 3 must be padded to 8
     assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 8, 64, 7, 7, 2, 3)) == OK
+    # an even C that is not a multiple of 8: legal, and only the alignment-2 instances take it
+    d46 = Cd(32, 20, 26, 46, 32, 3, 3, 1, 1)
+    assert chk(bolt.OP_CONV2D, d46) == OK
+    n = bolt.bolt_num_instances(bolt.OP_CONV2D)
+    a2 = [i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_CONV2D, i, d46)]
+    a8 = [i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_CONV2D, i, Cd(32, 20, 26, 48, 32, 3, 3, 1, 1))]
+    assert len(a2) >= 3 and a8 and not set(a2) & set(a8)
+    assert chk(bolt.OP_CONV2D, d46, None, {"kernel_id": a8[0]}) == UNSUPPORTED
+    assert chk(bolt.OP_B2B_CONV, d46, Cd(32, 20, 26, 32, 64, 1, 1, 1, 0)) == ALIGNMENT  # fused kernels need C % 8 == 0
     assert chk(bolt.OP_CONV2D, Cd(1, 8, 8, 8, 12, 3, 3, 1, 1)) == ALIGNMENT
     assert chk(bolt.OP_CONV2D, Cd(1, 2, 2, 8, 8, 3, 3, 1, 0)) == INVALID            # filter larger than image
     assert chk(bolt.OP_CONV2D, Cd(1, 8, 8, 8, 8, 3, 3, 0, 1)) == INVALID            # stride 0

@@ -237,3 +237,6 @@ TABLE2_B2B_CONV = [  # (H, IC, OC0, stride, OC1)
     (224, 3, 48, 2, 48), (112, 48, 48, 2, 48), (56, 48, 48, 1, 48),
     (224, 3, 64, 2, 64), (112, 64, 64, 2, 64), (56, 64, 64, 1, 64)]
 EPILOGUE_GEMM = GemmShape(1280, 3072, 768)
+TABLE3_PADDING = [  # (N, H, W, IC, OC, R, S, pad): stride 1, IC not divisible by 8
+    (32, 20, 26, 46, 32, 3, 3, 1), (32, 20, 26, 46, 32, 5, 5, 2), (128, 14, 19, 46, 32, 5, 7, 0),
+    (288, 11, 15, 46, 32, 5, 7, 0), (32, 20, 26, 174, 64, 3, 3, 1), (32, 20, 26, 174, 64, 5, 5, 2)]
