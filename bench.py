@@ -494,6 +494,73 @@ def main():
             entry["status"] = str(e)
         t3.append(entry)
     out["paper_table3_padding"] = t3
+
+    # ------------------------------------------------------------------ three-op chains (context)
+    # Section 3.1.1's extension to more than two ops: one launch against (a) three tuned single-op launches
+    # and (b) the tuned fused pair followed by the third op.  GEMM widths are those of Table 1's rows carried
+    # one layer further; the convolutions are a 3x3 followed by two 1x1 (Section 3.3's deepening), batch 32.
+    chains = []
+    for (M, K0, N0, N1, N2) in ((16384, 256, 64, 128, 64), (32768, 576, 128, 64, 64), (128320, 96, 32, 96, 32)):
+        entry = dict(name="GEMM chain M=%d %d->%d->%d->%d" % (M, K0, N0, N1, N2))
+        try:
+            nk = bolt.LAYOUT_NK
+            A, Wc, bc = rnd(M, K0), [rnd(N0, K0, scale=0.1), rnd(N1, N0, scale=0.1), rnd(N2, N1, scale=0.1)], [rnd(N0), rnd(N1), rnd(N2)]
+            gd = [bolt.gemm_desc(M, N0, K0, b_layout=nk), bolt.gemm_desc(M, N1, N0, b_layout=nk), bolt.gemm_desc(M, N2, N1, b_layout=nk)]
+            Da, Db, Dc, Dp, Df = empty(M, N0), empty(M, N1), empty(M, N2), empty(M, N1), empty(M, N2)
+            cf = bolt.bolt_tune_chain(bolt.OP_GEMM_CHAIN3, gd, [A, Wc[0], bc[0], Wc[1], bc[1], Wc[2], bc[2], Df]).config
+            c0 = tuned(entry["name"] + " op0", bolt.OP_GEMM, gd[0], None, [A, Wc[0], bc[0], Da], ws)
+            c1 = tuned(entry["name"] + " op1", bolt.OP_GEMM, gd[1], None, [Da, Wc[1], bc[1], Db], ws)
+            c2 = tuned(entry["name"] + " op2", bolt.OP_GEMM, gd[2], None, [Db, Wc[2], bc[2], Dc], ws)
+            cp = tuned(entry["name"] + " pair", bolt.OP_B2B_GEMM, gd[0], gd[1], [A, Wc[0], bc[0], Wc[1], bc[1], Dp])
+
+            def three():
+                bolt.bolt_gemm_epilogue(gd[0], A, Wc[0], bc[0], Da, c0, ws)
+                bolt.bolt_gemm_epilogue(gd[1], Da, Wc[1], bc[1], Db, c1, ws)
+                bolt.bolt_gemm_epilogue(gd[2], Db, Wc[2], bc[2], Dc, c2, ws)
+
+            def pair_then_one():
+                bolt.bolt_b2b_gemm(gd[0], gd[1], A, Wc[0], bc[0], Wc[1], bc[1], Dp, cp)
+                bolt.bolt_gemm_epilogue(gd[2], Dp, Wc[2], bc[2], Dc, c2, ws)
+            mf = timed(lambda: bolt.bolt_b2b_gemm_chain(gd, A, Wc, bc, Df, cf), args.reps)
+            m3, m2 = timed(three, args.reps), timed(pair_then_one, args.reps)
+            entry.update(fused_ms=round(mf, 5), three_launches_ms=round(m3, 5), pair_plus_one_ms=round(m2, 5),
+                         speedup_vs_three=round(m3 / mf, 3), speedup_vs_pair_plus_one=round(m2 / mf, 3))
+        except bolt.BoltError as e:
+            entry["status"] = str(e)
+        chains.append(entry)
+    for (H, IC, OC, st) in ((56, 64, 64, 1), (112, 48, 48, 2), (224, 3, 64, 2)):
+        entry = dict(name="conv chain %dx%d IC=%d 3x3/%d -> 1x1 -> 1x1, OC=%d" % (H, H, IC, st, OC))
+        try:
+            ic = pad8(IC)
+            x, wc = rnd(32, H, H, ic), [rnd(OC, 3, 3, ic, scale=0.1), rnd(OC, 1, 1, OC, scale=0.1), rnd(OC, 1, 1, OC, scale=0.1)]
+            bc = [rnd(OC), rnd(OC), rnd(OC)]
+            d0 = bolt.conv_desc(32, H, H, ic, OC, 3, 3, st, 1)
+            P, Q = bolt.conv_out_hw(d0)
+            cd = [d0, bolt.conv_desc(32, P, Q, OC, OC, 1, 1, 1, 0), bolt.conv_desc(32, P, Q, OC, OC, 1, 1, 1, 0)]
+            ya, yb, yc, yp, yf = (empty(32, P, Q, OC) for _ in range(5))
+            cf = bolt.bolt_tune_chain(bolt.OP_CONV_CHAIN3, cd, [x, wc[0], bc[0], wc[1], bc[1], wc[2], bc[2], yf]).config
+            c0 = tuned(entry["name"] + " op0", bolt.OP_CONV2D, cd[0], None, [x, wc[0], bc[0], ya], ws)
+            c1 = tuned(entry["name"] + " op1", bolt.OP_CONV2D, cd[1], None, [ya, wc[1], bc[1], yb], ws)
+            c2 = tuned(entry["name"] + " op2", bolt.OP_CONV2D, cd[2], None, [yb, wc[2], bc[2], yc], ws)
+            cp = tuned(entry["name"] + " pair", bolt.OP_B2B_CONV, cd[0], cd[1], [x, wc[0], bc[0], wc[1], bc[1], yp])
+
+            def three_c():
+                bolt.bolt_conv2d_fprop_nhwc(cd[0], x, wc[0], bc[0], ya, c0, ws)
+                bolt.bolt_conv2d_fprop_nhwc(cd[1], ya, wc[1], bc[1], yb, c1, ws)
+                bolt.bolt_conv2d_fprop_nhwc(cd[2], yb, wc[2], bc[2], yc, c2, ws)
+
+            def pair_then_one_c():
+                bolt.bolt_b2b_conv(cd[0], cd[1], x, wc[0], bc[0], wc[1], bc[1], yp, cp)
+                bolt.bolt_conv2d_fprop_nhwc(cd[2], yp, wc[2], bc[2], yc, c2, ws)
+            mf = timed(lambda: bolt.bolt_b2b_conv_chain(cd, x, wc, bc, yf, cf), args.reps)
+            m3, m2 = timed(three_c, args.reps), timed(pair_then_one_c, args.reps)
+            entry.update(fused_ms=round(mf, 5), three_launches_ms=round(m3, 5), pair_plus_one_ms=round(m2, 5),
+                         speedup_vs_three=round(m3 / mf, 3), speedup_vs_pair_plus_one=round(m2 / mf, 3))
+            del x, ya, yb, yc, yp, yf
+        except bolt.BoltError as e:
+            entry["status"] = str(e)
+        chains.append(entry)
+    out["chains_of_three"] = chains
     try:
         out["probes"] = {"mfma_loop_tflops": round(bolt.bolt_probe_mfma_peak(20000), 1),
                          "copy_gbs_1GiB": round(bolt.bolt_probe_copy_bandwidth(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"), 5), 1)}

@@ -52,7 +52,14 @@ typedef enum {
   BOLT_ACT_SOFTPLUS = 4    /* log(1 + exp v)               */
 } bolt_act;
 
-typedef enum { BOLT_OP_GEMM = 0, BOLT_OP_CONV2D = 1, BOLT_OP_B2B_GEMM = 2, BOLT_OP_B2B_CONV = 3 } bolt_op;
+typedef enum {
+  BOLT_OP_GEMM = 0,
+  BOLT_OP_CONV2D = 1,
+  BOLT_OP_B2B_GEMM = 2,
+  BOLT_OP_B2B_CONV = 3,
+  BOLT_OP_GEMM_CHAIN3 = 4, /* three GEMMs fused (the *_chain entry points)                    */
+  BOLT_OP_CONV_CHAIN3 = 5  /* a convolution and two 1x1 convolutions fused                    */
+} bolt_op;
 
 /* Storage of a GEMM's second operand. */
 typedef enum {
@@ -134,6 +141,32 @@ bolt_status bolt_b2b_gemm(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1, co
 bolt_status bolt_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc* c1, const void* x, const void* w0,
                           const void* b0, const void* w1, const void* b1, void* y, const bolt_config* config,
                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Persistent fusion of more than two ops (Section 3.1.1: the scheme extends to longer chains by
+ * duplicating the pipeline; Section 3.3 deepens models with extra 1x1 convolutions that fuse this way).
+ * n_ops = 3 is compiled; any other positive n_ops is BOLT_ERR_UNSUPPORTED.
+ *   D_i = act_i(alpha_i * D_{i-1} . W_i + beta_i * bias_i),  D_{-1} = A0 (or the input image),
+ * every D_i but the last stays in registers, rounded to FP16 between ops as if it had been stored.
+ * descs: host array of n_ops descriptor pointers.  Legality is that of bolt_b2b_gemm / bolt_b2b_conv
+ * applied to each consecutive pair (else BOLT_ERR_ILLEGAL_FUSION): same M, K_i = N_{i-1}; for
+ * convolutions every op after the first is 1x1, stride 1, no padding, on the previous op's output
+ * extent.  GEMM chains need every weight matrix stored [N][K] (BOLT_LAYOUT_NK).  Each N_i must fit a
+ * compiled bound (N_0, N_1 <= 128, N_2 <= 256), else BOLT_ERR_UNSUPPORTED.
+ * weights, biases: host arrays of n_ops device pointers (biases, or single entries of it, may be NULL).
+ * config->kernel_id indexes the instances of BOLT_OP_GEMM_CHAIN3 / BOLT_OP_CONV_CHAIN3. */
+bolt_status bolt_b2b_gemm_chain(int32_t n_ops, const bolt_gemm_desc* const* descs, const void* A0,
+                                const void* const* weights, const void* const* biases, void* D,
+                                const bolt_config* config, void* stream);
+bolt_status bolt_b2b_conv_chain(int32_t n_ops, const bolt_conv_desc* const* descs, const void* x,
+                                const void* const* weights, const void* const* biases, void* y,
+                                const bolt_config* config, void* stream);
+/* bolt_tune for a chain: op is BOLT_OP_GEMM_CHAIN3 or BOLT_OP_CONV_CHAIN3, ptrs = {x, w0, b0, w1, b1,
+ * w2, b2, y} (biases may be NULL).  Synchronises the stream; y is overwritten; nothing is cached. */
+bolt_status bolt_tune_chain(bolt_op op, int32_t n_ops, const void* const* descs, const void* const* ptrs, void* stream,
+                            bolt_config* best, float* best_ms, int32_t* n_tried);
+/* Validation only (no GPU needed), and whether instance kernel_id can run the chain (1) or not (0). */
+bolt_status bolt_check_chain(bolt_op op, int32_t n_ops, const void* const* descs, const bolt_config* config);
+int32_t bolt_chain_instance_supports(bolt_op op, int32_t kernel_id, int32_t n_ops, const void* const* descs);
 
 /* Light-weight profiler (Section 3.2.2): runs every compiled instance that is legal for the given
  * problem (and a few split-K / swizzle settings) on the caller's real buffers, times them with

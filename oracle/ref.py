@@ -205,6 +205,24 @@ def b2b_conv_rows(x, w0, b0, w1, b1, rows, stride=1, pad=0, alpha0=1.0, beta0=1.
     return out
 
 
+def gemm_chain(A, Ws, bs, acts, alphas=None, betas=None):
+    """Eq. 1-2 carried on to more ops (Section 3.1.1): D_i = act_i(alpha_i D_{i-1} W_i + beta_i b_i), every D_i
+    rounded to FP16 before the next op reads it, as if it had been stored.  Ws[i] is [K_i][N_i]."""
+    D = _h(A)
+    for i, (W, b) in enumerate(zip(Ws, bs)):
+        D = gemm(D, W, b, 1.0 if alphas is None else alphas[i], 1.0 if betas is None else betas[i], acts[i])
+    return D
+
+
+def conv_chain(x, ws, bs, acts, stride=1, pad=0):
+    """A convolution followed by 1x1 / stride 1 / unpadded convolutions, FP16 between ops.  ws[i] is KRSC."""
+    y = conv2d_nhwc(x, ws[0], bs[0], stride=stride, pad=pad, act=acts[0])
+    for w, b, act in zip(ws[1:], bs[1:], acts[1:]):
+        assert w.shape[1:3] == (1, 1)
+        y = conv2d_nhwc(y, w, b, stride=1, pad=0, act=act)
+    return y
+
+
 def pad_channels(src, C8):
     src = _h(src)
     Cc = src.shape[-1]

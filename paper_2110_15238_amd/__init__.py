@@ -4,7 +4,7 @@ persistent back-to-back fusion, channel padding and the light-weight tuner, behi
 The Python layer only marshals arguments; importing it fails if the HIP library is not built.
 """
 from . import binding
-from .binding import (ACT, LAYOUT_KN, LAYOUT_NK, OP_B2B_CONV, OP_B2B_GEMM, OP_CONV2D, OP_GEMM, BoltConfig, BoltError,
+from .binding import (ACT, LAYOUT_KN, LAYOUT_NK, OP_B2B_CONV, OP_B2B_GEMM, OP_CONV2D, OP_CONV_CHAIN3, OP_GEMM, OP_GEMM_CHAIN3, BoltConfig, BoltError,
                       ConvDesc, GemmDesc, TuneResult, conv_desc, conv_out_hw, gemm_desc)
 
 # the C ABI's entry points under their own names
@@ -13,6 +13,11 @@ bolt_conv2d_fprop_nhwc = binding.conv2d_fprop_nhwc
 bolt_b2b_gemm = binding.b2b_gemm
 bolt_b2b_conv = binding.b2b_conv
 bolt_tune = binding.tune
+bolt_b2b_gemm_chain = binding.b2b_gemm_chain
+bolt_b2b_conv_chain = binding.b2b_conv_chain
+bolt_tune_chain = binding.tune_chain
+bolt_check_chain = binding.check_chain
+bolt_chain_instance_supports = binding.chain_instance_supports
 bolt_pad_channels_nhwc = binding.pad_channels_nhwc
 bolt_bias_act = binding.bias_act
 bolt_workspace_bytes = binding.workspace_bytes

@@ -14,7 +14,7 @@ from typing import Optional, Sequence, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbolt.so")
 
-OP_GEMM, OP_CONV2D, OP_B2B_GEMM, OP_B2B_CONV = 0, 1, 2, 3
+OP_GEMM, OP_CONV2D, OP_B2B_GEMM, OP_B2B_CONV, OP_GEMM_CHAIN3, OP_CONV_CHAIN3 = 0, 1, 2, 3, 4, 5
 ACT = {"none": 0, "relu": 1, "gelu": 2, "hardswish": 3, "softplus": 4}
 LAYOUT_KN, LAYOUT_NK = 0, 1
 STATUS_NAMES = ["BOLT_OK", "BOLT_ERR_INVALID_ARG", "BOLT_ERR_UNSUPPORTED", "BOLT_ERR_ALIGNMENT",
@@ -87,6 +87,17 @@ _lib.bolt_b2b_conv.argtypes = [C.POINTER(ConvDesc), C.POINTER(ConvDesc), _vp, _v
 _lib.bolt_tune.restype = C.c_int
 _lib.bolt_tune.argtypes = [C.c_int, _vp, _vp, C.POINTER(_vp), _vp, _sz, _vp, C.POINTER(BoltConfig),
                            C.POINTER(C.c_float), C.POINTER(_i32)]
+_pp = C.POINTER(_vp)
+_lib.bolt_b2b_gemm_chain.restype = C.c_int
+_lib.bolt_b2b_gemm_chain.argtypes = [_i32, _pp, _vp, _pp, _pp, _vp, C.POINTER(BoltConfig), _vp]
+_lib.bolt_b2b_conv_chain.restype = C.c_int
+_lib.bolt_b2b_conv_chain.argtypes = [_i32, _pp, _vp, _pp, _pp, _vp, C.POINTER(BoltConfig), _vp]
+_lib.bolt_tune_chain.restype = C.c_int
+_lib.bolt_tune_chain.argtypes = [C.c_int, _i32, _pp, _pp, _vp, C.POINTER(BoltConfig), C.POINTER(C.c_float), C.POINTER(_i32)]
+_lib.bolt_check_chain.restype = C.c_int
+_lib.bolt_check_chain.argtypes = [C.c_int, _i32, _pp, C.POINTER(BoltConfig)]
+_lib.bolt_chain_instance_supports.restype = _i32
+_lib.bolt_chain_instance_supports.argtypes = [C.c_int, _i32, _i32, _pp]
 _lib.bolt_pad_channels_nhwc.restype = C.c_int
 _lib.bolt_pad_channels_nhwc.argtypes = [_vp, _vp, C.c_int64, _i32, _i32, _vp]
 _lib.bolt_bias_act.restype = C.c_int
@@ -97,6 +108,8 @@ _lib.bolt_probe_copy_bandwidth.restype = C.c_int
 _lib.bolt_probe_copy_bandwidth.argtypes = [_vp, _sz, _i32, _vp, C.POINTER(C.c_float)]
 
 EXPORTED = ["bolt_gemm_epilogue", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune",
+            "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain", "bolt_tune_chain", "bolt_check_chain",
+            "bolt_chain_instance_supports",
             "bolt_pad_channels_nhwc", "bolt_bias_act", "bolt_workspace_bytes", "bolt_check", "bolt_status_string",
             "bolt_num_instances", "bolt_instance_config", "bolt_instance_supports", "bolt_probe_mfma_peak",
             "bolt_probe_copy_bandwidth"]
@@ -249,6 +262,47 @@ def tune(op: int, desc0, desc1, tensors: Sequence, workspace=None) -> TuneResult
     _check(_lib.bolt_tune(op, C.addressof(desc0), None if desc1 is None else C.addressof(desc1), ptrs, wp, wb,
                           _stream(), C.byref(best), C.byref(ms), C.byref(tried)), "bolt_tune")
     return TuneResult(best, float(ms.value), int(tried.value))
+
+
+def _desc_array(descs):
+    return (_vp * len(descs))(*[C.addressof(d) for d in descs])
+
+
+def _ptr_array(tensors):
+    return (_vp * len(tensors))(*[_ptr(t) for t in tensors])
+
+
+def b2b_gemm_chain(descs, A0, weights, biases, D, config=None):
+    """descs: GemmDesc list; weights / biases: lists of device tensors (a bias may be None)."""
+    c = _cfg(config)
+    _check(_lib.bolt_b2b_gemm_chain(len(descs), _desc_array(descs), _ptr(A0), _ptr_array(weights), _ptr_array(biases),
+                                    _ptr(D), None if c is None else C.byref(c), _stream()), "bolt_b2b_gemm_chain")
+    return D
+
+
+def b2b_conv_chain(descs, x, weights, biases, y, config=None):
+    c = _cfg(config)
+    _check(_lib.bolt_b2b_conv_chain(len(descs), _desc_array(descs), _ptr(x), _ptr_array(weights), _ptr_array(biases),
+                                    _ptr(y), None if c is None else C.byref(c), _stream()), "bolt_b2b_conv_chain")
+    return y
+
+
+def tune_chain(op: int, descs, tensors) -> TuneResult:
+    """tensors: [x, w0, b0, w1, b1, w2, b2, y] (biases may be None)."""
+    best, ms, tried = BoltConfig(), C.c_float(0), _i32(0)
+    _check(_lib.bolt_tune_chain(op, len(descs), _desc_array(descs), _ptr_array(tensors), _stream(), C.byref(best),
+                                C.byref(ms), C.byref(tried)), "bolt_tune_chain")
+    return TuneResult(best, float(ms.value), int(tried.value))
+
+
+def check_chain(op: int, descs, config=None) -> int:
+    c = _cfg(config)
+    return int(_lib.bolt_check_chain(op, len(descs), _desc_array(descs) if descs else None,
+                                     None if c is None else C.byref(c)))
+
+
+def chain_instance_supports(op: int, kernel_id: int, descs) -> bool:
+    return bool(_lib.bolt_chain_instance_supports(op, kernel_id, len(descs), _desc_array(descs)))
 
 
 def pad_channels_nhwc(src, dst, C_padded: int):

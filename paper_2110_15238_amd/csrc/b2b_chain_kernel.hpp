@@ -1,0 +1,80 @@
+// Persistent fusion of a chain of three ops (Section 3.1.1: the two-op pipeline "duplicated" once
+// more): op0 is a GEMM or an implicit-GEMM convolution, op1 and op2 are GEMMs / 1x1 convolutions
+// whose whole weight matrices stay in LDS.  One workgroup owns BM rows and all N0, N1 and N2
+// columns (threadblock residence for every op of the chain); D0 and D1 never leave the registers
+// of the wave that computed them (RF-resident fusion): after each epilogue the FP16 results are
+// re-used as the activation fragments of the next MFMA chain, exactly as in b2b_dma_kernel.hpp.
+// K-contiguous weights only (conv KRSC, GEMM B as [N][K]).
+#pragma once
+#include "b2b_dma_kernel.hpp"
+
+namespace bolt {
+
+template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS>
+struct B2bChainTraits {
+  static constexpr int WTM = BM / NW, FM = WTM / 32;
+  static constexpr int STAGE_HALVES = (BM + N0T) * BK;
+  static constexpr int PIPE_BYTES = (NS * STAGE_HALVES + N0T * N1T + N1T * N2T) * 2;
+  static constexpr int CTILE_BYTES = BM * N2T * 2;
+  static constexpr int LDS_BYTES = PIPE_BYTES > CTILE_BYTES ? PIPE_BYTES : CTILE_BYTES;
+  static_assert(WTM % 32 == 0 && N0T % 32 == 0 && N1T % 32 == 0 && N2T % 32 == 0, "tile shape");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+  static int lds_bytes(int) { return LDS_BYTES; }
+};
+
+template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS>
+__global__ __launch_bounds__(64 * NW) void b2b_chain_kernel(const B2bParams p) {
+  using T = B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>;
+  constexpr int FM = T::FM;
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  half_t* W1s = lds + NS * T::STAGE_HALVES;  // [N0T / KB1][N1T * KB1]
+  half_t* W2s = W1s + N0T * N1T;             // [N1T / KB2][N2T * KB2]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int m0 = blockIdx.x * BM;
+
+  // resident weights first: the oldest loads, covered by the main loop's final wait
+  b2b_issue_weights<N1T, N0T, NW>(p.W1, p.ldw1, p.N1, p.N0, W1s, p.cg, wave, lane);
+  b2b_issue_weights<N2T, N1T, NW>(p.W2, p.ldw2, p.N2, p.N1, W2s, p.cg, wave, lane);
+
+  floatx16 acc0[N0T / 32][FM];
+  b2b_dma_op0<BM, BK, NW, N0T, XMODE, NS>(p, lds, m0, wave, lane, acc0);
+
+  half8 d0[N0T / 16][FM];
+  b2b_make_d<N0T / 32, FM>(EpilogueArgs{p.b0, p.b0_on, p.N0, p.alpha0, p.beta0, p.act0}, acc0, d0, g);
+  floatx16 acc1[N1T / 32][FM];
+  b2b_rf_gemm<N0T, N1T, FM>(W1s, d0, acc1, l32, g);
+
+  half8 d1[N1T / 16][FM];
+  b2b_make_d<N1T / 32, FM>(EpilogueArgs{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1}, acc1, d1, g);
+  floatx16 acc2[N2T / 32][FM];
+  b2b_rf_gemm<N1T, N2T, FM>(W2s, d1, acc2, l32, g);
+
+  const EpilogueArgs ep{p.b2, p.b2_on, p.N2, p.alpha2, p.beta2, p.act2};
+  b2b_tile_out<BM, NW, N2T>(lds, acc2, ep, p.Y, p.ldy, p.M, m0, wave, tid);
+}
+
+struct ChainInstance {
+  const char* name;
+  int bm, bk, waves, n0t, n1t, n2t, xmode, stages, lds_bytes;
+  hipError_t (*launch)(const B2bParams&, hipStream_t);
+};
+
+template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS>
+hipError_t launch_b2b_chain(const B2bParams& p, hipStream_t stream) {
+  static bool attr_set = false;
+  return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>, attr_set, p, p.tiles_m, 64 * NW,
+                           B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>::LDS_BYTES, stream);
+}
+
+#define BOLT_B2B_CHAIN_INSTANCE(BM, BK, NW, N0T, N1T, N2T, NS, XMODE)                                          \
+  {                                                                                                            \
+    "chain_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_" #N2T "_s" #NS, BM, BK, NW, N0T, N1T, N2T, XMODE, NS,     \
+        bolt::B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>::LDS_BYTES,                                   \
+        &bolt::launch_b2b_chain<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>                                            \
+  }
+
+}  // namespace bolt

@@ -34,35 +34,35 @@ struct B2bDmaTraits {
   static int lds_bytes(int) { return LDS_BYTES; }
 };
 
-template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
-__global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::MIN_WAVES)) void b2b_dma_kernel(
-    const B2bParams p) {
-  using T = B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>;
-  constexpr int NT = T::NT, WTM = T::WTM, FM = T::FM, FN0 = T::FN0, FN1 = T::FN1;
-  constexpr int KB1 = T::KB1, NKT1 = T::NKT1, STAGE = T::STAGE_HALVES, KS = BK / 16;
+// ---- building blocks shared by the two-op kernel below and the three-op chain (b2b_chain_kernel.hpp) ----
+
+// Weights of a later op, W [n_valid][k_valid] with leading dimension ld, K-contiguous: all of it goes to LDS
+// once as [NKT][NOUT_T][KB] k-tiles of width KB = min(NIN_T, 64); missing rows and columns are zero-filled.
+template <int NOUT_T, int NIN_T, int NW>
+__device__ __forceinline__ void b2b_issue_weights(const half_t* W, int ld, int n_valid, int k_valid, half_t* Ws,
+                                                  const ConvGeom& cg, int wave, int lane) {
+  constexpr int KB = NIN_T < 64 ? NIN_T : 64, NKT = NIN_T / KB;
+  DmaTileLoader<NOUT_T, KB, NW, 0> wl;
+  const int64_t bytes = ((int64_t)(n_valid - 1) * ld + k_valid) * 2;
+  wl.init(W, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), ld, n_valid, k_valid, cg, 0, 0, wave, lane);
+#pragma unroll
+  for (int kt = 0; kt < NKT; ++kt) wl.issue(kt, Ws + kt * NOUT_T * KB, cg);
+}
+
+// op0: acc0 = X tile (GEMM rows or implicit im2col) x W0^T over K0, NS-deep direct-to-LDS pipeline with the
+// fragments double-buffered across the k-tile barrier.  On return every load this wave has issued, the
+// resident weights of the later ops included, has landed (the loop's final wait is vmcnt 0).
+template <int BM, int BK, int NW, int N0T, int XMODE, int NS>
+__device__ __forceinline__ void b2b_dma_op0(const B2bParams& p, half_t* lds, int m0, int wave, int lane,
+                                            floatx16 (&acc0)[N0T / 32][BM / NW / 32]) {
+  constexpr int WTM = BM / NW, FM = WTM / 32, FN0 = N0T / 32, STAGE = (BM + N0T) * BK, KS = BK / 16;
   using XL = DmaTileLoader<BM, BK, NW, XMODE>;
   using WL = DmaTileLoader<N0T, BK, NW, 0>;
   constexpr int L = XL::NI + WL::NI;
   static_assert((NS - 1) * L < 64, "vmcnt range");
   static_assert(KS % 2 == 0, "fragment double buffering");
-
-  extern __shared__ __attribute__((aligned(16))) half_t lds[];
-  half_t* W1s = lds + NS * STAGE;  // [NKT1][N1T*KB1]
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = lane >> 5, l32 = lane & 31;
-  const int m0 = blockIdx.x * BM;
   const int n_tiles = (p.K0 + BK - 1) / BK;
-
-  // W1 first: these are the oldest loads, any later wait for an operand tile covers them
-  {
-    DmaTileLoader<N1T, KB1, NW, 0> w1l;
-    const int64_t bytes = ((int64_t)(p.N1 - 1) * p.ldw1 + p.N0) * 2;
-    w1l.init(p.W1, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), p.ldw1, p.N1, p.N0, p.cg, 0, 0, wave, lane);
-#pragma unroll
-    for (int kt = 0; kt < NKT1; ++kt) w1l.issue(kt, W1s + kt * N1T * KB1, p.cg);
-  }
   XL xl;
   WL wl;
   if constexpr (XMODE == 0) {
@@ -77,8 +77,6 @@ __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE,
     const int64_t bytes = ((int64_t)(p.N0 - 1) * p.ldw0 + p.K0) * 2;
     wl.init(p.W0, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), p.ldw0, p.N0, p.K0, p.cg, 0, 0, wave, lane);
   }
-
-  floatx16 acc0[FN0][FM];
 #pragma unroll
   for (int a = 0; a < FN0; ++a)
 #pragma unroll
@@ -101,104 +99,137 @@ __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE,
 #pragma unroll
     for (int a = 0; a < FN0; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(a * 32 + l32, chunk));
   };
-
-  // ---- op0: NS-deep pipeline, fragments double-buffered across the k-tile barrier -------------
-  {
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
-      if (s < n_tiles) issue(s, s);
-    if (n_tiles >= NS) barrier_after_loads<(NS - 1) * L>();
-    else barrier_after_loads<0>();
-    read_frags(0, 0, xf[0], wf[0]);
-    int stage = 0;
-    for (int it = 0; it < n_tiles; ++it) {
+  for (int s = 0; s < NS; ++s)
+    if (s < n_tiles) issue(s, s);
+  if (n_tiles >= NS) barrier_after_loads<(NS - 1) * L>();
+  else barrier_after_loads<0>();
+  read_frags(0, 0, xf[0], wf[0]);
+  int stage = 0;
+  for (int it = 0; it < n_tiles; ++it) {
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        if (ks + 1 < KS) {
-          read_frags(stage, ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
-        } else {
-          __builtin_amdgcn_sched_barrier(0);
-          if (n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS - 2) * L>();
-          else barrier_after_reads_and_loads<0>();
-          if (it + NS < n_tiles) issue(it + NS, stage);
-          stage = stage + 1 == NS ? 0 : stage + 1;
-          read_frags(stage, 0, xf[0], wf[0]);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int a = 0; a < FN0; ++a)
-#pragma unroll
-          for (int b = 0; b < FM; ++b) acc0[a][b] = mfma_32x32x16(wf[ks & 1][a], xf[ks & 1][b], acc0[a][b]);
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) {
+        read_frags(stage, ks + 1, xf[(ks + 1) & 1], wf[(ks + 1) & 1]);
+      } else {
+        __builtin_amdgcn_sched_barrier(0);
+        if (n_tiles - 2 - it >= NS - 2) barrier_after_reads_and_loads<(NS - 2) * L>();
+        else barrier_after_reads_and_loads<0>();
+        if (it + NS < n_tiles) issue(it + NS, stage);
+        stage = stage + 1 == NS ? 0 : stage + 1;
+        read_frags(stage, 0, xf[0], wf[0]);
+        __builtin_amdgcn_sched_barrier(0);
       }
+#pragma unroll
+      for (int a = 0; a < FN0; ++a)
+#pragma unroll
+        for (int b = 0; b < FM; ++b) acc0[a][b] = mfma_32x32x16(wf[ks & 1][a], xf[ks & 1][b], acc0[a][b]);
     }
   }
-  // after the last k-tile every load, W1 included, has landed (the loop's final wait is vmcnt 0)
+}
 
-  // ---- epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 ----------------
-  // Step t = 2a + h of op1 reduces over D0 columns [32a + 16h, 32a + 16h + 16).  Lane group g holds
-  // columns 32a+16h+4g+{0..3} (registers 8h..8h+3) and 32a+16h+8+4g+{0..3} (registers 8h+4..8h+7).
-  half8 d0[FN0 * 2][FM];
-  b2b_make_d0<FN0, FM>(p, acc0, d0, g);
-
-  // ---- op1: all N1 columns accumulate in registers; W1 fragments carry the matching permutation
-  floatx16 acc1[FN1][FM];
+// A later op entirely out of registers and LDS: acc[NOUT_T columns] = d (FP16 fragments of the previous
+// op's output, NIN_T columns) x Ws^T, Ws as b2b_issue_weights leaves it.  Step t reduces over input columns
+// [16t, 16t + 16); the fragment reads apply the permutation of the reduction index that b2b_make_d documents.
+template <int NIN_T, int NOUT_T, int FM>
+__device__ __forceinline__ void b2b_rf_gemm(const half_t* Ws, const half8 (&d)[NIN_T / 16][FM],
+                                            floatx16 (&acc)[NOUT_T / 32][FM], int l32, int g) {
+  constexpr int KB = NIN_T < 64 ? NIN_T : 64, FNO = NOUT_T / 32;
 #pragma unroll
-  for (int a = 0; a < FN1; ++a)
+  for (int a = 0; a < FNO; ++a)
 #pragma unroll
     for (int b = 0; b < FM; ++b)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc1[a][b][r] = 0.f;
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 #pragma unroll
-  for (int t = 0; t < FN0 * 2; ++t) {
+  for (int t = 0; t < NIN_T / 16; ++t) {
     const int kbase = t * 16;
-    const half_t* ws = W1s + (kbase / KB1) * N1T * KB1;
-    const int chunk = (kbase % KB1) / 8;
+    const half_t* ws = Ws + (kbase / KB) * NOUT_T * KB;
+    const int chunk = (kbase % KB) / 8;
 #pragma unroll
-    for (int a = 0; a < FN1; ++a) {
+    for (int a = 0; a < FNO; ++a) {
       const int row = a * 32 + l32;
-      const half4 lo = *(const half4*)(ws + dma_chunk_offset<KB1>(row, chunk) + g * 4);
-      const half4 hi = *(const half4*)(ws + dma_chunk_offset<KB1>(row, chunk + 1) + g * 4);
-      const half8 w1 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      const half4 lo = *(const half4*)(ws + dma_chunk_offset<KB>(row, chunk) + g * 4);
+      const half4 hi = *(const half4*)(ws + dma_chunk_offset<KB>(row, chunk + 1) + g * 4);
+      const half8 w = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
-      for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(w1, d0[t][b], acc1[a][b]);
+      for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(w, d[t][b], acc[a][b]);
     }
   }
+}
 
-  // ---- epilogue1: registers -> FP16 D1 tile in LDS (over the dead stages and W1) -> global -----
-  constexpr int CPR = T::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
-  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
-  barrier_after_lds_writes();  // every wave is done reading W1 and the operand stages
+// Last epilogue: accumulators -> FP16 tile [BM][NOUT_T] in LDS (over whatever the main loop left there) ->
+// 16-byte coalesced non-temporal row stores.  Every wave must be done with the LDS it overwrites.
+template <int BM, int NW, int NOUT_T>
+__device__ __forceinline__ void b2b_tile_out(half_t* lds, const floatx16 (&acc)[NOUT_T / 32][BM / NW / 32],
+                                             const EpilogueArgs& ep, half_t* Y, int ldy, int M, int m0, int wave, int tid) {
+  constexpr int NT = 64 * NW, WTM = BM / NW, FM = WTM / 32, FNO = NOUT_T / 32;
+  constexpr int CPR = NOUT_T / 8, ROWS_PER_PASS = NT / CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
+  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
+  barrier_after_lds_writes();
   auto tile_to_lds = [&](auto slow) {
 #pragma unroll
-    for (int a = 0; a < FN1; ++a)
+    for (int a = 0; a < FNO; ++a)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int nl = a * 32 + q * 8 + g * 4;
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
           const int row = wave * WTM + b * 32 + l32;
-          *(half4*)(lds + row * N1T + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
-              epilogue_quad<decltype(slow)::value>(acc1[a][b], q, nl, ep);
+          *(half4*)(lds + row * NOUT_T + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
+              epilogue_quad<decltype(slow)::value>(acc[a][b], q, nl, ep);
         }
       }
   };
-  if (p.act1 > ACT_RELU) tile_to_lds(std::true_type{});
+  if (ep.act > ACT_RELU) tile_to_lds(std::true_type{});
   else tile_to_lds(std::false_type{});
   barrier_after_lds_writes();
-  {
-    const int chunk = tid % CPR, r0 = tid / CPR;
-    const int n = chunk * 8;
-    if (n < p.N1) {
+  const int chunk = tid % CPR, r0 = tid / CPR;
+  const int n = chunk * 8;
+  if (n < ep.N) {
 #pragma unroll
-      for (int i = 0; i < BM / T::ROWS_PER_PASS; ++i) {
-        const int row = r0 + i * T::ROWS_PER_PASS;
-        if (m0 + row < p.M) {
-          const half8 v = *(const half8*)(lds + row * N1T + ((chunk ^ (row & CSW)) << 3));
-          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
-        }
+    for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
+      const int row = r0 + i * ROWS_PER_PASS;
+      if (m0 + row < M) {
+        const half8 v = *(const half8*)(lds + row * NOUT_T + ((chunk ^ (row & CSW)) << 3));
+        __builtin_nontemporal_store(v, (half8*)(Y + (int64_t)(m0 + row) * ldy + n));
       }
     }
   }
+}
+
+template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
+__global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::MIN_WAVES)) void b2b_dma_kernel(
+    const B2bParams p) {
+  using T = B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>;
+  constexpr int FM = T::FM, FN0 = T::FN0, FN1 = T::FN1;
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  half_t* W1s = lds + NS * T::STAGE_HALVES;  // [NKT1][N1T*KB1]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int m0 = blockIdx.x * BM;
+
+  // W1 first: these are the oldest loads, any later wait for an operand tile covers them
+  b2b_issue_weights<N1T, N0T, NW>(p.W1, p.ldw1, p.N1, p.N0, W1s, p.cg, wave, lane);
+
+  floatx16 acc0[FN0][FM];
+  b2b_dma_op0<BM, BK, NW, N0T, XMODE, NS>(p, lds, m0, wave, lane, acc0);
+
+  // epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 (b2b_make_d0)
+  half8 d0[FN0 * 2][FM];
+  b2b_make_d0<FN0, FM>(p, acc0, d0, g);
+
+  // op1: all N1 columns accumulate in registers
+  floatx16 acc1[FN1][FM];
+  b2b_rf_gemm<N0T, N1T, FM>(W1s, d0, acc1, l32, g);
+
+  // epilogue1 through LDS (over the dead stages and W1)
+  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
+  b2b_tile_out<BM, NW, N1T>(lds, acc1, ep, p.Y, p.ldy, p.M, m0, wave, tid);
 }
 
 template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>

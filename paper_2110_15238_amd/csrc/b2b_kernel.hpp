@@ -39,6 +39,12 @@ struct B2bParams {
   int act0, act1;
   int tiles_m;
   ConvGeom cg;  // XMODE 1 only (geometry of op0)
+  // third op of a chain (b2b_chain_kernel.hpp); N2 == 0 for the two-op kernels
+  const half_t* W2;
+  const half_t* b2;
+  int b2_on, N2, ldw2;
+  float alpha2, beta2;
+  int act2;
 };
 
 template <int N0T>
@@ -99,9 +105,8 @@ __device__ __forceinline__ void b2b_store_tile(const B2bParams& p, floatx16 (&ac
 // holds columns 32a+16h+4g+{0..3} (accumulator quad 2h) and 32a+16h+8+4g+{0..3} (quad 2h+1), and the
 // W1 fragment reads apply the same permutation of the reduction index.  Columns >= N0 become 0.
 template <int FN0, int FM>
-__device__ __forceinline__ void b2b_make_d0(const B2bParams& p, const floatx16 (&acc0)[FN0][FM], half8 (&d0)[FN0 * 2][FM],
-                                            int g) {
-  const EpilogueArgs ep{p.b0, p.b0_on, p.N0, p.alpha0, p.beta0, p.act0};
+__device__ __forceinline__ void b2b_make_d(const EpilogueArgs& ep, const floatx16 (&acc0)[FN0][FM], half8 (&d0)[FN0 * 2][FM],
+                                           int g) {
   auto make = [&](auto slow) {
 #pragma unroll
     for (int a = 0; a < FN0; ++a)
@@ -113,15 +118,20 @@ __device__ __forceinline__ void b2b_make_d0(const B2bParams& p, const floatx16 (
           half4 lo = epilogue_quad<decltype(slow)::value>(acc0[a][b], 2 * h, c0, ep);
           half4 hi = epilogue_quad<decltype(slow)::value>(acc0[a][b], 2 * h + 1, c0 + 8, ep);
           const half4 z = {0, 0, 0, 0};
-          if (c0 >= p.N0) lo = z;
-          if (c0 + 8 >= p.N0) hi = z;
+          if (c0 >= ep.N) lo = z;
+          if (c0 + 8 >= ep.N) hi = z;
           const half8 d = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
           d0[a * 2 + h][b] = d;
         }
       }
   };
-  if (p.act0 > ACT_RELU) make(std::true_type{});
+  if (ep.act > ACT_RELU) make(std::true_type{});
   else make(std::false_type{});
+}
+template <int FN0, int FM>
+__device__ __forceinline__ void b2b_make_d0(const B2bParams& p, const floatx16 (&acc0)[FN0][FM], half8 (&d0)[FN0 * 2][FM],
+                                            int g) {
+  b2b_make_d<FN0, FM>(EpilogueArgs{p.b0, p.b0_on, p.N0, p.alpha0, p.beta0, p.act0}, acc0, d0, g);
 }
 
 template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>

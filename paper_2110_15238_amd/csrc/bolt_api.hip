@@ -131,7 +131,10 @@ static const half_t* zero_bias() {
 struct Tables {
   std::vector<FpropInstance> gemm, conv;
   std::vector<B2bInstance> b2b_gemm, b2b_conv;
+  std::vector<ChainInstance> gemm_chain, conv_chain;
   Tables() {
+    register_gemm_chain_instances(gemm_chain);
+    register_conv_chain_instances(conv_chain);
     register_gemm_kn_instances(gemm);
     register_gemm_nk_instances(gemm);
     register_conv_instances(conv);
@@ -500,6 +503,93 @@ static bolt_status resolve_b2b(const std::vector<B2bInstance>& tab, const B2bPro
 }
 
 // ------------------------------------------------------------------------------------------
+// three-op chains
+// ------------------------------------------------------------------------------------------
+static bool chain_supports(const ChainInstance& in, const B2bProblem& pr) {
+  if (in.xmode != pr.xmode || pr.wmode != 0) return false;
+  const B2bParams& p = pr.p;
+  if (p.N0 > in.n0t || p.N1 > in.n1t || p.N2 > in.n2t) return false;
+  // threadblock residence with the tightest compiled bounds: no more than 2x padding per op
+  if ((in.n0t > 64 && in.n0t / 2 >= p.N0) || (in.n1t > 64 && in.n1t / 2 >= p.N1) || (in.n2t > 64 && in.n2t / 2 >= p.N2))
+    return false;
+  return in.lds_bytes <= kLdsPerCU;
+}
+
+static void chain_fill_config(const ChainInstance& in, int id, bolt_config* c) {
+  c->kernel_id = id;
+  c->tile_m = in.bm; c->tile_n = in.n2t; c->tile_k = in.bk;
+  c->waves_m = in.waves; c->waves_n = 1;
+  c->mfma_shape = 32; c->stages = in.stages; c->swizzle = 0; c->split_k = 1; c->b2b_mode = BOLT_B2B_RF;
+}
+
+static bolt_status chain_launch(const ChainInstance& in, B2bProblem pr, hipStream_t stream) {
+  B2bParams& p = pr.p;
+  p.b0_on = p.b0 ? 1 : 0;
+  p.b1_on = p.b1 ? 1 : 0;
+  p.b2_on = p.b2 ? 1 : 0;
+  if (!p.b0) p.b0 = zero_bias();
+  if (!p.b1) p.b1 = zero_bias();
+  if (!p.b2) p.b2 = zero_bias();
+  if (!p.b0 || !p.b1 || !p.b2) return BOLT_ERR_LAUNCH;
+  p.tiles_m = ceil_div(p.M, in.bm);
+  return in.launch(p, stream) == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+}
+
+// Validates a chain of three descriptors and builds its problem (pointers left null).
+static bolt_status make_chain_problem(bolt_op op, int32_t n_ops, const void* const* descs, B2bProblem* pr) {
+  if (op != BOLT_OP_GEMM_CHAIN3 && op != BOLT_OP_CONV_CHAIN3) return BOLT_ERR_INVALID_ARG;
+  if (!descs || n_ops <= 0) return BOLT_ERR_INVALID_ARG;
+  if (n_ops != 3) return BOLT_ERR_UNSUPPORTED;
+  if (!descs[0] || !descs[1] || !descs[2]) return BOLT_ERR_INVALID_ARG;
+  bolt_status s;
+  if (op == BOLT_OP_GEMM_CHAIN3) {
+    const bolt_gemm_desc* g0 = (const bolt_gemm_desc*)descs[0];
+    const bolt_gemm_desc* g1 = (const bolt_gemm_desc*)descs[1];
+    const bolt_gemm_desc* g2 = (const bolt_gemm_desc*)descs[2];
+    if ((s = make_b2b_gemm_problem(g0, g1, pr)) != BOLT_OK) return s;
+    if ((s = check_b2b_gemm(g1, g2)) != BOLT_OK) return s;
+    if (g0->b_layout != BOLT_LAYOUT_NK) return BOLT_ERR_UNSUPPORTED;  // the chain kernels stream K-contiguous weights
+    B2bParams& p = pr->p;
+    p.N2 = g2->N; p.ldw2 = g2->ldb; p.ldy = g2->ldd;
+    p.alpha2 = g2->alpha; p.beta2 = g2->beta; p.act2 = g2->act;
+  } else {
+    const bolt_conv_desc* c0 = (const bolt_conv_desc*)descs[0];
+    const bolt_conv_desc* c1 = (const bolt_conv_desc*)descs[1];
+    const bolt_conv_desc* c2 = (const bolt_conv_desc*)descs[2];
+    if ((s = make_b2b_conv_problem(c0, c1, pr)) != BOLT_OK) return s;
+    if ((s = check_b2b_conv(c1, c2, nullptr)) != BOLT_OK) return s;
+    B2bParams& p = pr->p;
+    p.N2 = c2->K; p.ldw2 = c2->C; p.ldy = c2->K;
+    p.alpha2 = c2->alpha; p.beta2 = c2->beta; p.act2 = c2->act;
+  }
+  return BOLT_OK;
+}
+
+static int chain_heuristic(const std::vector<ChainInstance>& tab, const B2bProblem& pr) {
+  int best = -1;
+  double best_cost = 0;
+  for (int i = 0; i < (int)tab.size(); ++i) {
+    if (!chain_supports(tab[i], pr)) continue;
+    const double cost = (double)tab[i].n0t * tab[i].n1t + (double)tab[i].n1t * tab[i].n2t + 1e-3 * tab[i].lds_bytes;
+    if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
+  }
+  return best;
+}
+
+static bolt_status resolve_chain(const std::vector<ChainInstance>& tab, const B2bProblem& pr, const bolt_config* cfg,
+                                 int* id) {
+  if (cfg && cfg->kernel_id >= 0) {
+    if (cfg->kernel_id >= (int)tab.size()) return BOLT_ERR_INVALID_ARG;
+    if (!chain_supports(tab[cfg->kernel_id], pr)) return BOLT_ERR_UNSUPPORTED;
+    *id = cfg->kernel_id;
+    return BOLT_OK;
+  }
+  if (cfg && cfg->kernel_id < -1) return BOLT_ERR_INVALID_ARG;
+  *id = chain_heuristic(tab, pr);
+  return *id < 0 ? BOLT_ERR_UNSUPPORTED : BOLT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // profiler
 // ------------------------------------------------------------------------------------------
 struct TuneKey {
@@ -646,6 +736,8 @@ int32_t bolt_num_instances(bolt_op op) {
     case BOLT_OP_CONV2D: return (int32_t)tables().conv.size();
     case BOLT_OP_B2B_GEMM: return (int32_t)tables().b2b_gemm.size();
     case BOLT_OP_B2B_CONV: return (int32_t)tables().b2b_conv.size();
+    case BOLT_OP_GEMM_CHAIN3: return (int32_t)tables().gemm_chain.size();
+    case BOLT_OP_CONV_CHAIN3: return (int32_t)tables().conv_chain.size();
     default: return 0;
   }
 }
@@ -659,6 +751,8 @@ bolt_status bolt_instance_config(bolt_op op, int32_t id, bolt_config* out) {
     case BOLT_OP_CONV2D: fprop_fill_config(tables().conv[id], id, out); break;
     case BOLT_OP_B2B_GEMM: b2b_fill_config(tables().b2b_gemm[id], id, out); break;
     case BOLT_OP_B2B_CONV: b2b_fill_config(tables().b2b_conv[id], id, out); break;
+    case BOLT_OP_GEMM_CHAIN3: chain_fill_config(tables().gemm_chain[id], id, out); break;
+    case BOLT_OP_CONV_CHAIN3: chain_fill_config(tables().conv_chain[id], id, out); break;
     default: return BOLT_ERR_INVALID_ARG;
   }
   return BOLT_OK;
@@ -868,6 +962,87 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
   if (n_tried) *n_tried = tried;
   std::lock_guard<std::mutex> lock(tune_mutex());
   tune_cache()[key] = TuneVal{cfg, win.ms, tried};
+  return BOLT_OK;
+}
+
+bolt_status bolt_check_chain(bolt_op op, int32_t n_ops, const void* const* descs, const bolt_config* config) {
+  B2bProblem pr;
+  bolt_status s = make_chain_problem(op, n_ops, descs, &pr);
+  if (s != BOLT_OK) return s;
+  int id;
+  return resolve_chain(op == BOLT_OP_GEMM_CHAIN3 ? tables().gemm_chain : tables().conv_chain, pr, config, &id);
+}
+
+int32_t bolt_chain_instance_supports(bolt_op op, int32_t kernel_id, int32_t n_ops, const void* const* descs) {
+  B2bProblem pr;
+  if (make_chain_problem(op, n_ops, descs, &pr) != BOLT_OK) return 0;
+  const auto& tab = op == BOLT_OP_GEMM_CHAIN3 ? tables().gemm_chain : tables().conv_chain;
+  return kernel_id >= 0 && kernel_id < (int)tab.size() && chain_supports(tab[kernel_id], pr);
+}
+
+// ptrs: {x, w0, b0, w1, b1, w2, b2, y}
+static bolt_status chain_bind(B2bProblem* pr, const void* const* ptrs) {
+  for (int i = 0; i < 8; ++i) {
+    const bool optional = i == 2 || i == 4 || i == 6;
+    if (!ptrs[i] && !optional) return BOLT_ERR_INVALID_ARG;
+    if (ptrs[i] && !is_aligned16(ptrs[i])) return BOLT_ERR_ALIGNMENT;
+  }
+  B2bParams& p = pr->p;
+  p.X = (const half_t*)ptrs[0]; p.W0 = (const half_t*)ptrs[1]; p.b0 = (const half_t*)ptrs[2];
+  p.W1 = (const half_t*)ptrs[3]; p.b1 = (const half_t*)ptrs[4]; p.W2 = (const half_t*)ptrs[5];
+  p.b2 = (const half_t*)ptrs[6]; p.Y = (half_t*)ptrs[7];
+  return BOLT_OK;
+}
+
+static bolt_status chain_call(bolt_op op, int32_t n_ops, const void* const* descs, const void* x,
+                              const void* const* weights, const void* const* biases, void* y, const bolt_config* config,
+                              void* stream) {
+  B2bProblem pr;
+  bolt_status s = make_chain_problem(op, n_ops, descs, &pr);
+  if (s != BOLT_OK) return s;
+  if (!weights) return BOLT_ERR_INVALID_ARG;
+  const void* ptrs[8] = {x, weights[0], biases ? biases[0] : nullptr, weights[1], biases ? biases[1] : nullptr,
+                         weights[2], biases ? biases[2] : nullptr, y};
+  if ((s = chain_bind(&pr, ptrs)) != BOLT_OK) return s;
+  const auto& tab = op == BOLT_OP_GEMM_CHAIN3 ? tables().gemm_chain : tables().conv_chain;
+  int id;
+  if ((s = resolve_chain(tab, pr, config, &id)) != BOLT_OK) return s;
+  return chain_launch(tab[id], pr, (hipStream_t)stream);
+}
+
+bolt_status bolt_b2b_gemm_chain(int32_t n_ops, const bolt_gemm_desc* const* descs, const void* A0,
+                                const void* const* weights, const void* const* biases, void* D,
+                                const bolt_config* config, void* stream) {
+  return chain_call(BOLT_OP_GEMM_CHAIN3, n_ops, (const void* const*)descs, A0, weights, biases, D, config, stream);
+}
+
+bolt_status bolt_b2b_conv_chain(int32_t n_ops, const bolt_conv_desc* const* descs, const void* x,
+                                const void* const* weights, const void* const* biases, void* y,
+                                const bolt_config* config, void* stream) {
+  return chain_call(BOLT_OP_CONV_CHAIN3, n_ops, (const void* const*)descs, x, weights, biases, y, config, stream);
+}
+
+bolt_status bolt_tune_chain(bolt_op op, int32_t n_ops, const void* const* descs, const void* const* ptrs, void* stream_v,
+                            bolt_config* best, float* best_ms, int32_t* n_tried) {
+  if (!ptrs || !best) return BOLT_ERR_INVALID_ARG;
+  B2bProblem pr;
+  bolt_status s = make_chain_problem(op, n_ops, descs, &pr);
+  if (s != BOLT_OK) return s;
+  if ((s = chain_bind(&pr, ptrs)) != BOLT_OK) return s;
+  hipStream_t stream = (hipStream_t)stream_v;
+  const auto& tab = op == BOLT_OP_GEMM_CHAIN3 ? tables().gemm_chain : tables().conv_chain;
+  std::vector<Candidate> cands;
+  for (int i = 0; i < (int)tab.size(); ++i)
+    if (chain_supports(tab[i], pr)) cands.push_back({i, 0, 1, 0.f});
+  if (cands.empty()) return BOLT_ERR_UNSUPPORTED;
+  Candidate win{};
+  int tried = 0;
+  s = tune_candidates(cands, [&](const Candidate& c) { return chain_launch(tab[c.id], pr, stream); }, stream, &win, &tried);
+  if (s != BOLT_OK) return s;
+  std::memset(best, 0, sizeof(*best));
+  chain_fill_config(tab[win.id], win.id, best);
+  if (best_ms) *best_ms = win.ms;
+  if (n_tried) *n_tried = tried;
   return BOLT_OK;
 }
 

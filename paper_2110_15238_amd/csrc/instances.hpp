@@ -12,6 +12,7 @@
 #include "b2b_dma_kernel.hpp"
 #include "b2b_kernel.hpp"
 #include "conv_halo_kernel.hpp"
+#include "b2b_chain_kernel.hpp"
 #include "b2b_halo_kernel.hpp"
 #include "fprop_dma_kernel.hpp"
 #include "fprop_kernel.hpp"
@@ -121,4 +122,6 @@ void register_b2b_gemm_dma_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_stream_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_dma_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_halo_instances(std::vector<B2bInstance>& v);
+void register_gemm_chain_instances(std::vector<ChainInstance>& v);
+void register_conv_chain_instances(std::vector<ChainInstance>& v);
 }  // namespace bolt

@@ -561,6 +561,101 @@ def test_config5_layer_full_size_tuned_sampled(bolt, index):
     assert_close(got[idx], want, "config5 layer %d" % index)
 
 
+# ---------------------------------------------------------------------------------------------
+# three-op chains
+# ---------------------------------------------------------------------------------------------
+GEMM_CHAINS = [  # (M, K0, N0, N1, N2): ragged M, widths at and below the compiled bounds
+    (1000, 72, 64, 64, 64), (515, 256, 64, 128, 64), (700, 96, 40, 64, 256), (260, 200, 128, 64, 120),
+    (333, 64, 64, 256, 64), (129, 136, 128, 128, 128), (1, 8, 8, 8, 8)]
+
+
+@pytest.mark.parametrize("shape", GEMM_CHAINS)
+def test_gemm_chain3_every_instance(bolt, shape):
+    M, K0, N0, N1, N2 = shape
+    A = wl.uniform_fp16(301, 0, (M, K0), -0.5, 0.5)
+    Ws = [wl.uniform_fp16(301, 1, (K0, N0), -0.5, 0.5), wl.uniform_fp16(301, 2, (N0, N1), -0.5, 0.5),
+          wl.uniform_fp16(301, 3, (N1, N2), -0.5, 0.5)]
+    bs = [wl.uniform_fp16(301, 4, (N0,), -1, 1), None, wl.uniform_fp16(301, 6, (N2,), -1, 1)]
+    acts = ["relu", "gelu", "none"]
+    want = ref.gemm_chain(A, Ws, bs, acts)
+    descs = [bolt.gemm_desc(M, N0, K0, act=acts[0], b_layout=bolt.LAYOUT_NK),
+             bolt.gemm_desc(M, N1, N0, act=acts[1], b_layout=bolt.LAYOUT_NK),
+             bolt.gemm_desc(M, N2, N1, act=acts[2], b_layout=bolt.LAYOUT_NK)]
+    Wd = [dev(np.ascontiguousarray(W.T)) for W in Ws]
+    bd = [dev(b) for b in bs]
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_GEMM_CHAIN3)):
+        if not bolt.bolt_chain_instance_supports(bolt.OP_GEMM_CHAIN3, kid, descs):
+            continue
+        _say("gemm chain %s instance %d" % (shape, kid))
+        D = torch.full((M, N2), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_b2b_gemm_chain(descs, dev(A), Wd, bd, D, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(D), want, "gemm chain %s instance %d" % (shape, kid))
+        ran += 1
+    assert ran >= 1
+    D = torch.full((M, N2), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_b2b_gemm_chain(descs, dev(A), Wd, bd, D)  # built-in pick rule
+    torch.cuda.synchronize()
+    assert_close(host(D), want, "gemm chain %s heuristic" % (shape,))
+
+
+CONV_CHAINS = [  # (N, H, W, C, K0, R, S, stride, pad, K1, K2)
+    (2, 12, 12, 64, 64, 3, 3, 1, 1, 64, 64), (1, 17, 13, 24, 48, 3, 3, 2, 1, 48, 48), (2, 23, 23, 8, 64, 7, 7, 2, 3, 64, 256),
+    (3, 9, 11, 64, 64, 1, 1, 1, 0, 256, 64), (1, 10, 9, 16, 128, 5, 3, (1, 2), (2, 0), 64, 128)]
+
+
+@pytest.mark.parametrize("shape", CONV_CHAINS)
+def test_conv_chain3_every_instance_and_tuner(bolt, shape):
+    N, H, W, Cc, K0, R, S, stride, pad, K1, K2 = shape
+    x = wl.uniform_fp16(302, 0, (N, H, W, Cc), -1, 1)
+    ws = [wl.normal_fp16(302, 1, (K0, R, S, Cc), (2.0 / (R * S * Cc)) ** 0.5), wl.normal_fp16(302, 2, (K1, 1, 1, K0), (2.0 / K0) ** 0.5),
+          wl.normal_fp16(302, 3, (K2, 1, 1, K1), (2.0 / K1) ** 0.5)]
+    bs = [wl.uniform_fp16(302, 4, (K0,), -1, 1), wl.uniform_fp16(302, 5, (K1,), -1, 1), wl.uniform_fp16(302, 6, (K2,), -1, 1)]
+    acts = ["relu", "relu", "hardswish"]
+    want = ref.conv_chain(x, ws, bs, acts, stride=stride, pad=pad)
+    d0 = bolt.conv_desc(N, H, W, Cc, K0, R, S, stride, pad, act=acts[0])
+    P, Q = bolt.conv_out_hw(d0)
+    descs = [d0, bolt.conv_desc(N, P, Q, K0, K1, 1, 1, 1, 0, act=acts[1]), bolt.conv_desc(N, P, Q, K1, K2, 1, 1, 1, 0, act=acts[2])]
+    wd, bd = [dev(w) for w in ws], [dev(b) for b in bs]
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_CONV_CHAIN3)):
+        if not bolt.bolt_chain_instance_supports(bolt.OP_CONV_CHAIN3, kid, descs):
+            continue
+        _say("conv chain %s instance %d" % (shape, kid))
+        y = torch.full((N, P, Q, K2), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_b2b_conv_chain(descs, dev(x), wd, bd, y, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(y), want, "conv chain %s instance %d" % (shape, kid))
+        ran += 1
+    assert ran >= 1
+    y = torch.full((N, P, Q, K2), float("nan"), dtype=torch.float16, device="cuda")
+    res = bolt.bolt_tune_chain(bolt.OP_CONV_CHAIN3, descs, [dev(x), wd[0], bd[0], wd[1], bd[1], wd[2], bd[2], y])
+    assert res.tried == ran and res.ms > 0
+    y.fill_(float("nan"))
+    bolt.bolt_b2b_conv_chain(descs, dev(x), wd, bd, y, res.config)
+    torch.cuda.synchronize()
+    assert_close(host(y), want, "conv chain %s tuned" % (shape,))
+
+
+def test_gemm_chain3_integer_bit_exact(bolt):
+    M, K0, N0, N1, N2 = 300, 72, 64, 64, 128
+    A = wl.integer_fp16(303, 0, (M, K0), -2, 2)
+    Ws = [wl.integer_fp16(303, 1, (K0, N0), -1, 1), wl.integer_fp16(303, 2, (N0, N1), -1, 1), wl.integer_fp16(303, 3, (N1, N2), -1, 1)]
+    # keep intermediates small: sparse weights so that |D_i| stays exactly representable
+    for W in Ws:
+        W[np.arange(W.shape[0])[:, None] % 4 != np.arange(W.shape[1])[None, :] % 4] = 0
+    bs = [wl.integer_fp16(303, 4, (N0,), -2, 2), wl.integer_fp16(303, 5, (N1,), -2, 2), wl.integer_fp16(303, 6, (N2,), -2, 2)]
+    want = ref.gemm_chain(A, Ws, bs, ["relu", "relu", "relu"])
+    assert np.abs(want.astype(np.float64)).max() < 2048
+    descs = [bolt.gemm_desc(M, N0, K0, b_layout=bolt.LAYOUT_NK), bolt.gemm_desc(M, N1, N0, b_layout=bolt.LAYOUT_NK),
+             bolt.gemm_desc(M, N2, N1, b_layout=bolt.LAYOUT_NK)]
+    D = torch.empty((M, N2), dtype=torch.float16, device="cuda")
+    bolt.bolt_b2b_gemm_chain(descs, dev(A), [dev(np.ascontiguousarray(W.T)) for W in Ws], [dev(b) for b in bs], D)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(D), want, "integer gemm chain")
+
+
 @pytest.mark.parametrize("act", ["none", "relu", "gelu", "hardswish", "softplus"])
 def test_bias_act_standalone_epilogue(bolt, act):
     # several grid strides plus a ragged last block; with and without a bias; also M = 1 and M = 0

@@ -125,6 +125,31 @@ def test_b2b_fusion_legality(bolt):
     assert chk(bolt.OP_B2B_CONV, c0s, Cd(32, 28, 28, 64, 64, 1, 1, 1, 0)) == OK
 
 
+def test_chain_legality(bolt):
+    G, Cd, chk = bolt.gemm_desc, bolt.conv_desc, bolt.bolt_check_chain
+    nk = bolt.LAYOUT_NK
+    g = [G(4096, 64, 256, b_layout=nk), G(4096, 128, 64, b_layout=nk), G(4096, 64, 128, b_layout=nk)]
+    assert chk(bolt.OP_GEMM_CHAIN3, g) == OK
+    assert chk(bolt.OP_GEMM_CHAIN3, g[:2]) == UNSUPPORTED                                  # only three-op chains are compiled
+    assert chk(bolt.OP_GEMM_CHAIN3, [g[0], g[1], G(4096, 64, 120, b_layout=nk)]) == ILLEGAL  # K2 must equal N1
+    assert chk(bolt.OP_GEMM_CHAIN3, [g[0], g[1], G(4000, 64, 128, b_layout=nk)]) == ILLEGAL  # same M
+    assert chk(bolt.OP_GEMM_CHAIN3, [G(4096, 64, 256), G(4096, 128, 64), G(4096, 64, 128)]) == UNSUPPORTED  # row-major weights
+    assert chk(bolt.OP_GEMM_CHAIN3, [g[0], g[1], G(4096, 512, 128, b_layout=nk)]) == UNSUPPORTED  # N2 beyond every bound
+    assert chk(bolt.OP_GEMM, g) == INVALID
+    assert chk(bolt.OP_GEMM_CHAIN3, g, {"kernel_id": 9999}) == INVALID
+    c = [Cd(32, 56, 56, 64, 64, 3, 3, 1, 1), Cd(32, 56, 56, 64, 64, 1, 1, 1, 0), Cd(32, 56, 56, 64, 256, 1, 1, 1, 0)]
+    assert chk(bolt.OP_CONV_CHAIN3, c) == OK
+    assert chk(bolt.OP_CONV_CHAIN3, [c[0], c[1], Cd(32, 56, 56, 64, 256, 3, 3, 1, 1)]) == ILLEGAL   # later ops must be 1x1
+    assert chk(bolt.OP_CONV_CHAIN3, [c[0], c[1], Cd(32, 28, 28, 64, 256, 1, 1, 1, 0)]) == ILLEGAL   # extent must carry over
+    for op in (bolt.OP_GEMM_CHAIN3, bolt.OP_CONV_CHAIN3):
+        n = bolt.bolt_num_instances(op)
+        assert n >= 8
+        descs = g if op == bolt.OP_GEMM_CHAIN3 else c
+        ok = [i for i in range(n) if bolt.bolt_chain_instance_supports(op, i, descs)]
+        assert ok and all(bolt.bolt_instance_config(op, i).as_dict()["tile_n"] >= descs[2].N if op == bolt.OP_GEMM_CHAIN3
+                          else True for i in ok)
+
+
 def test_workspace_bytes(bolt):
     d = bolt.conv_desc(32, 7, 7, 512, 512, 3, 3, 1, 1)
     assert bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d, None, {"kernel_id": 0, "split_k": 4}) == 4 * 1568 * 512 * 4

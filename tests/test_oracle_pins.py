@@ -382,6 +382,41 @@ def test_b2b_conv_stride2_first_op():
     assert np.array_equal(y, t1)
 
 
+def test_chain_of_three_ops_rounds_between_ops_and_extends_b2b():
+    # integers small enough that every intermediate is exactly representable: the chain must equal float64
+    # matrix products with ReLUs, and the first two ops of it must be the b2b oracle bit for bit
+    A = wl.integer_fp16(41, 0, (37, 24), -2, 2)
+    Ws = [wl.integer_fp16(41, 1, (24, 16), -1, 1), wl.integer_fp16(41, 2, (16, 8), -1, 1), wl.integer_fp16(41, 3, (8, 24), -1, 1)]
+    bs = [wl.integer_fp16(41, 4, (16,), -2, 2), None, wl.integer_fp16(41, 5, (24,), -2, 2)]
+    got = ref.gemm_chain(A, Ws, bs, ["relu", "relu", "none"])
+    f = lambda a: a.astype(np.float64)
+    d0 = np.maximum(f(A) @ f(Ws[0]) + f(bs[0]), 0)
+    d1 = np.maximum(d0 @ f(Ws[1]), 0)
+    want = d1 @ f(Ws[2]) + f(bs[2])
+    assert np.abs(want).max() < 2048 and np.array_equal(f(got), want)
+    two = ref.b2b_gemm(A, Ws[0], bs[0], Ws[1], bs[1])
+    assert np.array_equal(ref.gemm_chain(A, Ws[:2], bs[:2], ["relu", "relu"]), two)
+    # with fractions the FP16 rounding between ops is visible: an unrounded chain differs somewhere
+    A = wl.uniform_fp16(42, 0, (64, 32), -1, 1)
+    Ws = [wl.uniform_fp16(42, 1 + i, s, -1, 1) for i, s in enumerate([(32, 32), (32, 32), (32, 16)])]
+    got = ref.gemm_chain(A, Ws, [None] * 3, ["relu"] * 3)
+    stepwise = f(A)
+    for W in Ws:
+        stepwise = f(np.maximum(stepwise @ f(W), 0).astype(np.float16))
+    unrounded = f(A)
+    for W in Ws:
+        unrounded = np.maximum(unrounded @ f(W), 0)
+    assert np.array_equal(f(got), stepwise) and not np.array_equal(f(got), unrounded.astype(np.float16).astype(np.float64))
+    # convolution chain == GEMM chain on the im2col of the first op
+    x = wl.integer_fp16(43, 0, (2, 6, 5, 8), -2, 2)
+    ws = [wl.integer_fp16(43, 1, (16, 3, 3, 8), -1, 1), wl.integer_fp16(43, 2, (8, 1, 1, 16), -1, 1), wl.integer_fp16(43, 3, (24, 1, 1, 8), -1, 1)]
+    cb = [wl.integer_fp16(43, 4, (16,), -2, 2), wl.integer_fp16(43, 5, (8,), -2, 2), None]
+    y = ref.conv_chain(x, ws, cb, ["relu", "relu", "relu"], stride=2, pad=1)
+    col = ref.im2col(x, 3, 3, 2, 1)
+    gw = [w.reshape(w.shape[0], -1).T for w in ws]
+    assert np.array_equal(y.reshape(-1, 24), ref.gemm_chain(col, gw, cb, ["relu"] * 3))
+
+
 # --------------------------------------------------------------------------------------------
 # epilogue activations (closed forms)
 # --------------------------------------------------------------------------------------------
