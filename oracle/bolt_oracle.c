@@ -197,6 +197,42 @@ void bolt_ref_conv2d_nhwc_at(int64_t N, int64_t H, int64_t W, int64_t C, int64_t
   }
 }
 
+/* ---- Eq. 1 with C a full pre-existing matrix (the skip connection of a residual block) ------------
+ * D[m,n] = act(alpha * sum_k A[m,k] B[k,n] + beta * bias[n] + gamma * C[m,n]); C is FP16, ldc elements
+ * per row.  The convolution form takes C in the output's NHWC layout. */
+static double epilogue_residual(double s, float alpha, float beta, const uint16_t *bias, int n, float gamma,
+                                uint16_t c, int act) {
+  double v = (double)alpha * s;
+  if (bias) v += (double)beta * bolt_ref_half_to_double(bias[n]);
+  v += (double)gamma * bolt_ref_half_to_double(c);
+  return apply_act(v, act);
+}
+
+void bolt_ref_gemm_residual(int64_t M, int64_t N, int64_t K, const uint16_t *A, int64_t lda, const uint16_t *B,
+                            int64_t ldb, const uint16_t *bias, const uint16_t *C, int64_t ldc, float alpha,
+                            float beta, float gamma, int act, uint16_t *D, int64_t ldd) {
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m)
+    for (int64_t n = 0; n < N; ++n)
+      D[m * ldd + n] = bolt_ref_double_to_half(
+          epilogue_residual(gemm_dot(A, lda, B, ldb, m, n, K), alpha, beta, bias, (int)n, gamma, C[m * ldc + n], act));
+}
+
+void bolt_ref_conv2d_nhwc_residual(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                                   int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                   const uint16_t *x, const uint16_t *w, const uint16_t *bias, const uint16_t *res,
+                                   float alpha, float beta, float gamma, int act, uint16_t *y) {
+  conv_dims d = {N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w};
+  int64_t P = out_extent(H, pad_h, R, stride_h), Q = out_extent(W, pad_w, S, stride_w);
+#pragma omp parallel for schedule(static)
+  for (int64_t row = 0; row < N * P * Q; ++row) {
+    int64_t n = row / (P * Q), p = (row / Q) % P, q = row % Q;
+    for (int64_t k = 0; k < K; ++k)
+      y[row * K + k] = bolt_ref_double_to_half(
+          epilogue_residual(conv_dot(&d, x, w, n, p, q, k), alpha, beta, bias, (int)k, gamma, res[row * K + k], act));
+  }
+}
+
 /* ---- back-to-back chains: two explicit ops, D0 stored as binary16 ------------------------ */
 
 void bolt_ref_b2b_gemm(int64_t M, int64_t N0, int64_t K0, int64_t N1, const uint16_t *A0, int64_t lda,

@@ -44,6 +44,11 @@ def lib():
         L.bolt_ref_double_to_half.argtypes = [C.c_double]
         L.bolt_ref_bias_act.restype = None
         L.bolt_ref_bias_act.argtypes = [_i64, _i64, _p, _i64, _p, _f32, _f32, _int, _p, _i64]
+        L.bolt_ref_gemm_residual.restype = None
+        L.bolt_ref_gemm_residual.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i64, _f32, _f32, _f32, _int,
+                                             _p, _i64]
+        L.bolt_ref_conv2d_nhwc_residual.restype = None
+        L.bolt_ref_conv2d_nhwc_residual.argtypes = [_i64] * 11 + [_p, _p, _p, _p, _f32, _f32, _f32, _int, _p]
         L.bolt_ref_gemm.restype = None
         L.bolt_ref_gemm.argtypes = [_i64] * 3 + [_p, _i64, _p, _i64, _p, _f32, _f32, _int, _p, _i64]
         L.bolt_ref_gemm_at.restype = None
@@ -203,6 +208,33 @@ def b2b_conv_rows(x, w0, b0, w1, b1, rows, stride=1, pad=0, alpha0=1.0, beta0=1.
                                  beta0, ACT[act0], _ptr(w1), _ptr(b1), alpha1, beta1, ACT[act1], rows.size,
                                  _ptr(rows), _ptr(out))
     return out
+
+
+def gemm_residual(A, B, bias, C, alpha=1.0, beta=1.0, gamma=1.0, act="relu"):
+    """act(alpha * A @ B + beta * bias + gamma * C) -> float16; Eq. 1 with a full matrix C (B is [K][N])."""
+    A, B, C = _h(A), _h(B), _h(C)
+    M, K = A.shape
+    N = B.shape[1]
+    assert B.shape[0] == K and C.shape == (M, N)
+    bias = None if bias is None else _h(bias)
+    D = np.empty((M, N), np.float16)
+    lib().bolt_ref_gemm_residual(M, N, K, _ptr(A), K, _ptr(B), N, _ptr(bias), _ptr(C), N, alpha, beta, gamma, ACT[act],
+                                 _ptr(D), N)
+    return D
+
+
+def conv2d_nhwc_residual(x, w, bias, res, stride=1, pad=0, alpha=1.0, beta=1.0, gamma=1.0, act="relu"):
+    """act(alpha * conv(x, w) + beta * bias + gamma * res), res in the output's NHWC layout."""
+    x, w, res = _h(x), _h(w), _h(res)
+    N, H, W, Cc = x.shape
+    K, R, S, _ = w.shape
+    P, Q, sh, sw, ph, pw = out_hw(H, W, R, S, stride, pad)
+    assert res.shape == (N, P, Q, K)
+    bias = None if bias is None else _h(bias)
+    y = np.empty((N, P, Q, K), np.float16)
+    lib().bolt_ref_conv2d_nhwc_residual(N, H, W, Cc, K, R, S, sh, sw, ph, pw, _ptr(x), _ptr(w), _ptr(bias), _ptr(res),
+                                        alpha, beta, gamma, ACT[act], _ptr(y))
+    return y
 
 
 def gemm_chain(A, Ws, bs, acts, alphas=None, betas=None):

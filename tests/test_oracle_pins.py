@@ -382,6 +382,34 @@ def test_b2b_conv_stride2_first_op():
     assert np.array_equal(y, t1)
 
 
+def test_residual_epilogue_full_matrix_c():
+    # Eq. 1 with C a full matrix: against numpy float64 (exact on integers, half-ulp on fractions), the
+    # gamma = 0 and C = 0 cases reduce to the plain ops, and conv == im2col GEMM with the same residual
+    A = wl.integer_fp16(51, 0, (33, 24), -3, 3)
+    B = wl.integer_fp16(51, 1, (24, 16), -3, 3)
+    bias = wl.integer_fp16(51, 2, (16,), -4, 4)
+    Cm = wl.integer_fp16(51, 3, (33, 16), -9, 9)
+    f = lambda a: a.astype(np.float64)
+    got = ref.gemm_residual(A, B, bias, Cm, 1.0, 1.0, -2.0, "relu")
+    assert np.array_equal(f(got), np.maximum(f(A) @ f(B) + f(bias) - 2.0 * f(Cm), 0))
+    assert np.array_equal(ref.gemm_residual(A, B, bias, Cm, gamma=0.0), ref.gemm(A, B, bias))
+    assert np.array_equal(ref.gemm_residual(A, B, bias, np.zeros_like(Cm)), ref.gemm(A, B, bias))
+    # a transposed or row-shifted C would break this: C varies along both axes
+    Au, Bu, Cu = wl.uniform_fp16(52, 0, (20, 40), -1, 1), wl.uniform_fp16(52, 1, (40, 24), -1, 1), wl.uniform_fp16(52, 2, (20, 24), -4, 4)
+    got = f(ref.gemm_residual(Au, Bu, None, Cu, 0.5, 1.0, 0.25, "none"))
+    want = 0.5 * (f(Au) @ f(Bu)) + 0.25 * f(Cu)
+    ulp = np.spacing(np.abs(want).astype(np.float16)).astype(np.float64)
+    assert np.all(np.abs(got - want) <= 0.5 * ulp * (1 + 1e-6) + 1e-300)
+    x = wl.integer_fp16(53, 0, (2, 6, 5, 8), -2, 2)
+    w = wl.integer_fp16(53, 1, (16, 3, 3, 8), -1, 1)
+    b = wl.integer_fp16(53, 2, (16,), -2, 2)
+    res = wl.integer_fp16(53, 3, (2, 3, 3, 16), -5, 5)
+    y = ref.conv2d_nhwc_residual(x, w, b, res, stride=2, pad=1)
+    col = ref.im2col(x, 3, 3, 2, 1)
+    assert np.array_equal(y.reshape(-1, 16), ref.gemm_residual(col, w.reshape(16, -1).T, b, res.reshape(-1, 16)))
+    assert not np.array_equal(y, ref.conv2d_nhwc(x, w, b, stride=2, pad=1))
+
+
 def test_chain_of_three_ops_rounds_between_ops_and_extends_b2b():
     # integers small enough that every intermediate is exactly representable: the chain must equal float64
     # matrix products with ReLUs, and the first two ops of it must be the b2b oracle bit for bit
