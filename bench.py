@@ -561,6 +561,27 @@ def main():
             entry["status"] = str(e)
         chains.append(entry)
     out["chains_of_three"] = chains
+
+    # ------------------------------------------------------------------ residual epilogue (context)
+    # The last 1x1 convolution of a ResNet bottleneck block with its skip connection added in the epilogue
+    # (Eq. 1's C as a full matrix), against the same tuned kernel without it: the cost of the extra read.
+    resid = []
+    try:
+        for (H, Cin, Cout) in ((56, 64, 256), (28, 128, 512), (14, 256, 1024), (7, 512, 2048)):
+            x, w, b = rnd(32, H, H, Cin), rnd(Cout, 1, 1, Cin, scale=0.1), rnd(Cout)
+            r, y = rnd(32, H, H, Cout), empty(32, H, H, Cout)
+            d = bolt.conv_desc(32, H, H, Cin, Cout, 1, 1, 1, 0)
+            cfg = tuned("residual 1x1 %dx%d %d->%d" % (H, H, Cin, Cout), bolt.OP_CONV2D, d, None, [x, w, b, y], ws)
+            mp = timed(lambda: bolt.bolt_conv2d_fprop_nhwc(d, x, w, b, y, cfg, ws), args.reps)
+            mr = timed(lambda: bolt.bolt_conv2d_fprop_nhwc_residual(d, x, w, b, r, y, 1.0, cfg, ws), args.reps)
+            extra = 2.0 * r.numel()
+            resid.append(dict(name="conv1x1 %dx%d %d->%d + bias + skip + ReLU" % (H, H, Cin, Cout), plain_ms=round(mp, 5),
+                              residual_ms=round(mr, 5), extra_read_mb=round(extra / 1e6, 1),
+                              extra_read_gbs=round(extra / max(mr - mp, 1e-6) / 1e6, 1)))
+            del x, r, y
+    except Exception as e:  # context only
+        resid.append({"error": str(e)})
+    out["residual_epilogue"] = resid
     try:
         out["probes"] = {"mfma_loop_tflops": round(bolt.bolt_probe_mfma_peak(20000), 1),
                          "copy_gbs_1GiB": round(bolt.bolt_probe_copy_bandwidth(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"), 5), 1)}

@@ -142,6 +142,21 @@ bolt_status bolt_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc* c1, co
                           const void* b0, const void* w1, const void* b1, void* y, const bolt_config* config,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same two ops with Eq. 1's C as a full pre-existing matrix next to the broadcast bias (the skip
+ * connection of a residual block, added before the activation):
+ *   D[m, n] = act(alpha * (A . B)[m, n] + beta * bias[n] + gamma * C[m, n]).
+ * C: device, FP16, M x N with row stride ldc (GEMM; ldc >= N, ldc % 8 == 0), or in the output's NHWC
+ * layout N*P*Q*K (convolution).  C may be the output buffer itself (each element is read before it is
+ * written, by the workgroup that owns it) unless split_k > 1.  Everything else as in the calls above;
+ * a config tuned for the plain op is valid here unless it names one of the persistent weights-resident
+ * instances (BOLT_ERR_UNSUPPORTED). */
+bolt_status bolt_gemm_epilogue_residual(const bolt_gemm_desc* desc, const void* A, const void* B, const void* bias,
+                                        const void* C, int32_t ldc, float gamma, void* D, const bolt_config* config,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+bolt_status bolt_conv2d_fprop_nhwc_residual(const bolt_conv_desc* desc, const void* x, const void* w, const void* bias,
+                                            const void* residual, float gamma, void* y, const bolt_config* config,
+                                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* Persistent fusion of more than two ops (Section 3.1.1: the scheme extends to longer chains by
  * duplicating the pipeline; Section 3.3 deepens models with extra 1x1 convolutions that fuse this way).
  * n_ops = 3 is compiled; any other positive n_ops is BOLT_ERR_UNSUPPORTED.

@@ -10,6 +10,8 @@ from .binding import (ACT, LAYOUT_KN, LAYOUT_NK, OP_B2B_CONV, OP_B2B_GEMM, OP_CO
 # the C ABI's entry points under their own names
 bolt_gemm_epilogue = binding.gemm_epilogue
 bolt_conv2d_fprop_nhwc = binding.conv2d_fprop_nhwc
+bolt_gemm_epilogue_residual = binding.gemm_epilogue_residual
+bolt_conv2d_fprop_nhwc_residual = binding.conv2d_fprop_nhwc_residual
 bolt_b2b_gemm = binding.b2b_gemm
 bolt_b2b_conv = binding.b2b_conv
 bolt_tune = binding.tune

@@ -87,6 +87,12 @@ _lib.bolt_b2b_conv.argtypes = [C.POINTER(ConvDesc), C.POINTER(ConvDesc), _vp, _v
 _lib.bolt_tune.restype = C.c_int
 _lib.bolt_tune.argtypes = [C.c_int, _vp, _vp, C.POINTER(_vp), _vp, _sz, _vp, C.POINTER(BoltConfig),
                            C.POINTER(C.c_float), C.POINTER(_i32)]
+_lib.bolt_gemm_epilogue_residual.restype = C.c_int
+_lib.bolt_gemm_epilogue_residual.argtypes = [C.POINTER(GemmDesc), _vp, _vp, _vp, _vp, _i32, C.c_float, _vp,
+                                             C.POINTER(BoltConfig), _vp, _sz, _vp]
+_lib.bolt_conv2d_fprop_nhwc_residual.restype = C.c_int
+_lib.bolt_conv2d_fprop_nhwc_residual.argtypes = [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, C.c_float, _vp,
+                                                 C.POINTER(BoltConfig), _vp, _sz, _vp]
 _pp = C.POINTER(_vp)
 _lib.bolt_b2b_gemm_chain.restype = C.c_int
 _lib.bolt_b2b_gemm_chain.argtypes = [_i32, _pp, _vp, _pp, _pp, _vp, C.POINTER(BoltConfig), _vp]
@@ -108,7 +114,7 @@ _lib.bolt_probe_copy_bandwidth.restype = C.c_int
 _lib.bolt_probe_copy_bandwidth.argtypes = [_vp, _sz, _i32, _vp, C.POINTER(C.c_float)]
 
 EXPORTED = ["bolt_gemm_epilogue", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune",
-            "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain", "bolt_tune_chain", "bolt_check_chain",
+            "bolt_gemm_epilogue_residual", "bolt_conv2d_fprop_nhwc_residual", "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain", "bolt_tune_chain", "bolt_check_chain",
             "bolt_chain_instance_supports",
             "bolt_pad_channels_nhwc", "bolt_bias_act", "bolt_workspace_bytes", "bolt_check", "bolt_status_string",
             "bolt_num_instances", "bolt_instance_config", "bolt_instance_supports", "bolt_probe_mfma_peak",
@@ -230,6 +236,25 @@ def conv2d_fprop_nhwc(desc: ConvDesc, x, w, bias, y, config=None, workspace=None
     _check(_lib.bolt_conv2d_fprop_nhwc(C.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y),
                                        None if c is None else C.byref(c), wp, wb, _stream()),
            "bolt_conv2d_fprop_nhwc")
+    return y
+
+
+def gemm_epilogue_residual(desc: GemmDesc, A, B, bias, Cres, D, gamma: float = 1.0, config=None, workspace=None):
+    """D = act(alpha A.B + beta bias + gamma Cres); Cres is a contiguous M x N tensor."""
+    c = _cfg(config)
+    wp, wb = _ws(workspace)
+    _check(_lib.bolt_gemm_epilogue_residual(C.byref(desc), _ptr(A), _ptr(B), _ptr(bias), _ptr(Cres), Cres.shape[-1], gamma,
+                                            _ptr(D), None if c is None else C.byref(c), wp, wb, _stream()),
+           "bolt_gemm_epilogue_residual")
+    return D
+
+
+def conv2d_fprop_nhwc_residual(desc: ConvDesc, x, w, bias, residual, y, gamma: float = 1.0, config=None, workspace=None):
+    c = _cfg(config)
+    wp, wb = _ws(workspace)
+    _check(_lib.bolt_conv2d_fprop_nhwc_residual(C.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), gamma, _ptr(y),
+                                                None if c is None else C.byref(c), wp, wb, _stream()),
+           "bolt_conv2d_fprop_nhwc_residual")
     return y
 
 

@@ -28,7 +28,8 @@ static constexpr int kMaxSplitK = 8;
 // Sums split-K partials and applies the epilogue once.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial, const half_t* bias, half_t* Y,
                                                             int M, int N, int ldy, int split_k, float alpha,
-                                                            float beta, int act) {
+                                                            float beta, int act, const half_t* res, int ldr,
+                                                            float gamma) {
   const int64_t quads = (int64_t)M * (N / 4);
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < quads; i += (int64_t)gridDim.x * blockDim.x) {
     const int m = (int)(i / (N / 4)), n = (int)(i % (N / 4)) * 4;
@@ -39,6 +40,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial
     for (int e = 0; e < 4; ++e) {
       float v = alpha * s[e];
       if (bias) v += beta * (float)bias[n + e];
+      if (res) v += gamma * (float)res[(int64_t)m * ldr + n + e];
       o[e] = (half_t)apply_act(v, act);
     }
     *(half4*)(Y + (int64_t)m * ldy + n) = o;
@@ -243,6 +245,7 @@ static bolt_status check_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc
 struct FpropProblem {
   FpropParams p;  // pointers filled in at launch
   int xmode, wmode;
+  bool residual;  // the call carries a residual matrix (Eq. 1's C): kernels without that epilogue are excluded
 };
 
 static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
@@ -253,6 +256,7 @@ static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
   } else if (in.xmode != pr.xmode) {
     return false;
   }
+  if (in.stream_launch && pr.residual) return false;  // the persistent kernels have no residual epilogue
   if (in.stream_launch) {
     // persistent weights-resident kernel: the tile spans all of N and the whole weight matrix
     // must fit in LDS next to the activation stages
@@ -343,7 +347,7 @@ static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int sw
     const int blocks = (int)std::min<int64_t>((quads + 255) / 256, kNumCU * 8);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, stream, p.partial,
                        p.bias_on ? p.bias : (const half_t*)nullptr, p.Y, p.M, p.N,
-                       p.ldy, split_k, p.alpha, p.beta, p.act);
+                       p.ldy, split_k, p.alpha, p.beta, p.act, p.res, p.ldr, p.gamma);
     if (hipGetLastError() != hipSuccess) return BOLT_ERR_LAUNCH;
   }
   return BOLT_OK;
@@ -844,6 +848,44 @@ bolt_status bolt_conv2d_fprop_nhwc(const bolt_conv_desc* desc, const void* x, co
   s = resolve_fprop(tables().conv, pr, config, &id, &swz, &sk);
   if (s != BOLT_OK) return s;
   pr.p.X = (const half_t*)x; pr.p.W = (const half_t*)w; pr.p.bias = (const half_t*)bias; pr.p.Y = (half_t*)y;
+  return fprop_launch(tables().conv[id], pr, swz, sk, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+bolt_status bolt_gemm_epilogue_residual(const bolt_gemm_desc* desc, const void* A, const void* B, const void* bias,
+                                        const void* C, int32_t ldc, float gamma, void* D, const bolt_config* config,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  FpropProblem pr;
+  bolt_status s = make_gemm_problem(desc, &pr);
+  if (s != BOLT_OK) return s;
+  if (!A || !B || !C || !D || ldc < desc->N) return BOLT_ERR_INVALID_ARG;
+  if ((ldc & 7) || !is_aligned16(A) || !is_aligned16(B) || !is_aligned16(C) || !is_aligned16(D) ||
+      (bias && !is_aligned16(bias)))
+    return BOLT_ERR_ALIGNMENT;
+  pr.residual = true;
+  int id, swz, sk;
+  s = resolve_fprop(tables().gemm, pr, config, &id, &swz, &sk);
+  if (s != BOLT_OK) return s;
+  pr.p.X = (const half_t*)A; pr.p.W = (const half_t*)B; pr.p.bias = (const half_t*)bias; pr.p.Y = (half_t*)D;
+  pr.p.res = (const half_t*)C; pr.p.ldr = ldc; pr.p.gamma = gamma;
+  return fprop_launch(tables().gemm[id], pr, swz, sk, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+bolt_status bolt_conv2d_fprop_nhwc_residual(const bolt_conv_desc* desc, const void* x, const void* w, const void* bias,
+                                            const void* residual, float gamma, void* y, const bolt_config* config,
+                                            void* workspace, size_t workspace_bytes, void* stream) {
+  FpropProblem pr;
+  bolt_status s = make_conv_problem(desc, &pr);
+  if (s != BOLT_OK) return s;
+  if (!x || !w || !residual || !y) return BOLT_ERR_INVALID_ARG;
+  if (!is_aligned16(x) || !is_aligned16(w) || !is_aligned16(residual) || !is_aligned16(y) ||
+      (bias && !is_aligned16(bias)))
+    return BOLT_ERR_ALIGNMENT;
+  pr.residual = true;
+  int id, swz, sk;
+  s = resolve_fprop(tables().conv, pr, config, &id, &swz, &sk);
+  if (s != BOLT_OK) return s;
+  pr.p.X = (const half_t*)x; pr.p.W = (const half_t*)w; pr.p.bias = (const half_t*)bias; pr.p.Y = (half_t*)y;
+  pr.p.res = (const half_t*)residual; pr.p.ldr = desc->K; pr.p.gamma = gamma;
   return fprop_launch(tables().conv[id], pr, swz, sk, workspace, workspace_bytes, (hipStream_t)stream);
 }
 

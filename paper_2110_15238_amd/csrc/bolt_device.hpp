@@ -121,15 +121,19 @@ struct EpilogueArgs {
   int bias_on, N;
   float alpha, beta;
   int act;
+  float gamma = 0.f;  // scale of the residual quad (Eq. 1 with a full matrix C), epilogue_quad_res only
 };
 
-template <bool SLOW>
-__device__ __forceinline__ half4 epilogue_quad(const floatx16& acc, int q, int n, const EpilogueArgs& ep) {
+template <bool SLOW, bool RES>
+__device__ __forceinline__ half4 epilogue_quad_impl(const floatx16& acc, int q, int n, const EpilogueArgs& ep, half4 res) {
   const half4 hb = *(const half4*)(ep.bias + (n < ep.N ? n : 0) * ep.bias_on);
   half4 o;
   floatx4 v;
 #pragma unroll
-  for (int e = 0; e < 4; ++e) v[e] = ep.alpha * acc[q * 4 + e] + ep.beta * (float)hb[e];
+  for (int e = 0; e < 4; ++e) {
+    v[e] = ep.alpha * acc[q * 4 + e] + ep.beta * (float)hb[e];
+    if constexpr (RES) v[e] += ep.gamma * (float)res[e];
+  }
   if constexpr (SLOW) {
     v = apply_act_slow4(v, ep.act);
   } else {
@@ -142,6 +146,16 @@ __device__ __forceinline__ half4 epilogue_quad(const floatx16& acc, int q, int n
 #pragma unroll
   for (int e = 0; e < 4; ++e) o[e] = (half_t)v[e];
   return o;
+}
+template <bool SLOW>
+__device__ __forceinline__ half4 epilogue_quad(const floatx16& acc, int q, int n, const EpilogueArgs& ep) {
+  const half4 none = {0, 0, 0, 0};
+  return epilogue_quad_impl<SLOW, false>(acc, q, n, ep, none);
+}
+// The same with a residual: out = act(alpha * acc + beta * bias[n + e] + gamma * res[e]) (Eq. 1, C a full matrix).
+template <bool SLOW>
+__device__ __forceinline__ half4 epilogue_quad_res(const floatx16& acc, int q, int n, const EpilogueArgs& ep, half4 res) {
+  return epilogue_quad_impl<SLOW, true>(acc, q, n, ep, res);
 }
 
 // Workgroup id -> output tile.  mode 0: n-tile fastest.  mode g > 0: ids are first regrouped so

@@ -295,7 +295,7 @@ __device__ __forceinline__ void conv_halo_mainloop(const HaloArgs& h, half_t* ld
 
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG = 1>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG = 1, bool RES = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(const FpropParams p) {
   using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>;
   constexpr int NW = T_::NW, WTM = T_::WTM, WTN = T_::WTN, FM = T_::FM, FN = T_::FN;
@@ -342,54 +342,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void conv_halo_kernel(
     }
   }
 
-  // ---- epilogue: registers -> FP16 C tile in LDS -> coalesced stores ---------------------------------
-  constexpr int CPR = T_::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
-  const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act};
-  barrier_after_lds_writes();
-  auto tile_to_lds = [&](auto slow) {
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;
-#pragma unroll
-        for (int b = 0; b < FM; ++b) {
-          const int row = wm * WTM + b * 32 + l32;
-          *(half4*)(lds + row * BN + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
-              epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
-        }
-      }
-  };
-  if (kg == 0) {
-    if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
-    else tile_to_lds(std::false_type{});
-  }
-  barrier_after_lds_writes();
-  if (tid < T_::STORE_THREADS) {
-    const int chunk16 = tid % CPR, r0 = tid / CPR;
-    const int n = n0 + chunk16 * 8;
-    if (n < p.N) {
-#pragma unroll
-      for (int i = 0; i < BM / T_::ROWS_PER_PASS; ++i) {
-        const int row = r0 + i * T_::ROWS_PER_PASS;
-        if (m0 + row < p.M) {
-          const half8 v = *(const half8*)(lds + row * BN + ((chunk16 ^ (row & CSW)) << 3));
-          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
-        }
-      }
-    }
-  }
+  // ---- epilogue: registers -> FP16 C tile in LDS -> coalesced stores (fprop_dma_kernel.hpp) ----------------
+  fprop_tile_out<RES, BM, BN, WTM, WTN, T_::STORE_THREADS, T_::ROWS_PER_PASS>(lds, acc, p, m0, n0, wm, wn, kg == 0, tid);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int NS, int XI, int KG = 1>
 hipError_t launch_conv_halo(const FpropParams& p, hipStream_t stream) {
   using T_ = ConvHaloTraits<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>;
-  auto kern = conv_halo_kernel<BM, BN, WAVES_M, WAVES_N, NS, XI, KG>;
-  static bool attr_set = false;
-  if (!attr_set) {
+  // the residual epilogue is a kernel of its own (fprop_tile_out in fprop_dma_kernel.hpp)
+  auto kern = p.res ? conv_halo_kernel<BM, BN, WAVES_M, WAVES_N, NS, XI, KG, true>
+                    : conv_halo_kernel<BM, BN, WAVES_M, WAVES_N, NS, XI, KG, false>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[p.res ? 1 : 0]) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[p.res ? 1 : 0] = true;
   }
   dim3 grid(p.tiles_m * p.tiles_n, 1, 1);
   hipLaunchKernelGGL(kern, grid, dim3(T_::NT), T_::lds_bytes(p), stream, p);

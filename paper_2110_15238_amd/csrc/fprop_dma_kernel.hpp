@@ -207,6 +207,74 @@ struct DmaTileLoader {
   }
 };
 
+// Last step of the tiled single-op kernels: accumulators -> FP16 C tile in LDS ([BM][BN], 16-byte chunks
+// XOR-swizzled by row, over whatever the main loop left there) -> 16-byte coalesced non-temporal row stores.
+// RES (Eq. 1's C as a full matrix, p.res): the residual tile is first brought into the same LDS locations
+// and every lane reads the quad it is about to overwrite.  RES is a compile-time switch: the residual kernels
+// are separate instantiations, so the plain kernels keep their register allocation and occupancy.
+// `writer`: this wave holds the final accumulators (k-group 0).  Called by every thread of the workgroup.
+template <bool RES, int BM, int BN, int WTM, int WTN, int STORE_THREADS, int ROWS_PER_PASS, int FN, int FM>
+__device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc)[FN][FM], const FpropParams& p, int m0,
+                                               int n0, int wm, int wn, bool writer, int tid) {
+  constexpr int CPR = BN / 8, CSW = CPR >= 8 ? 7 : CPR - 1;
+  const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
+  const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act, p.gamma};
+  barrier_after_lds_writes();  // every wave has finished reading what the tile overwrites
+  if constexpr (RES) {
+    // direct-to-LDS, 16 bytes per lane: one instruction fills 1024 contiguous LDS bytes = RPI whole tile
+    // rows; a lane's slot is fixed, so the row swizzle is applied to which global chunk it fetches.
+    // Rows beyond M and columns beyond N are zero-filled.  No registers are held while the loads fly.
+    constexpr int RPI = 64 / CPR > 0 ? 64 / CPR : 1, LPR = CPR < 64 ? CPR : 64;
+    static_assert(CPR <= 64 && BM % RPI == 0, "residual tile rows per load instruction");
+    const int64_t rem = ((int64_t)(p.M - m0 - 1) * p.ldr + p.N) * 2;
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(p.res + (int64_t)m0 * p.ldr, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff));
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = (int)(blockDim.x >> 6);
+    for (int i = wave_all; i < BM / RPI; i += nwaves) {
+      const int row = i * RPI + lane / LPR;
+      const int c = (lane % LPR) ^ (row & CSW);
+      const bool ok = m0 + row < p.M && n0 + c * 8 < p.N;
+      const unsigned off = ok ? (unsigned)((row * p.ldr + n0 + c * 8) * 2) : kInvalidOffset;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rr, BOLT_LDS_PTR(lds + i * RPI * BN), 16, off, 0, 0, 0);
+    }
+    barrier_after_loads<0>();
+  }
+  auto tile_to_lds = [&](auto slow) {
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;  // column inside the tile
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+          const int row = wm * WTM + b * 32 + l32;
+          half4* slot = (half4*)(lds + row * BN + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4));
+          if constexpr (RES) *slot = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep, *slot);
+          else *slot = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
+        }
+      }
+  };
+  if (writer) {
+    if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
+    else tile_to_lds(std::false_type{});
+  }
+  barrier_after_lds_writes();
+  // LDS -> global: each thread moves 16 bytes, consecutive threads cover consecutive row bytes
+  if (tid < STORE_THREADS) {
+    const int chunk = tid % CPR, r0 = tid / CPR;
+    const int n = n0 + chunk * 8;
+    if (n < p.N) {
+#pragma unroll
+      for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
+        const int row = r0 + i * ROWS_PER_PASS;
+        if (m0 + row < p.M) {
+          const half8 v = *(const half8*)(lds + row * BN + ((chunk ^ (row & CSW)) << 3));
+          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
+        }
+      }
+    }
+  }
+}
+
 // KG k-groups: KG sets of WAVES_M x WAVES_N waves work on the same output tile, set g on the k-tiles
 // g, g+KG, ...; the sets' accumulators are summed through LDS before the epilogue.  This multiplies
 // the waves in flight for problems whose tile count cannot fill the chip, without a second kernel.
@@ -234,7 +302,7 @@ struct FpropDmaTraits {
   static_assert(STORE_THREADS % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
 };
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1, bool RES = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(const FpropParams p) {
   using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
   constexpr int WPG = T::WPG, WTM = T::WTM, WTN = T::WTN, FM = T::FM, FN = T::FN;
@@ -491,55 +559,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
     return;
   }
 
-  // registers -> FP16 C tile in LDS ([BM][BN], 16-byte chunks XOR-swizzled by row)
-  constexpr int CPR = T::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
-  const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act};
-  barrier_after_lds_writes();  // every wave has finished reading the operand stages
-  auto tile_to_lds = [&](auto slow) {
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;  // column inside the tile
-#pragma unroll
-        for (int b = 0; b < FM; ++b) {
-          const int row = wm * WTM + b * 32 + l32;
-          *(half4*)(lds + row * BN + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
-              epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
-        }
-      }
-  };
-  if (kg == 0) {
-    if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
-    else tile_to_lds(std::false_type{});
-  }
-  barrier_after_lds_writes();
-  // LDS -> global: each thread moves 16 bytes, consecutive threads cover consecutive row bytes
-  if (tid < T::STORE_THREADS) {
-    const int chunk = tid % CPR, r0 = tid / CPR;
-    const int n = n0 + chunk * 8;
-    if (n < p.N) {
-#pragma unroll
-      for (int i = 0; i < BM / T::ROWS_PER_PASS; ++i) {
-        const int row = r0 + i * T::ROWS_PER_PASS;
-        if (m0 + row < p.M) {
-          const half8 v = *(const half8*)(lds + row * BN + ((chunk ^ (row & CSW)) << 3));
-          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
-        }
-      }
-    }
-  }
+  fprop_tile_out<RES, BM, BN, WTM, WTN, T::STORE_THREADS, T::ROWS_PER_PASS>(lds, acc, p, m0, n0, wm, wn, kg == 0, tid);
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1>
 hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
   using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
-  auto kern = fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
-  static bool attr_set = false;
-  if (!attr_set) {
+  // the residual epilogue is a kernel of its own (see fprop_tile_out)
+  auto kern = p.res ? fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG, true>
+                    : fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG, false>;
+  static bool attr_set[2] = {false, false};
+  if (!attr_set[p.res ? 1 : 0]) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[p.res ? 1 : 0] = true;
   }
   dim3 grid(p.tiles_m * p.tiles_n, p.split_k, 1);
   hipLaunchKernelGGL(kern, grid, dim3(T::NT), T::LDS_BYTES, stream, p);

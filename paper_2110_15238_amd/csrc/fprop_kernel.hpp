@@ -29,6 +29,9 @@ struct FpropParams {
   const half_t* bias;  // [N]; never null inside the kernels: without a bias it addresses 8 zero halves
   int bias_on;         // 1 with a bias, 0 without (multiplies the bias index)
   half_t* Y;           // [M][ldy]
+  const half_t* res;   // residual matrix C of Eq. 1, [M][ldr], or nullptr: Y = act(alpha acc + beta bias + gamma res)
+  int ldr;
+  float gamma;
   float* partial;      // split-K partial sums [split_k][M][N], or nullptr
   int M, N, K;
   int ldx, ldw, ldy;
@@ -142,8 +145,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_kernel(const Fpr
         }
     return;
   }
-  const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act};
-  auto store_tile = [&](auto slow) {
+  const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act, p.gamma};
+  auto store_tile = [&](auto slow, auto with_res) {
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
@@ -152,13 +155,26 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_kernel(const Fpr
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
           const int m = mrow + b * 32;
-          const half4 o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n, ep);
-          if (n < p.N && m < p.M) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
+          const bool ok = n < p.N && m < p.M;
+          half4 o;
+          if constexpr (decltype(with_res)::value) {
+            const half4 zero = {0, 0, 0, 0};
+            const half4 r = ok ? *(const half4*)(p.res + (int64_t)m * p.ldr + n) : zero;
+            o = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n, ep, r);
+          } else {
+            o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n, ep);
+          }
+          if (ok) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
         }
       }
   };
-  if (p.act > ACT_RELU) store_tile(std::true_type{});
-  else store_tile(std::false_type{});
+  if (p.res) {
+    if (p.act > ACT_RELU) store_tile(std::true_type{}, std::true_type{});
+    else store_tile(std::false_type{}, std::true_type{});
+  } else {
+    if (p.act > ACT_RELU) store_tile(std::true_type{}, std::false_type{});
+    else store_tile(std::false_type{}, std::false_type{});
+  }
 }
 
 struct FpropInstance {

@@ -562,6 +562,89 @@ def test_config5_layer_full_size_tuned_sampled(bolt, index):
 
 
 # ---------------------------------------------------------------------------------------------
+# residual epilogue (Eq. 1 with C a full matrix)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("layout", ["kn", "nk"])
+def test_gemm_residual_every_instance(bolt, layout):
+    lay = bolt.LAYOUT_KN if layout == "kn" else bolt.LAYOUT_NK
+    for (M, N, K, act) in [(333, 136, 200, "relu"), (200, 72, 64, "gelu"), (1, 8, 8, "none")]:
+        A = wl.uniform_fp16(401, 0, (M, K), -1, 1)
+        B = wl.uniform_fp16(401, 1, (K, N), -1, 1)
+        bias = wl.uniform_fp16(401, 2, (N,), -1, 1)
+        Cm = wl.uniform_fp16(401, 3, (M, N), -4, 4)
+        want = ref.gemm_residual(A, B, bias, Cm, 1.0, 1.0, 0.5, act)
+        d = bolt.gemm_desc(M, N, K, act=act, b_layout=lay)
+        Bd = dev(B) if layout == "kn" else dev(np.ascontiguousarray(B.T))
+        ran = 0
+        for kid in range(bolt.bolt_num_instances(bolt.OP_GEMM)):
+            if not bolt.bolt_instance_supports(bolt.OP_GEMM, kid, d):
+                continue
+            _say("gemm residual %s %dx%dx%d instance %d" % (layout, M, N, K, kid))
+            D = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+            try:
+                bolt.bolt_gemm_epilogue_residual(d, dev(A), Bd, dev(bias), dev(Cm), D, 0.5, {"kernel_id": kid})
+            except bolt.BoltError as e:
+                assert e.status == 2  # a persistent instance: no residual epilogue
+                continue
+            torch.cuda.synchronize()
+            assert_close(host(D), want, "gemm residual instance %d" % kid)
+            ran += 1
+        assert ran >= 3
+
+
+@pytest.mark.parametrize("case", [(2, 12, 12, 64, 72, 3, 3, 1, 1), (1, 17, 13, 24, 40, 3, 3, 2, 1), (3, 9, 11, 64, 72, 1, 1, 1, 0),
+                                  (2, 9, 10, 256, 72, 3, 3, 1, 1), (2, 10, 13, 46, 32, 5, 5, 1, 2), (2, 7, 7, 512, 64, 3, 3, 1, 1)])
+def test_conv_residual_every_instance_in_place_and_split_k(bolt, case):
+    N, H, W, Cc, K, R, S, stride, pad = case
+    x = wl.uniform_fp16(402, 0, (N, H, W, Cc), -1, 1)
+    w = wl.normal_fp16(402, 1, (K, R, S, Cc), (2.0 / (R * S * Cc)) ** 0.5)
+    bias = wl.uniform_fp16(402, 2, (K,), -1, 1)
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
+    P, Q = bolt.conv_out_hw(d)
+    res = wl.uniform_fp16(402, 3, (N, P, Q, K), -2, 2)
+    want = ref.conv2d_nhwc_residual(x, w, bias, res, stride=stride, pad=pad)
+    ws = torch.empty(max(bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d), 16), dtype=torch.uint8, device="cuda")
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_CONV2D)):
+        if not bolt.bolt_instance_supports(bolt.OP_CONV2D, kid, d):
+            continue
+        _say("conv residual %s instance %d" % (case, kid))
+        y = dev(res).clone()  # in place: the residual is the output buffer
+        try:
+            bolt.bolt_conv2d_fprop_nhwc_residual(d, dev(x), dev(w), dev(bias), y, y, 1.0, {"kernel_id": kid})
+        except bolt.BoltError as e:
+            assert e.status == 2
+            continue
+        torch.cuda.synchronize()
+        assert_close(host(y), want, "conv residual %s instance %d" % (case, kid))
+        ran += 1
+        if bolt.bolt_check(bolt.OP_CONV2D, d, None, {"kernel_id": kid, "split_k": 2}) == 0:
+            y2 = torch.full((N, P, Q, K), float("nan"), dtype=torch.float16, device="cuda")
+            bolt.bolt_conv2d_fprop_nhwc_residual(d, dev(x), dev(w), dev(bias), dev(res), y2, 1.0,
+                                                 {"kernel_id": kid, "split_k": 2}, ws)
+            torch.cuda.synchronize()
+            assert_close(host(y2), want, "conv residual %s instance %d split-K" % (case, kid))
+    assert ran >= 3
+    y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_conv2d_fprop_nhwc_residual(d, dev(x), dev(w), dev(bias), dev(res), y)  # built-in pick rule
+    torch.cuda.synchronize()
+    assert_close(host(y), want, "conv residual %s heuristic" % (case,))
+
+
+def test_residual_integer_bit_exact(bolt):
+    A = wl.integer_fp16(403, 0, (300, 72), -3, 3)
+    B = wl.integer_fp16(403, 1, (72, 136), -3, 3)
+    bias = wl.integer_fp16(403, 2, (136,), -4, 4)
+    Cm = wl.integer_fp16(403, 3, (300, 136), -9, 9)
+    want = ref.gemm_residual(A, B, bias, Cm, 1.0, 1.0, -2.0, "relu")
+    d = bolt.gemm_desc(300, 136, 72)
+    D = torch.empty((300, 136), dtype=torch.float16, device="cuda")
+    bolt.bolt_gemm_epilogue_residual(d, dev(A), dev(B), dev(bias), dev(Cm), D, -2.0)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(D), want, "integer gemm residual")
+
+
+# ---------------------------------------------------------------------------------------------
 # three-op chains
 # ---------------------------------------------------------------------------------------------
 GEMM_CHAINS = [  # (M, K0, N0, N1, N2): ragged M, widths at and below the compiled bounds
