@@ -223,6 +223,9 @@ def main():
     other_ops = [op for op in ops if op["kind"] != "conv"]
     conv_launches = sum(op["count"] for op in conv_ops)
     conv_flops = sum(op["flops"] * op["count"] for op in conv_ops)
+    conv_bytes = sum(op["bytes"] * op["count"] for op in conv_ops)
+    conv_floor_ms = sum(max(op["flops"] / (MFMA_PEAK_TFLOPS * 1e9), op["bytes"] / (HBM_PEAK_GBS * 1e6)) * op["count"]
+                        for op in conv_ops)
     step_flops = conv_flops + sum(op["flops"] for op in other_ops)
 
     def step(ev=None):
@@ -331,7 +334,13 @@ def main():
                      "achieved": round(achieved, 3), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / MFMA_PEAK_TFLOPS, 4), "traffic": traffic,
                      "launches_per_step": conv_launches, "avg_launch_ms": round(avg_launch_ms, 5),
-                     "flops_per_launch": round(conv_flops / conv_launches)},
+                     "flops_per_launch": round(conv_flops / conv_launches),
+                     # the same launches against the other roof, and against whichever roof binds each layer
+                     # (a layer's floor is max(flops / MFMA peak, algorithmic bytes / HBM peak))
+                     "bytes_per_launch": round(conv_bytes / conv_launches),
+                     "achieved_hbm_gbs": round(conv_bytes / conv_launches / (avg_launch_ms * 1e-3) / 1e9, 1),
+                     "hbm_frac": round(conv_bytes / conv_launches / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "frac_of_binding_roof": round(conv_floor_ms / conv_ms, 4)},
         "b2b": b2b,
         "shapes": shapes_out,
     }

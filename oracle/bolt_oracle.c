@@ -293,6 +293,23 @@ void bolt_ref_pad_channels(const uint16_t *src, uint16_t *dst, int64_t pixels, i
   }
 }
 
+/* Layout transformation (Section 3.2.3): dst[n, h, w, c] = src[n, c, h, w] for c < C, 0 for C <= c < C8. */
+void bolt_ref_nchw_to_nhwc(const uint16_t *src, uint16_t *dst, int64_t N, int64_t C, int64_t H, int64_t W, int64_t C8) {
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t h = 0; h < H; ++h)
+      for (int64_t w = 0; w < W; ++w)
+        for (int64_t c = 0; c < C8; ++c)
+          dst[((n * H + h) * W + w) * C8 + c] = c < C ? src[((n * C + c) * H + h) * W + w] : 0;
+}
+
+/* ... and back: dst[n, c, h, w] = src[n, h, w, c] for c < C; src holds Cs >= C channels per pixel. */
+void bolt_ref_nhwc_to_nchw(const uint16_t *src, uint16_t *dst, int64_t N, int64_t C, int64_t H, int64_t W, int64_t Cs) {
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t c = 0; c < C; ++c)
+      for (int64_t h = 0; h < H; ++h)
+        for (int64_t w = 0; w < W; ++w) dst[((n * C + c) * H + h) * W + w] = src[((n * H + h) * W + w) * Cs + c];
+}
+
 /* col[(n,p,q), (r,s,c)] = x[n, p*sh-ph+r, q*sw-pw+s, c] or 0 outside the image. */
 void bolt_ref_im2col(int64_t N, int64_t H, int64_t W, int64_t C, int64_t R, int64_t S, int64_t stride_h,
                      int64_t stride_w, int64_t pad_h, int64_t pad_w, const uint16_t *x, uint16_t *col) {

@@ -44,6 +44,10 @@ def lib():
         L.bolt_ref_double_to_half.argtypes = [C.c_double]
         L.bolt_ref_bias_act.restype = None
         L.bolt_ref_bias_act.argtypes = [_i64, _i64, _p, _i64, _p, _f32, _f32, _int, _p, _i64]
+        L.bolt_ref_nchw_to_nhwc.restype = None
+        L.bolt_ref_nchw_to_nhwc.argtypes = [_p, _p, _i64, _i64, _i64, _i64, _i64]
+        L.bolt_ref_nhwc_to_nchw.restype = None
+        L.bolt_ref_nhwc_to_nchw.argtypes = [_p, _p, _i64, _i64, _i64, _i64, _i64]
         L.bolt_ref_gemm_residual.restype = None
         L.bolt_ref_gemm_residual.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i64, _f32, _f32, _f32, _int,
                                              _p, _i64]
@@ -253,6 +257,26 @@ def conv_chain(x, ws, bs, acts, stride=1, pad=0):
         assert w.shape[1:3] == (1, 1)
         y = conv2d_nhwc(y, w, b, stride=1, pad=0, act=act)
     return y
+
+
+def nchw_to_nhwc(src, C8=None):
+    """[N][C][H][W] -> [N][H][W][C8], channels C..C8-1 zero (Section 3.2.3, layout transformation + padding)."""
+    src = _h(src)
+    N, Cc, H, W = src.shape
+    C8 = Cc if C8 is None else C8
+    dst = np.empty((N, H, W, C8), np.float16)
+    lib().bolt_ref_nchw_to_nhwc(_ptr(src), _ptr(dst), N, Cc, H, W, C8)
+    return dst
+
+
+def nhwc_to_nchw(src, C=None):
+    """[N][H][W][Cs] -> [N][C][H][W], keeping the first C channels."""
+    src = _h(src)
+    N, H, W, Cs = src.shape
+    C = Cs if C is None else C
+    dst = np.empty((N, C, H, W), np.float16)
+    lib().bolt_ref_nhwc_to_nchw(_ptr(src), _ptr(dst), N, C, H, W, Cs)
+    return dst
 
 
 def pad_channels(src, C8):

@@ -382,6 +382,17 @@ def test_b2b_conv_stride2_first_op():
     assert np.array_equal(y, t1)
 
 
+def test_layout_transforms_against_numpy_transpose():
+    x = wl.uniform_fp16(61, 0, (3, 5, 7, 6), -1, 1)  # N C H W, all extents different
+    y = ref.nchw_to_nhwc(x, 8)
+    assert y.shape == (3, 7, 6, 8)
+    assert np.array_equal(y[..., :5], np.transpose(x, (0, 2, 3, 1))) and not y[..., 5:].any()
+    assert np.array_equal(ref.nchw_to_nhwc(x), np.transpose(x, (0, 2, 3, 1)))
+    assert np.array_equal(ref.nhwc_to_nchw(y, 5), x)                      # round trip drops the padding
+    assert np.array_equal(ref.nhwc_to_nchw(y), np.transpose(y, (0, 3, 1, 2)))
+    assert np.array_equal(ref.pad_channels(np.transpose(x, (0, 2, 3, 1)), 8), y)  # transform + pad == transpose, then pad
+
+
 def test_residual_epilogue_full_matrix_c():
     # Eq. 1 with C a full matrix: against numpy float64 (exact on integers, half-ulp on fractions), the
     # gamma = 0 and C = 0 cases reduce to the plain ops, and conv == im2col GEMM with the same residual
