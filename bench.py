@@ -591,6 +591,28 @@ def main():
     except Exception as e:  # context only
         resid.append({"error": str(e)})
     out["residual_epilogue"] = resid
+
+    # ------------------------------------------------------------------ layout transformation (context)
+    # Section 3.2.3: NCHW in / out.  First layer: transform + channel padding in one pass against the padding
+    # pass alone on an already-NHWC image; last layer: a 7x7x2048 feature map back to NCHW.
+    lay = []
+    try:
+        xn, xh = rnd(32, 3, 224, 224), rnd(32, 224, 224, 3)
+        xp8 = empty(32, 224, 224, 8)
+        t_tp = timed(lambda: bolt.bolt_nchw_to_nhwc(xn, xp8), args.reps)
+        t_p = timed(lambda: bolt.bolt_pad_channels_nhwc(xh, xp8, 8), args.reps)
+        moved = 2.0 * (xn.numel() + xp8.numel())
+        lay.append(dict(name="NCHW 32x3x224x224 -> NHWC, padded to 8 channels", ms=round(t_tp, 5), pad_only_ms=round(t_p, 5),
+                        gbs=round(moved / t_tp / 1e6, 1)))
+        yh, yn = rnd(32, 7, 7, 2048), empty(32, 2048, 7, 7)
+        t_b = timed(lambda: bolt.bolt_nhwc_to_nchw(yh, yn), args.reps)
+        lay.append(dict(name="NHWC 32x7x7x2048 -> NCHW", ms=round(t_b, 5), gbs=round(4.0 * yh.numel() / t_b / 1e6, 1)))
+        yh2, yn2 = rnd(32, 56, 56, 256), empty(32, 256, 56, 56)
+        t_b2 = timed(lambda: bolt.bolt_nhwc_to_nchw(yh2, yn2), args.reps)
+        lay.append(dict(name="NHWC 32x56x56x256 -> NCHW", ms=round(t_b2, 5), gbs=round(4.0 * yh2.numel() / t_b2 / 1e6, 1)))
+    except Exception as e:  # context only
+        lay.append({"error": str(e)})
+    out["layout_transformation"] = lay
     try:
         out["probes"] = {"mfma_loop_tflops": round(bolt.bolt_probe_mfma_peak(20000), 1),
                          "copy_gbs_1GiB": round(bolt.bolt_probe_copy_bandwidth(torch.empty(1 << 30, dtype=torch.uint8, device="cuda"), 5), 1)}

@@ -200,6 +200,18 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
 bolt_status bolt_pad_channels_nhwc(const void* src, void* dst, int64_t pixels, int32_t C, int32_t C_padded,
                                    void* stream);
 
+/* Layout transformation (Section 3.2.3: the kernels are NHWC only, frameworks hand over NCHW) into and out
+ * of buffers the caller has pre-allocated, as the paper keeps them with the model's parameters.
+ *   bolt_nchw_to_nhwc: dst[n, h, w, c] = src[n, c, h, w] for c < C, 0 for C <= c < C_padded: the transform
+ *     of a network's first layer and its channel padding in one pass.  C_padded >= C, C_padded % 8 == 0.
+ *   bolt_nhwc_to_nchw: dst[n, c, h, w] = src[n, h, w, c] for c < C, where src holds C_src >= C channels per
+ *     pixel (C_src % 8 == 0): the transform of the last layer, dropping any padding.
+ * FP16, device pointers, the NHWC side 16-byte aligned; src and dst must not overlap.  N <= 65535. */
+bolt_status bolt_nchw_to_nhwc(const void* src, void* dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t C_padded,
+                              void* stream);
+bolt_status bolt_nhwc_to_nchw(const void* src, void* dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t C_src,
+                              void* stream);
+
 /* Stand-alone epilogue, in place: D[m, n] = act(alpha * D[m, n] + beta * bias[n]) for m < M, n < N,
  * FP16 in and out, arithmetic in FP32.  This is the separate element-wise pass that epilogue fusion
  * removes (Section 3.1; Section 4.1.1 measures the fused GEMM against GEMM followed by this pass);

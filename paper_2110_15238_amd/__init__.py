@@ -21,6 +21,8 @@ bolt_tune_chain = binding.tune_chain
 bolt_check_chain = binding.check_chain
 bolt_chain_instance_supports = binding.chain_instance_supports
 bolt_pad_channels_nhwc = binding.pad_channels_nhwc
+bolt_nchw_to_nhwc = binding.nchw_to_nhwc
+bolt_nhwc_to_nchw = binding.nhwc_to_nchw
 bolt_bias_act = binding.bias_act
 bolt_workspace_bytes = binding.workspace_bytes
 bolt_check = binding.check

@@ -108,6 +108,10 @@ _lib.bolt_pad_channels_nhwc.restype = C.c_int
 _lib.bolt_pad_channels_nhwc.argtypes = [_vp, _vp, C.c_int64, _i32, _i32, _vp]
 _lib.bolt_bias_act.restype = C.c_int
 _lib.bolt_bias_act.argtypes = [_vp, _vp, C.c_int64, _i32, _i32, C.c_float, C.c_float, C.c_int, _vp]
+_lib.bolt_nchw_to_nhwc.restype = C.c_int
+_lib.bolt_nchw_to_nhwc.argtypes = [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]
+_lib.bolt_nhwc_to_nchw.restype = C.c_int
+_lib.bolt_nhwc_to_nchw.argtypes = [_vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]
 _lib.bolt_probe_mfma_peak.restype = C.c_int
 _lib.bolt_probe_mfma_peak.argtypes = [_i32, _vp, C.POINTER(C.c_float)]
 _lib.bolt_probe_copy_bandwidth.restype = C.c_int
@@ -116,7 +120,7 @@ _lib.bolt_probe_copy_bandwidth.argtypes = [_vp, _sz, _i32, _vp, C.POINTER(C.c_fl
 EXPORTED = ["bolt_gemm_epilogue", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune",
             "bolt_gemm_epilogue_residual", "bolt_conv2d_fprop_nhwc_residual", "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain", "bolt_tune_chain", "bolt_check_chain",
             "bolt_chain_instance_supports",
-            "bolt_pad_channels_nhwc", "bolt_bias_act", "bolt_workspace_bytes", "bolt_check", "bolt_status_string",
+            "bolt_pad_channels_nhwc", "bolt_nchw_to_nhwc", "bolt_nhwc_to_nchw", "bolt_bias_act", "bolt_workspace_bytes", "bolt_check", "bolt_status_string",
             "bolt_num_instances", "bolt_instance_config", "bolt_instance_supports", "bolt_probe_mfma_peak",
             "bolt_probe_copy_bandwidth"]
 
@@ -335,6 +339,22 @@ def pad_channels_nhwc(src, dst, C_padded: int):
     pixels = src.numel() // Cin
     _check(_lib.bolt_pad_channels_nhwc(_ptr(src), _ptr(dst), pixels, Cin, C_padded, _stream()),
            "bolt_pad_channels_nhwc")
+    return dst
+
+
+def nchw_to_nhwc(src, dst):
+    """src [N][C][H][W] -> dst [N][H][W][C_padded] (dst's last extent; extra channels are zeroed)."""
+    N, Cc, H, W = src.shape
+    assert dst.shape[:3] == (N, H, W)
+    _check(_lib.bolt_nchw_to_nhwc(_ptr(src), _ptr(dst), N, Cc, H, W, dst.shape[3], _stream()), "bolt_nchw_to_nhwc")
+    return dst
+
+
+def nhwc_to_nchw(src, dst):
+    """src [N][H][W][C_src] -> dst [N][C][H][W] (the first C channels of src)."""
+    N, Cc, H, W = dst.shape
+    assert src.shape[:3] == (N, H, W)
+    _check(_lib.bolt_nhwc_to_nchw(_ptr(src), _ptr(dst), N, Cc, H, W, src.shape[3], _stream()), "bolt_nhwc_to_nchw")
     return dst
 
 

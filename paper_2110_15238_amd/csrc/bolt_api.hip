@@ -72,6 +72,71 @@ __global__ __launch_bounds__(256) void pad_channels_kernel(const half_t* src, ha
   }
 }
 
+// Layout transformation (Section 3.2.3): NCHW <-> NHWC through a 64-channel x 64-pixel LDS tile, so that both
+// sides are coalesced: 128-byte runs of consecutive pixels of one channel plane on the NCHW side, 16-byte
+// chunks of 8 consecutive channels (128 bytes per pixel) on the NHWC side.  Channels C .. C8-1 of the NHWC
+// tensor are written as zeros (kernel padding in the same pass).  grid = (pixel tiles, channel tiles, N).
+static constexpr int kLayoutTile = 64, kLayoutPitch = 66;  // LDS row pitch in halves: 33 words, conflict-free columns
+__global__ __launch_bounds__(256) void nchw_to_nhwc_kernel(const half_t* src, half_t* dst, int C, int HW, int C8) {
+  __shared__ half_t tile[kLayoutTile * kLayoutPitch];  // [channel][pixel]
+  const int t = threadIdx.x, p0 = blockIdx.x * kLayoutTile, c0 = blockIdx.y * kLayoutTile;
+  const int64_t n = blockIdx.z;
+  {
+    const int p = t & 63;
+#pragma unroll 4
+    for (int c = t >> 6; c < kLayoutTile; c += 4) {
+      const bool ok = c0 + c < C && p0 + p < HW;
+      tile[c * kLayoutPitch + p] = ok ? src[(n * C + c0 + c) * HW + p0 + p] : (half_t)0.f;
+    }
+  }
+  __syncthreads();
+  const int ch = t & 7;
+#pragma unroll
+  for (int p = t >> 3; p < kLayoutTile; p += 32) {
+    if (p0 + p < HW && c0 + ch * 8 < C8) {
+      half8 v;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = tile[(ch * 8 + e) * kLayoutPitch + p];
+      *(half8*)(dst + (n * HW + p0 + p) * C8 + c0 + ch * 8) = v;
+    }
+  }
+}
+
+// The same for thin tensors (C <= 8, a network's input image): one thread per pixel reads its C channel planes
+// (consecutive threads read consecutive pixels: coalesced) and writes one 16-byte chunk.
+__global__ __launch_bounds__(256) void nchw_to_nhwc8_kernel(const half_t* src, half_t* dst, int C, int HW, int64_t pixels) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < pixels; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t n = i / HW, p = i - n * HW;
+    half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+      if (c < C) v[c] = src[(n * C + c) * HW + p];
+    *(half8*)(dst + i * 8) = v;
+  }
+}
+
+// src holds Cs >= C channels per pixel (Cs % 8 == 0); the first C are kept.
+__global__ __launch_bounds__(256) void nhwc_to_nchw_kernel(const half_t* src, half_t* dst, int C, int HW, int Cs) {
+  __shared__ half_t tile[kLayoutTile * kLayoutPitch];  // [channel][pixel]
+  const int t = threadIdx.x, p0 = blockIdx.x * kLayoutTile, c0 = blockIdx.y * kLayoutTile;
+  const int64_t n = blockIdx.z;
+  {
+    const int ch = t & 7;
+#pragma unroll
+    for (int p = t >> 3; p < kLayoutTile; p += 32) {
+      half8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (p0 + p < HW && c0 + ch * 8 < Cs) v = *(const half8*)(src + (n * HW + p0 + p) * Cs + c0 + ch * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) tile[(ch * 8 + e) * kLayoutPitch + p] = v[e];
+    }
+  }
+  __syncthreads();
+  const int p = t & 63;
+#pragma unroll 4
+  for (int c = t >> 6; c < kLayoutTile; c += 4)
+    if (c0 + c < C && p0 + p < HW) dst[(n * C + c0 + c) * HW + p0 + p] = tile[c * kLayoutPitch + p];
+}
+
 // Stand-alone epilogue (the un-fused baseline of Section 4.1.1): one thread rewrites one 16-byte
 // chunk of D in place, D = act(alpha * D + beta * bias[n]).  ldd and N are multiples of 8.
 __global__ __launch_bounds__(256) void bias_act_kernel(half_t* D, const half_t* bias, int64_t M, int N, int ldd,
@@ -1101,6 +1166,45 @@ bolt_status bolt_pad_channels_nhwc(const void* src, void* dst, int64_t pixels, i
   const bool even = !(C & 1) && !((uintptr_t)src & 3);
   hipLaunchKernelGGL(even ? pad_channels_kernel<true> : pad_channels_kernel<false>, dim3(blocks), dim3(256), 0,
                      (hipStream_t)stream, (const half_t*)src, (half_t*)dst, (int)pixels, C, C_padded);
+  return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+}
+
+static bolt_status check_layout_args(const void* src, const void* dst, int32_t N, int32_t C, int32_t H, int32_t W,
+                                     int32_t C8, const void* nhwc_side) {
+  if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0 || C8 < C) return BOLT_ERR_INVALID_ARG;
+  if ((C8 & 7) || !is_aligned16(nhwc_side) || ((uintptr_t)src & 1) || ((uintptr_t)dst & 1)) return BOLT_ERR_ALIGNMENT;
+  if ((int64_t)N * H * W * C8 >= (1ll << 40) || (int64_t)H * W >= (1ll << 30) || N > 65535) return BOLT_ERR_UNSUPPORTED;
+  return BOLT_OK;
+}
+
+bolt_status bolt_nchw_to_nhwc(const void* src, void* dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t C_padded,
+                              void* stream) {
+  bolt_status s = check_layout_args(src, dst, N, C, H, W, C_padded, dst);
+  if (s != BOLT_OK) return s;
+  const int HW = H * W;
+  if (C_padded == 8) {
+    const int64_t pixels = (int64_t)N * HW;
+    const int blocks = (int)std::min<int64_t>((pixels + 255) / 256, kNumCU * 16);
+    hipLaunchKernelGGL(nchw_to_nhwc8_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, (const half_t*)src,
+                       (half_t*)dst, C, HW, pixels);
+    return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+  }
+  const dim3 grid(ceil_div(HW, kLayoutTile), ceil_div(C_padded, kLayoutTile), N);
+  if (grid.y > 65535) return BOLT_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(nchw_to_nhwc_kernel, grid, dim3(256), 0, (hipStream_t)stream, (const half_t*)src, (half_t*)dst, C, HW,
+                     C_padded);
+  return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
+}
+
+bolt_status bolt_nhwc_to_nchw(const void* src, void* dst, int32_t N, int32_t C, int32_t H, int32_t W, int32_t C_src,
+                              void* stream) {
+  bolt_status s = check_layout_args(src, dst, N, C, H, W, C_src, src);
+  if (s != BOLT_OK) return s;
+  const int HW = H * W;
+  const dim3 grid(ceil_div(HW, kLayoutTile), ceil_div(C, kLayoutTile), N);
+  if (grid.y > 65535) return BOLT_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(nhwc_to_nchw_kernel, grid, dim3(256), 0, (hipStream_t)stream, (const half_t*)src, (half_t*)dst, C, HW,
+                     C_src);
   return hipGetLastError() == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
 }
 

@@ -562,6 +562,45 @@ def test_config5_layer_full_size_tuned_sampled(bolt, index):
 
 
 # ---------------------------------------------------------------------------------------------
+# layout transformation
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("shape", [(2, 3, 32, 32, 8), (1, 3, 224, 224, 8), (3, 64, 9, 11, 64), (2, 70, 13, 5, 72), (1, 1, 1, 1, 8),
+                                   (2, 136, 7, 7, 136), (1, 46, 20, 26, 48)])
+def test_layout_transforms_bit_exact(bolt, shape):
+    N, Cc, H, W, C8 = shape
+    x = wl.uniform_fp16(501, 0, (N, Cc, H, W), -4, 4)
+    y = torch.full((N, H, W, C8), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_nchw_to_nhwc(dev(x), y)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(y), ref.nchw_to_nhwc(x, C8), "nchw -> nhwc %s" % (shape,))
+    back = torch.full((N, Cc, H, W), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_nhwc_to_nchw(y, back)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(back), x, "nhwc -> nchw %s" % (shape,))
+    assert_bit_equal(host(back), ref.nhwc_to_nchw(host(y), Cc), "nhwc -> nchw vs oracle %s" % (shape,))
+
+
+def test_first_layer_from_nchw_input(bolt):
+    # a framework's NCHW image through transform + padding, the tuned stem convolution, and back to NCHW
+    x = wl.uniform_fp16(502, 0, (2, 3, 40, 36), -1, 1)
+    w = wl.normal_fp16(502, 1, (64, 7, 7, 3), 0.1)
+    b = wl.uniform_fp16(502, 2, (64,), -1, 1)
+    want = ref.nhwc_to_nchw(ref.conv2d_nhwc(ref.nchw_to_nhwc(x), w, b, stride=2, pad=3))
+    xp = torch.empty((2, 40, 36, 8), dtype=torch.float16, device="cuda")
+    wp = torch.empty((64, 7, 7, 8), dtype=torch.float16, device="cuda")
+    bolt.bolt_nchw_to_nhwc(dev(x), xp)
+    bolt.bolt_pad_channels_nhwc(dev(w), wp, 8)
+    d = bolt.conv_desc(2, 40, 36, 8, 64, 7, 7, 2, 3)
+    P, Q = bolt.conv_out_hw(d)
+    y = torch.empty((2, P, Q, 64), dtype=torch.float16, device="cuda")
+    bolt.bolt_conv2d_fprop_nhwc(d, xp, wp, dev(b), y)
+    out = torch.empty((2, 64, P, Q), dtype=torch.float16, device="cuda")
+    bolt.bolt_nhwc_to_nchw(y, out)
+    torch.cuda.synchronize()
+    assert_close(host(out), want, "NCHW in, NCHW out")
+
+
+# ---------------------------------------------------------------------------------------------
 # residual epilogue (Eq. 1 with C a full matrix)
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("layout", ["kn", "nk"])

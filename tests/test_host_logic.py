@@ -178,6 +178,12 @@ def test_null_pointers_are_rejected_before_any_launch(bolt):
     assert lib.bolt_gemm_epilogue_residual(ctypes.byref(d), 16, 32, None, 64, 32, 1.0, 48, None, None, 0, None) == INVALID  # ldc < N
     assert lib.bolt_gemm_epilogue_residual(ctypes.byref(d), 16, 32, None, 72, 64, 1.0, 48, None, None, 0, None) == ALIGNMENT
     assert lib.bolt_conv2d_fprop_nhwc_residual(ctypes.byref(c), 16, 32, None, None, 1.0, 48, None, None, 0, None) == INVALID
+    assert lib.bolt_nchw_to_nhwc(None, 32, 1, 3, 8, 8, 8, None) == INVALID
+    assert lib.bolt_nchw_to_nhwc(16, 32, 1, 3, 8, 8, 7, None) == ALIGNMENT      # C_padded % 8
+    assert lib.bolt_nchw_to_nhwc(16, 40, 1, 3, 8, 8, 8, None) == ALIGNMENT      # NHWC side misaligned
+    assert lib.bolt_nchw_to_nhwc(16, 32, 1, 9, 8, 8, 8, None) == INVALID        # C_padded < C
+    assert lib.bolt_nhwc_to_nchw(16, 32, 1, 3, 8, 8, 12, None) == ALIGNMENT
+    assert lib.bolt_nhwc_to_nchw(16, 32, 70000, 3, 8, 8, 8, None) == UNSUPPORTED
     assert lib.bolt_bias_act(None, None, 4, 8, 8, 1.0, 1.0, 1, None) == INVALID
     assert lib.bolt_bias_act(32, None, 4, 12, 16, 1.0, 1.0, 1, None) == ALIGNMENT
     assert lib.bolt_bias_act(32, None, 4, 16, 8, 1.0, 1.0, 1, None) == INVALID    # ldd < N
