@@ -309,6 +309,50 @@ def main():
             ms = sum(m[i][0].elapsed_time(m[i][1]) for m in marks) / diag_steps / op["count"]
             by_name[op["name"]]["ms_in_step"] = round(ms, 5)
 
+    # The ops of a step are independent problems, so nothing but the launch order keeps them from overlapping.
+    # For context (not `value`, which stays the in-order single-stream step that the profiles describe): the same
+    # step with its ops dealt round-robin over 2 and 4 streams, each stream's share captured in a HIP graph.
+    overlapped = []
+    if not args.steps_only:
+        try:
+            all_runs = [op["run"] for op in other_ops] + [op["pad"] for op in conv_ops if op["pad"] is not None]
+            for op in conv_ops:
+                all_runs += [op["run"]] * op["count"]
+            for ns in (2, 4):
+                side = [torch.cuda.Stream() for _ in range(ns)]
+                graphs = []
+                torch.cuda.synchronize()
+                for k in range(ns):
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=side[k]):
+                        for j, fn in enumerate(all_runs):
+                            if j % ns == k:
+                                fn()
+                    graphs.append(g)
+
+                def step_overlapped():
+                    fork = torch.cuda.Event()
+                    fork.record(stream)
+                    for k in range(ns):
+                        side[k].wait_event(fork)
+                        with torch.cuda.stream(side[k]):
+                            graphs[k].replay()
+                        join = torch.cuda.Event()
+                        join.record(side[k])
+                        stream.wait_event(join)
+                for _ in range(3):
+                    step_overlapped()
+                torch.cuda.synchronize()
+                c0 = time.perf_counter()
+                for _ in range(args.steps):
+                    step_overlapped()
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - c0) * 1e3 / args.steps
+                overlapped.append(dict(streams=ns, ms_per_step=round(ms, 4), tflops=round(step_flops / (ms * 1e-3) / 1e12, 1)))
+                del graphs
+        except Exception as e:  # context only
+            overlapped.append({"error": str(e)})
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")  # written from the rocprofv3 --pmc passes
     if os.path.exists(tpath):
@@ -342,6 +386,7 @@ def main():
                      "hbm_frac": round(conv_bytes / conv_launches / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                      "frac_of_binding_roof": round(conv_floor_ms / conv_ms, 4)},
         "b2b": b2b,
+        "step_overlapped": overlapped,
         "shapes": shapes_out,
     }
     if args.steps_only:
