@@ -19,6 +19,9 @@ namespace bolt {
 
 #define BOLT_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+#ifndef BOLT_INTERLEAVE_READS
+#define BOLT_INTERLEAVE_READS 1
+#endif
 #ifndef BOLT_FRAG_DEPTH
 #define BOLT_FRAG_DEPTH 4  // MFMAs a register set of fragments should feed
 #endif
@@ -438,6 +441,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
     auto tile_body = [&](int it, auto par) {
       constexpr int P = decltype(par)::value;
       if constexpr (NG > 1) {
+        // Large wave tiles: one LDS read between consecutive MFMAs instead of a burst of FM + FN reads in front
+        // of them (a burst is FM + FN issue slots during which this wave feeds the matrix pipe nothing).
+        constexpr bool IL = BOLT_INTERLEAVE_READS && G == 1 && FM * FN > FM + FN;
         auto group = [&](auto jc) {
           constexpr int j = decltype(jc)::value;
           constexpr int cur = (P + j) & 1, nxt = cur ^ 1;
@@ -448,6 +454,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
             // slice j+1 of the tile whose slice 0 went out at the barrier that ended tile it-1
             if (it >= 1 && it - 1 + NS < n_tiles)
               issue_slice(kt_begin + (it - 1 + NS) * KG, fill_stage, std::integral_constant<int, (j + 1 < NG ? j + 1 : 0)>{});
+            if constexpr (IL) __builtin_amdgcn_sched_barrier(0);
             read_group(stage, j + 1, xf[nxt], wf[nxt]);
           } else {
             // end of tile `it`: this wave's reads of the tile are complete (lgkmcnt 0) and tile it+1 has
@@ -461,10 +468,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
             if (it + NS < n_tiles) issue_slice(kt_begin + (it + NS) * KG, stage, std::integral_constant<int, 0>{});
             fill_stage = stage;
             stage = stage + 1 == NS ? 0 : stage + 1;
+            if constexpr (IL) __builtin_amdgcn_sched_barrier(0);
             read_group(stage, 0, xf[nxt], wf[nxt]);
           }
-          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (!IL) __builtin_amdgcn_sched_barrier(0);
           mfma_group(xf[cur], wf[cur]);
+          if constexpr (IL) {
+#pragma unroll
+            for (int i = 0; i < FM + FN; ++i) {
+              __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+              __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - (FM + FN), 0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
         };
         group(std::integral_constant<int, 0>{});
         group(std::integral_constant<int, 1>{});
