@@ -164,7 +164,7 @@ template <int BM, int NW, int NOUT_T>
 __device__ __forceinline__ void b2b_tile_out(half_t* lds, const floatx16 (&acc)[NOUT_T / 32][BM / NW / 32],
                                              const EpilogueArgs& ep, half_t* Y, int ldy, int M, int m0, int wave, int tid) {
   constexpr int NT = 64 * NW, WTM = BM / NW, FM = WTM / 32, FNO = NOUT_T / 32;
-  constexpr int CPR = NOUT_T / 8, ROWS_PER_PASS = NT / CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
+  constexpr int CPR = NOUT_T / 8, ROWS_PER_PASS = NT / CPR;
   static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
   const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
   barrier_after_lds_writes();
@@ -177,7 +177,7 @@ __device__ __forceinline__ void b2b_tile_out(half_t* lds, const floatx16 (&acc)[
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
           const int row = wave * WTM + b * 32 + l32;
-          *(half4*)(lds + row * NOUT_T + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
+          *(half4*)(lds + row * NOUT_T + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4)) =
               epilogue_quad<decltype(slow)::value>(acc[a][b], q, nl, ep);
         }
       }
@@ -192,7 +192,7 @@ __device__ __forceinline__ void b2b_tile_out(half_t* lds, const floatx16 (&acc)[
     for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
       const int row = r0 + i * ROWS_PER_PASS;
       if (m0 + row < M) {
-        const half8 v = *(const half8*)(lds + row * NOUT_T + ((chunk ^ (row & CSW)) << 3));
+        const half8 v = *(const half8*)(lds + row * NOUT_T + ((chunk ^ ctile_swizzle<CPR>(row)) << 3));
         __builtin_nontemporal_store(v, (half8*)(Y + (int64_t)(m0 + row) * ldy + n));
       }
     }

@@ -5,7 +5,7 @@
 // start, and the accumulators of op0 become the activation operand of op1 in registers exactly
 // as in b2b_dma_kernel.hpp (waves split the tile along M only).
 #pragma once
-#include "b2b_kernel.hpp"
+#include "b2b_dma_kernel.hpp"
 #include "conv_halo_kernel.hpp"
 
 namespace bolt {
@@ -92,40 +92,8 @@ __global__ __launch_bounds__(64 * NW, 2) void b2b_halo_kernel(const B2bParams p)
   }
 
   // ---- epilogue1: registers -> FP16 D1 tile in LDS (over the dead buffers and W1) -> global -----
-  constexpr int CPR = T::CPR, CSW = CPR >= 8 ? 7 : CPR - 1;
   const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
-  barrier_after_lds_writes();  // every wave is done reading W1, the halo and the weight stages
-  auto tile_to_lds = [&](auto slow) {
-#pragma unroll
-    for (int a = 0; a < FN1; ++a)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nl = a * 32 + q * 8 + g * 4;
-#pragma unroll
-        for (int b = 0; b < FM; ++b) {
-          const int row = wave * WTM + b * 32 + l32;
-          *(half4*)(lds + row * N1T + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4)) =
-              epilogue_quad<decltype(slow)::value>(acc1[a][b], q, nl, ep);
-        }
-      }
-  };
-  if (p.act1 > ACT_RELU) tile_to_lds(std::true_type{});
-  else tile_to_lds(std::false_type{});
-  barrier_after_lds_writes();
-  {
-    const int chunk = tid % CPR, r0 = tid / CPR;
-    const int n = chunk * 8;
-    if (n < p.N1) {
-#pragma unroll
-      for (int i = 0; i < BM / T::ROWS_PER_PASS; ++i) {
-        const int row = r0 + i * T::ROWS_PER_PASS;
-        if (m0 + row < p.M) {
-          const half8 v = *(const half8*)(lds + row * N1T + ((chunk ^ (row & CSW)) << 3));
-          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
-        }
-      }
-    }
-  }
+  b2b_tile_out<BM, NW, N1T>(lds, acc1, ep, p.Y, p.ldy, p.M, m0, wave, tid);
 }
 
 template <int BM, int NW, int N0T, int N1T, int NS, int XI>

@@ -210,6 +210,16 @@ struct DmaTileLoader {
   }
 };
 
+// XOR term of the FP16 C tile staged in LDS ([rows][BN], 16-byte chunks): physical chunk = chunk ^ term(row).
+// The term walks through all 16 bank groups (256 bytes) over 16 consecutive rows whatever the row length,
+// so the 8-byte accumulator-quad writes of 32 rows conflict two ways (rows r and r + 16) instead of four, and
+// the 16-byte reads of the store phase (16 lanes: consecutive chunks of one or two rows) not at all.
+template <int CPR>
+__device__ __forceinline__ int ctile_swizzle(int row) {
+  static_assert(CPR == 4 || CPR == 8 || CPR == 16 || CPR == 32, "chunks per C-tile row");
+  return CPR >= 16 ? (row & 15) : CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+
 // Last step of the tiled single-op kernels: accumulators -> FP16 C tile in LDS ([BM][BN], 16-byte chunks
 // XOR-swizzled by row, over whatever the main loop left there) -> 16-byte coalesced non-temporal row stores.
 // RES (Eq. 1's C as a full matrix, p.res): the residual tile is first brought into the same LDS locations
@@ -219,7 +229,7 @@ struct DmaTileLoader {
 template <bool RES, int BM, int BN, int WTM, int WTN, int STORE_THREADS, int ROWS_PER_PASS, int FN, int FM>
 __device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc)[FN][FM], const FpropParams& p, int m0,
                                                int n0, int wm, int wn, bool writer, int tid) {
-  constexpr int CPR = BN / 8, CSW = CPR >= 8 ? 7 : CPR - 1;
+  constexpr int CPR = BN / 8;
   const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
   const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act, p.gamma};
   barrier_after_lds_writes();  // every wave has finished reading what the tile overwrites
@@ -234,7 +244,7 @@ __device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc
     const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = (int)(blockDim.x >> 6);
     for (int i = wave_all; i < BM / RPI; i += nwaves) {
       const int row = i * RPI + lane / LPR;
-      const int c = (lane % LPR) ^ (row & CSW);
+      const int c = (lane % LPR) ^ ctile_swizzle<CPR>(row);
       const bool ok = m0 + row < p.M && n0 + c * 8 < p.N;
       const unsigned off = ok ? (unsigned)((row * p.ldr + n0 + c * 8) * 2) : kInvalidOffset;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rr, BOLT_LDS_PTR(lds + i * RPI * BN), 16, off, 0, 0, 0);
@@ -250,7 +260,7 @@ __device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
           const int row = wm * WTM + b * 32 + l32;
-          half4* slot = (half4*)(lds + row * BN + (((nl >> 3) ^ (row & CSW)) << 3) + (nl & 4));
+          half4* slot = (half4*)(lds + row * BN + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4));
           if constexpr (RES) *slot = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep, *slot);
           else *slot = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
         }
@@ -270,7 +280,7 @@ __device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc
       for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
         const int row = r0 + i * ROWS_PER_PASS;
         if (m0 + row < p.M) {
-          const half8 v = *(const half8*)(lds + row * BN + ((chunk ^ (row & CSW)) << 3));
+          const half8 v = *(const half8*)(lds + row * BN + ((chunk ^ ctile_swizzle<CPR>(row)) << 3));
           __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
         }
       }
