@@ -71,7 +71,11 @@
   X(64, 64, 64, 2, 1, 4, XMODE),           \
   X(32, 64, 64, 1, 2, 4, XMODE),           \
   X(32, 64, 64, 1, 2, 8, XMODE),           \
-  X(64, 32, 64, 2, 1, 4, XMODE)
+  X(64, 32, 64, 2, 1, 4, XMODE),           \
+  X(128, 64, 64, 2, 2, 2, XMODE),          \
+  X(64, 128, 64, 2, 2, 2, XMODE),          \
+  X(128, 128, 32, 2, 2, 3, XMODE),         \
+  X(64, 64, 64, 2, 2, 2, XMODE)
 
 // Single-stage tiles: the whole reduction is one k-tile (K <= tile K), so one operand buffer is
 // enough and several workgroups share a compute unit, which hides the load and store latencies
