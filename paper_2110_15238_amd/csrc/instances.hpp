@@ -80,7 +80,11 @@
   X(128, 128, 64, 2, 4, 3, XMODE),         \
   X(128, 128, 64, 1, 4, 2, XMODE),         \
   X(128, 256, 32, 2, 4, 3, XMODE),         \
-  X(256, 64, 64, 4, 2, 2, XMODE)
+  X(256, 64, 64, 4, 2, 2, XMODE),          \
+  X(128, 128, 64, 2, 4, 4, XMODE),         \
+  X(256, 128, 32, 4, 2, 2, XMODE),         \
+  X(256, 128, 32, 2, 4, 3, XMODE),         \
+  X(128, 64, 32, 2, 2, 3, XMODE)
 
 // Single-stage tiles: the whole reduction is one k-tile (K <= tile K), so one operand buffer is
 // enough and several workgroups share a compute unit, which hides the load and store latencies
