@@ -118,7 +118,9 @@
   X(128, 64, 64, 2, 2, 2, XMODE, 2),          \
   X(128, 128, 64, 2, 2, 2, XMODE, 2),         \
   X(32, 64, 64, 1, 2, 3, XMODE, 2),           \
-  X(32, 64, 64, 1, 2, 2, XMODE, 4)
+  X(32, 64, 64, 1, 2, 2, XMODE, 4),           \
+  X(128, 64, 64, 2, 2, 3, XMODE, 2),          \
+  X(64, 128, 64, 2, 2, 3, XMODE, 2)
 
 namespace bolt {
 // Each function appends its instances in a fixed order; kernel_id is the index in the op's table.
