@@ -7,6 +7,7 @@ void register_b2b_conv_halo_instances(std::vector<B2bInstance>& v) {
   static const B2bInstance table[] = {
       BH(128, 4, 64, 256, 2, 2), BH(128, 4, 64, 256, 3, 2), BH(256, 8, 64, 256, 2, 1), BH(256, 8, 64, 256, 3, 1),
       BH(64, 2, 64, 256, 3, 2),  BH(128, 4, 64, 64, 3, 2),  BH(128, 4, 64, 128, 3, 2), BH(128, 4, 128, 128, 2, 2),
+      BH(256, 8, 64, 64, 3, 1),  BH(128, 4, 64, 64, 2, 2),  BH(256, 8, 64, 64, 2, 1),  BH(64, 2, 64, 64, 3, 2), BH(256, 4, 64, 64, 2, 2),
   };
   for (const auto& t : table) v.push_back(t);
 }
