@@ -637,6 +637,47 @@ def main():
         resid.append({"error": str(e)})
     out["residual_epilogue"] = resid
 
+    # ------------------------------------------------------------------ bottleneck block (context)
+    # A whole residual bottleneck block of the 56x56 stage (1x1 256->64, 3x3 64->64, 1x1 64->256 + skip + ReLU):
+    # three tuned launches (the last with the residual epilogue) against 1x1, then the fused pair
+    # 3x3 -> 1x1 with the skip connection in its second epilogue.
+    block = []
+    try:
+        for (H, Cw, Cb) in ((56, 256, 64),):
+            x = rnd(32, H, H, Cw)
+            wa, wb_, wc_ = rnd(Cb, 1, 1, Cw, scale=0.1), rnd(Cb, 3, 3, Cb, scale=0.1), rnd(Cw, 1, 1, Cb, scale=0.1)
+            ba, bb, bc_ = rnd(Cb), rnd(Cb), rnd(Cw)
+            da = bolt.conv_desc(32, H, H, Cw, Cb, 1, 1, 1, 0)
+            db = bolt.conv_desc(32, H, H, Cb, Cb, 3, 3, 1, 1)
+            dc = bolt.conv_desc(32, H, H, Cb, Cw, 1, 1, 1, 0)
+            ya, yb, y3, y2 = empty(32, H, H, Cb), empty(32, H, H, Cb), empty(32, H, H, Cw), empty(32, H, H, Cw)
+            nm = "bottleneck %dx%d %d->%d->%d->%d + skip" % (H, H, Cw, Cb, Cb, Cw)
+            ca = tuned(nm + " 1x1 a", bolt.OP_CONV2D, da, None, [x, wa, ba, ya], ws)
+            cb = tuned(nm + " 3x3", bolt.OP_CONV2D, db, None, [ya, wb_, bb, yb], ws)
+            cc = tuned(nm + " 1x1 c", bolt.OP_CONV2D, dc, None, [yb, wc_, bc_, y3], ws)
+            try:  # a persistent instance has no residual epilogue: fall back to the built-in pick
+                bolt.bolt_conv2d_fprop_nhwc_residual(dc, yb, wc_, bc_, x, y3, 1.0, cc, ws)
+            except bolt.BoltError:
+                cc = None
+            cp = tuned(nm + " pair", bolt.OP_B2B_CONV_RES, db, dc, [ya, wb_, bb, wc_, bc_, y2, x])
+
+            def three_b():
+                bolt.bolt_conv2d_fprop_nhwc(da, x, wa, ba, ya, ca, ws)
+                bolt.bolt_conv2d_fprop_nhwc(db, ya, wb_, bb, yb, cb, ws)
+                bolt.bolt_conv2d_fprop_nhwc_residual(dc, yb, wc_, bc_, x, y3, 1.0, cc, ws)
+
+            def two_b():
+                bolt.bolt_conv2d_fprop_nhwc(da, x, wa, ba, ya, ca, ws)
+                bolt.bolt_b2b_conv_residual(db, dc, ya, wb_, bb, wc_, bc_, x, y2, 1.0, cp)
+            m3, m2 = timed(three_b, args.reps), timed(two_b, args.reps)
+            gflop = 2.0 * 32 * H * H * (Cw * Cb + 9 * Cb * Cb + Cb * Cw) / 1e9
+            block.append(dict(name=nm + " + ReLU, batch 32", three_launches_ms=round(m3, 5), fused_tail_ms=round(m2, 5),
+                              speedup=round(m3 / m2, 3), fused_tflops=round(gflop / m2, 1)))
+            del x, ya, yb, y3, y2
+    except Exception as e:  # context only
+        block.append({"error": str(e)})
+    out["bottleneck_block"] = block
+
     # ------------------------------------------------------------------ layout transformation (context)
     # Section 3.2.3: NCHW in / out.  First layer: transform + channel padding in one pass against the padding
     # pass alone on an already-NHWC image; last layer: a 7x7x2048 feature map back to NCHW.

@@ -58,7 +58,9 @@ typedef enum {
   BOLT_OP_B2B_GEMM = 2,
   BOLT_OP_B2B_CONV = 3,
   BOLT_OP_GEMM_CHAIN3 = 4, /* three GEMMs fused (the *_chain entry points)                    */
-  BOLT_OP_CONV_CHAIN3 = 5  /* a convolution and two 1x1 convolutions fused                    */
+  BOLT_OP_CONV_CHAIN3 = 5, /* a convolution and two 1x1 convolutions fused                    */
+  BOLT_OP_B2B_GEMM_RES = 6, /* bolt_b2b_gemm_residual: the instances of BOLT_OP_B2B_GEMM, those  */
+  BOLT_OP_B2B_CONV_RES = 7  /* without the residual epilogue unsupported; same for _CONV         */
 } bolt_op;
 
 /* Storage of a GEMM's second operand. */
@@ -156,6 +158,24 @@ bolt_status bolt_gemm_epilogue_residual(const bolt_gemm_desc* desc, const void* 
 bolt_status bolt_conv2d_fprop_nhwc_residual(const bolt_conv_desc* desc, const void* x, const void* w, const void* bias,
                                             const void* residual, float gamma, void* y, const bolt_config* config,
                                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* The fused pair with the same full-matrix C in the epilogue of its second op (Section 3.1.1's C1):
+ *   D1 = act1(alpha1 * D0 . W1 + beta1 * b1 + gamma * C),  D0 as in bolt_b2b_gemm / bolt_b2b_conv.
+ * With bolt_conv2d_fprop_nhwc for the first 1x1 this runs a residual bottleneck block (1x1, then
+ * 3x3 -> 1x1 + skip connection + activation) in two launches.  C: M x N1 with row stride ldc (GEMM;
+ * ldc >= N1, ldc % 8 == 0) or the output's NHWC layout (convolution); it may be the output buffer.
+ * Only part of the fused instances have this epilogue: kernel_id indexes the BOLT_OP_B2B_GEMM /
+ * BOLT_OP_B2B_CONV tables, an instance without it returns BOLT_ERR_UNSUPPORTED, and bolt_tune,
+ * bolt_check, bolt_instance_supports take BOLT_OP_B2B_GEMM_RES / BOLT_OP_B2B_CONV_RES to restrict
+ * themselves to the ones that have it (bolt_tune: ptrs = {x, w0, b0, w1, b1, y, C}, C dense). */
+bolt_status bolt_b2b_gemm_residual(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1, const void* A0, const void* W0,
+                                   const void* b0, const void* W1, const void* b1, const void* C, int32_t ldc,
+                                   float gamma, void* D1, const bolt_config* config, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+bolt_status bolt_b2b_conv_residual(const bolt_conv_desc* c0, const bolt_conv_desc* c1, const void* x, const void* w0,
+                                   const void* b0, const void* w1, const void* b1, const void* residual, float gamma,
+                                   void* y, const bolt_config* config, void* workspace, size_t workspace_bytes,
+                                   void* stream);
 
 /* Persistent fusion of more than two ops (Section 3.1.1: the scheme extends to longer chains by
  * duplicating the pipeline; Section 3.3 deepens models with extra 1x1 convolutions that fuse this way).

@@ -241,6 +241,20 @@ def conv2d_nhwc_residual(x, w, bias, res, stride=1, pad=0, alpha=1.0, beta=1.0, 
     return y
 
 
+def b2b_gemm_residual(A, W0, b0, W1, b1, C, gamma=1.0, act0="relu", act1="relu"):
+    """Eq. 1-2 with Eq. 2's C1 a full matrix: D0 = act0(A W0 + b0) rounded to FP16 as if stored, then
+    D1 = act1(D0 W1 + b1 + gamma C).  W0 is [K0][N0], W1 is [N0][N1], C is [M][N1]."""
+    return gemm_residual(gemm(A, W0, b0, act=act0), W1, b1, C, gamma=gamma, act=act1)
+
+
+def b2b_conv_residual(x, w0, b0, w1, b1, res, stride=1, pad=0, gamma=1.0, act0="relu", act1="relu"):
+    """The convolution pair of Section 3.1.1 (any conv, then 1x1 / stride 1 / unpadded) with a full residual
+    tensor in the second epilogue: the tail of a bottleneck block (3x3, 1x1, + skip connection, activation)."""
+    assert w1.shape[1:3] == (1, 1)
+    y0 = conv2d_nhwc(x, w0, b0, stride=stride, pad=pad, act=act0)
+    return conv2d_nhwc_residual(y0, w1, b1, res, stride=1, pad=0, gamma=gamma, act=act1)
+
+
 def gemm_chain(A, Ws, bs, acts, alphas=None, betas=None):
     """Eq. 1-2 carried on to more ops (Section 3.1.1): D_i = act_i(alpha_i D_{i-1} W_i + beta_i b_i), every D_i
     rounded to FP16 before the next op reads it, as if it had been stored.  Ws[i] is [K_i][N_i]."""

@@ -4,7 +4,7 @@ persistent back-to-back fusion, channel padding and the light-weight tuner, behi
 The Python layer only marshals arguments; importing it fails if the HIP library is not built.
 """
 from . import binding
-from .binding import (ACT, LAYOUT_KN, LAYOUT_NK, OP_B2B_CONV, OP_B2B_GEMM, OP_CONV2D, OP_CONV_CHAIN3, OP_GEMM, OP_GEMM_CHAIN3, BoltConfig, BoltError,
+from .binding import (ACT, LAYOUT_KN, LAYOUT_NK, OP_B2B_CONV, OP_B2B_CONV_RES, OP_B2B_GEMM, OP_B2B_GEMM_RES, OP_CONV2D, OP_CONV_CHAIN3, OP_GEMM, OP_GEMM_CHAIN3, BoltConfig, BoltError,
                       ConvDesc, GemmDesc, TuneResult, conv_desc, conv_out_hw, gemm_desc)
 
 # the C ABI's entry points under their own names
@@ -14,6 +14,8 @@ bolt_gemm_epilogue_residual = binding.gemm_epilogue_residual
 bolt_conv2d_fprop_nhwc_residual = binding.conv2d_fprop_nhwc_residual
 bolt_b2b_gemm = binding.b2b_gemm
 bolt_b2b_conv = binding.b2b_conv
+bolt_b2b_gemm_residual = binding.b2b_gemm_residual
+bolt_b2b_conv_residual = binding.b2b_conv_residual
 bolt_tune = binding.tune
 bolt_b2b_gemm_chain = binding.b2b_gemm_chain
 bolt_b2b_conv_chain = binding.b2b_conv_chain

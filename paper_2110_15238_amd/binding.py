@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbolt.so")
 
 OP_GEMM, OP_CONV2D, OP_B2B_GEMM, OP_B2B_CONV, OP_GEMM_CHAIN3, OP_CONV_CHAIN3 = 0, 1, 2, 3, 4, 5
+OP_B2B_GEMM_RES, OP_B2B_CONV_RES = 6, 7
 ACT = {"none": 0, "relu": 1, "gelu": 2, "hardswish": 3, "softplus": 4}
 LAYOUT_KN, LAYOUT_NK = 0, 1
 STATUS_NAMES = ["BOLT_OK", "BOLT_ERR_INVALID_ARG", "BOLT_ERR_UNSUPPORTED", "BOLT_ERR_ALIGNMENT",
@@ -93,6 +94,12 @@ _lib.bolt_gemm_epilogue_residual.argtypes = [C.POINTER(GemmDesc), _vp, _vp, _vp,
 _lib.bolt_conv2d_fprop_nhwc_residual.restype = C.c_int
 _lib.bolt_conv2d_fprop_nhwc_residual.argtypes = [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, C.c_float, _vp,
                                                  C.POINTER(BoltConfig), _vp, _sz, _vp]
+_lib.bolt_b2b_gemm_residual.restype = C.c_int
+_lib.bolt_b2b_gemm_residual.argtypes = [C.POINTER(GemmDesc), C.POINTER(GemmDesc), _vp, _vp, _vp, _vp, _vp, _vp, _i32,
+                                        C.c_float, _vp, C.POINTER(BoltConfig), _vp, _sz, _vp]
+_lib.bolt_b2b_conv_residual.restype = C.c_int
+_lib.bolt_b2b_conv_residual.argtypes = [C.POINTER(ConvDesc), C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp,
+                                        C.c_float, _vp, C.POINTER(BoltConfig), _vp, _sz, _vp]
 _pp = C.POINTER(_vp)
 _lib.bolt_b2b_gemm_chain.restype = C.c_int
 _lib.bolt_b2b_gemm_chain.argtypes = [_i32, _pp, _vp, _pp, _pp, _vp, C.POINTER(BoltConfig), _vp]
@@ -118,7 +125,8 @@ _lib.bolt_probe_copy_bandwidth.restype = C.c_int
 _lib.bolt_probe_copy_bandwidth.argtypes = [_vp, _sz, _i32, _vp, C.POINTER(C.c_float)]
 
 EXPORTED = ["bolt_gemm_epilogue", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune",
-            "bolt_gemm_epilogue_residual", "bolt_conv2d_fprop_nhwc_residual", "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain", "bolt_tune_chain", "bolt_check_chain",
+            "bolt_gemm_epilogue_residual", "bolt_conv2d_fprop_nhwc_residual", "bolt_b2b_gemm_residual",
+            "bolt_b2b_conv_residual", "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain", "bolt_tune_chain", "bolt_check_chain",
             "bolt_chain_instance_supports",
             "bolt_pad_channels_nhwc", "bolt_nchw_to_nhwc", "bolt_nhwc_to_nchw", "bolt_bias_act", "bolt_workspace_bytes", "bolt_check", "bolt_status_string",
             "bolt_num_instances", "bolt_instance_config", "bolt_instance_supports", "bolt_probe_mfma_peak",
@@ -273,6 +281,23 @@ def b2b_conv(c0: ConvDesc, c1: ConvDesc, x, w0, b0, w1, b1, y, config=None):
     c = _cfg(config)
     _check(_lib.bolt_b2b_conv(C.byref(c0), C.byref(c1), _ptr(x), _ptr(w0), _ptr(b0), _ptr(w1), _ptr(b1), _ptr(y),
                               None if c is None else C.byref(c), None, 0, _stream()), "bolt_b2b_conv")
+    return y
+
+
+def b2b_gemm_residual(g0: GemmDesc, g1: GemmDesc, A0, W0, b0, W1, b1, Cres, D1, gamma: float = 1.0, config=None):
+    """D1 = act1(alpha1 D0.W1 + beta1 b1 + gamma Cres), D0 the first op's output; Cres is a contiguous M x N1 tensor."""
+    c = _cfg(config)
+    _check(_lib.bolt_b2b_gemm_residual(C.byref(g0), C.byref(g1), _ptr(A0), _ptr(W0), _ptr(b0), _ptr(W1), _ptr(b1),
+                                       _ptr(Cres), Cres.shape[-1], gamma, _ptr(D1), None if c is None else C.byref(c),
+                                       None, 0, _stream()), "bolt_b2b_gemm_residual")
+    return D1
+
+
+def b2b_conv_residual(c0: ConvDesc, c1: ConvDesc, x, w0, b0, w1, b1, residual, y, gamma: float = 1.0, config=None):
+    c = _cfg(config)
+    _check(_lib.bolt_b2b_conv_residual(C.byref(c0), C.byref(c1), _ptr(x), _ptr(w0), _ptr(b0), _ptr(w1), _ptr(b1),
+                                       _ptr(residual), gamma, _ptr(y), None if c is None else C.byref(c), None, 0,
+                                       _stream()), "bolt_b2b_conv_residual")
     return y
 
 

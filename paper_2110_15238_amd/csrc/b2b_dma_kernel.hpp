@@ -160,14 +160,33 @@ __device__ __forceinline__ void b2b_rf_gemm(const half_t* Ws, const half8 (&d)[N
 
 // Last epilogue: accumulators -> FP16 tile [BM][NOUT_T] in LDS (over whatever the main loop left there) ->
 // 16-byte coalesced non-temporal row stores.  Every wave must be done with the LDS it overwrites.
-template <int BM, int NW, int NOUT_T>
+// RES (Eq. 1's C as a full matrix): the [BM][NOUT_T] tile of `res` is first brought into the same LDS slots,
+// direct-to-LDS with the row swizzle applied to which global chunk a lane fetches, and every lane reads the
+// quad it is about to overwrite; ep.gamma scales it.  A compile-time switch, so the plain kernels keep
+// their register allocation.
+template <int BM, int NW, int NOUT_T, bool RES = false>
 __device__ __forceinline__ void b2b_tile_out(half_t* lds, const floatx16 (&acc)[NOUT_T / 32][BM / NW / 32],
-                                             const EpilogueArgs& ep, half_t* Y, int ldy, int M, int m0, int wave, int tid) {
+                                             const EpilogueArgs& ep, half_t* Y, int ldy, int M, int m0, int wave, int tid,
+                                             const half_t* res = nullptr, int ldr = 0) {
   constexpr int NT = 64 * NW, WTM = BM / NW, FM = WTM / 32, FNO = NOUT_T / 32;
   constexpr int CPR = NOUT_T / 8, ROWS_PER_PASS = NT / CPR;
   static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
   const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
   barrier_after_lds_writes();
+  if constexpr (RES) {
+    constexpr int RPI = 64 / CPR;  // tile rows per load instruction (1024 contiguous LDS bytes)
+    static_assert(CPR <= 64 && BM % RPI == 0, "residual tile rows per load instruction");
+    const int64_t rem = ((int64_t)(M - m0 - 1) * ldr + ep.N) * 2;
+    const __amdgpu_buffer_rsrc_t rr = make_rsrc(res + (int64_t)m0 * ldr, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff));
+    for (int i = wave; i < BM / RPI; i += NW) {
+      const int row = i * RPI + lane / CPR;
+      const int c = (lane % CPR) ^ ctile_swizzle<CPR>(row);
+      const bool ok = m0 + row < M && c * 8 < ep.N;
+      const unsigned off = ok ? (unsigned)((row * ldr + c * 8) * 2) : kInvalidOffset;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rr, BOLT_LDS_PTR(lds + i * RPI * NOUT_T), 16, off, 0, 0, 0);
+    }
+    barrier_after_loads<0>();
+  }
   auto tile_to_lds = [&](auto slow) {
 #pragma unroll
     for (int a = 0; a < FNO; ++a)
@@ -177,8 +196,15 @@ __device__ __forceinline__ void b2b_tile_out(half_t* lds, const floatx16 (&acc)[
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
           const int row = wave * WTM + b * 32 + l32;
-          *(half4*)(lds + row * NOUT_T + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4)) =
-              epilogue_quad<decltype(slow)::value>(acc[a][b], q, nl, ep);
+          const int at = row * NOUT_T + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4);
+          if constexpr (RES) {
+            half4* slot = (half4*)(lds + at);
+            *slot = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, nl, ep, *slot);
+          } else {
+            // (written as one expression: naming the pointer first costs the 128-wide instances a workgroup per CU)
+            *(half4*)(lds + row * NOUT_T + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4)) =
+                epilogue_quad<decltype(slow)::value>(acc[a][b], q, nl, ep);
+          }
         }
       }
   };
@@ -199,7 +225,7 @@ __device__ __forceinline__ void b2b_tile_out(half_t* lds, const floatx16 (&acc)[
   }
 }
 
-template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
+template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS, bool RES = false>
 __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::MIN_WAVES)) void b2b_dma_kernel(
     const B2bParams p) {
   using T = B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>;
@@ -228,15 +254,19 @@ __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE,
   b2b_rf_gemm<N0T, N1T, FM>(W1s, d0, acc1, l32, g);
 
   // epilogue1 through LDS (over the dead stages and W1)
-  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
-  b2b_tile_out<BM, NW, N1T>(lds, acc1, ep, p.Y, p.ldy, p.M, m0, wave, tid);
+  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
+  b2b_tile_out<BM, NW, N1T, RES>(lds, acc1, ep, p.Y, p.ldy, p.M, m0, wave, tid, p.res, p.ldr);
 }
 
 template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
 hipError_t launch_b2b_dma(const B2bParams& p, int /*grid*/, int lds_bytes, hipStream_t stream) {
-  static bool attr_set = false;
-  return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS>, attr_set, p, p.tiles_m, 64 * NW, lds_bytes,
-                           stream);
+  static bool attr_set[2] = {false, false};
+  // the residual epilogue is a kernel of its own (see b2b_tile_out)
+  if (p.res)
+    return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, true>, attr_set[1], p, p.tiles_m, 64 * NW,
+                             lds_bytes, stream);
+  return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, false>, attr_set[0], p, p.tiles_m, 64 * NW,
+                           lds_bytes, stream);
 }
 
 // mode 0 = RF-resident fusion
@@ -244,7 +274,7 @@ hipError_t launch_b2b_dma(const B2bParams& p, int /*grid*/, int lds_bytes, hipSt
   {                                                                                                       \
     "b2bdma_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_s" #NS, 0, BM, BK, NW, 1, N0T, N1T, XMODE, 0, 64 * NW, \
         NS, &bolt::B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::lds_bytes,                                \
-        &bolt::launch_b2b_dma<BM, BK, NW, N0T, N1T, XMODE, NS>                                             \
+        &bolt::launch_b2b_dma<BM, BK, NW, N0T, N1T, XMODE, NS>, nullptr, nullptr, true                     \
   }
 
 }  // namespace bolt

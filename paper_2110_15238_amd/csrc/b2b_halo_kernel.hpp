@@ -34,7 +34,7 @@ struct B2bHaloTraits {
   }
 };
 
-template <int BM, int NW, int N0T, int N1T, int NS, int XI>
+template <int BM, int NW, int N0T, int N1T, int NS, int XI, bool RES = false>
 __global__ __launch_bounds__(64 * NW, 2) void b2b_halo_kernel(const B2bParams p) {
   using T = B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>;
   constexpr int NT = T::NT, WTM = T::WTM, FM = T::FM, FN0 = T::FN0, FN1 = T::FN1;
@@ -69,37 +69,21 @@ __global__ __launch_bounds__(64 * NW, 2) void b2b_halo_kernel(const B2bParams p)
 
   // ---- op1: all N1 columns accumulate in registers; W1 fragments carry the matching permutation
   floatx16 acc1[FN1][FM];
-#pragma unroll
-  for (int a = 0; a < FN1; ++a)
-#pragma unroll
-    for (int b = 0; b < FM; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc1[a][b][r] = 0.f;
-#pragma unroll
-  for (int t = 0; t < FN0 * 2; ++t) {
-    const int kbase = t * 16;
-    const half_t* ws = W1s + (kbase / KB1) * N1T * KB1;
-    const int chunk = (kbase % KB1) / 8;
-#pragma unroll
-    for (int a = 0; a < FN1; ++a) {
-      const int row = a * 32 + l32;
-      const half4 lo = *(const half4*)(ws + dma_chunk_offset<KB1>(row, chunk) + g * 4);
-      const half4 hi = *(const half4*)(ws + dma_chunk_offset<KB1>(row, chunk + 1) + g * 4);
-      const half8 w1 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-#pragma unroll
-      for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(w1, d0[t][b], acc1[a][b]);
-    }
-  }
+  b2b_rf_gemm<N0T, N1T, FM>(W1s, d0, acc1, l32, g);
 
   // ---- epilogue1: registers -> FP16 D1 tile in LDS (over the dead buffers and W1) -> global -----
-  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
-  b2b_tile_out<BM, NW, N1T>(lds, acc1, ep, p.Y, p.ldy, p.M, m0, wave, tid);
+  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
+  b2b_tile_out<BM, NW, N1T, RES>(lds, acc1, ep, p.Y, p.ldy, p.M, m0, wave, tid, p.res, p.ldr);
 }
 
 template <int BM, int NW, int N0T, int N1T, int NS, int XI>
 hipError_t launch_b2b_halo(const B2bParams& p, int /*grid*/, int lds_bytes, hipStream_t stream) {
-  static bool attr_set = false;
-  return b2b_launch_common(b2b_halo_kernel<BM, NW, N0T, N1T, NS, XI>, attr_set, p, p.tiles_m, 64 * NW, lds_bytes, stream);
+  static bool attr_set[2] = {false, false};
+  if (p.res)  // the residual epilogue is a kernel of its own (see b2b_tile_out)
+    return b2b_launch_common(b2b_halo_kernel<BM, NW, N0T, N1T, NS, XI, true>, attr_set[1], p, p.tiles_m, 64 * NW, lds_bytes,
+                             stream);
+  return b2b_launch_common(b2b_halo_kernel<BM, NW, N0T, N1T, NS, XI, false>, attr_set[0], p, p.tiles_m, 64 * NW, lds_bytes,
+                           stream);
 }
 
 // mode 0 = RF-resident fusion; legality and LDS need depend on the geometry (dyn hooks)
@@ -108,7 +92,7 @@ hipError_t launch_b2b_halo(const B2bParams& p, int /*grid*/, int lds_bytes, hipS
     "b2bhalo_" #BM "_w" #NW "_n" #N0T "_" #N1T "_s" #NS "_x" #XI, 0, BM, 64, NW, 1, N0T, N1T, 1, 0, 64 * NW, \
         NS, nullptr, &bolt::launch_b2b_halo<BM, NW, N0T, N1T, NS, XI>,                                     \
         &bolt::B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::supports,                                          \
-        &bolt::B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::lds_bytes                                          \
+        &bolt::B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::lds_bytes, true                                    \
   }
 
 }  // namespace bolt

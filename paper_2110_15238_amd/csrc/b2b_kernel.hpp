@@ -45,6 +45,10 @@ struct B2bParams {
   int b2_on, N2, ldw2;
   float alpha2, beta2;
   int act2;
+  // full-matrix C of the last op (Eq. 1), [M][N1] with leading dimension ldr, scaled by gamma; null = none
+  const half_t* res;
+  int ldr;
+  float gamma;
 };
 
 template <int N0T>
@@ -376,6 +380,7 @@ struct B2bInstance {
   // instances whose legality / LDS need depends on the geometry (b2b_halo_kernel.hpp); null otherwise
   bool (*dyn_supports)(const B2bParams&);
   int (*dyn_lds_bytes)(const B2bParams&);
+  bool residual;  // has the variant whose last epilogue adds a full matrix C (B2bParams::res)
 };
 
 template <typename KernT>

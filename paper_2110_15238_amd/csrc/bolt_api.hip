@@ -479,10 +479,12 @@ static bolt_status resolve_fprop(const std::vector<FpropInstance>& tab, const Fp
 struct B2bProblem {
   B2bParams p;
   int xmode, wmode;
+  bool residual;  // the call carries a residual matrix for the last op: kernels without that epilogue are excluded
 };
 
 static bool b2b_supports(const B2bInstance& in, const B2bProblem& pr) {
   if (in.xmode != pr.xmode || in.wmode != pr.wmode) return false;
+  if (pr.residual && !in.residual) return false;
   if (pr.p.N0 > in.n0t || pr.p.N1 > in.n1t) return false;
   // threadblock residence with the tightest compiled bound: do not carry more than 2x padding
   if ((in.n0t > 32 && in.n0t / 2 >= pr.p.N0) || (in.n1t > 32 && in.n1t / 2 >= pr.p.N1)) return false;
@@ -803,8 +805,8 @@ int32_t bolt_num_instances(bolt_op op) {
   switch (op) {
     case BOLT_OP_GEMM: return (int32_t)tables().gemm.size();
     case BOLT_OP_CONV2D: return (int32_t)tables().conv.size();
-    case BOLT_OP_B2B_GEMM: return (int32_t)tables().b2b_gemm.size();
-    case BOLT_OP_B2B_CONV: return (int32_t)tables().b2b_conv.size();
+    case BOLT_OP_B2B_GEMM: case BOLT_OP_B2B_GEMM_RES: return (int32_t)tables().b2b_gemm.size();
+    case BOLT_OP_B2B_CONV: case BOLT_OP_B2B_CONV_RES: return (int32_t)tables().b2b_conv.size();
     case BOLT_OP_GEMM_CHAIN3: return (int32_t)tables().gemm_chain.size();
     case BOLT_OP_CONV_CHAIN3: return (int32_t)tables().conv_chain.size();
     default: return 0;
@@ -818,8 +820,8 @@ bolt_status bolt_instance_config(bolt_op op, int32_t id, bolt_config* out) {
   switch (op) {
     case BOLT_OP_GEMM: fprop_fill_config(tables().gemm[id], id, out); break;
     case BOLT_OP_CONV2D: fprop_fill_config(tables().conv[id], id, out); break;
-    case BOLT_OP_B2B_GEMM: b2b_fill_config(tables().b2b_gemm[id], id, out); break;
-    case BOLT_OP_B2B_CONV: b2b_fill_config(tables().b2b_conv[id], id, out); break;
+    case BOLT_OP_B2B_GEMM: case BOLT_OP_B2B_GEMM_RES: b2b_fill_config(tables().b2b_gemm[id], id, out); break;
+    case BOLT_OP_B2B_CONV: case BOLT_OP_B2B_CONV_RES: b2b_fill_config(tables().b2b_conv[id], id, out); break;
     case BOLT_OP_GEMM_CHAIN3: chain_fill_config(tables().gemm_chain[id], id, out); break;
     case BOLT_OP_CONV_CHAIN3: chain_fill_config(tables().conv_chain[id], id, out); break;
     default: return BOLT_ERR_INVALID_ARG;
@@ -836,12 +838,14 @@ int32_t bolt_instance_supports(bolt_op op, int32_t id, const void* desc0, const 
       return make_gemm_problem((const bolt_gemm_desc*)desc0, &fp) == BOLT_OK && fprop_supports(tables().gemm[id], fp);
     case BOLT_OP_CONV2D:
       return make_conv_problem((const bolt_conv_desc*)desc0, &fp) == BOLT_OK && fprop_supports(tables().conv[id], fp);
-    case BOLT_OP_B2B_GEMM:
-      return make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp) == BOLT_OK &&
-             b2b_supports(tables().b2b_gemm[id], bp);
-    case BOLT_OP_B2B_CONV:
-      return make_b2b_conv_problem((const bolt_conv_desc*)desc0, (const bolt_conv_desc*)desc1, &bp) == BOLT_OK &&
-             b2b_supports(tables().b2b_conv[id], bp);
+    case BOLT_OP_B2B_GEMM: case BOLT_OP_B2B_GEMM_RES:
+      if (make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp) != BOLT_OK) return 0;
+      bp.residual = op == BOLT_OP_B2B_GEMM_RES;
+      return b2b_supports(tables().b2b_gemm[id], bp);
+    case BOLT_OP_B2B_CONV: case BOLT_OP_B2B_CONV_RES:
+      if (make_b2b_conv_problem((const bolt_conv_desc*)desc0, (const bolt_conv_desc*)desc1, &bp) != BOLT_OK) return 0;
+      bp.residual = op == BOLT_OP_B2B_CONV_RES;
+      return b2b_supports(tables().b2b_conv[id], bp);
     default: return 0;
   }
 }
@@ -858,12 +862,16 @@ bolt_status bolt_check(bolt_op op, const void* desc0, const void* desc1, const b
     case BOLT_OP_CONV2D:
       s = make_conv_problem((const bolt_conv_desc*)desc0, &fp);
       return s != BOLT_OK ? s : resolve_fprop(tables().conv, fp, config, &id, &swz, &sk);
-    case BOLT_OP_B2B_GEMM:
+    case BOLT_OP_B2B_GEMM: case BOLT_OP_B2B_GEMM_RES:
       s = make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp);
-      return s != BOLT_OK ? s : resolve_b2b(tables().b2b_gemm, bp, config, &id);
-    case BOLT_OP_B2B_CONV:
+      if (s != BOLT_OK) return s;
+      bp.residual = op == BOLT_OP_B2B_GEMM_RES;
+      return resolve_b2b(tables().b2b_gemm, bp, config, &id);
+    case BOLT_OP_B2B_CONV: case BOLT_OP_B2B_CONV_RES:
       s = make_b2b_conv_problem((const bolt_conv_desc*)desc0, (const bolt_conv_desc*)desc1, &bp);
-      return s != BOLT_OK ? s : resolve_b2b(tables().b2b_conv, bp, config, &id);
+      if (s != BOLT_OK) return s;
+      bp.residual = op == BOLT_OP_B2B_CONV_RES;
+      return resolve_b2b(tables().b2b_conv, bp, config, &id);
     default: return BOLT_ERR_INVALID_ARG;
   }
 }
@@ -994,15 +1002,63 @@ bolt_status bolt_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc* c1, co
   return b2b_launch(tables().b2b_conv[id], pr, (hipStream_t)stream);
 }
 
+bolt_status bolt_b2b_gemm_residual(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1, const void* A0, const void* W0,
+                                   const void* b0, const void* W1, const void* b1, const void* C, int32_t ldc,
+                                   float gamma, void* D1, const bolt_config* config, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  B2bProblem pr;
+  bolt_status s = make_b2b_gemm_problem(g0, g1, &pr);
+  if (s != BOLT_OK) return s;
+  if (!A0 || !W0 || !W1 || !C || !D1 || ldc < g1->N) return BOLT_ERR_INVALID_ARG;
+  if ((ldc & 7) || !is_aligned16(A0) || !is_aligned16(W0) || !is_aligned16(W1) || !is_aligned16(C) || !is_aligned16(D1) ||
+      (b0 && !is_aligned16(b0)) || (b1 && !is_aligned16(b1)))
+    return BOLT_ERR_ALIGNMENT;
+  pr.residual = true;
+  int id;
+  s = resolve_b2b(tables().b2b_gemm, pr, config, &id);
+  if (s != BOLT_OK) return s;
+  B2bParams& p = pr.p;
+  p.X = (const half_t*)A0; p.W0 = (const half_t*)W0; p.b0 = (const half_t*)b0;
+  p.W1 = (const half_t*)W1; p.b1 = (const half_t*)b1; p.Y = (half_t*)D1;
+  p.res = (const half_t*)C; p.ldr = ldc; p.gamma = gamma;
+  return b2b_launch(tables().b2b_gemm[id], pr, (hipStream_t)stream);
+}
+
+bolt_status bolt_b2b_conv_residual(const bolt_conv_desc* c0, const bolt_conv_desc* c1, const void* x, const void* w0,
+                                   const void* b0, const void* w1, const void* b1, const void* residual, float gamma,
+                                   void* y, const bolt_config* config, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  B2bProblem pr;
+  bolt_status s = make_b2b_conv_problem(c0, c1, &pr);
+  if (s != BOLT_OK) return s;
+  if (!x || !w0 || !w1 || !residual || !y) return BOLT_ERR_INVALID_ARG;
+  if (!is_aligned16(x) || !is_aligned16(w0) || !is_aligned16(w1) || !is_aligned16(residual) || !is_aligned16(y) ||
+      (b0 && !is_aligned16(b0)) || (b1 && !is_aligned16(b1)))
+    return BOLT_ERR_ALIGNMENT;
+  pr.residual = true;
+  int id;
+  s = resolve_b2b(tables().b2b_conv, pr, config, &id);
+  if (s != BOLT_OK) return s;
+  B2bParams& p = pr.p;
+  p.X = (const half_t*)x; p.W0 = (const half_t*)w0; p.b0 = (const half_t*)b0;
+  p.W1 = (const half_t*)w1; p.b1 = (const half_t*)b1; p.Y = (half_t*)y;
+  p.res = (const half_t*)residual; p.ldr = c1->K; p.gamma = gamma;
+  return b2b_launch(tables().b2b_conv[id], pr, (hipStream_t)stream);
+}
+
 bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const void* const* ptrs, void* workspace,
                       size_t workspace_bytes, void* stream_v, bolt_config* best, float* best_ms, int32_t* n_tried) {
   if (!desc0 || !ptrs || !best) return BOLT_ERR_INVALID_ARG;
   hipStream_t stream = (hipStream_t)stream_v;
   const bool single = op == BOLT_OP_GEMM || op == BOLT_OP_CONV2D;
-  const bool is_b2b = op == BOLT_OP_B2B_GEMM || op == BOLT_OP_B2B_CONV;
+  const bool with_res = op == BOLT_OP_B2B_GEMM_RES || op == BOLT_OP_B2B_CONV_RES;
+  const bool b2b_gemm = op == BOLT_OP_B2B_GEMM || op == BOLT_OP_B2B_GEMM_RES;
+  const bool is_b2b = b2b_gemm || op == BOLT_OP_B2B_CONV || op == BOLT_OP_B2B_CONV_RES;
   if (!single && !is_b2b) return BOLT_ERR_INVALID_ARG;
   if (is_b2b && !desc1) return BOLT_ERR_INVALID_ARG;
-  const size_t dsz = (op == BOLT_OP_GEMM || op == BOLT_OP_B2B_GEMM) ? sizeof(bolt_gemm_desc) : sizeof(bolt_conv_desc);
+  const size_t dsz = (op == BOLT_OP_GEMM || b2b_gemm) ? sizeof(bolt_gemm_desc) : sizeof(bolt_conv_desc);
   TuneKey key{(int)op, std::string((const char*)desc0, dsz)};
   if (is_b2b) key.bytes.append((const char*)desc1, dsz);
 
@@ -1011,10 +1067,10 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
   B2bProblem bp;
   if (op == BOLT_OP_GEMM) s = make_gemm_problem((const bolt_gemm_desc*)desc0, &fp);
   else if (op == BOLT_OP_CONV2D) s = make_conv_problem((const bolt_conv_desc*)desc0, &fp);
-  else if (op == BOLT_OP_B2B_GEMM) s = make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp);
+  else if (b2b_gemm) s = make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp);
   else s = make_b2b_conv_problem((const bolt_conv_desc*)desc0, (const bolt_conv_desc*)desc1, &bp);
   if (s != BOLT_OK) return s;
-  const int nptr = single ? 4 : 6;
+  const int nptr = single ? 4 : with_res ? 7 : 6;  // the residual ops take the residual matrix as ptrs[6]
   for (int i = 0; i < nptr; ++i) {
     const bool optional = single ? (i == 2) : (i == 2 || i == 4);
     if (!ptrs[i] && !optional) return BOLT_ERR_INVALID_ARG;
@@ -1051,10 +1107,14 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
     cfg.swizzle = win.swizzle;
     cfg.split_k = win.split_k;
   } else {
-    const auto& tab = op == BOLT_OP_B2B_GEMM ? tables().b2b_gemm : tables().b2b_conv;
+    const auto& tab = b2b_gemm ? tables().b2b_gemm : tables().b2b_conv;
     B2bParams& p = bp.p;
     p.X = (const half_t*)ptrs[0]; p.W0 = (const half_t*)ptrs[1]; p.b0 = (const half_t*)ptrs[2];
     p.W1 = (const half_t*)ptrs[3]; p.b1 = (const half_t*)ptrs[4]; p.Y = (half_t*)ptrs[5];
+    if (with_res) {  // dense residual ([M][N1]), gamma 1: the timing does not depend on the values
+      bp.residual = true;
+      p.res = (const half_t*)ptrs[6]; p.ldr = p.N1; p.gamma = 1.f;
+    }
     std::vector<Candidate> cands;
     for (int i = 0; i < (int)tab.size(); ++i)
       if (b2b_supports(tab[i], bp)) cands.push_back({i, 0, 1, 0.f});

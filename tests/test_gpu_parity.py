@@ -683,6 +683,94 @@ def test_residual_integer_bit_exact(bolt):
     assert_bit_equal(host(D), want, "integer gemm residual")
 
 
+@pytest.mark.parametrize("shape", [(1000, 72, 64, 128), (515, 576, 128, 64), (700, 96, 32, 96), (260, 200, 64, 256),
+                                   (333, 256, 64, 16), (129, 64, 64, 64)])
+def test_b2b_gemm_residual_every_instance_and_tuner(bolt, shape):
+    """Fused pair with Eq. 2's C1 a full matrix (weights stored [N][K]); also in place and through bolt_tune."""
+    M, K0, N0, N1 = shape
+    A, W0 = wl.uniform_fp16(405, 0, (M, K0), -0.5, 0.5), wl.uniform_fp16(405, 1, (K0, N0), -0.5, 0.5)
+    b0, W1 = wl.uniform_fp16(405, 2, (N0,), -0.5, 0.5), wl.uniform_fp16(405, 3, (N0, N1), -0.5, 0.5)
+    b1, Cm = wl.uniform_fp16(405, 4, (N1,), -0.5, 0.5), wl.uniform_fp16(405, 5, (M, N1), -4, 4)
+    want = ref.b2b_gemm_residual(A, W0, b0, W1, b1, Cm, gamma=0.5)
+    g0 = bolt.gemm_desc(M, N0, K0, b_layout=bolt.LAYOUT_NK)
+    g1 = bolt.gemm_desc(M, N1, N0, b_layout=bolt.LAYOUT_NK)
+    W0d, W1d = dev(np.ascontiguousarray(W0.T)), dev(np.ascontiguousarray(W1.T))
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_GEMM_RES)):
+        if not bolt.bolt_instance_supports(bolt.OP_B2B_GEMM_RES, kid, g0, g1):
+            continue
+        _say("b2b gemm residual %s instance %d" % (shape, kid))
+        D = dev(Cm).clone()  # in place: the residual is the output buffer
+        bolt.bolt_b2b_gemm_residual(g0, g1, dev(A), W0d, dev(b0), W1d, dev(b1), D, D, 0.5, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(D), want, "b2b gemm residual %s instance %d" % (shape, kid))
+        ran += 1
+    assert ran >= 1, "no instance for %s" % (shape,)
+    D = torch.full((M, N1), float("nan"), dtype=torch.float16, device="cuda")
+    r = bolt.bolt_tune(bolt.OP_B2B_GEMM_RES, g0, g1, [dev(A), W0d, dev(b0), W1d, dev(b1), D, dev(Cm)])
+    assert bolt.bolt_instance_supports(bolt.OP_B2B_GEMM_RES, r.config.kernel_id, g0, g1) and r.tried == ran
+    D.fill_(float("nan"))
+    bolt.bolt_b2b_gemm_residual(g0, g1, dev(A), W0d, dev(b0), W1d, dev(b1), dev(Cm), D, 0.5, r.config)
+    torch.cuda.synchronize()
+    assert_close(host(D), want, "b2b gemm residual %s tuned" % (shape,))
+
+
+@pytest.mark.parametrize("shape", B2B_CONV_SHAPES + [(2, 14, 14, 64, 64, 1, 256), (1, 10, 12, 32, 64, 1, 200)])
+def test_b2b_conv_residual_every_instance_and_tuner(bolt, shape):
+    """The tail of a bottleneck block: 3x3 -> 1x1 + skip connection + ReLU in one launch."""
+    N, H, W, Cc, K0, stride, K1 = shape
+    x, w0 = wl.uniform_fp16(406, 0, (N, H, W, Cc), -1, 1), wl.normal_fp16(406, 1, (K0, 3, 3, Cc), (2.0 / (9 * Cc)) ** 0.5)
+    b0, w1 = wl.uniform_fp16(406, 2, (K0,), -1, 1), wl.normal_fp16(406, 3, (K1, 1, 1, K0), (2.0 / K0) ** 0.5)
+    b1 = wl.uniform_fp16(406, 4, (K1,), -1, 1)
+    c0 = bolt.conv_desc(N, H, W, Cc, K0, 3, 3, stride, 1)
+    P, Q = bolt.conv_out_hw(c0)
+    c1 = bolt.conv_desc(N, P, Q, K0, K1, 1, 1, 1, 0)
+    res = wl.uniform_fp16(406, 5, (N, P, Q, K1), -2, 2)
+    want = ref.b2b_conv_residual(x, w0, b0, w1, b1, res, stride=stride, pad=1)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_CONV_RES)):
+        if not bolt.bolt_instance_supports(bolt.OP_B2B_CONV_RES, kid, c0, c1):
+            continue
+        _say("b2b conv residual %s instance %d" % (shape, kid))
+        y = torch.full((N, P, Q, K1), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_b2b_conv_residual(c0, c1, dev(x), dev(w0), dev(b0), dev(w1), dev(b1), dev(res), y, 1.0, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(y), want, "b2b conv residual %s instance %d" % (shape, kid))
+        ran += 1
+    assert ran >= 1, "no instance for %s" % (shape,)
+    y = dev(res).clone()
+    r = bolt.bolt_tune(bolt.OP_B2B_CONV_RES, c0, c1, [dev(x), dev(w0), dev(b0), dev(w1), dev(b1), y, dev(res)])
+    assert r.tried == ran
+    y = dev(res).clone()  # in place, tuned config
+    bolt.bolt_b2b_conv_residual(c0, c1, dev(x), dev(w0), dev(b0), dev(w1), dev(b1), y, y, 1.0, r.config)
+    torch.cuda.synchronize()
+    assert_close(host(y), want, "b2b conv residual %s tuned, in place" % (shape,))
+    # an instance without the residual epilogue is refused, not silently run without it
+    plain_only = [k for k in range(bolt.bolt_num_instances(bolt.OP_B2B_CONV))
+                  if bolt.bolt_instance_supports(bolt.OP_B2B_CONV, k, c0, c1)
+                  and not bolt.bolt_instance_supports(bolt.OP_B2B_CONV_RES, k, c0, c1)]
+    if plain_only:
+        with pytest.raises(bolt.BoltError) as e:
+            bolt.bolt_b2b_conv_residual(c0, c1, dev(x), dev(w0), dev(b0), dev(w1), dev(b1), dev(res), y, 1.0,
+                                        {"kernel_id": plain_only[0]})
+        assert e.value.status == 2
+
+
+def test_b2b_residual_integer_bit_exact(bolt):
+    M, K0, N0, N1 = 300, 64, 32, 96
+    A, W0 = wl.integer_fp16(407, 0, (M, K0), -2, 2), wl.integer_fp16(407, 1, (K0, N0), -1, 1)
+    b0, W1 = wl.integer_fp16(407, 2, (N0,), -2, 2), wl.integer_fp16(407, 3, (N0, N1), -1, 1)
+    b1, Cm = wl.integer_fp16(407, 4, (N1,), -2, 2), wl.integer_fp16(407, 5, (M, N1), -9, 9)
+    want = ref.b2b_gemm_residual(A, W0, b0, W1, b1, Cm, gamma=-3.0)
+    g0 = bolt.gemm_desc(M, N0, K0, b_layout=bolt.LAYOUT_NK)
+    g1 = bolt.gemm_desc(M, N1, N0, b_layout=bolt.LAYOUT_NK)
+    D = torch.empty((M, N1), dtype=torch.float16, device="cuda")
+    bolt.bolt_b2b_gemm_residual(g0, g1, dev(A), dev(np.ascontiguousarray(W0.T)), dev(b0), dev(np.ascontiguousarray(W1.T)),
+                                dev(b1), dev(Cm), D, -3.0)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(D), want, "integer b2b gemm residual")
+
+
 # ---------------------------------------------------------------------------------------------
 # three-op chains
 # ---------------------------------------------------------------------------------------------

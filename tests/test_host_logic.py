@@ -125,6 +125,28 @@ def test_b2b_fusion_legality(bolt):
     assert chk(bolt.OP_B2B_CONV, c0s, Cd(32, 28, 28, 64, 64, 1, 1, 1, 0)) == OK
 
 
+def test_fused_pair_residual_instance_sets(bolt):
+    # the residual ops index the same instance tables; only the instances with that epilogue support them
+    G, Cd = bolt.gemm_desc, bolt.conv_desc
+    nk = bolt.LAYOUT_NK
+    g0, g1 = G(16384, 64, 256, b_layout=nk), G(16384, 128, 64, b_layout=nk)
+    c0, c1 = Cd(32, 56, 56, 64, 64, 3, 3, 1, 1), Cd(32, 56, 56, 64, 256, 1, 1, 1, 0)
+    for plain, res, d0, d1 in ((bolt.OP_B2B_GEMM, bolt.OP_B2B_GEMM_RES, g0, g1), (bolt.OP_B2B_CONV, bolt.OP_B2B_CONV_RES, c0, c1)):
+        n = bolt.bolt_num_instances(plain)
+        assert bolt.bolt_num_instances(res) == n
+        a = {i for i in range(n) if bolt.bolt_instance_supports(plain, i, d0, d1)}
+        b = {i for i in range(n) if bolt.bolt_instance_supports(res, i, d0, d1)}
+        assert b and b <= a
+        assert bolt.bolt_check(res, d0, d1) == OK
+        if plain == bolt.OP_B2B_CONV:  # the persistent weights-resident conv instances lack it
+            assert b < a and bolt.bolt_check(res, d0, d1, {"kernel_id": min(a - b)}) == UNSUPPORTED
+        assert bolt.bolt_check(res, d0, d1, {"kernel_id": min(b)}) == OK
+        assert bolt.bolt_instance_config(res, min(b)).as_dict() == bolt.bolt_instance_config(plain, min(b)).as_dict()
+    # row-major weights: only the weights-resident kernels take them, and those have no residual epilogue
+    assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, G(16384, 64, 256), G(16384, 128, 64)) == UNSUPPORTED
+    assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, g0, G(16000, 128, 64, b_layout=nk)) == ILLEGAL
+
+
 def test_chain_legality(bolt):
     G, Cd, chk = bolt.gemm_desc, bolt.conv_desc, bolt.bolt_check_chain
     nk = bolt.LAYOUT_NK
@@ -178,6 +200,19 @@ def test_null_pointers_are_rejected_before_any_launch(bolt):
     assert lib.bolt_gemm_epilogue_residual(ctypes.byref(d), 16, 32, None, 64, 32, 1.0, 48, None, None, 0, None) == INVALID  # ldc < N
     assert lib.bolt_gemm_epilogue_residual(ctypes.byref(d), 16, 32, None, 72, 64, 1.0, 48, None, None, 0, None) == ALIGNMENT
     assert lib.bolt_conv2d_fprop_nhwc_residual(ctypes.byref(c), 16, 32, None, None, 1.0, 48, None, None, 0, None) == INVALID
+    g0, g1 = bolt.gemm_desc(64, 64, 64, b_layout=bolt.LAYOUT_NK), bolt.gemm_desc(64, 64, 64, b_layout=bolt.LAYOUT_NK)
+    r = lambda C_, ldc, D_: lib.bolt_b2b_gemm_residual(ctypes.byref(g0), ctypes.byref(g1), 16, 32, None, 48, None, C_, ldc, 1.0,
+                                                       D_, None, None, 0, None)
+    assert r(None, 64, 80) == INVALID      # no residual matrix
+    assert r(64, 32, 80) == INVALID        # ldc < N1
+    assert r(64, 68, 80) == ALIGNMENT      # ldc not a multiple of 8
+    assert r(72, 64, 80) == ALIGNMENT      # residual pointer not 16-byte aligned
+    c0, c1 = bolt.conv_desc(1, 8, 8, 8, 64, 3, 3, 1, 1), bolt.conv_desc(1, 8, 8, 64, 64, 1, 1, 1, 0)
+    assert lib.bolt_b2b_conv_residual(ctypes.byref(c0), ctypes.byref(c1), 16, 32, None, 48, None, None, 1.0, 80, None, None, 0,
+                                      None) == INVALID
+    c1bad = bolt.conv_desc(1, 8, 8, 64, 64, 3, 3, 1, 1)
+    assert lib.bolt_b2b_conv_residual(ctypes.byref(c0), ctypes.byref(c1bad), 16, 32, None, 48, None, 64, 1.0, 80, None, None, 0,
+                                      None) == ILLEGAL
     assert lib.bolt_nchw_to_nhwc(None, 32, 1, 3, 8, 8, 8, None) == INVALID
     assert lib.bolt_nchw_to_nhwc(16, 32, 1, 3, 8, 8, 7, None) == ALIGNMENT      # C_padded % 8
     assert lib.bolt_nchw_to_nhwc(16, 40, 1, 3, 8, 8, 8, None) == ALIGNMENT      # NHWC side misaligned

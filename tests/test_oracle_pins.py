@@ -421,6 +421,34 @@ def test_residual_epilogue_full_matrix_c():
     assert not np.array_equal(y, ref.conv2d_nhwc(x, w, b, stride=2, pad=1))
 
 
+def test_fused_pair_with_residual_in_the_second_epilogue():
+    # Eq. 1-2 with C1 a full matrix, on integers small enough that D0 and every sum are exact: against numpy
+    # float64 written out here; gamma = 0 reduces to the plain pair; the conv pair equals the GEMM pair on im2col
+    A = wl.integer_fp16(54, 0, (21, 16), -2, 2)
+    W0 = wl.integer_fp16(54, 1, (16, 8), -1, 1)
+    b0 = wl.integer_fp16(54, 2, (8,), -2, 2)
+    W1 = wl.integer_fp16(54, 3, (8, 24), -1, 1)
+    b1 = wl.integer_fp16(54, 4, (24,), -2, 2)
+    Cm = wl.integer_fp16(54, 5, (21, 24), -9, 9)
+    f = lambda a: a.astype(np.float64)
+    d0 = np.maximum(f(A) @ f(W0) + f(b0), 0)
+    want = np.maximum(d0 @ f(W1) + f(b1) - 3.0 * f(Cm), 0)
+    got = ref.b2b_gemm_residual(A, W0, b0, W1, b1, Cm, gamma=-3.0)
+    assert np.array_equal(f(got), want) and np.abs(want).max() < 2048 and want.any()
+    assert np.array_equal(ref.b2b_gemm_residual(A, W0, b0, W1, b1, Cm, gamma=0.0), ref.b2b_gemm(A, W0, b0, W1, b1))
+    # the residual enters after op1 only: adding it to op0's output instead gives something else
+    assert not np.array_equal(f(got), np.maximum(np.maximum(d0 - 3.0 * f(Cm)[:, :8], 0) @ f(W1) + f(b1), 0))
+    x = wl.integer_fp16(55, 0, (2, 6, 5, 8), -2, 2)
+    w0 = wl.integer_fp16(55, 1, (8, 3, 3, 8), -1, 1)
+    w1 = wl.integer_fp16(55, 2, (16, 1, 1, 8), -1, 1)
+    res = wl.integer_fp16(55, 3, (2, 3, 3, 16), -5, 5)
+    y = ref.b2b_conv_residual(x, w0, b0, w1, b1[:16], res, stride=2, pad=1, gamma=2.0)
+    col = ref.im2col(x, 3, 3, 2, 1)
+    want = ref.b2b_gemm_residual(col, w0.reshape(8, -1).T, b0, w1.reshape(16, 8).T, b1[:16], res.reshape(-1, 16), gamma=2.0)
+    assert np.array_equal(y.reshape(-1, 16), want)
+    assert not np.array_equal(y, ref.b2b_conv(x, w0, b0, w1, b1[:16], stride=2, pad=1))
+
+
 def test_chain_of_three_ops_rounds_between_ops_and_extends_b2b():
     # integers small enough that every intermediate is exactly representable: the chain must equal float64
     # matrix products with ReLUs, and the first two ops of it must be the b2b oracle bit for bit
