@@ -562,6 +562,35 @@ def test_config5_layer_full_size_tuned_sampled(bolt, index):
 
 
 # ---------------------------------------------------------------------------------------------
+# maximum sizes: an input tensor just below the 2 GiB that one buffer descriptor addresses
+# ---------------------------------------------------------------------------------------------
+def test_conv_input_just_below_the_size_limit_sampled(bolt):
+    N, H, W, Cc, K = 8, 512, 512, 504, 64          # 8 * 512 * 512 * 504 = 2^30 - 16.8 M elements = 2.11 GB of FP16
+    assert bolt.bolt_check(bolt.OP_CONV2D, bolt.conv_desc(N, H, W, Cc + 8, K, 3, 3, 1, 1)) == 2  # one step further: unsupported
+    block = wl.uniform_fp16(601, 0, (H, W, Cc), -1, 1)
+    x = np.empty((N, H, W, Cc), np.float16)
+    for n, scale in enumerate((1.0, -1.0, 0.5, -0.5, 0.25, -0.25, 2.0, -2.0)):  # exact in FP16, every image different
+        np.multiply(block, np.float16(scale), out=x[n])
+    del block
+    bias = wl.uniform_fp16(601, 2, (K,), -1, 1)
+    xd = dev(x)
+    edge_rows = np.array([0, 1, W - 1, W, N * H * W - W - 1, N * H * W - 2, N * H * W - 1])  # first / last pixels: smallest and largest offsets
+    for (R, pad) in ((3, 1), (1, 0)):               # the im2col gather, and the GEMM addressing of 1x1 / stride 1
+        w = wl.normal_fp16(601, 1, (K, R, R, Cc), (2.0 / (R * R * Cc)) ** 0.5)
+        d = bolt.conv_desc(N, H, W, Cc, K, R, R, 1, pad)
+        y = torch.full((N, H, W, K), float("nan"), dtype=torch.float16, device="cuda")
+        _say("conv %dx%d on a %.2f GB input" % (R, R, x.nbytes / 1e9))
+        bolt.bolt_conv2d_fprop_nhwc(d, xd, dev(w), dev(bias), y)
+        torch.cuda.synchronize()
+        got = host(y).reshape(-1)
+        assert np.all(np.isfinite(got)), "unwritten or non-finite outputs"
+        idx = np.unique(np.concatenate([_sample_idx(got.size, 1500, 7), (edge_rows[:, None] * K + np.arange(K)[None, :]).reshape(-1)]))
+        want = ref.conv2d_nhwc_at(x, w, idx, bias, stride=1, pad=pad)
+        assert_close(got[idx], want, "conv %dx%d, input just below 2 GiB" % (R, R))
+        del y
+
+
+# ---------------------------------------------------------------------------------------------
 # layout transformation
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("shape", [(2, 3, 32, 32, 8), (1, 3, 224, 224, 8), (3, 64, 9, 11, 64), (2, 70, 13, 5, 72), (1, 1, 1, 1, 8),
