@@ -925,6 +925,57 @@ def test_unfused_gemm_plus_bias_act_matches_fused_on_integers(bolt):
     assert_bit_equal(fused, ref.gemm(A, B, bias), "fused vs oracle")
 
 
+def test_calls_are_capturable_in_a_hip_graph_and_replays_repeat_the_eager_result(bolt):
+    """The entry points only enqueue kernels on the given stream (no allocation, no synchronisation, no memset), so a
+    caller can capture them; every replay must reproduce the eager outputs bit for bit."""
+    x = wl.uniform_fp16(901, 0, (2, 14, 14, 64), -1, 1)
+    w = wl.normal_fp16(901, 1, (64, 3, 3, 64), (2.0 / 576) ** 0.5)
+    b = wl.uniform_fp16(901, 2, (64,), -1, 1)
+    res = wl.uniform_fp16(901, 3, (2, 14, 14, 64), -2, 2)
+    w1 = wl.normal_fp16(901, 4, (64, 1, 1, 64), (2.0 / 64) ** 0.5)
+    b1 = wl.uniform_fp16(901, 5, (64,), -1, 1)
+    x3 = wl.uniform_fp16(901, 6, (2, 14, 14, 6), -1, 1)
+    d = bolt.conv_desc(2, 14, 14, 64, 64, 3, 3, 1, 1)
+    d1 = bolt.conv_desc(2, 14, 14, 64, 64, 1, 1, 1, 0)
+    xd, wd, bd, rd, w1d, b1d, x3d = (dev(a) for a in (x, w, b, res, w1, b1, x3))
+    ws = torch.empty(max(bolt.bolt_workspace_bytes(bolt.OP_CONV2D, d), 16), dtype=torch.uint8, device="cuda")
+    sk = next(k for k in range(bolt.bolt_num_instances(bolt.OP_CONV2D))
+              if bolt.bolt_check(bolt.OP_CONV2D, d, None, {"kernel_id": k, "split_k": 2}) == 0)
+    outs = dict(y_split=torch.empty((2, 14, 14, 64), dtype=torch.float16, device="cuda"),
+                y_res=torch.empty((2, 14, 14, 64), dtype=torch.float16, device="cuda"),
+                y_pair=torch.empty((2, 14, 14, 64), dtype=torch.float16, device="cuda"),
+                x8=torch.empty((2, 14, 14, 8), dtype=torch.float16, device="cuda"))
+
+    def enqueue():
+        bolt.bolt_conv2d_fprop_nhwc(d, xd, wd, bd, outs["y_split"], {"kernel_id": sk, "split_k": 2}, ws)   # two kernels + workspace
+        bolt.bolt_conv2d_fprop_nhwc_residual(d, xd, wd, bd, rd, outs["y_res"])
+        bolt.bolt_b2b_conv(d, d1, xd, wd, bd, w1d, b1d, outs["y_pair"])
+        bolt.bolt_pad_channels_nhwc(x3d, outs["x8"], 8)
+
+    enqueue()  # eager: the expected values (and every kernel's one-time attribute call happens outside the capture)
+    torch.cuda.synchronize()
+    eager = {k: host(v).copy() for k, v in outs.items()}
+    assert_close(eager["y_split"], ref.conv2d_nhwc(x, w, b, stride=1, pad=1), "eager split-K conv")
+    assert_close(eager["y_res"], ref.conv2d_nhwc_residual(x, w, b, res, stride=1, pad=1), "eager residual conv")
+    assert_close(eager["y_pair"], ref.b2b_conv(x, w, b, w1, b1, stride=1, pad=1), "eager fused pair")
+    assert_bit_equal(eager["x8"], ref.pad_channels(x3, 8), "eager padding")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    for rep in range(3):
+        for v in outs.values():
+            v.fill_(float("nan"))
+        ws.fill_(0xFF)                      # stale workspace contents must not matter
+        torch.cuda.synchronize()
+        _say("graph replay %d" % rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in outs.items():
+            assert_bit_equal(host(v), eager[k], "graph replay %d, %s" % (rep, k))
+        enqueue()                           # eager work between replays
+        torch.cuda.synchronize()
+
+
 def test_tune_is_cached_and_probes_run(bolt):
     M, N, K = 512, 256, 256
     A, B = dev(wl.uniform_fp16(601, 0, (M, K), -1, 1)), dev(wl.uniform_fp16(601, 1, (K, N), -1, 1))
