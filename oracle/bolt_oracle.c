@@ -253,7 +253,7 @@ void bolt_ref_b2b_conv(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K0, i
                        uint16_t *y) {
   int64_t P = out_extent(H, pad_h, R, stride_h), Q = out_extent(W, pad_w, S, stride_w);
   int64_t rows = N * P * Q;
-  uint16_t *y0 = (uint16_t *)malloc((size_t)(rows * K0 ? rows * K0 : 1) * sizeof(uint16_t));
+  uint16_t *y0 = (uint16_t *)malloc((size_t)(rows * K0 > 0 ? rows * K0 : 1) * sizeof(uint16_t));
   bolt_ref_conv2d_nhwc(N, H, W, C, K0, R, S, stride_h, stride_w, pad_h, pad_w, x, w0, b0, alpha0, beta0, act0, y0);
   bolt_ref_conv2d_nhwc(N, P, Q, K0, K1, 1, 1, 1, 1, 0, 0, y0, w1, b1, alpha1, beta1, act1, y);
   free(y0);
