@@ -239,7 +239,7 @@ void bolt_ref_b2b_gemm(int64_t M, int64_t N0, int64_t K0, int64_t N1, const uint
                        const uint16_t *W0, int64_t ldw0, const uint16_t *b0, float alpha0, float beta0,
                        int act0, const uint16_t *W1, int64_t ldw1, const uint16_t *b1, float alpha1,
                        float beta1, int act1, uint16_t *D1, int64_t ldd) {
-  uint16_t *D0 = (uint16_t *)malloc((size_t)(M * N0 ? M * N0 : 1) * sizeof(uint16_t));
+  uint16_t *D0 = (uint16_t *)malloc((size_t)(M * N0 > 0 ? M * N0 : 1) * sizeof(uint16_t));
   bolt_ref_gemm(M, N0, K0, A0, lda, W0, ldw0, b0, alpha0, beta0, act0, D0, N0);
   bolt_ref_gemm(M, N1, N0, D0, N0, W1, ldw1, b1, alpha1, beta1, act1, D1, ldd);
   free(D0);
