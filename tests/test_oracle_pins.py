@@ -505,6 +505,51 @@ def test_activation_closed_forms(act):
     assert np.all(np.abs(got - want) <= 0.5 * ulp * (1 + 1e-6) + 1e-300)
 
 
+def _oracle_act(act, v16):
+    """act(v) for a vector of halves through the oracle: a K = 1 GEMM against B = [1]."""
+    return ref.gemm(v16.reshape(-1, 1), np.ones((1, 1), np.float16), None, act=act).reshape(-1).astype(np.float64)
+
+
+def _half_ulp_ok(got, want):
+    ulp = np.spacing(np.abs(want).astype(np.float16)).astype(np.float64)
+    return np.all(np.abs(got - want) <= 0.5 * ulp * (1 + 1e-6) + 1e-300)
+
+
+@pytest.mark.parametrize("act", ["gelu", "hardswish", "softplus"])
+def test_activation_values_from_an_independent_implementation(act):
+    # Values that do not come from the formula the oracle evaluates: PyTorch's own float64 activation kernels
+    # (Section 3.2.3 lists these three next to ReLU) over every finite half in [-10, 10] (a wrong constant,
+    # a tanh approximation in place of the exact GELU, a shifted Hardswish knee all fail here).
+    import torch
+    import torch.nn.functional as F
+    allh = np.arange(0x10000, dtype=np.uint32).astype(np.uint16).view(np.float16)
+    v = allh[np.isfinite(allh) & (np.abs(allh.astype(np.float64)) <= 10)]
+    t = torch.from_numpy(v.astype(np.float64))
+    want = {"gelu": lambda: F.gelu(t, approximate="none"), "hardswish": lambda: F.hardswish(t),
+            "softplus": lambda: F.softplus(t, beta=1.0, threshold=1e9)}[act]().numpy()
+    assert _half_ulp_ok(_oracle_act(act, v), want)
+
+
+def test_gelu_is_v_times_the_gaussian_cdf_by_quadrature_and_table_values():
+    # GELU(v) = v * Phi(v) with Phi the integral of the standard normal density: the integral is evaluated by
+    # adaptive quadrature (no erf anywhere), plus the table values Phi(1) = 0.8413447461, Phi(2) = 0.9772498681.
+    from scipy import integrate
+    pts = np.array([-6, -3.5, -2, -1, -0.5, -0.125, 0, 0.125, 0.5, 1, 2, 3.5, 6], dtype=np.float16)
+    dens = lambda u: math.exp(-0.5 * u * u) / math.sqrt(2 * math.pi)
+    phi = np.array([integrate.quad(dens, -np.inf, float(a), epsabs=1e-14, epsrel=1e-13)[0] for a in pts])
+    assert _half_ulp_ok(_oracle_act("gelu", pts), pts.astype(np.float64) * phi)
+    table = {1.0: 0.8413447461, 2.0: 1.9544997361, -1.0: -0.1586552539, 0.0: 0.0}
+    got = _oracle_act("gelu", np.array(list(table), dtype=np.float16))
+    assert _half_ulp_ok(got, np.array(list(table.values())))
+
+
+def test_hardswish_knees_and_table_values():
+    # v * relu6(v + 3) / 6: zero up to -3, the identity from +3, exact rationals in between
+    v = np.array([-8, -3, -1.5, -1, 0, 1, 1.5, 3, 8], dtype=np.float16)
+    want = np.array([0, 0, -0.375, -1.0 / 3, 0, 2.0 / 3, 1.125, 3, 8])
+    assert _half_ulp_ok(_oracle_act("hardswish", v), want)
+
+
 @pytest.mark.parametrize("act", ["none", "relu", "gelu", "hardswish", "softplus"])
 def test_bias_act_closed_forms_with_alpha_beta(act):
     # the stand-alone epilogue pass (Section 4.1.1's un-fused baseline): every finite-range half in a
