@@ -226,11 +226,13 @@ __device__ __forceinline__ int ctile_swizzle(int row) {
 // and every lane reads the quad it is about to overwrite.  RES is a compile-time switch: the residual kernels
 // are separate instantiations, so the plain kernels keep their register allocation and occupancy.
 // `writer`: this wave holds the final accumulators (k-group 0).  Called by every thread of the workgroup.
-template <bool RES, int BM, int BN, int WTM, int WTN, int STORE_THREADS, int ROWS_PER_PASS, int FN, int FM>
-__device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc)[FN][FM], const FpropParams& p, int m0,
-                                               int n0, int wm, int wn, bool writer, int tid) {
+// `to_lds(slow, ep)` writes this wave's accumulators as FP16 quads into the staged tile (the layout of the quads
+// depends on the matrix-core instruction the main loop used).
+template <bool RES, int BM, int BN, int STORE_THREADS, int ROWS_PER_PASS, typename ToLds>
+__device__ __forceinline__ void fprop_tile_out_with(half_t* lds, const FpropParams& p, int m0, int n0, bool writer, int tid,
+                                                    ToLds&& to_lds) {
   constexpr int CPR = BN / 8;
-  const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
+  const int lane = tid & 63;
   const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act, p.gamma};
   barrier_after_lds_writes();  // every wave has finished reading what the tile overwrites
   if constexpr (RES) {
@@ -251,24 +253,9 @@ __device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc
     }
     barrier_after_loads<0>();
   }
-  auto tile_to_lds = [&](auto slow) {
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;  // column inside the tile
-#pragma unroll
-        for (int b = 0; b < FM; ++b) {
-          const int row = wm * WTM + b * 32 + l32;
-          half4* slot = (half4*)(lds + row * BN + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4));
-          if constexpr (RES) *slot = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep, *slot);
-          else *slot = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
-        }
-      }
-  };
   if (writer) {
-    if (p.act > ACT_RELU) tile_to_lds(std::true_type{});
-    else tile_to_lds(std::false_type{});
+    if (p.act > ACT_RELU) to_lds(std::true_type{}, ep);
+    else to_lds(std::false_type{}, ep);
   }
   barrier_after_lds_writes();
   // LDS -> global: each thread moves 16 bytes, consecutive threads cover consecutive row bytes
@@ -286,6 +273,30 @@ __device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc
       }
     }
   }
+}
+
+// The 32 x 32 accumulator layout: lane l of a fragment holds, in registers 4q .. 4q+3, columns 8q + 4(l / 32) .. +3
+// of row l % 32.
+template <bool RES, int BM, int BN, int WTM, int WTN, int STORE_THREADS, int ROWS_PER_PASS, int FN, int FM>
+__device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc)[FN][FM], const FpropParams& p, int m0,
+                                               int n0, int wm, int wn, bool writer, int tid) {
+  constexpr int CPR = BN / 8;
+  const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
+  fprop_tile_out_with<RES, BM, BN, STORE_THREADS, ROWS_PER_PASS>(lds, p, m0, n0, writer, tid, [&](auto slow, const EpilogueArgs& ep) {
+#pragma unroll
+    for (int a = 0; a < FN; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;  // column inside the tile
+#pragma unroll
+        for (int b = 0; b < FM; ++b) {
+          const int row = wm * WTM + b * 32 + l32;
+          half4* slot = (half4*)(lds + row * BN + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4));
+          if constexpr (RES) *slot = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep, *slot);
+          else *slot = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
+        }
+      }
+  });
 }
 
 // KG k-groups: KG sets of WAVES_M x WAVES_N waves work on the same output tile, set g on the k-tiles
