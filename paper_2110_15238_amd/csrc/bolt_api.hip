@@ -341,17 +341,24 @@ static void fprop_fill_config(const FpropInstance& in, int id, bolt_config* c) {
   c->kernel_id = id;
   c->tile_m = in.bm; c->tile_n = in.bn; c->tile_k = in.bk;
   c->waves_m = in.waves_m; c->waves_n = in.waves_n;
-  c->mfma_shape = 32; c->stages = in.stages; c->b2b_mode = 0;
+  c->mfma_shape = in.mi ? in.mi : 32; c->stages = in.stages; c->b2b_mode = 0;
 }
 
 // Built-in pick rule: smallest estimated time under a crude model -- rounds of workgroups over
 // the compute units times the work of one tile, de-rated for small tiles (low FLOP per LDS byte).
-static int fprop_heuristic(const std::vector<FpropInstance>& tab, const FpropProblem& pr) {
+// The weights-resident, halo, single-stage and ping-pong kernels have no partial-sum output.
+static bool fprop_can_split_k(const FpropInstance& in) {
+  return !in.stream_launch && !in.dyn_supports && in.stages != 1 && !in.no_split_k;
+}
+
+// need_split_k: only instances that can write partial sums qualify (the caller asked for split-K).
+static int fprop_heuristic(const std::vector<FpropInstance>& tab, const FpropProblem& pr, bool need_split_k = false) {
   int best = -1;
   double best_cost = 0;
   for (int i = 0; i < (int)tab.size(); ++i) {
     const FpropInstance& in = tab[i];
     if (!fprop_supports(in, pr)) continue;
+    if (need_split_k && !fprop_can_split_k(in)) continue;
     const double tiles = (double)ceil_div(pr.p.M, in.bm) * ceil_div(pr.p.N, in.bn);
     const int lds = in.stream_launch ? in.stream_lds_bytes(pr.p.K) : (in.dyn_lds_bytes ? in.dyn_lds_bytes(pr.p) : in.lds_bytes);
     const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n * std::max(1, in.kgroups)) / 2));
@@ -394,7 +401,7 @@ static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int sw
   p.tiles_m = ceil_div(p.M, in.bm);
   p.tiles_n = ceil_div(p.N, in.bn);
   p.swizzle = swizzle < 0 ? 0 : swizzle;
-  if (in.dyn_supports && split_k > 1) return BOLT_ERR_UNSUPPORTED;
+  if (split_k > 1 && !fprop_can_split_k(in) && !in.stream_launch) return BOLT_ERR_UNSUPPORTED;
   const int nk = in.xmode == 3 ? p.cg.R : ceil_div(p.K, in.bk);  // x mode 3: one k-tile per filter row
   split_k = std::max(1, std::min(std::min(split_k, kMaxSplitK), nk));
   p.ktiles_per_split = ceil_div(nk, split_k);
@@ -461,15 +468,12 @@ static bolt_status resolve_fprop(const std::vector<FpropInstance>& tab, const Fp
   if (cfg && cfg->kernel_id >= 0) {
     if (cfg->kernel_id >= (int)tab.size()) return BOLT_ERR_INVALID_ARG;
     if (!fprop_supports(tab[cfg->kernel_id], pr)) return BOLT_ERR_UNSUPPORTED;
-    // the weights-resident, halo and single-stage kernels have no split-K variant
-    if (*split_k > 1 && (tab[cfg->kernel_id].stream_launch || tab[cfg->kernel_id].dyn_supports ||
-                         tab[cfg->kernel_id].stages == 1))
-      return BOLT_ERR_UNSUPPORTED;
+    if (*split_k > 1 && !fprop_can_split_k(tab[cfg->kernel_id])) return BOLT_ERR_UNSUPPORTED;
     *id = cfg->kernel_id;
     return BOLT_OK;
   }
   if (cfg && cfg->kernel_id < -1) return BOLT_ERR_INVALID_ARG;
-  *id = fprop_heuristic(tab, pr);
+  *id = fprop_heuristic(tab, pr, *split_k > 1);
   return *id < 0 ? BOLT_ERR_UNSUPPORTED : BOLT_OK;
 }
 
@@ -770,7 +774,7 @@ static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>&
       out.push_back({i, swz[s], 1, 0.f});
     }
     // split-K only when the grid cannot fill the chip and K is deep enough to share
-    for (int sk = 2; sk <= kMaxSplitK && in.stages != 1; sk *= 2) {
+    for (int sk = 2; sk <= kMaxSplitK && fprop_can_split_k(in); sk *= 2) {
       if (tiles * (sk / 2) >= kNumCU || nk < 2 * sk) break;
       if (!have_ws || ws_bytes < splitk_bytes(pr.p.M, pr.p.N, sk)) break;
       out.push_back({i, 0, sk, 0.f});

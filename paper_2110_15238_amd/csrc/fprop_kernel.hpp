@@ -192,6 +192,8 @@ struct FpropInstance {
   bool (*dyn_supports)(const FpropParams&);
   int (*dyn_lds_bytes)(const FpropParams&);
   int kgroups;  // k-groups of waves per workgroup (0 or 1: none); threads = 64 * waves_m * waves_n * kgroups
+  int mi;       // matrix-core instruction: 0 or 32 = 32 x 32 x 16, 16 = 16 x 16 x 32
+  bool no_split_k;  // the kernel has no partial-sum output
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>

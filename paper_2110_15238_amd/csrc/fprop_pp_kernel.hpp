@@ -24,10 +24,6 @@
 //          but its newest 8 loads - at the end of the same phase; X(t+2) is first read in slot 2t + 4.
 // Loads of tiles beyond the reduction are issued all the same: their offsets fall outside the buffer, the
 // hardware writes zeros into a stage nobody reads any more, and the wait counts stay uniform.
-//
-// EB: the barrier that ends a C phase is executed EB MFMAs before the end of the phase; the remaining MFMAs are
-// issued behind it, while the other wave of the SIMD starts its own, so the matrix pipe does not drain for the
-// latency of the barrier.
 #pragma once
 #include <type_traits>
 #include <utility>
@@ -60,22 +56,25 @@ __device__ __forceinline__ void pp_static_for(F&& f, std::integer_sequence<int, 
 // bounds and every wave still reaches every barrier): 1 = no global loads in the steady state,
 // 2 = no fragment reads in the steady state, 4 = no MFMAs, 8 = every workgroup computes tile (0, 0).
 // MI: the matrix-core instruction, 32 (32 x 32 x 16) or 16 (16 x 16 x 32, see mfma_16x16x32).
-template <int XMODE, int MI = 16, int EB = 0, bool RES = false, int ABL = 0>
+// PK: reduction depth of one phase, 64 (one M and one C phase per k-tile) or 32 (two of each: half the fragment
+//     registers, which the implicit-GEMM gather needs for its per-row state, and twice the barriers).  With two
+//     phases per tile the loads still go out in the first M phase of a tile and the waits stay where they are.
+template <int XMODE, int MI = 16, int PK = 64, bool RES = false, int ABL = 0>
 __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
   using T = FpropPpTraits;
   static_assert(MI == 16 || MI == 32, "matrix-core instruction");
+  static_assert(PK == 32 || PK == 64, "phase depth");
   constexpr int BM = T::BM, BN = T::BN, BK = T::BK, WTM = T::WTM, WTN = T::WTN;
   constexpr int FM = WTM / MI, FN = WTN / MI;  // fragments per wave tile along M and N
   constexpr int MK = MI == 32 ? 16 : 32;       // reduction depth of one instruction
-  constexpr int KS = BK / MK;                  // k-steps per k-tile
+  constexpr int P = BK / PK;                   // phases per k-tile
+  constexpr int KS = PK / MK;                  // k-steps per phase
   constexpr int KL = MK / 8;                   // lane groups along k: lane l reads chunk k * KL + l / MI of row l % MI
   using acc_t = std::conditional_t<MI == 32, floatx16, floatx4>;
   using XL = DmaTileLoader<BM, BK, 4, XMODE>;
   using WL = DmaTileLoader<BN, BK, 4, 0>;
   constexpr int L = 8;  // load instructions per wave per k-tile
   static_assert(XL::NI == L && WL::NI == L, "each group moves one operand tile with 8 instructions per wave");
-  constexpr int NMFMA = KS * FM * FN;
-  static_assert(EB >= 0 && EB < NMFMA, "MFMAs issued behind the barrier");
 
   extern __shared__ __attribute__((aligned(16))) half_t lds[];
   half_t* const wring = lds;
@@ -118,50 +117,50 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
       for (int r = 0; r < (MI == 32 ? 16 : 4); ++r) acc[a][b][r] = 0.f;
 
   half8 xf[KS][FM], wf[KS][FN];
-  // One M phase: the L load instructions of k-tile kt (into dst) interleaved with the KS * (FM + FN) fragment
-  // reads of the tile in (xs, ws), 1 load : 3 reads, so that the address path and the LDS pipe work side by side.
-  constexpr int NREAD = KS * (FM + FN), RPL = NREAD / L;
-  static_assert(NREAD % L == 0, "reads per load instruction");
-  auto read_one = [&](const half_t* xs, const half_t* ws, auto rc) {
+  constexpr int NREAD = KS * (FM + FN);  // fragment reads per phase
+  auto read_one = [&](const half_t* xs, const half_t* ws, int h, auto rc) {
     constexpr int r = decltype(rc)::value, k = r / (FM + FN), i = r % (FM + FN);
-    const int chunk = k * KL + g;
+    const int chunk = (h * KS + k) * KL + g;
     if constexpr (i < FM) xf[k][i] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + i * MI + lr, chunk));
     else wf[k][i - FM] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + (i - FM) * MI + lr, chunk));
   };
-  auto m_phase = [&](auto& loader, half_t* dst, int kt, const half_t* xs, const half_t* ws, bool first) {
+  // An M phase that also loads: the L load instructions of k-tile kt (into dst) interleaved with the phase's fragment
+  // reads, so that the address path and the LDS pipe work side by side.
+  auto m_phase_loads = [&](auto& loader, half_t* dst, int kt, const half_t* xs, const half_t* ws, bool first) {
     pp_static_for([&](auto jc) {
-      constexpr int j = decltype(jc)::value;
+      constexpr int j = decltype(jc)::value, r0 = j * NREAD / L, r1 = (j + 1) * NREAD / L;
       if constexpr (!(ABL & 1)) loader.template issue_part<j, j + 1>(kt, dst, p.cg);
       if (!(ABL & 2) || first)
-        pp_static_for([&](auto ic) { read_one(xs, ws, std::integral_constant<int, j * RPL + decltype(ic)::value>{}); },
-                      std::make_integer_sequence<int, RPL>{});
+        pp_static_for([&](auto ic) { read_one(xs, ws, 0, std::integral_constant<int, r0 + decltype(ic)::value>{}); },
+                      std::make_integer_sequence<int, r1 - r0>{});
     }, std::make_integer_sequence<int, L>{});
     if constexpr (!(ABL & 1)) loader.advance(p.cg);
     if constexpr (!(ABL & 3)) {
-#pragma unroll
-      for (int j = 0; j < L; ++j) {
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);    // one load
-        __builtin_amdgcn_sched_group_barrier(0x100, RPL, 0);  // RPL LDS reads
-      }
+      pp_static_for([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                        // one load
+        __builtin_amdgcn_sched_group_barrier(0x100, (j + 1) * NREAD / L - j * NREAD / L, 0);      // its share of reads
+      }, std::make_integer_sequence<int, L>{});
     }
   };
-  auto mfma_range = [&](auto lo, auto hi) {
+  auto m_phase_reads = [&](const half_t* xs, const half_t* ws, int h) {
+    if constexpr (!(ABL & 2))
+      pp_static_for([&](auto ic) { read_one(xs, ws, h, ic); }, std::make_integer_sequence<int, NREAD>{});
+  };
+  auto c_phase = [&]() {
     pp_static_for([&](auto ic) {
-      constexpr int i = decltype(lo)::value + decltype(ic)::value, k = i / (FM * FN), a = (i / FM) % FN, b = i % FM;
+      constexpr int i = decltype(ic)::value, k = i / (FM * FN), a = (i / FM) % FN, b = i % FM;
       if constexpr (!(ABL & 4)) {
         if constexpr (MI == 32) acc[a][b] = mfma_32x32x16(wf[k][a], xf[k][b], acc[a][b]);
         else acc[a][b] = mfma_16x16x32(wf[k][a], xf[k][b], acc[a][b]);
       }
-    }, std::make_integer_sequence<int, decltype(hi)::value - decltype(lo)::value>{});
+    }, std::make_integer_sequence<int, KS * FM * FN>{});
   };
   auto fence = [] { __builtin_amdgcn_sched_barrier(0); };
   // gfx9 s_waitcnt encoding: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8]
   auto wait_reads = [] { __builtin_amdgcn_s_waitcnt(0xC07F); };            // lgkmcnt(0)
   auto wait_loads_0 = [] { __builtin_amdgcn_s_waitcnt(0x0F70); };          // vmcnt(0)
   auto wait_loads_L = [] { __builtin_amdgcn_s_waitcnt(0x0F70 | L); };      // vmcnt(L): all but the newest tile
-  using I0 = std::integral_constant<int, 0>;
-  using IC = std::integral_constant<int, NMFMA - EB>;
-  using IE = std::integral_constant<int, NMFMA>;
 
   // ---- prologue: W(0), X(0), X(1); tile 0 landed for everyone; group 1 drops one slot behind --------------------
   if (grp == 0) {
@@ -184,33 +183,35 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
     const int xs_fill = xs_cur == 0 ? 2 : xs_cur - 1;        // stage of X(t+2) = stage of X(t-1)
     const half_t* xs = xring + xs_cur * T::X_HALVES;
     const half_t* ws = wring + ws_cur * T::W_HALVES;
-    // ---- M phase ------------------------------------------------------------------------------------------
-    fence();
-    if (EB > 0 && t > 0) mfma_range(IC{}, IE{});  // the tail of this wave's previous C phase
-    if (grp == 0) {
-      m_phase(wl, wring + ws_next * T::W_HALVES, t + 1, xs, ws, t == 0);
+#pragma unroll
+    for (int h = 0; h < P; ++h) {
+      // ---- M phase ----------------------------------------------------------------------------------------
+      fence();
+      if (h == 0) {
+        if (grp == 0) m_phase_loads(wl, wring + ws_next * T::W_HALVES, t + 1, xs, ws, t == 0);
+        else m_phase_loads(xl, xring + xs_fill * T::X_HALVES, t + 2, xs, ws, t == 0);
+      } else {
+        m_phase_reads(xs, ws, h);
+      }
       wait_reads();
-    } else {
-      m_phase(xl, xring + xs_fill * T::X_HALVES, t + 2, xs, ws, t == 0);
-      wait_reads();
-      if constexpr (ABL & 1) wait_loads_0();
-      else wait_loads_L();  // X(t+1) has landed
+      if (h == P - 1 && grp == 1) {
+        if constexpr (ABL & 1) wait_loads_0();
+        else wait_loads_L();  // X(t+1) has landed
+      }
+      fence();
+      raw_barrier();
+      // ---- C phase ----------------------------------------------------------------------------------------
+      fence();
+      __builtin_amdgcn_s_setprio(1);
+      c_phase();
+      __builtin_amdgcn_s_setprio(0);
+      if (h == P - 1 && grp == 0) wait_loads_0();  // W(t+1) has landed
+      fence();
+      raw_barrier();
     }
-    fence();
-    raw_barrier();
-    // ---- C phase ------------------------------------------------------------------------------------------
-    fence();
-    __builtin_amdgcn_s_setprio(1);
-    mfma_range(I0{}, IC{});
-    __builtin_amdgcn_s_setprio(0);
-    if (grp == 0) wait_loads_0();  // W(t+1) has landed
-    fence();
-    raw_barrier();
     ws_cur = ws_next;
     xs_cur = xs_cur == 2 ? 0 : xs_cur + 1;
   }
-  fence();
-  if (EB > 0 && n_tiles > 0) mfma_range(IC{}, IE{});
   if (grp == 0) raw_barrier();
   wait_loads_0();  // nothing of this wave is still on its way into LDS
 
@@ -234,10 +235,10 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
   }
 }
 
-template <int XMODE, int MI = 16, int EB = 0, int ABL = 0>
+template <int XMODE, int MI = 16, int PK = 64, int ABL = 0>
 hipError_t launch_fprop_pp(const FpropParams& p, hipStream_t stream) {
   using T = FpropPpTraits;
-  auto kern = p.res ? fprop_pp_kernel<XMODE, MI, EB, true, ABL> : fprop_pp_kernel<XMODE, MI, EB, false, ABL>;
+  auto kern = p.res ? fprop_pp_kernel<XMODE, MI, PK, true, ABL> : fprop_pp_kernel<XMODE, MI, PK, false, ABL>;
   static bool attr_set[2] = {false, false};
   if (!attr_set[p.res ? 1 : 0]) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
@@ -248,5 +249,13 @@ hipError_t launch_fprop_pp(const FpropParams& p, hipStream_t stream) {
   hipLaunchKernelGGL(kern, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
   return hipGetLastError();
 }
+
+// In the instance table: 8 waves as 2 (M) x 4 (N), two LDS stages of weights,
+// three of activations (reported as 2), no split-K.
+#define BOLT_FPROP_PP_INSTANCE(XMODE, MI, PK)                                                               \
+  {                                                                                                         \
+    "pp_256x256x64_w2x4_mi" #MI "_pk" #PK, 256, 256, 64, 2, 4, XMODE, 0, 2, bolt::FpropPpTraits::LDS_BYTES,  \
+        &bolt::launch_fprop_pp<XMODE, MI, PK>, 0, nullptr, nullptr, nullptr, nullptr, 0, MI, true           \
+  }
 
 }  // namespace bolt

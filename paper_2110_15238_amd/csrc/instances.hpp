@@ -16,6 +16,7 @@
 #include "b2b_halo_kernel.hpp"
 #include "fprop_dma_kernel.hpp"
 #include "fprop_kernel.hpp"
+#include "fprop_pp_kernel.hpp"
 #include "stream_kernel.hpp"
 
 // X(BM, BN, BK, WAVES_M, WAVES_N)
