@@ -126,6 +126,21 @@ bolt_status bolt_conv2d_fprop_nhwc(const bolt_conv_desc* desc, const void* x, co
                                    void* y, const bolt_config* config, void* workspace, size_t workspace_bytes,
                                    void* stream);
 
+/* bolt_gemm_epilogue for callers that cannot allocate device memory and have no workspace to hand over (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the FP32 partial sums of a
+ * split-K config go to a fixed array of BOLT_NOALLOC_SCRATCH_BYTES that lives in the library's device image, one
+ * copy per GPU, held until the process ends.  The call itself allocates and frees nothing.
+ * Arguments, layouts, alignment rules and results are those of bolt_gemm_epilogue (all pointers device, FP16,
+ * borrowed); a config with split_k <= 1 needs no scratch at all.
+ * Errors: as bolt_gemm_epilogue; BOLT_ERR_WORKSPACE if split_k * M * N * 4 exceeds BOLT_NOALLOC_SCRATCH_BYTES
+ * (nothing is launched); BOLT_ERR_LAUNCH if the array's address cannot be obtained on the current device.
+ * The partial sums are fully overwritten before they are read, so nothing has to be cleared between calls; all
+ * calls on one GPU share the one array, so two calls that overlap in time on the same GPU (different streams)
+ * race on it: keep them on one stream or order them yourself. */
+#define BOLT_NOALLOC_SCRATCH_BYTES (16u << 20)
+bolt_status bolt_gemm_epilogue_noalloc(const bolt_gemm_desc* desc, const void* A, const void* B, const void* bias,
+                                       void* D, const bolt_config* config, void* stream);
+
 /* Persistent back-to-back GEMM (Eq. 1-2, Section 3.1.1): D0 = act0(alpha0 A0.W0 + beta0 b0) is
  * rounded to FP16 and stays on chip; D1 = act1(alpha1 D0.W1 + beta1 b1) is the only output.
  * Legal only if g1->M == g0->M and g1->K == g0->N (else BOLT_ERR_ILLEGAL_FUSION).  Threadblock

@@ -10,6 +10,7 @@ from .binding import (ACT, LAYOUT_KN, LAYOUT_NK, OP_B2B_CONV, OP_B2B_CONV_RES, O
 # the C ABI's entry points under their own names
 bolt_gemm_epilogue = binding.gemm_epilogue
 bolt_conv2d_fprop_nhwc = binding.conv2d_fprop_nhwc
+bolt_gemm_epilogue_noalloc = binding.gemm_epilogue_noalloc
 bolt_gemm_epilogue_residual = binding.gemm_epilogue_residual
 bolt_conv2d_fprop_nhwc_residual = binding.conv2d_fprop_nhwc_residual
 bolt_b2b_gemm = binding.b2b_gemm

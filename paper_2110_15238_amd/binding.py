@@ -77,6 +77,8 @@ _lib.bolt_workspace_bytes.restype = _sz
 _lib.bolt_workspace_bytes.argtypes = [C.c_int, _vp, _vp, C.POINTER(BoltConfig)]
 _lib.bolt_gemm_epilogue.restype = C.c_int
 _lib.bolt_gemm_epilogue.argtypes = [C.POINTER(GemmDesc), _vp, _vp, _vp, _vp, C.POINTER(BoltConfig), _vp, _sz, _vp]
+_lib.bolt_gemm_epilogue_noalloc.restype = C.c_int
+_lib.bolt_gemm_epilogue_noalloc.argtypes = [C.POINTER(GemmDesc), _vp, _vp, _vp, _vp, C.POINTER(BoltConfig), _vp]
 _lib.bolt_conv2d_fprop_nhwc.restype = C.c_int
 _lib.bolt_conv2d_fprop_nhwc.argtypes = [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, C.POINTER(BoltConfig), _vp, _sz, _vp]
 _lib.bolt_b2b_gemm.restype = C.c_int
@@ -124,7 +126,7 @@ _lib.bolt_probe_mfma_peak.argtypes = [_i32, _vp, C.POINTER(C.c_float)]
 _lib.bolt_probe_copy_bandwidth.restype = C.c_int
 _lib.bolt_probe_copy_bandwidth.argtypes = [_vp, _sz, _i32, _vp, C.POINTER(C.c_float)]
 
-EXPORTED = ["bolt_gemm_epilogue", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune",
+EXPORTED = ["bolt_gemm_epilogue", "bolt_gemm_epilogue_noalloc", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune",
             "bolt_gemm_epilogue_residual", "bolt_conv2d_fprop_nhwc_residual", "bolt_b2b_gemm_residual",
             "bolt_b2b_conv_residual", "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain", "bolt_tune_chain", "bolt_check_chain",
             "bolt_chain_instance_supports",
@@ -239,6 +241,14 @@ def gemm_epilogue(desc: GemmDesc, A, B, bias, D, config=None, workspace=None):
     wp, wb = _ws(workspace)
     _check(_lib.bolt_gemm_epilogue(C.byref(desc), _ptr(A), _ptr(B), _ptr(bias), _ptr(D),
                                    None if c is None else C.byref(c), wp, wb, _stream()), "bolt_gemm_epilogue")
+    return D
+
+
+def gemm_epilogue_noalloc(desc: GemmDesc, A, B, bias, D, config=None):
+    """bolt_gemm_epilogue with the split-K partial sums in the library's own fixed device array."""
+    c = _cfg(config)
+    _check(_lib.bolt_gemm_epilogue_noalloc(C.byref(desc), _ptr(A), _ptr(B), _ptr(bias), _ptr(D),
+                                           None if c is None else C.byref(c), _stream()), "bolt_gemm_epilogue_noalloc")
     return D
 
 

@@ -192,6 +192,25 @@ static const half_t* zero_bias() {
   return ptr;
 }
 
+// Split-K partial sums of bolt_gemm_epilogue_noalloc: a file-scope device array, so that entry point never
+// allocates.  Every GPU the library runs on holds its own copy (at its own address) until the process ends.
+static __device__ __align__(256) unsigned char scratch[BOLT_NOALLOC_SCRATCH_BYTES];
+
+// The array's name is a host-side stand-in, not a device address: host code only ever uses the pointer that
+// hipGetSymbolAddress returns for the current device, looked up once per device.
+static constexpr int kMaxDevices = 64;
+static void* scratch_of_current_device() {
+  static std::once_flag once[kMaxDevices];
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::call_once(once[dev], [dev] {
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) == hipSuccess) ptr[dev] = q;
+  });
+  return ptr[dev];
+}
+
 // ------------------------------------------------------------------------------------------
 // instance tables
 // ------------------------------------------------------------------------------------------
@@ -911,6 +930,26 @@ bolt_status bolt_gemm_epilogue(const bolt_gemm_desc* desc, const void* A, const 
   if (s != BOLT_OK) return s;
   pr.p.X = (const half_t*)A; pr.p.W = (const half_t*)B; pr.p.bias = (const half_t*)bias; pr.p.Y = (half_t*)D;
   return fprop_launch(tables().gemm[id], pr, swz, sk, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+bolt_status bolt_gemm_epilogue_noalloc(const bolt_gemm_desc* desc, const void* A, const void* B, const void* bias,
+                                       void* D, const bolt_config* config, void* stream) {
+  FpropProblem pr;
+  bolt_status s = make_gemm_problem(desc, &pr);
+  if (s != BOLT_OK) return s;
+  if (!A || !B || !D) return BOLT_ERR_INVALID_ARG;
+  if (!is_aligned16(A) || !is_aligned16(B) || !is_aligned16(D) || (bias && !is_aligned16(bias))) return BOLT_ERR_ALIGNMENT;
+  int id, swz, sk;
+  s = resolve_fprop(tables().gemm, pr, config, &id, &swz, &sk);
+  if (s != BOLT_OK) return s;
+  // the partial sums of this call must fit the fixed array (the same clamp of split_k as the launch applies)
+  const int nk = ceil_div(pr.p.K, tables().gemm[id].bk);
+  const int sk_eff = std::max(1, std::min(std::min(sk, kMaxSplitK), nk));
+  if (splitk_bytes(pr.p.M, pr.p.N, sk_eff) > (size_t)BOLT_NOALLOC_SCRATCH_BYTES) return BOLT_ERR_WORKSPACE;
+  void* ws = scratch_of_current_device();
+  if (!ws) return BOLT_ERR_LAUNCH;
+  pr.p.X = (const half_t*)A; pr.p.W = (const half_t*)B; pr.p.bias = (const half_t*)bias; pr.p.Y = (half_t*)D;
+  return fprop_launch(tables().gemm[id], pr, swz, sk, ws, (size_t)BOLT_NOALLOC_SCRATCH_BYTES, (hipStream_t)stream);
 }
 
 bolt_status bolt_conv2d_fprop_nhwc(const bolt_conv_desc* desc, const void* x, const void* w, const void* bias,
