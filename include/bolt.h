@@ -87,7 +87,7 @@ typedef struct {
   int32_t kernel_id;
   int32_t tile_m, tile_n, tile_k; /* workgroup tile                                              */
   int32_t waves_m, waves_n;       /* wave grid inside the workgroup (64-lane wavefronts)          */
-  int32_t mfma_shape;             /* 32 = v_mfma_f32_32x32x16_f16                                 */
+  int32_t mfma_shape;             /* 32 = v_mfma_f32_32x32x16_f16, 16 = v_mfma_f32_16x16x32_f16    */
   int32_t stages;                 /* LDS buffers in the operand pipeline                          */
   int32_t swizzle;                /* 0: n-tile fastest; g>0: XCD-aware remap, bands of g m-tiles  */
   int32_t split_k;                /* >1: K split over workgroups, FP32 partials in the workspace  */

@@ -196,6 +196,67 @@ def test_conv_every_instance_shape_sweep(bolt, case):
     assert ran >= 3
 
 
+def _pingpong_ids(bolt, op):
+    """Instances built on the 16 x 16 x 32 matrix-core instruction (the two-wave-group 256 x 256 kernel)."""
+    return [k for k in range(bolt.bolt_num_instances(op)) if bolt.bolt_instance_config(op, k).mfma_shape == 16]
+
+
+PINGPONG_CONV = [
+    # N H W C K R S stride pad: several 256-row tiles with a ragged last one, K_out ragged against 256, k-tiles that
+    # walk taps and 64-channel chunks, strides, non-square filters, windows hanging over every image edge
+    (3, 20, 20, 128, 264, 3, 3, 1, 1),
+    (2, 23, 19, 64, 136, 3, 3, 2, 1),
+    (1, 11, 12, 64, 264, 2, 4, 1, (1, 2)),
+    (5, 9, 14, 192, 512, 3, 1, (2, 1), (1, 0)),
+    (1, 40, 40, 64, 256, 1, 1, 2, 0),
+]
+
+
+@pytest.mark.parametrize("case", PINGPONG_CONV)
+def test_conv_pingpong_instance_integer_bit_exact(bolt, case):
+    N, H, W, Cc, K, R, S, stride, pad = case
+    x = wl.integer_fp16(231, 0, (N, H, W, Cc), -2, 2)
+    w = wl.integer_fp16(231, 1, (K, R, S, Cc), -1, 1)
+    bias = wl.integer_fp16(231, 2, (K,), -3, 3)
+    want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad)
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
+    ids = [k for k in _pingpong_ids(bolt, bolt.OP_CONV2D) if bolt.bolt_instance_supports(bolt.OP_CONV2D, k, d)]
+    assert ids, "no ping-pong convolution instance accepts %s" % (case,)
+    for kid in ids:
+        for swz in (0, 4):
+            _say("ping-pong conv %s instance %d swizzle %d" % (case, kid, swz))
+            got, _ = _run_conv(bolt, x, w, bias, stride, pad, config={"kernel_id": kid, "swizzle": swz})
+            assert_bit_equal(got, want, "ping-pong conv %s instance %d" % (case, kid))
+    # uniform data, every activation, alpha / beta: the elementwise bound
+    x = wl.uniform_fp16(232, 0, (N, H, W, Cc), -1, 1)
+    w = wl.uniform_fp16(232, 1, (K, R, S, Cc), -0.1, 0.1)
+    bias = wl.uniform_fp16(232, 2, (K,), -1, 1)
+    for act in ("none", "gelu"):
+        want = ref.conv2d_nhwc(x, w, bias, stride=stride, pad=pad, alpha=0.5, beta=2.0, act=act)
+        got, _ = _run_conv(bolt, x, w, bias, stride, pad, act=act, alpha=0.5, beta=2.0, config={"kernel_id": ids[0]})
+        assert_close(got, want, "ping-pong conv %s act %s" % (case, act))
+
+
+def test_gemm_pingpong_instance_integer_bit_exact_k_tails_and_split_k_refusal(bolt):
+    ids = _pingpong_ids(bolt, bolt.OP_GEMM)
+    assert ids
+    for (M, N, K) in ((700, 264, 200), (257, 520, 64), (1, 136, 8), (513, 256, 1096)):
+        A = wl.integer_fp16(233, 0, (M, K), -2, 2)
+        B = wl.integer_fp16(233, 1, (K, N), -1, 1)
+        bias = wl.integer_fp16(233, 2, (N,), -3, 3)
+        want = ref.gemm(A, B, bias)
+        d = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK)
+        for kid in [k for k in ids if bolt.bolt_instance_supports(bolt.OP_GEMM, k, d)]:
+            _say("ping-pong gemm %s instance %d" % ((M, N, K), kid))
+            got, _ = _run_gemm(bolt, A, B, bias, layout="nk", config={"kernel_id": kid, "swizzle": 4})
+            assert_bit_equal(got, want, "ping-pong gemm %s instance %d" % ((M, N, K), kid))
+            # the kernel has no partial-sum output: asking for split-K is an error, not a silent full-K run
+            ws = torch.empty(8 * M * N, dtype=torch.float32, device="cuda")
+            with pytest.raises(bolt.BoltError) as e:
+                _run_gemm(bolt, A, B, bias, layout="nk", config={"kernel_id": kid, "split_k": 2}, workspace=ws)
+            assert e.value.status == 2
+
+
 # Even channel counts that are not multiples of 8 run on the alignment-2 instances (the unpadded side of
 # Table 3): that table's geometries at a small batch, plus C = 2, a strided 1x1 and non-square strides.
 ALIGN2_SWEEP = [(2,) + row[1:7] + (1, row[7]) for row in wl.TABLE3_PADDING] + [
