@@ -65,8 +65,8 @@ struct ChainInstance {
 
 template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS>
 hipError_t launch_b2b_chain(const B2bParams& p, hipStream_t stream) {
-  static bool attr_set = false;
-  return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>, attr_set, p, p.tiles_m, 64 * NW,
+  static LdsOptIn opt_in;
+  return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>, opt_in, p, p.tiles_m, 64 * NW,
                            B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>::LDS_BYTES, stream);
 }
 

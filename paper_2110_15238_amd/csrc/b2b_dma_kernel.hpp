@@ -260,12 +260,12 @@ __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE,
 
 template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
 hipError_t launch_b2b_dma(const B2bParams& p, int /*grid*/, int lds_bytes, hipStream_t stream) {
-  static bool attr_set[2] = {false, false};
+  static LdsOptIn opt_in[2];
   // the residual epilogue is a kernel of its own (see b2b_tile_out)
   if (p.res)
-    return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, true>, attr_set[1], p, p.tiles_m, 64 * NW,
+    return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, true>, opt_in[1], p, p.tiles_m, 64 * NW,
                              lds_bytes, stream);
-  return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, false>, attr_set[0], p, p.tiles_m, 64 * NW,
+  return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, false>, opt_in[0], p, p.tiles_m, 64 * NW,
                            lds_bytes, stream);
 }
 

@@ -78,11 +78,11 @@ __global__ __launch_bounds__(64 * NW, 2) void b2b_halo_kernel(const B2bParams p)
 
 template <int BM, int NW, int N0T, int N1T, int NS, int XI>
 hipError_t launch_b2b_halo(const B2bParams& p, int /*grid*/, int lds_bytes, hipStream_t stream) {
-  static bool attr_set[2] = {false, false};
+  static LdsOptIn opt_in[2];
   if (p.res)  // the residual epilogue is a kernel of its own (see b2b_tile_out)
-    return b2b_launch_common(b2b_halo_kernel<BM, NW, N0T, N1T, NS, XI, true>, attr_set[1], p, p.tiles_m, 64 * NW, lds_bytes,
+    return b2b_launch_common(b2b_halo_kernel<BM, NW, N0T, N1T, NS, XI, true>, opt_in[1], p, p.tiles_m, 64 * NW, lds_bytes,
                              stream);
-  return b2b_launch_common(b2b_halo_kernel<BM, NW, N0T, N1T, NS, XI, false>, attr_set[0], p, p.tiles_m, 64 * NW, lds_bytes,
+  return b2b_launch_common(b2b_halo_kernel<BM, NW, N0T, N1T, NS, XI, false>, opt_in[0], p, p.tiles_m, 64 * NW, lds_bytes,
                            stream);
 }
 

@@ -384,28 +384,24 @@ struct B2bInstance {
 };
 
 template <typename KernT>
-hipError_t b2b_launch_common(KernT kern, bool& attr_set, const B2bParams& p, int grid, int nthreads, int lds_bytes,
+hipError_t b2b_launch_common(KernT kern, LdsOptIn& opt_in, const B2bParams& p, int grid, int nthreads, int lds_bytes,
                              hipStream_t stream) {
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (hipError_t e = opt_in.ensure((const void*)kern, 160 * 1024); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(nthreads), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
 template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
 hipError_t launch_b2b_rf(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
-  static bool attr_set = false;
-  return b2b_launch_common(b2b_rf_kernel<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE>, attr_set, p, grid, 64 * NWAVES,
+  static LdsOptIn opt_in;
+  return b2b_launch_common(b2b_rf_kernel<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE>, opt_in, p, grid, 64 * NWAVES,
                            lds_bytes, stream);
 }
 
 template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE>
 hipError_t launch_b2b_lds(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
-  static bool attr_set = false;
-  return b2b_launch_common(b2b_lds_kernel<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>, attr_set, p, grid,
+  static LdsOptIn opt_in;
+  return b2b_launch_common(b2b_lds_kernel<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>, opt_in, p, grid,
                            64 * WM0 * WN0, lds_bytes, stream);
 }
 

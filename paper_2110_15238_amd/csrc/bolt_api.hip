@@ -1120,6 +1120,15 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
     if (ptrs[i] && !is_aligned16(ptrs[i])) return BOLT_ERR_ALIGNMENT;
   }
 
+  if (single) {
+    // a winner found with a workspace may use split-K that a later call without one (or with a smaller one) cannot
+    // run: the largest split the workspace admits is part of the key
+    char ws_class = 1;
+    const bool have_ws = workspace && is_aligned16(workspace);
+    for (int sk = 2; sk <= kMaxSplitK; sk *= 2)
+      if (have_ws && workspace_bytes >= splitk_bytes(fp.p.M, fp.p.N, sk)) ws_class = (char)sk;
+    key.bytes.push_back(ws_class);
+  }
   {
     std::lock_guard<std::mutex> lock(tune_mutex());
     auto it = tune_cache().find(key);
@@ -1327,8 +1336,8 @@ bolt_status bolt_bias_act(void* D, const void* bias, int64_t M, int32_t N, int32
 bolt_status bolt_probe_mfma_peak(int32_t iterations, void* stream_v, float* tflops) {
   if (iterations <= 0 || !tflops) return BOLT_ERR_INVALID_ARG;
   hipStream_t stream = (hipStream_t)stream_v;
-  float* sink = nullptr;
-  if (hipMalloc(&sink, 256) != hipSuccess) return BOLT_ERR_LAUNCH;
+  float* sink = (float*)scratch_of_current_device();  // never written in practice (see mfma_peak_kernel)
+  if (!sink) return BOLT_ERR_LAUNCH;
   hipEvent_t e0, e1;
   (void)hipEventCreate(&e0);
   (void)hipEventCreate(&e1);
@@ -1340,7 +1349,6 @@ bolt_status bolt_probe_mfma_peak(int32_t iterations, void* stream_v, float* tflo
   }, 1, 3, stream, e0, e1, &ms);
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
-  (void)hipFree(sink);
   if (s != BOLT_OK) return s;
   const double flop = (double)blocks * 4 /*waves*/ * iterations * 4.0 * (2.0 * 32 * 32 * 16);
   *tflops = (float)(flop / (ms * 1e-3) / 1e12);

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 namespace bolt {
 
 typedef _Float16 half_t;
@@ -121,7 +123,7 @@ __device__ __forceinline__ float apply_act(float v, int act) {
 //   out = act(alpha * acc + beta * bias[n + e]),  converted to FP16 with round-to-nearest-even.
 // The caller never passes a null bias: without a bias the pointer addresses 8 zero halves and
 // bias_on is 0, which keeps the hot path free of branches (the loads can be scheduled early).
-// Columns beyond N read bias[0..3]; their results are never stored.
+// Columns beyond N take a zero bias; their results are never stored.
 // SLOW = false handles "none" and ReLU with a select; SLOW = true calls the transcendental
 // activations.  The choice between the two is ONE wave-uniform branch around a whole tile.
 struct EpilogueArgs {
@@ -134,7 +136,10 @@ struct EpilogueArgs {
 
 template <bool SLOW, bool RES>
 __device__ __forceinline__ half4 epilogue_quad4_impl(floatx4 a4, int n, const EpilogueArgs& ep, half4 res) {
-  const half4 hb = *(const half4*)(ep.bias + (n < ep.N ? n : 0) * ep.bias_on);
+  // columns beyond N (the zero-padded part of a compiled width) take a zero bias: their value is act(0), finite
+  // whatever beta * bias is, so a fused op that multiplies them by zero weights never sees inf * 0
+  const half4 hb_in = *(const half4*)(ep.bias + (n < ep.N ? n : 0) * ep.bias_on);
+  const half4 hb = n < ep.N ? hb_in : half4{0, 0, 0, 0};
   half4 o;
   floatx4 v;
 #pragma unroll
@@ -170,6 +175,19 @@ template <bool SLOW>
 __device__ __forceinline__ half4 epilogue_quad_res(const floatx16& acc, int q, int n, const EpilogueArgs& ep, half4 res) {
   return epilogue_quad_impl<SLOW, true>(acc, q, n, ep, res);
 }
+
+// Host side: a kernel that wants more than 64 KiB of dynamic LDS has to opt in once per process.  Every launcher
+// owns one of these per kernel; call_once makes the first launch safe from several host threads, and the
+// attribute is set before (never as part of) the first launch, so it does not matter whether that launch is
+// being captured into a graph.
+struct LdsOptIn {
+  std::once_flag once;
+  hipError_t status = hipSuccess;
+  hipError_t ensure(const void* kernel, int bytes) {
+    std::call_once(once, [&] { status = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
+    return status;
+  }
+};
 
 // Workgroup id -> output tile.  mode 0: n-tile fastest.  mode g > 0: ids are first regrouped so
 // that the ids one XCD receives (hardware deals consecutive ids round-robin over 8 XCDs, each with

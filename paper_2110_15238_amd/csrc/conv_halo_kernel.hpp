@@ -352,12 +352,8 @@ hipError_t launch_conv_halo(const FpropParams& p, hipStream_t stream) {
   // the residual epilogue is a kernel of its own (fprop_tile_out in fprop_dma_kernel.hpp)
   auto kern = p.res ? conv_halo_kernel<BM, BN, WAVES_M, WAVES_N, NS, XI, KG, true>
                     : conv_halo_kernel<BM, BN, WAVES_M, WAVES_N, NS, XI, KG, false>;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[p.res ? 1 : 0]) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set[p.res ? 1 : 0] = true;
-  }
+  static LdsOptIn opt_in[2];
+  if (hipError_t e = opt_in[p.res ? 1 : 0].ensure((const void*)kern, 160 * 1024); e != hipSuccess) return e;
   dim3 grid(p.tiles_m * p.tiles_n, 1, 1);
   hipLaunchKernelGGL(kern, grid, dim3(T_::NT), T_::lds_bytes(p), stream, p);
   return hipGetLastError();

@@ -606,12 +606,8 @@ hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
   // the residual epilogue is a kernel of its own (see fprop_tile_out)
   auto kern = p.res ? fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG, true>
                     : fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG, false>;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[p.res ? 1 : 0]) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set[p.res ? 1 : 0] = true;
-  }
+  static LdsOptIn opt_in[2];
+  if (hipError_t e = opt_in[p.res ? 1 : 0].ensure((const void*)kern, T::LDS_BYTES); e != hipSuccess) return e;
   dim3 grid(p.tiles_m * p.tiles_n, p.split_k, 1);
   hipLaunchKernelGGL(kern, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
   return hipGetLastError();

@@ -200,12 +200,8 @@ template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE
 hipError_t launch_fprop(const FpropParams& p, hipStream_t stream) {
   using T = FpropTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, WMODE>;
   auto kern = fprop_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, WMODE>;
-  static bool attr_set = false;  // opt in to more than 64 KiB of dynamic LDS once per kernel
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsOptIn opt_in;
+  if (hipError_t e = opt_in.ensure((const void*)kern, T::LDS_BYTES); e != hipSuccess) return e;
   dim3 grid(p.tiles_m * p.tiles_n, p.split_k, 1);
   hipLaunchKernelGGL(kern, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
   return hipGetLastError();

@@ -471,12 +471,8 @@ template <int XMODE, int MI = 16, int PK = 64>
 hipError_t launch_fprop_pp(const FpropParams& p, hipStream_t stream) {
   using T = FpropPpTraits;
   auto kern = p.res ? fprop_pp_kernel<XMODE, MI, PK, true> : fprop_pp_kernel<XMODE, MI, PK, false>;
-  static bool attr_set[2] = {false, false};
-  if (!attr_set[p.res ? 1 : 0]) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_set[p.res ? 1 : 0] = true;
-  }
+  static LdsOptIn opt_in[2];
+  if (hipError_t e = opt_in[p.res ? 1 : 0].ensure((const void*)kern, T::LDS_BYTES); e != hipSuccess) return e;
   // one workgroup per compute unit; 256 is a multiple of the 8 XCDs, so the tiles w, w + 256, ... of a workgroup
   // stay on the XCD that tile_of_workgroup assumes for them
   constexpr int kComputeUnits = 256;

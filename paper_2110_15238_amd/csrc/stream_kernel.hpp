@@ -276,8 +276,8 @@ __global__ __launch_bounds__(64 * NW) void stream_kernel(const B2bParams p) {
 
 template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int WMODE, int NS>
 hipError_t launch_stream(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
-  static bool attr_set = false;
-  return b2b_launch_common(stream_kernel<BM, BK, NW, N0T, N1T, XMODE, WMODE, NS>, attr_set, p, grid, 64 * NW, lds_bytes,
+  static LdsOptIn opt_in;
+  return b2b_launch_common(stream_kernel<BM, BK, NW, N0T, N1T, XMODE, WMODE, NS>, opt_in, p, grid, 64 * NW, lds_bytes,
                            stream);
 }
 

@@ -328,3 +328,116 @@ def test_conv_chain3_full_size_sampled_rows(bolt):
     want = ref.gemm(d1, np.ascontiguousarray(ws[2].reshape(C, C).T), bs[2])
     _say("conv chain tuned %s, %d rows sampled" % (cfg.as_dict(), rows.size))
     assert_close(got[rows], want, "conv chain of three at batch 32")
+
+
+# ---------------------------------------------------------------------------------------------
+# host-side robustness
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("layout", ["kn", "nk"])
+def test_b2b_padded_columns_stay_finite_with_a_huge_bias_term(bolt, layout):
+    # N0 = 40 runs on kernels compiled for 64 columns: the 24 padded columns of D0 are multiplied by zero weights
+    # in the second op.  beta0 * bias0 alone overflows FP16 in columns 0-3 (the product term brings the true value
+    # back into range), so a padded column that borrowed that bias would be inf, and inf * 0 would poison every
+    # output of its row.
+    M, K0, N0, N1 = 100, 64, 40, 64
+    A = np.full((M, K0), 30, np.float16)
+    W0 = wl.uniform_fp16(651, 0, (K0, N0), -0.01, 0.01)
+    W0[:, :4] = -36
+    b0 = wl.uniform_fp16(651, 1, (N0,), -0.001, 0.001)
+    b0[:4] = 70
+    W1 = wl.uniform_fp16(651, 2, (N0, N1), -0.05, 0.05)
+    b1 = wl.uniform_fp16(651, 3, (N1,), -1, 1)
+    want = ref.b2b_gemm(A, W0, b0, W1, b1, beta0=1000.0, act0="none", act1="none")
+    assert np.all(np.isfinite(want))
+    lay = bolt.LAYOUT_KN if layout == "kn" else bolt.LAYOUT_NK
+    W0d = dev(W0 if layout == "kn" else np.ascontiguousarray(W0.T))
+    W1d = dev(W1 if layout == "kn" else np.ascontiguousarray(W1.T))
+    g0 = bolt.gemm_desc(M, N0, K0, beta=1000.0, act="none", b_layout=lay)
+    g1 = bolt.gemm_desc(M, N1, N0, act="none", b_layout=lay)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_B2B_GEMM)):
+        if not bolt.bolt_instance_supports(bolt.OP_B2B_GEMM, kid, g0, g1):
+            continue
+        _say("padded-column b2b gemm %s instance %d" % (layout, kid))
+        D = _nan16(M, N1)
+        bolt.bolt_b2b_gemm(g0, g1, dev(A), W0d, dev(b0), W1d, dev(b1), D, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(D), want, "padded-column b2b gemm %s instance %d" % (layout, kid))
+        ran += 1
+    assert ran >= 1
+
+
+def test_tune_with_a_workspace_does_not_leak_split_k_into_a_call_without_one(bolt):
+    # a deep, narrow problem: with a workspace the search may pick split-K; the same problem tuned afterwards
+    # without a workspace must come back with a config that runs without one
+    M, N, K = 64, 64, 8192
+    A, B, bias = wl.uniform_fp16(661, 0, (M, K), -1, 1), wl.uniform_fp16(661, 1, (K, N), -1, 1), wl.uniform_fp16(661, 2, (N,), -1, 1)
+    d = bolt.gemm_desc(M, N, K)
+    Ad, Bd, bd = dev(A), dev(B), dev(bias)
+    D = _nan16(M, N)
+    ws = torch.empty(8 * M * N, dtype=torch.float32, device="cuda")
+    with_ws = bolt.bolt_tune(bolt.OP_GEMM, d, None, [Ad, Bd, bd, D], ws)
+    without = bolt.bolt_tune(bolt.OP_GEMM, d, None, [Ad, Bd, bd, D])
+    _say("with workspace: %s; without: %s" % (with_ws.config.as_dict(), without.config.as_dict()))
+    assert without.config.split_k <= 1
+    D.fill_(float("nan"))
+    bolt.bolt_gemm_epilogue(d, Ad, Bd, bd, D, without.config)
+    torch.cuda.synchronize()
+    assert_close(host(D), ref.gemm(A, B, bias), "config tuned without a workspace")
+    D.fill_(float("nan"))
+    bolt.bolt_gemm_epilogue(d, Ad, Bd, bd, D, with_ws.config, ws)
+    torch.cuda.synchronize()
+    assert_close(host(D), ref.gemm(A, B, bias), "config tuned with a workspace")
+
+
+def test_first_launch_of_a_kernel_inside_a_graph_capture():
+    # A fresh process, so that no kernel has been launched before: the very first call of each entry point happens
+    # while the stream is being captured (the opt-in to large dynamic LDS is part of that first call).  The replays
+    # must reproduce what the same calls give eagerly afterwards.
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, %r)
+import paper_2110_15238_amd as bolt
+import workloads as wl
+M, N, K = 300, 264, 200
+A = torch.from_numpy(wl.uniform_fp16(671, 0, (M, K), -1, 1)).cuda()
+B = torch.from_numpy(wl.uniform_fp16(671, 1, (N, K), -1, 1)).cuda()
+bias = torch.from_numpy(wl.uniform_fp16(671, 2, (N,), -1, 1)).cuda()
+x = torch.from_numpy(wl.uniform_fp16(671, 3, (2, 12, 12, 64), -1, 1)).cuda()
+w = torch.from_numpy(wl.uniform_fp16(671, 4, (72, 3, 3, 64), -0.1, 0.1)).cuda()
+cb = torch.from_numpy(wl.uniform_fp16(671, 5, (72,), -1, 1)).cuda()
+gd = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK)
+cd = bolt.conv_desc(2, 12, 12, 64, 72, 3, 3, 1, 1)
+kids = [k for k in range(bolt.bolt_num_instances(bolt.OP_GEMM)) if bolt.bolt_instance_supports(bolt.OP_GEMM, k, gd)]
+cids = [k for k in range(bolt.bolt_num_instances(bolt.OP_CONV2D)) if bolt.bolt_instance_supports(bolt.OP_CONV2D, k, cd)]
+outs = [torch.zeros((M, N), dtype=torch.float16, device="cuda") for _ in kids] + [torch.zeros((2, 12, 12, 72), dtype=torch.float16, device="cuda") for _ in cids]
+def calls(dst):
+    for i, k in enumerate(kids):
+        bolt.bolt_gemm_epilogue(gd, A, B, bias, dst[i], {"kernel_id": k})
+    for i, k in enumerate(cids):
+        bolt.bolt_conv2d_fprop_nhwc(cd, x, w, cb, dst[len(kids) + i], {"kernel_id": k})
+torch.cuda.synchronize()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g):
+    calls(outs)
+for rep in range(3):
+    for o in outs:
+        o.fill_(float("nan"))
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    snap = [o.clone() for o in outs]
+    eager = [torch.zeros_like(o) for o in outs]
+    calls(eager)
+    torch.cuda.synchronize()
+    for a, b in zip(snap, eager):
+        assert torch.equal(a, b), "replay %%d differs from the eager result" %% rep
+print("captured-first-launch ok: %%d gemm and %%d conv instances" %% (len(kids), len(cids)))
+""" % root
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=240)
+    _say(r.stdout[-400:] + r.stderr[-800:])
+    assert r.returncode == 0 and "captured-first-launch ok" in r.stdout
