@@ -270,8 +270,10 @@ bolt_status bolt_instance_config(bolt_op op, int32_t kernel_id, bolt_config* out
 /* Whether instance kernel_id can run the described problem (1) or not (0). */
 int32_t bolt_instance_supports(bolt_op op, int32_t kernel_id, const void* desc0, const void* desc1);
 
-/* Measured roofline denominators: runs an MFMA-only loop (returns sustained FP16 TFLOP/s) or a
- * streaming copy of `bytes` bytes between two halves of `buffer` (returns GB/s, read + write). */
+/* Measured roofline denominators: runs an MFMA-only loop of v_mfma_f32_16x16x32_f16 on pseudo-random FP16
+ * operands, `iterations` x 16 instructions per wave, 8 waves per compute unit (returns the sustained FP16 TFLOP/s
+ * under the chip's power limit), or a streaming copy of `bytes` bytes between two halves of `buffer` (returns
+ * GB/s, read + write).  Neither allocates. */
 bolt_status bolt_probe_mfma_peak(int32_t iterations, void* stream, float* tflops);
 bolt_status bolt_probe_copy_bandwidth(void* buffer, size_t bytes, int32_t repeats, void* stream, float* gbps);
 

@@ -157,22 +157,34 @@ __global__ __launch_bounds__(256) void bias_act_kernel(half_t* D, const half_t* 
   }
 }
 
-// MFMA-only loop: 4 independent accumulator chains per wave, no memory traffic.
+// MFMA-only loop, no memory traffic: the measured ceiling of the matrix pipes under the chip's power limit.
+// v_mfma_f32_16x16x32_f16 (the instruction of the ping-pong kernel) on operands that look like data: the
+// sustained rate depends on how many operand bits toggle (all-zero operands run at the nominal 2.5 PFLOP/s, random
+// halves at about 1.9-2.0 with this instruction and 1.7 with the 32 x 32 x 16 form).  Six operand registers and
+// 16 independent accumulators per wave, cycled as a 128 x 64 wave tile would use them.
 __global__ __launch_bounds__(256) void mfma_peak_kernel(float* sink, int iters) {
-  half8 a, b;
-  for (int e = 0; e < 8; ++e) {
-    a[e] = (half_t)(0.001f * (threadIdx.x + e));
-    b[e] = (half_t)(0.002f * (threadIdx.x - e));
-  }
-  floatx16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  half8 x[4], w[4];
+  unsigned z = 0x9E3779B9u * (threadIdx.x + 1) + blockIdx.x;
+  for (int i = 0; i < 4; ++i)
+    for (int e = 0; e < 8; ++e) {
+      z = z * 1664525u + 1013904223u;
+      x[i][e] = (half_t)((float)(z >> 8) * (2.f / 16777216.f) - 1.f);
+      z = z * 1664525u + 1013904223u;
+      w[i][e] = (half_t)((float)(z >> 8) * (2.f / 16777216.f) - 1.f);
+    }
+  floatx4 c[4][4];
+  for (int a = 0; a < 4; ++a)
+    for (int b = 0; b < 4; ++b) c[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
   for (int i = 0; i < iters; ++i) {
-    c0 = mfma_32x32x16(a, b, c0);
-    c1 = mfma_32x32x16(a, b, c1);
-    c2 = mfma_32x32x16(a, b, c2);
-    c3 = mfma_32x32x16(a, b, c3);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) c[a][b] = mfma_16x16x32(w[a], x[b], c[a][b]);
   }
   float s = 0.f;
-  for (int e = 0; e < 16; ++e) s += c0[e] + c1[e] + c2[e] + c3[e];
+  for (int a = 0; a < 4; ++a)
+    for (int b = 0; b < 4; ++b)
+      for (int e = 0; e < 4; ++e) s += c[a][b][e];
   if (s == 123.456f) sink[0] = s;  // keeps the loop alive; practically never true
 }
 
@@ -1350,7 +1362,7 @@ bolt_status bolt_probe_mfma_peak(int32_t iterations, void* stream_v, float* tflo
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   if (s != BOLT_OK) return s;
-  const double flop = (double)blocks * 4 /*waves*/ * iterations * 4.0 * (2.0 * 32 * 32 * 16);
+  const double flop = (double)blocks * 4 /*waves*/ * iterations * 16.0 * (2.0 * 16 * 16 * 32);
   *tflops = (float)(flop / (ms * 1e-3) / 1e12);
   return BOLT_OK;
 }
