@@ -46,11 +46,11 @@
 namespace bolt {
 
 struct FpropPpTraits {
-  static constexpr int BM = 256, BN = 256, BK = 64;
+  static constexpr int BN = 256, BK = 64;
   static constexpr int NT = 512;
-  static constexpr int WTM = 128, WTN = 64;  // group g owns rows [128 g, 128 g + 128), wave q of a group 64 columns
+  static constexpr int WTN = 64;  // wave q of a group owns 64 columns; group g owns half of the tile's rows
   static constexpr int W_STAGES = 2, X_STAGES = 3;
-  static constexpr int W_HALVES = BN * BK, X_HALVES = BM * BK;  // one stage
+  static constexpr int W_HALVES = BN * BK, X_HALVES = 256 * BK;  // one stage (an activation stage has room for 256 rows)
   static constexpr int LDS_BYTES = (W_STAGES * W_HALVES + X_STAGES * X_HALVES) * 2;
   static constexpr int CPR = BN / 8;  // 16-byte chunks per output row
   static_assert(LDS_BYTES <= 160 * 1024, "stages must fit the 160 KB LDS");
@@ -66,13 +66,17 @@ __device__ __forceinline__ void pp_static_for(F&& f, std::integer_sequence<int, 
 // PK: reduction depth of one phase, 64 (one M and one C phase per k-tile) or 32 (two of each: half the fragment
 //     registers and twice the barriers).  With two phases per tile the loads still go out in the first M phase of
 //     a tile and the waits stay where they are.
-template <int XMODE, int MI = 16, int PK = 64, bool RES = false>
+// BM: rows of the output tile, 256 or 224 (two wave groups of 128 or 112 rows).  The narrower tile exists for the
+//     tuner: 256 compute units each take whole tiles, and a problem of 6.1 rounds of 256-row tiles is 7.0 rounds of
+//     224-row tiles that are 12.5 % shorter.
+template <int XMODE, int MI = 16, int PK = 64, bool RES = false, int BM = 256>
 __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
   using T = FpropPpTraits;
   static_assert(MI == 16 || MI == 32, "matrix-core instruction");
   static_assert(PK == 32 || PK == 64, "phase depth");
   static_assert(XMODE == 0 || XMODE == 1, "row-major matrix or implicit im2col");
-  constexpr int BM = T::BM, BN = T::BN, BK = T::BK, WTM = T::WTM, WTN = T::WTN, CPR = T::CPR;
+  static_assert(BM <= 256 && (BM / 2) % MI == 0, "two wave groups of whole fragments");
+  constexpr int BN = T::BN, BK = T::BK, WTM = BM / 2, WTN = T::WTN, CPR = T::CPR;
   constexpr int FM = WTM / MI, FN = WTN / MI;  // fragments per wave tile along M and N
   constexpr int MK = MI == 32 ? 16 : 32;       // reduction depth of one instruction
   constexpr int P = BK / PK;                   // phases per k-tile
@@ -130,7 +134,7 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
 #pragma unroll
       for (int j = 0; j < L; ++j) {
         const int row = (j * 4 + wq) * 8 + lrow;
-        st[j] = row < rows_valid ? row * ld * 2 : (int)kInvalidOffset;
+        st[j] = row < rows_valid && (grp == 0 || row < BM) ? row * ld * 2 : (int)kInvalidOffset;
       }
     } else {
       const int64_t bytes = (int64_t)p.cg.H * p.cg.Wi * p.cg.C * 2 * (int64_t)(p.M / (p.cg.P * p.cg.Q));
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
 #pragma unroll
       for (int j = 0; j < L; ++j) {
         int pix0 = 0, mask = 0x3ff;
-        if (mfirst + j * 32 < p.M) {
+        if (mfirst + j * 32 < p.M && wq * 8 + lrow + j * 32 < BM) {
           const int ih0 = op * p.cg.stride_h - p.cg.pad_h, iw0 = oq * p.cg.stride_w - p.cg.pad_w;
           pix0 = (img * p.cg.H + ih0) * p.cg.Wi + iw0;
           int rows_in = 0, cols_in = 0;  // bit r: window row r inside the image; bit s: window column s inside
@@ -334,6 +338,7 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
 #pragma unroll
         for (int bb = 0; bb < BPS; ++bb) {
           const int b = sp * BPS + bb, srow = bb * MI + elr;
+          if (b >= FM) continue;  // the last sub-pass of a 112-row group holds 48 rows
           half4* slot = (half4*)(stage + srow * BN + (((nl >> 3) ^ ctile_swizzle<CPR>(srow)) << 3) + (nl & 4));
           floatx4 v;
           if constexpr (MI == 32) {
@@ -361,7 +366,7 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
         for (int i = wq; i < 32; i += 4) {
           const int srow = i * 2 + (elane >> 5);
           const int c = (elane & 31) ^ ctile_swizzle<CPR>(srow);
-          const bool ok = r_base + srow < p.M && en0 + c * 8 < p.N;
+          const bool ok = r_base + srow < p.M && sp * 64 + srow < WTM && en0 + c * 8 < p.N;
           const unsigned off = ok ? (unsigned)((srow * p.ldr + en0 + c * 8) * 2) : kInvalidOffset;
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rr, BOLT_LDS_PTR(stage + i * 2 * BN), 16, off, 0, 0, 0);
         }
@@ -377,7 +382,7 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int srow = r0 + i * 8;
-          if (r_base + srow < p.M) {
+          if (r_base + srow < p.M && sp * 64 + srow < WTM) {
             const half8 v = *(const half8*)(stage + srow * BN + ((chunk ^ ctile_swizzle<CPR>(srow)) << 3));
             __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(r_base + srow) * p.ldy + n));
           }
@@ -467,10 +472,10 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
   }
 }
 
-template <int XMODE, int MI = 16, int PK = 64>
+template <int XMODE, int MI = 16, int PK = 64, int BM = 256>
 hipError_t launch_fprop_pp(const FpropParams& p, hipStream_t stream) {
   using T = FpropPpTraits;
-  auto kern = p.res ? fprop_pp_kernel<XMODE, MI, PK, true> : fprop_pp_kernel<XMODE, MI, PK, false>;
+  auto kern = p.res ? fprop_pp_kernel<XMODE, MI, PK, true, BM> : fprop_pp_kernel<XMODE, MI, PK, false, BM>;
   static LdsOptIn opt_in[2];
   if (hipError_t e = opt_in[p.res ? 1 : 0].ensure((const void*)kern, T::LDS_BYTES); e != hipSuccess) return e;
   // one workgroup per compute unit; 256 is a multiple of the 8 XCDs, so the tiles w, w + 256, ... of a workgroup
@@ -492,10 +497,10 @@ inline int fprop_pp_lds_bytes(const FpropParams&) { return FpropPpTraits::LDS_BY
 
 // In the instance table: 8 waves as 2 (M) x 4 (N), two LDS stages of weights, three of activations (reported as 2),
 // no split-K.
-#define BOLT_FPROP_PP_INSTANCE(XMODE, MI, PK)                                                               \
+#define BOLT_FPROP_PP_INSTANCE(XMODE, MI, PK, BM)                                                           \
   {                                                                                                         \
-    "pp_256x256x64_w2x4_mi" #MI "_pk" #PK, 256, 256, 64, 2, 4, XMODE, 0, 2, bolt::FpropPpTraits::LDS_BYTES,  \
-        &bolt::launch_fprop_pp<XMODE, MI, PK>, 0, nullptr, nullptr,                                         \
+    "pp_" #BM "x256x64_w2x4_mi" #MI "_pk" #PK, BM, 256, 64, 2, 4, XMODE, 0, 2, bolt::FpropPpTraits::LDS_BYTES, \
+        &bolt::launch_fprop_pp<XMODE, MI, PK, BM>, 0, nullptr, nullptr,                                     \
         XMODE == 1 ? &bolt::fprop_pp_conv_supports : nullptr, XMODE == 1 ? &bolt::fprop_pp_lds_bytes : nullptr, 0, MI, true \
   }
 
