@@ -273,6 +273,22 @@ def conv_chain(x, ws, bs, acts, stride=1, pad=0):
     return y
 
 
+def gemm_chain_residual(A, Ws, bs, acts, C, gamma=1.0):
+    """The chain of gemm_chain with Eq. 1's full-matrix C in the epilogue of its LAST op only (Section 3.1.1: the
+    pipeline of fused ops extended, Eq. 2's C1 taken by the op that produces the stored output):
+    D_last = act_last(D_{last-1} W_last + b_last + gamma C); every earlier D_i is rounded to FP16 as if stored."""
+    D = gemm_chain(A, Ws[:-1], bs[:-1], acts[:-1])
+    return gemm_residual(D, Ws[-1], bs[-1], C, gamma=gamma, act=acts[-1])
+
+
+def conv_chain_residual(x, ws, bs, acts, res, stride=1, pad=0, gamma=1.0):
+    """conv_chain with a full residual tensor (the NHWC layout of the output) added in the last op's epilogue: a
+    bottleneck block written as one chain (1x1 or 3x3, then 1x1s, + skip connection, activation; Section 3.3)."""
+    y = conv_chain(x, ws[:-1], bs[:-1], acts[:-1], stride=stride, pad=pad)
+    assert ws[-1].shape[1:3] == (1, 1)
+    return conv2d_nhwc_residual(y, ws[-1], bs[-1], res, stride=1, pad=0, gamma=gamma, act=acts[-1])
+
+
 def nchw_to_nhwc(src, C8=None):
     """[N][C][H][W] -> [N][H][W][C8], channels C..C8-1 zero (Section 3.2.3, layout transformation + padding)."""
     src = _h(src)

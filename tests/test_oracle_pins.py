@@ -484,6 +484,42 @@ def test_chain_of_three_ops_rounds_between_ops_and_extends_b2b():
     assert np.array_equal(y.reshape(-1, 24), ref.gemm_chain(col, gw, cb, ["relu"] * 3))
 
 
+def test_chain_with_a_residual_adds_gamma_c_before_the_last_activation_only():
+    # small integers: every intermediate and the result are exact in FP16, so the chain must equal the float64
+    # expression relu(relu(relu(A W0 + b0) W1) W2 + b2 + gamma C) - the residual inside the LAST activation, scaled
+    # by gamma, and nowhere else
+    A = wl.integer_fp16(51, 0, (29, 16), -2, 2)
+    Ws = [wl.integer_fp16(51, 1, (16, 8), -1, 1), wl.integer_fp16(51, 2, (8, 8), -1, 1), wl.integer_fp16(51, 3, (8, 24), -1, 1)]
+    bs = [wl.integer_fp16(51, 4, (8,), -2, 2), None, wl.integer_fp16(51, 5, (24,), -2, 2)]
+    C = wl.integer_fp16(51, 6, (29, 24), -40, 40)
+    f = lambda a: a.astype(np.float64)
+    d0 = np.maximum(f(A) @ f(Ws[0]) + f(bs[0]), 0)
+    d1 = np.maximum(d0 @ f(Ws[1]), 0)
+    pre = d1 @ f(Ws[2]) + f(bs[2])
+    got = ref.gemm_chain_residual(A, Ws, bs, ["relu", "relu", "relu"], C, gamma=-3.0)
+    want = np.maximum(pre - 3.0 * f(C), 0)
+    assert np.abs(pre).max() + 120 < 2048 and np.array_equal(f(got), want)
+    # the residual matters, sits inside the activation (adding it after the ReLU differs), and gamma = 0 removes it
+    plain = ref.gemm_chain(A, Ws, bs, ["relu", "relu", "relu"])
+    assert not np.array_equal(got, plain)
+    assert not np.array_equal(f(got), np.maximum(pre, 0) - 3.0 * f(C))
+    assert np.array_equal(ref.gemm_chain_residual(A, Ws, bs, ["relu", "relu", "relu"], C, gamma=0.0), plain)
+    # a chain of two with a residual is the fused pair with a residual
+    assert np.array_equal(ref.gemm_chain_residual(A, Ws[:2], bs[:2], ["relu", "relu"], C[:, :8], gamma=2.0),
+                          ref.b2b_gemm_residual(A, Ws[0], bs[0], Ws[1], bs[1], C[:, :8], gamma=2.0))
+    # convolution chain with a residual == GEMM chain with a residual on the im2col of the first op
+    x = wl.integer_fp16(52, 0, (2, 6, 5, 8), -2, 2)
+    ws = [wl.integer_fp16(52, 1, (16, 3, 3, 8), -1, 1), wl.integer_fp16(52, 2, (8, 1, 1, 16), -1, 1), wl.integer_fp16(52, 3, (24, 1, 1, 8), -1, 1)]
+    cb = [wl.integer_fp16(52, 4, (16,), -2, 2), wl.integer_fp16(52, 5, (8,), -2, 2), None]
+    res = wl.integer_fp16(52, 6, (2, 3, 3, 24), -30, 30)
+    y = ref.conv_chain_residual(x, ws, cb, ["relu", "relu", "relu"], res, stride=2, pad=1, gamma=1.0)
+    col = ref.im2col(x, 3, 3, 2, 1)
+    gw = [w.reshape(w.shape[0], -1).T for w in ws]
+    assert y.shape == (2, 3, 3, 24)
+    assert np.array_equal(y.reshape(-1, 24), ref.gemm_chain_residual(col, gw, cb, ["relu"] * 3, res.reshape(-1, 24), gamma=1.0))
+    assert not np.array_equal(y, ref.conv_chain(x, ws, cb, ["relu"] * 3, stride=2, pad=1))
+
+
 # --------------------------------------------------------------------------------------------
 # epilogue activations (closed forms)
 # --------------------------------------------------------------------------------------------
