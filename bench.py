@@ -44,6 +44,8 @@ def main():
                     help="replay two captured HIP graphs per step instead of launching every op eagerly "
                          "(measured: no faster on MI355X, the default stays eager)")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold (rotating buffer sets) column of the HBM-bound rows")
+    ap.add_argument("--large-only", action="store_true",
+                    help="profiling runs: only the large-shape table (8192^3, 4096^3, the FFN GEMM, the batch-128 conv)")
     ap.add_argument("--steps-only", action="store_true",
                     help="profiling runs: only warm-up + timed steps (no per-shape table, no probes, no oracle)")
     args = ap.parse_args()
@@ -141,6 +143,53 @@ def main():
         cfg = bolt.bolt_tune(op, d0, d1, tensors, workspace).config
         cache[name] = cfg.as_dict()
         return cfg
+
+    def large_shapes_table():
+        # ------------------------------------------------------------------ large shapes (context, outside the step)
+        # The five configurations are small problems (7 GFLOP at most per launch); these two show what the
+        # same tuned templates reach when the problem fills the chip.
+        large = []
+        cfg_keys = ("kernel_id", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n", "stages", "swizzle")
+        try:
+            # 8192^3 and 4096^3 are ours (long enough for steady state); 1280 x 3072 x 768 is the FFN GEMM of
+            # the paper's epilogue-fusion experiment (Section 4.1.1)
+            for (M, N, K) in ((8192, 8192, 8192), (4096, 4096, 4096), (wl.EPILOGUE_GEMM.M, wl.EPILOGUE_GEMM.N, wl.EPILOGUE_GEMM.K)):
+                Ag = torch.randn((M, K), device="cuda", dtype=torch.float16) * 0.5
+                Bg = torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.5
+                biasg = torch.randn((N,), device="cuda", dtype=torch.float16)
+                Dg = empty(M, N)
+                gd = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK, act="relu")
+                cfg = tuned("large gemm %dx%dx%d NK" % (M, N, K), bolt.OP_GEMM, gd, None, [Ag, Bg, biasg, Dg], ws)
+                ms = timed(lambda: bolt.bolt_gemm_epilogue(gd, Ag, Bg, biasg, Dg, cfg, ws), 10 if M >= 8192 else 30)
+                large.append(dict(name="GEMM %dx%dx%d + bias + ReLU (B as [N][K])" % (M, N, K), ms=round(ms, 4),
+                                  tflops=round(2.0 * M * N * K / ms / 1e9, 1),
+                                  pct_mfma_peak=round(100 * 2.0 * M * N * K / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
+                                  config={k: cfg.as_dict()[k] for k in cfg_keys}))
+                del Ag, Bg, Dg
+            cs = wl.ConvShape(128, 56, 56, 256, 256, 3, 3, 1, 1)
+            xg = torch.randn((cs.N, cs.H, cs.W, cs.C), device="cuda", dtype=torch.float16) * 0.5
+            wg = torch.randn((cs.K, cs.R, cs.S, cs.C), device="cuda", dtype=torch.float16) * 0.05
+            bg = torch.zeros(cs.K, device="cuda", dtype=torch.float16)
+            yg = empty(cs.N, cs.P, cs.Q, cs.K)
+            cd = bolt.conv_desc(cs.N, cs.H, cs.W, cs.C, cs.K, cs.R, cs.S, cs.stride, cs.pad)
+            cfg = tuned("large conv 128x56x56x256", bolt.OP_CONV2D, cd, None, [xg, wg, bg, yg], ws)
+            ms = timed(lambda: bolt.bolt_conv2d_fprop_nhwc(cd, xg, wg, bg, yg, cfg, ws), 10)
+            large.append(dict(name="conv3x3 N=128 56x56 256->256", ms=round(ms, 4), tflops=round(cs.flops / ms / 1e9, 1),
+                              pct_mfma_peak=round(100 * cs.flops / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
+                              config={k: cfg.as_dict()[k] for k in cfg_keys}))
+            del xg, wg, yg
+        except Exception as e:  # context only
+            large.append({"error": str(e)})
+        return large
+
+
+    if args.large_only:
+        large = large_shapes_table()
+        if args.tune_cache:
+            json.dump(cache, open(args.tune_cache, "w"), indent=1)
+        print(json.dumps({"large_shapes": large, "data": "synthetic",
+                          "table_timing": "median of %d repetitions of a hip graph replay" % REPS_MEDIAN}))
+        return
 
     # ------------------------------------------------------------------ build + tune every op
     ops = []      # dicts: name, flops, bytes, run(), config
@@ -440,42 +489,7 @@ def main():
         print(json.dumps(out))
         return
 
-    # ------------------------------------------------------------------ large shapes (context, outside the step)
-    # The five configurations are small problems (7 GFLOP at most per launch); these two show what the
-    # same tuned templates reach when the problem fills the chip.
-    large = []
-    cfg_keys = ("kernel_id", "tile_m", "tile_n", "tile_k", "waves_m", "waves_n", "stages", "swizzle")
-    try:
-        # 8192^3 and 4096^3 are ours (long enough for steady state); 1280 x 3072 x 768 is the FFN GEMM of
-        # the paper's epilogue-fusion experiment (Section 4.1.1)
-        for (M, N, K) in ((8192, 8192, 8192), (4096, 4096, 4096), (wl.EPILOGUE_GEMM.M, wl.EPILOGUE_GEMM.N, wl.EPILOGUE_GEMM.K)):
-            Ag = torch.randn((M, K), device="cuda", dtype=torch.float16) * 0.5
-            Bg = torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.5
-            biasg = torch.randn((N,), device="cuda", dtype=torch.float16)
-            Dg = empty(M, N)
-            gd = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK, act="relu")
-            cfg = tuned("large gemm %dx%dx%d NK" % (M, N, K), bolt.OP_GEMM, gd, None, [Ag, Bg, biasg, Dg], ws)
-            ms = timed(lambda: bolt.bolt_gemm_epilogue(gd, Ag, Bg, biasg, Dg, cfg, ws), 10 if M >= 8192 else 30)
-            large.append(dict(name="GEMM %dx%dx%d + bias + ReLU (B as [N][K])" % (M, N, K), ms=round(ms, 4),
-                              tflops=round(2.0 * M * N * K / ms / 1e9, 1),
-                              pct_mfma_peak=round(100 * 2.0 * M * N * K / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
-                              config={k: cfg.as_dict()[k] for k in cfg_keys}))
-            del Ag, Bg, Dg
-        cs = wl.ConvShape(128, 56, 56, 256, 256, 3, 3, 1, 1)
-        xg = torch.randn((cs.N, cs.H, cs.W, cs.C), device="cuda", dtype=torch.float16) * 0.5
-        wg = torch.randn((cs.K, cs.R, cs.S, cs.C), device="cuda", dtype=torch.float16) * 0.05
-        bg = torch.zeros(cs.K, device="cuda", dtype=torch.float16)
-        yg = empty(cs.N, cs.P, cs.Q, cs.K)
-        cd = bolt.conv_desc(cs.N, cs.H, cs.W, cs.C, cs.K, cs.R, cs.S, cs.stride, cs.pad)
-        cfg = tuned("large conv 128x56x56x256", bolt.OP_CONV2D, cd, None, [xg, wg, bg, yg], ws)
-        ms = timed(lambda: bolt.bolt_conv2d_fprop_nhwc(cd, xg, wg, bg, yg, cfg, ws), 10)
-        large.append(dict(name="conv3x3 N=128 56x56 256->256", ms=round(ms, 4), tflops=round(cs.flops / ms / 1e9, 1),
-                          pct_mfma_peak=round(100 * cs.flops / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
-                          config={k: cfg.as_dict()[k] for k in cfg_keys}))
-        del xg, wg, yg
-    except Exception as e:  # context only
-        large.append({"error": str(e)})
-    out["large_shapes"] = large
+    out["large_shapes"] = large_shapes_table()
 
     # ------------------------------------------------------------------ the paper's b2b tables (context)
     # Tables 1 and 2 (Section 4.1.2): fused vs unfused on the paper's own shapes, random data.  Extents that
