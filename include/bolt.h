@@ -210,6 +210,19 @@ bolt_status bolt_b2b_gemm_chain(int32_t n_ops, const bolt_gemm_desc* const* desc
 bolt_status bolt_b2b_conv_chain(int32_t n_ops, const bolt_conv_desc* const* descs, const void* x,
                                 const void* const* weights, const void* const* biases, void* y,
                                 const bolt_config* config, void* stream);
+/* The chain with Eq. 1's full-matrix C in the epilogue of its last op (Section 3.1.1, Eq. 1-2 with C a matrix,
+ * taken by the op whose output is stored; Section 3.3's deepened blocks end in a skip connection):
+ *   D_2 = act_2(alpha_2 * D_1 . W_2 + beta_2 * bias_2 + gamma * C),  D_0, D_1 as in the plain chain.
+ * C: M x N_2 with row stride ldc (GEMM; ldc >= N_2 else BOLT_ERR_INVALID_ARG, ldc % 8 == 0 and C 16-byte
+ * aligned else BOLT_ERR_ALIGNMENT) or the output's NHWC layout (convolution); device memory, read only, it
+ * may be the output buffer.  Every chain instance has this epilogue: config, bolt_tune_chain, bolt_check_chain
+ * and bolt_chain_instance_supports are those of the plain chain.  All other arguments and errors as above. */
+bolt_status bolt_b2b_gemm_chain_residual(int32_t n_ops, const bolt_gemm_desc* const* descs, const void* A0,
+                                         const void* const* weights, const void* const* biases, const void* C,
+                                         int32_t ldc, float gamma, void* D, const bolt_config* config, void* stream);
+bolt_status bolt_b2b_conv_chain_residual(int32_t n_ops, const bolt_conv_desc* const* descs, const void* x,
+                                         const void* const* weights, const void* const* biases, const void* residual,
+                                         float gamma, void* y, const bolt_config* config, void* stream);
 /* bolt_tune for a chain: op is BOLT_OP_GEMM_CHAIN3 or BOLT_OP_CONV_CHAIN3, ptrs = {x, w0, b0, w1, b1,
  * w2, b2, y} (biases may be NULL).  Synchronises the stream; y is overwritten; nothing is cached. */
 bolt_status bolt_tune_chain(bolt_op op, int32_t n_ops, const void* const* descs, const void* const* ptrs, void* stream,

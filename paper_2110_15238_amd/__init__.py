@@ -20,6 +20,8 @@ bolt_b2b_conv_residual = binding.b2b_conv_residual
 bolt_tune = binding.tune
 bolt_b2b_gemm_chain = binding.b2b_gemm_chain
 bolt_b2b_conv_chain = binding.b2b_conv_chain
+bolt_b2b_gemm_chain_residual = binding.b2b_gemm_chain_residual
+bolt_b2b_conv_chain_residual = binding.b2b_conv_chain_residual
 bolt_tune_chain = binding.tune_chain
 bolt_check_chain = binding.check_chain
 bolt_chain_instance_supports = binding.chain_instance_supports

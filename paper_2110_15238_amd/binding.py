@@ -107,6 +107,10 @@ _lib.bolt_b2b_gemm_chain.restype = C.c_int
 _lib.bolt_b2b_gemm_chain.argtypes = [_i32, _pp, _vp, _pp, _pp, _vp, C.POINTER(BoltConfig), _vp]
 _lib.bolt_b2b_conv_chain.restype = C.c_int
 _lib.bolt_b2b_conv_chain.argtypes = [_i32, _pp, _vp, _pp, _pp, _vp, C.POINTER(BoltConfig), _vp]
+_lib.bolt_b2b_gemm_chain_residual.restype = C.c_int
+_lib.bolt_b2b_gemm_chain_residual.argtypes = [_i32, _pp, _vp, _pp, _pp, _vp, _i32, C.c_float, _vp, C.POINTER(BoltConfig), _vp]
+_lib.bolt_b2b_conv_chain_residual.restype = C.c_int
+_lib.bolt_b2b_conv_chain_residual.argtypes = [_i32, _pp, _vp, _pp, _pp, _vp, C.c_float, _vp, C.POINTER(BoltConfig), _vp]
 _lib.bolt_tune_chain.restype = C.c_int
 _lib.bolt_tune_chain.argtypes = [C.c_int, _i32, _pp, _pp, _vp, C.POINTER(BoltConfig), C.POINTER(C.c_float), C.POINTER(_i32)]
 _lib.bolt_check_chain.restype = C.c_int
@@ -128,7 +132,8 @@ _lib.bolt_probe_copy_bandwidth.argtypes = [_vp, _sz, _i32, _vp, C.POINTER(C.c_fl
 
 EXPORTED = ["bolt_gemm_epilogue", "bolt_gemm_epilogue_noalloc", "bolt_conv2d_fprop_nhwc", "bolt_b2b_gemm", "bolt_b2b_conv", "bolt_tune",
             "bolt_gemm_epilogue_residual", "bolt_conv2d_fprop_nhwc_residual", "bolt_b2b_gemm_residual",
-            "bolt_b2b_conv_residual", "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain", "bolt_tune_chain", "bolt_check_chain",
+            "bolt_b2b_conv_residual", "bolt_b2b_gemm_chain", "bolt_b2b_conv_chain",
+            "bolt_b2b_gemm_chain_residual", "bolt_b2b_conv_chain_residual", "bolt_tune_chain", "bolt_check_chain",
             "bolt_chain_instance_supports",
             "bolt_pad_channels_nhwc", "bolt_nchw_to_nhwc", "bolt_nhwc_to_nchw", "bolt_bias_act", "bolt_workspace_bytes", "bolt_check", "bolt_status_string",
             "bolt_num_instances", "bolt_instance_config", "bolt_instance_supports", "bolt_probe_mfma_peak",
@@ -348,6 +353,25 @@ def b2b_conv_chain(descs, x, weights, biases, y, config=None):
     c = _cfg(config)
     _check(_lib.bolt_b2b_conv_chain(len(descs), _desc_array(descs), _ptr(x), _ptr_array(weights), _ptr_array(biases),
                                     _ptr(y), None if c is None else C.byref(c), _stream()), "bolt_b2b_conv_chain")
+    return y
+
+
+def b2b_gemm_chain_residual(descs, A0, weights, biases, Cmat, D, gamma=1.0, ldc=None, config=None):
+    """The chain with gamma * Cmat (M x N_2, row stride ldc) added in the last op's epilogue."""
+    c = _cfg(config)
+    _check(_lib.bolt_b2b_gemm_chain_residual(len(descs), _desc_array(descs), _ptr(A0), _ptr_array(weights),
+                                             _ptr_array(biases), _ptr(Cmat), int(ldc if ldc is not None else descs[-1].N),
+                                             C.c_float(gamma), _ptr(D), None if c is None else C.byref(c), _stream()),
+           "bolt_b2b_gemm_chain_residual")
+    return D
+
+
+def b2b_conv_chain_residual(descs, x, weights, biases, residual, y, gamma=1.0, config=None):
+    c = _cfg(config)
+    _check(_lib.bolt_b2b_conv_chain_residual(len(descs), _desc_array(descs), _ptr(x), _ptr_array(weights),
+                                             _ptr_array(biases), _ptr(residual), C.c_float(gamma), _ptr(y),
+                                             None if c is None else C.byref(c), _stream()),
+           "bolt_b2b_conv_chain_residual")
     return y
 
 

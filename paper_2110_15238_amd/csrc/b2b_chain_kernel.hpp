@@ -22,7 +22,9 @@ struct B2bChainTraits {
   static int lds_bytes(int) { return LDS_BYTES; }
 };
 
-template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS>
+// RES: the last epilogue adds gamma * C, C a full M x N2 matrix (Eq. 1 with C0 a matrix, taken by the op whose output
+// is stored); its tile comes through LDS as in b2b_tile_out.
+template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS, bool RES = false>
 __global__ __launch_bounds__(64 * NW) void b2b_chain_kernel(const B2bParams p) {
   using T = B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>;
   constexpr int FM = T::FM;
@@ -53,8 +55,8 @@ __global__ __launch_bounds__(64 * NW) void b2b_chain_kernel(const B2bParams p) {
   floatx16 acc2[N2T / 32][FM];
   b2b_rf_gemm<N1T, N2T, FM>(W2s, d1, acc2, l32, g);
 
-  const EpilogueArgs ep{p.b2, p.b2_on, p.N2, p.alpha2, p.beta2, p.act2};
-  b2b_tile_out<BM, NW, N2T>(lds, acc2, ep, p.Y, p.ldy, p.M, m0, wave, tid);
+  const EpilogueArgs ep{p.b2, p.b2_on, p.N2, p.alpha2, p.beta2, p.act2, RES ? p.gamma : 0.f};
+  b2b_tile_out<BM, NW, N2T, RES>(lds, acc2, ep, p.Y, p.ldy, p.M, m0, wave, tid, p.res, p.ldr);
 }
 
 struct ChainInstance {
@@ -65,9 +67,13 @@ struct ChainInstance {
 
 template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS>
 hipError_t launch_b2b_chain(const B2bParams& p, hipStream_t stream) {
-  static LdsOptIn opt_in;
-  return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>, opt_in, p, p.tiles_m, 64 * NW,
-                           B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>::LDS_BYTES, stream);
+  static LdsOptIn opt_in[2];
+  constexpr int kLds = B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>::LDS_BYTES;
+  if (p.res)  // the residual epilogue is a kernel of its own (see b2b_tile_out)
+    return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS, true>, opt_in[1], p, p.tiles_m,
+                             64 * NW, kLds, stream);
+  return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS, false>, opt_in[0], p, p.tiles_m,
+                           64 * NW, kLds, stream);
 }
 
 #define BOLT_B2B_CHAIN_INSTANCE(BM, BK, NW, N0T, N1T, N2T, NS, XMODE)                                          \

@@ -1225,9 +1225,11 @@ static bolt_status chain_bind(B2bProblem* pr, const void* const* ptrs) {
   return BOLT_OK;
 }
 
+// res: null for the plain chain; else the full matrix of the last epilogue with row stride ldr (0: the last op's N)
 static bolt_status chain_call(bolt_op op, int32_t n_ops, const void* const* descs, const void* x,
                               const void* const* weights, const void* const* biases, void* y, const bolt_config* config,
-                              void* stream) {
+                              void* stream, bool with_res = false, const void* res = nullptr, int32_t ldr = 0,
+                              float gamma = 0.f) {
   B2bProblem pr;
   bolt_status s = make_chain_problem(op, n_ops, descs, &pr);
   if (s != BOLT_OK) return s;
@@ -1235,6 +1237,14 @@ static bolt_status chain_call(bolt_op op, int32_t n_ops, const void* const* desc
   const void* ptrs[8] = {x, weights[0], biases ? biases[0] : nullptr, weights[1], biases ? biases[1] : nullptr,
                          weights[2], biases ? biases[2] : nullptr, y};
   if ((s = chain_bind(&pr, ptrs)) != BOLT_OK) return s;
+  if (with_res) {
+    if (!res) return BOLT_ERR_INVALID_ARG;
+    if (ldr == 0) ldr = pr.p.N2;
+    if (ldr < pr.p.N2) return BOLT_ERR_INVALID_ARG;
+    if ((ldr & 7) || !is_aligned16(res)) return BOLT_ERR_ALIGNMENT;
+    if (ldr > (1 << 21)) return BOLT_ERR_UNSUPPORTED;
+    pr.p.res = (const half_t*)res; pr.p.ldr = ldr; pr.p.gamma = gamma;
+  }
   const auto& tab = op == BOLT_OP_GEMM_CHAIN3 ? tables().gemm_chain : tables().conv_chain;
   int id;
   if ((s = resolve_chain(tab, pr, config, &id)) != BOLT_OK) return s;
@@ -1251,6 +1261,21 @@ bolt_status bolt_b2b_conv_chain(int32_t n_ops, const bolt_conv_desc* const* desc
                                 const void* const* weights, const void* const* biases, void* y,
                                 const bolt_config* config, void* stream) {
   return chain_call(BOLT_OP_CONV_CHAIN3, n_ops, (const void* const*)descs, x, weights, biases, y, config, stream);
+}
+
+bolt_status bolt_b2b_gemm_chain_residual(int32_t n_ops, const bolt_gemm_desc* const* descs, const void* A0,
+                                         const void* const* weights, const void* const* biases, const void* C,
+                                         int32_t ldc, float gamma, void* D, const bolt_config* config, void* stream) {
+  if (ldc <= 0) return BOLT_ERR_INVALID_ARG;
+  return chain_call(BOLT_OP_GEMM_CHAIN3, n_ops, (const void* const*)descs, A0, weights, biases, D, config, stream, true,
+                    C, ldc, gamma);
+}
+
+bolt_status bolt_b2b_conv_chain_residual(int32_t n_ops, const bolt_conv_desc* const* descs, const void* x,
+                                         const void* const* weights, const void* const* biases, const void* residual,
+                                         float gamma, void* y, const bolt_config* config, void* stream) {
+  return chain_call(BOLT_OP_CONV_CHAIN3, n_ops, (const void* const*)descs, x, weights, biases, y, config, stream, true,
+                    residual, 0, gamma);
 }
 
 bolt_status bolt_tune_chain(bolt_op op, int32_t n_ops, const void* const* descs, const void* const* ptrs, void* stream_v,

@@ -956,6 +956,99 @@ def test_gemm_chain3_integer_bit_exact(bolt):
     assert_bit_equal(host(D), want, "integer gemm chain")
 
 
+@pytest.mark.parametrize("shape", [GEMM_CHAINS[0], GEMM_CHAINS[2], GEMM_CHAINS[3], GEMM_CHAINS[6]])
+def test_gemm_chain3_residual_every_instance(bolt, shape):
+    """Eq. 1 with a full matrix C in the last epilogue of a chain: strided C (ldc > N2), gamma != 1, every instance."""
+    M, K0, N0, N1, N2 = shape
+    A = wl.uniform_fp16(311, 0, (M, K0), -0.5, 0.5)
+    Ws = [wl.uniform_fp16(311, 1, (K0, N0), -0.5, 0.5), wl.uniform_fp16(311, 2, (N0, N1), -0.5, 0.5),
+          wl.uniform_fp16(311, 3, (N1, N2), -0.5, 0.5)]
+    bs = [wl.uniform_fp16(311, 4, (N0,), -1, 1), None, wl.uniform_fp16(311, 6, (N2,), -1, 1)]
+    ldc = N2 + 16
+    Cfull = wl.uniform_fp16(311, 7, (M, ldc), -3, 3)
+    acts = ["relu", "gelu", "relu"]
+    want = ref.gemm_chain_residual(A, Ws, bs, acts, np.ascontiguousarray(Cfull[:, :N2]), gamma=-0.75)
+    assert not np.array_equal(want, ref.gemm_chain(A, Ws, bs, acts))
+    descs = [bolt.gemm_desc(M, N0, K0, act=acts[0], b_layout=bolt.LAYOUT_NK),
+             bolt.gemm_desc(M, N1, N0, act=acts[1], b_layout=bolt.LAYOUT_NK),
+             bolt.gemm_desc(M, N2, N1, act=acts[2], b_layout=bolt.LAYOUT_NK)]
+    Wd = [dev(np.ascontiguousarray(W.T)) for W in Ws]
+    bd = [dev(b) for b in bs]
+    Cd = dev(Cfull)
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_GEMM_CHAIN3)):
+        if not bolt.bolt_chain_instance_supports(bolt.OP_GEMM_CHAIN3, kid, descs):
+            continue
+        _say("gemm chain residual %s instance %d" % (shape, kid))
+        D = torch.full((M, N2), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_b2b_gemm_chain_residual(descs, dev(A), Wd, bd, Cd, D, gamma=-0.75, ldc=ldc, config={"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(D), want, "gemm chain residual %s instance %d" % (shape, kid))
+        ran += 1
+    assert ran >= 1
+    # the residual may be the output buffer (each element is read before it is written, by the same workgroup)
+    D = dev(np.ascontiguousarray(Cfull[:, :N2]))
+    bolt.bolt_b2b_gemm_chain_residual(descs, dev(A), Wd, bd, D, D, gamma=-0.75)
+    torch.cuda.synchronize()
+    assert_close(host(D), want, "gemm chain residual %s in place" % (shape,))
+    # argument errors: a missing C, a row stride below N2, a misaligned one
+    D2 = torch.empty((M, N2), dtype=torch.float16, device="cuda")
+    for kwargs, C_arg in [(dict(ldc=N2 - 8), Cd), (dict(ldc=N2 + 4), Cd), (dict(), None)]:
+        with pytest.raises(bolt.BoltError):
+            bolt.bolt_b2b_gemm_chain_residual(descs, dev(A), Wd, bd, C_arg, D2, gamma=1.0, **kwargs)
+
+
+@pytest.mark.parametrize("shape", [CONV_CHAINS[0], CONV_CHAINS[1], CONV_CHAINS[3]])
+def test_conv_chain3_residual_every_instance(bolt, shape):
+    N, H, W, Cc, K0, R, S, stride, pad, K1, K2 = shape
+    x = wl.uniform_fp16(312, 0, (N, H, W, Cc), -1, 1)
+    ws = [wl.normal_fp16(312, 1, (K0, R, S, Cc), (2.0 / (R * S * Cc)) ** 0.5), wl.normal_fp16(312, 2, (K1, 1, 1, K0), (2.0 / K0) ** 0.5),
+          wl.normal_fp16(312, 3, (K2, 1, 1, K1), (2.0 / K1) ** 0.5)]
+    bs = [wl.uniform_fp16(312, 4, (K0,), -1, 1), wl.uniform_fp16(312, 5, (K1,), -1, 1), None]
+    acts = ["relu", "relu", "relu"]
+    d0 = bolt.conv_desc(N, H, W, Cc, K0, R, S, stride, pad, act=acts[0])
+    P, Q = bolt.conv_out_hw(d0)
+    res = wl.uniform_fp16(312, 7, (N, P, Q, K2), -2, 2)
+    want = ref.conv_chain_residual(x, ws, bs, acts, res, stride=stride, pad=pad, gamma=1.0)
+    assert not np.array_equal(want, ref.conv_chain(x, ws, bs, acts, stride=stride, pad=pad))
+    descs = [d0, bolt.conv_desc(N, P, Q, K0, K1, 1, 1, 1, 0, act=acts[1]), bolt.conv_desc(N, P, Q, K1, K2, 1, 1, 1, 0, act=acts[2])]
+    wd, bd = [dev(w) for w in ws], [dev(b) for b in bs]
+    ran = 0
+    for kid in range(bolt.bolt_num_instances(bolt.OP_CONV_CHAIN3)):
+        if not bolt.bolt_chain_instance_supports(bolt.OP_CONV_CHAIN3, kid, descs):
+            continue
+        _say("conv chain residual %s instance %d" % (shape, kid))
+        y = torch.full((N, P, Q, K2), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_b2b_conv_chain_residual(descs, dev(x), wd, bd, dev(res), y, gamma=1.0, config={"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(y), want, "conv chain residual %s instance %d" % (shape, kid))
+        ran += 1
+    assert ran >= 1
+
+
+def test_gemm_chain3_residual_integer_bit_exact(bolt):
+    M, K0, N0, N1, N2 = 300, 72, 64, 64, 120
+    A = wl.integer_fp16(313, 0, (M, K0), -2, 2)
+    Ws = [wl.integer_fp16(313, 1, (K0, N0), -1, 1), wl.integer_fp16(313, 2, (N0, N1), -1, 1), wl.integer_fp16(313, 3, (N1, N2), -1, 1)]
+    for W in Ws:
+        W[np.arange(W.shape[0])[:, None] % 4 != np.arange(W.shape[1])[None, :] % 4] = 0
+    bs = [wl.integer_fp16(313, 4, (N0,), -2, 2), wl.integer_fp16(313, 5, (N1,), -2, 2), wl.integer_fp16(313, 6, (N2,), -2, 2)]
+    Cm = wl.integer_fp16(313, 7, (M, N2), -50, 50)
+    want = ref.gemm_chain_residual(A, Ws, bs, ["relu", "relu", "relu"], Cm, gamma=2.0)
+    assert np.abs(want.astype(np.float64)).max() < 2048
+    descs = [bolt.gemm_desc(M, N0, K0, b_layout=bolt.LAYOUT_NK), bolt.gemm_desc(M, N1, N0, b_layout=bolt.LAYOUT_NK),
+             bolt.gemm_desc(M, N2, N1, b_layout=bolt.LAYOUT_NK)]
+    Wd, bd = [dev(np.ascontiguousarray(W.T)) for W in Ws], [dev(b) for b in bs]
+    for kid in range(bolt.bolt_num_instances(bolt.OP_GEMM_CHAIN3)):
+        if not bolt.bolt_chain_instance_supports(bolt.OP_GEMM_CHAIN3, kid, descs):
+            continue
+        _say("integer gemm chain residual instance %d" % kid)
+        D = torch.empty((M, N2), dtype=torch.float16, device="cuda")
+        bolt.bolt_b2b_gemm_chain_residual(descs, dev(A), Wd, bd, dev(Cm), D, gamma=2.0, config={"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_bit_equal(host(D), want, "integer gemm chain residual instance %d" % kid)
+
+
 @pytest.mark.parametrize("act", ["none", "relu", "gelu", "hardswish", "softplus"])
 def test_bias_act_standalone_epilogue(bolt, act):
     # several grid strides plus a ragged last block; with and without a bias; also M = 1 and M = 0
