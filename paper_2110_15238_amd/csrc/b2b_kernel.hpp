@@ -83,9 +83,11 @@ __device__ __forceinline__ void b2b_preload_weights(const B2bParams& p, half_t* 
 }
 
 // Epilogue of op1 for accumulators in the transposed MFMA layout, direct 8-byte stores.
-template <int FN, int FM>
+// RES: Eq. 1 with a full matrix C - each lane first reads the quad of C it is about to overwrite in D (8-byte loads of
+// the same shape as the stores; C may be the output buffer), p.gamma scales it.
+template <int FN, int FM, bool RES = false>
 __device__ __forceinline__ void b2b_store_tile(const B2bParams& p, floatx16 (&acc)[FN][FM], int mrow, int ncol) {
-  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1};
+  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
   auto store_tile = [&](auto slow) {
 #pragma unroll
     for (int a = 0; a < FN; ++a)
@@ -95,8 +97,16 @@ __device__ __forceinline__ void b2b_store_tile(const B2bParams& p, floatx16 (&ac
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
           const int m = mrow + b * 32;
-          const half4 o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n, ep);
-          if (n < p.N1 && m < p.M) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
+          const bool ok = n < p.N1 && m < p.M;
+          half4 o;
+          if constexpr (RES) {
+            half4 c = {0, 0, 0, 0};
+            if (ok) c = *(const half4*)(p.res + (int64_t)m * p.ldr + n);
+            o = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n, ep, c);
+          } else {
+            o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n, ep);
+          }
+          if (ok) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
         }
       }
   };
@@ -151,7 +161,7 @@ struct B2bRfTraits {
   }
 };
 
-template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
+template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE, bool RES = false>
 __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) {
   using T = B2bRfTraits<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE>;
   constexpr int NT = T::NT, WTM = T::WTM, FM = T::FM, FN0 = T::FN0, FN1 = T::FN1, NC1 = T::NC1;
@@ -238,7 +248,7 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
           for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(wf, d0[t][b], acc1[a][b]);
         }
       }
-      b2b_store_tile<NC1, FM>(p, acc1, mrow, c1 * NC1 * 32 + g * 4);
+      b2b_store_tile<NC1, FM, RES>(p, acc1, mrow, c1 * NC1 * 32 + g * 4);
     }
   }
 }
@@ -256,7 +266,7 @@ struct B2bLdsTraits {
   }
 };
 
-template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE>
+template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE, bool RES = false>
 __global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams p) {
   using T = B2bLdsTraits<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>;
   constexpr int NT = T::NT, FM0 = T::FM0, FN0 = T::FN0, FM1 = T::FM1, FN1 = T::FN1;
@@ -366,7 +376,7 @@ __global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams
           for (int b = 0; b < FM1; ++b) acc1[a][b] = mfma_32x32x16(wf[a], xf[b], acc1[a][b]);
       }
     }
-    b2b_store_tile<FN1, FM1>(p, acc1, m0 + wm1 * WTM1 + l32, wn1 * WTN1 + g * 4);
+    b2b_store_tile<FN1, FM1, RES>(p, acc1, m0 + wm1 * WTM1 + l32, wn1 * WTN1 + g * 4);
   }
 }
 
@@ -393,15 +403,21 @@ hipError_t b2b_launch_common(KernT kern, LdsOptIn& opt_in, const B2bParams& p, i
 
 template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
 hipError_t launch_b2b_rf(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
-  static LdsOptIn opt_in;
-  return b2b_launch_common(b2b_rf_kernel<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE>, opt_in, p, grid, 64 * NWAVES,
+  static LdsOptIn opt_in[2];
+  if (p.res)  // the residual epilogue is a kernel of its own (see b2b_store_tile)
+    return b2b_launch_common(b2b_rf_kernel<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE, true>, opt_in[1], p, grid, 64 * NWAVES,
+                             lds_bytes, stream);
+  return b2b_launch_common(b2b_rf_kernel<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE, false>, opt_in[0], p, grid, 64 * NWAVES,
                            lds_bytes, stream);
 }
 
 template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE>
 hipError_t launch_b2b_lds(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
-  static LdsOptIn opt_in;
-  return b2b_launch_common(b2b_lds_kernel<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>, opt_in, p, grid,
+  static LdsOptIn opt_in[2];
+  if (p.res)
+    return b2b_launch_common(b2b_lds_kernel<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE, true>, opt_in[1], p, grid,
+                             64 * WM0 * WN0, lds_bytes, stream);
+  return b2b_launch_common(b2b_lds_kernel<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE, false>, opt_in[0], p, grid,
                            64 * WM0 * WN0, lds_bytes, stream);
 }
 
@@ -409,14 +425,14 @@ hipError_t launch_b2b_lds(const B2bParams& p, int grid, int lds_bytes, hipStream
   {                                                                                                      \
     "rf_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T, 0, BM, BK, NW, 1, N0T, N1T, XMODE, WMODE, 64 * NW, 2,  \
         &bolt::B2bRfTraits<BM, BK, NW, N0T, N1T, XMODE, WMODE>::lds_bytes,                                \
-        &bolt::launch_b2b_rf<BM, BK, NW, N0T, N1T, XMODE, WMODE>                                          \
+        &bolt::launch_b2b_rf<BM, BK, NW, N0T, N1T, XMODE, WMODE>, nullptr, nullptr, true                  \
   }
 #define BOLT_B2B_LDS_INSTANCE(BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE)                          \
   {                                                                                                      \
     "lds_" #BM "x" #BK "_w" #WM0 "x" #WN0 "_" #WM1 "x" #WN1 "_n" #N0T "_" #N1T, 1, BM, BK, WM0, WN0, N0T, \
         N1T, XMODE, WMODE, 64 * WM0 * WN0, 2,                                                            \
         &bolt::B2bLdsTraits<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>::lds_bytes,               \
-        &bolt::launch_b2b_lds<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>                         \
+        &bolt::launch_b2b_lds<BM, BK, WM0, WN0, WM1, WN1, N0T, N1T, XMODE, WMODE>, nullptr, nullptr, true \
   }
 
 }  // namespace bolt

@@ -846,6 +846,38 @@ def test_b2b_conv_residual_every_instance_and_tuner(bolt, shape):
         assert e.value.status == 2
 
 
+@pytest.mark.parametrize("shape", [(1000, 72, 64, 128), (333, 256, 64, 16), (129, 64, 32, 96)])
+def test_b2b_gemm_residual_row_major_weights_every_instance(bolt, shape):
+    """Weights stored [K][N] run on the weights-resident kernels only; their residual epilogue reads C straight from
+    global memory.  Closeness on fractions with a strided C, bit-exactness on small integers, every instance."""
+    M, K0, N0, N1 = shape
+    g0, g1 = bolt.gemm_desc(M, N0, K0), bolt.gemm_desc(M, N1, N0)
+    ids = [k for k in range(bolt.bolt_num_instances(bolt.OP_B2B_GEMM_RES)) if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM_RES, k, g0, g1)]
+    assert ids, "no instance for %s" % (shape,)
+    A, W0 = wl.uniform_fp16(415, 0, (M, K0), -0.5, 0.5), wl.uniform_fp16(415, 1, (K0, N0), -0.5, 0.5)
+    b0, W1 = wl.uniform_fp16(415, 2, (N0,), -0.5, 0.5), wl.uniform_fp16(415, 3, (N0, N1), -0.5, 0.5)
+    b1, Cfull = wl.uniform_fp16(415, 4, (N1,), -0.5, 0.5), wl.uniform_fp16(415, 5, (M, N1 + 24), -4, 4)
+    want = ref.b2b_gemm_residual(A, W0, b0, W1, b1, np.ascontiguousarray(Cfull[:, :N1]), gamma=0.5)
+    Ai, W0i = wl.integer_fp16(416, 0, (M, K0), -2, 2), wl.integer_fp16(416, 1, (K0, N0), -1, 1)
+    W1i = wl.integer_fp16(416, 3, (N0, N1), -1, 1)
+    for Wm in (W0i, W1i):  # sparse, so that every intermediate stays exactly representable
+        Wm[np.arange(Wm.shape[0])[:, None] % 4 != np.arange(Wm.shape[1])[None, :] % 4] = 0
+    b0i, b1i = wl.integer_fp16(416, 2, (N0,), -2, 2), wl.integer_fp16(416, 4, (N1,), -2, 2)
+    Ci = wl.integer_fp16(416, 5, (M, N1), -9, 9)
+    want_i = ref.b2b_gemm_residual(Ai, W0i, b0i, W1i, b1i, Ci, gamma=-3.0)
+    assert np.abs(want_i.astype(np.float64)).max() < 2048
+    for kid in ids:
+        _say("b2b gemm residual [K][N] %s instance %d" % (shape, kid))
+        D = torch.full((M, N1), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_b2b_gemm_residual(g0, g1, dev(A), dev(W0), dev(b0), dev(W1), dev(b1), dev(Cfull), D, 0.5, {"kernel_id": kid})  # ldc = N1 + 24
+        torch.cuda.synchronize()
+        assert_close(host(D), want, "b2b gemm residual [K][N] %s instance %d" % (shape, kid))
+        D = dev(Ci).clone()  # in place
+        bolt.bolt_b2b_gemm_residual(g0, g1, dev(Ai), dev(W0i), dev(b0i), dev(W1i), dev(b1i), D, D, -3.0, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_bit_equal(host(D), want_i, "integer b2b gemm residual [K][N] %s instance %d" % (shape, kid))
+
+
 def test_b2b_residual_integer_bit_exact(bolt):
     M, K0, N0, N1 = 300, 64, 32, 96
     A, W0 = wl.integer_fp16(407, 0, (M, K0), -2, 2), wl.integer_fp16(407, 1, (K0, N0), -1, 1)
