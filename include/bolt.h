@@ -103,14 +103,24 @@ typedef struct {
   int32_t b_layout;      /* bolt_layout                                                           */
 } bolt_gemm_desc;
 
+/* Layout of a convolution's input tensor in memory (Section 3.2.3, Layout transformation). */
+typedef enum {
+  BOLT_TENSOR_NHWC = 0, /* [N][H][W][C], channels contiguous: what every kernel computes in          */
+  BOLT_TENSOR_NCHW = 1  /* [N][C][H][W]: accepted for the input of a first layer (C <= 4), whose    */
+                        /* loader reads it in place - no bolt_nchw_to_nhwc pass, no padded copy      */
+} bolt_tensor_layout;
+
 /* y[N,P,Q,K] = act(alpha * conv(x[N,H,W,C], w[K,R,S,C]) + beta * bias[K]); cross-correlation,
- * zero padding, P = (H + 2 pad_h - R) / stride_h + 1 (floor), Q likewise; dilation 1, groups 1. */
+ * zero padding, P = (H + 2 pad_h - R) / stride_h + 1 (floor), Q likewise; dilation 1, groups 1.
+ * x_layout: bolt_tensor_layout of x (0 = NHWC; a zero-initialised descriptor keeps the default).
+ * The weights are always [K][R][S][C], the output always NHWC. */
 typedef struct {
   int32_t N, H, W, C;
   int32_t K, R, S;
   int32_t stride_h, stride_w, pad_h, pad_w;
   float alpha, beta;
-  int32_t act; /* bolt_act */
+  int32_t act;      /* bolt_act */
+  int32_t x_layout; /* bolt_tensor_layout */
 } bolt_conv_desc;
 
 /* GEMM + fused epilogue (Section 2.2 tiling; Section 3.1 epilogue fusion patterns (i)-(iii)).
@@ -121,7 +131,11 @@ bolt_status bolt_gemm_epilogue(const bolt_gemm_desc* desc, const void* A, const 
 
 /* Implicit-GEMM NHWC forward convolution + fused epilogue (Section 3.2.3: NHWC only; workloads of
  * Section 4.1.1).  x: N*H*W*C, w: K*R*S*C, bias: K halves or NULL, y: N*P*Q*K.  Requires K a
- * multiple of 8 and C even; C a multiple of 8 for the fast (128-bit) kernels. */
+ * multiple of 8.  C a multiple of 8: the fast (128-bit) kernels; another even C: the alignment-2
+ * kernels (Table 3's "unpadded" side); C <= 4 of either parity, e.g. the 3 colour planes of a first
+ * layer: the first-layer kernels, which read x without channel padding and, with
+ * desc->x_layout = BOLT_TENSOR_NCHW, in NCHW (they need R * C <= 24, S <= 8, stride_w <= 2, else
+ * BOLT_ERR_UNSUPPORTED; an odd C > 4 is BOLT_ERR_ALIGNMENT: pad it with bolt_pad_channels_nhwc). */
 bolt_status bolt_conv2d_fprop_nhwc(const bolt_conv_desc* desc, const void* x, const void* w, const void* bias,
                                    void* y, const bolt_config* config, void* workspace, size_t workspace_bytes,
                                    void* stream);

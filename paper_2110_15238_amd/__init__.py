@@ -5,7 +5,7 @@ The Python layer only marshals arguments; importing it fails if the HIP library 
 """
 from . import binding
 from .binding import (ACT, LAYOUT_KN, LAYOUT_NK, OP_B2B_CONV, OP_B2B_CONV_RES, OP_B2B_GEMM, OP_B2B_GEMM_RES, OP_CONV2D, OP_CONV_CHAIN3, OP_GEMM, OP_GEMM_CHAIN3, BoltConfig, BoltError,
-                      ConvDesc, GemmDesc, TuneResult, conv_desc, conv_out_hw, gemm_desc)
+                      ConvDesc, GemmDesc, TENSOR_NCHW, TENSOR_NHWC, TuneResult, conv_desc, conv_out_hw, gemm_desc)
 
 # the C ABI's entry points under their own names
 bolt_gemm_epilogue = binding.gemm_epilogue

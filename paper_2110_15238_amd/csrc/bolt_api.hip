@@ -240,6 +240,7 @@ struct Tables {
     register_conv_halo_instances(conv);
     register_gemm_nk_instances(conv);  // for 1x1 / stride 1 / pad 0 filters
     register_conv_align2_instances(conv);  // even channel counts that are not multiples of 8
+    register_conv_smallc_instances(conv);  // first layers: at most 4 channels, unpadded NHWC or NCHW
     register_b2b_gemm_instances(b2b_gemm);
     register_b2b_gemm_stream_instances(b2b_gemm);
     register_b2b_gemm_dma_instances(b2b_gemm);
@@ -284,8 +285,11 @@ static bolt_status check_conv_desc(const bolt_conv_desc* d, ConvDims* out) {
   if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return BOLT_ERR_INVALID_ARG;
   if (!valid_act(d->act)) return BOLT_ERR_INVALID_ARG;
   if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return BOLT_ERR_INVALID_ARG;
-  // C % 8 == 0 is the fast path (128-bit accesses); an even C runs on the alignment-2 instances
-  if ((d->K & 7) || (d->C & 1)) return BOLT_ERR_ALIGNMENT;
+  if (d->x_layout != BOLT_TENSOR_NHWC && d->x_layout != BOLT_TENSOR_NCHW) return BOLT_ERR_INVALID_ARG;
+  // C % 8 == 0 is the fast path (128-bit accesses); an even C runs on the alignment-2 instances; C <= 4 (any
+  // parity, either input layout) on the first-layer instances
+  if ((d->K & 7) || ((d->C & 1) && d->C > 4)) return BOLT_ERR_ALIGNMENT;
+  if (d->x_layout == BOLT_TENSOR_NCHW && d->C > 4) return BOLT_ERR_UNSUPPORTED;
   const int64_t P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
   const int64_t Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
   const int64_t M = (int64_t)d->N * P * Q;
@@ -345,6 +349,12 @@ struct FpropProblem {
 };
 
 static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
+  if (in.xmode == 4) {
+    // first-layer kernels: at most 4 channels of any parity, NHWC or NCHW input, weights [K][R][S][C] as they are; no
+    // residual epilogue.  The geometry test is the instance's own.
+    const bool small_nhwc = pr.xmode == 2 && pr.p.cg.C <= 4;
+    return (pr.xmode == 4 || small_nhwc) && !pr.residual && in.dyn_supports(pr.p);
+  }
   if (in.wmode != pr.wmode) return false;
   if (in.xmode == 3) {
     // filter-row gather: a whole filter row of one output pixel (S*C halves) fits one k-tile
@@ -488,6 +498,9 @@ static bolt_status make_conv_problem(const bolt_conv_desc* d, FpropProblem* pr) 
     p.ldx = d->C;
   }
   if (d->C & 7) pr->xmode = pr->wmode = 2;  // alignment 2 (Section 3.2.3): the unpadded kernels
+  // odd channel counts and NCHW inputs: only the first-layer instances (which also take C = 2 and 4 from NHWC)
+  if ((d->C & 1) || d->x_layout == BOLT_TENSOR_NCHW) pr->xmode = 4;
+  p.x_nchw = d->x_layout == BOLT_TENSOR_NCHW ? 1 : 0;
   return BOLT_OK;
 }
 

@@ -39,7 +39,8 @@ struct FpropParams {
   int act;
   int tiles_m, tiles_n, swizzle;
   int split_k, ktiles_per_split;
-  ConvGeom cg;  // XMODE 1 only
+  ConvGeom cg;  // convolutions only
+  int x_nchw;   // x mode 4 only: the input is [N][C][H][W]
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>

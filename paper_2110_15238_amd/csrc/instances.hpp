@@ -12,6 +12,7 @@
 #include "b2b_dma_kernel.hpp"
 #include "b2b_kernel.hpp"
 #include "conv_halo_kernel.hpp"
+#include "conv_smallc_kernel.hpp"
 #include "b2b_chain_kernel.hpp"
 #include "b2b_halo_kernel.hpp"
 #include "fprop_dma_kernel.hpp"
@@ -131,6 +132,7 @@ void register_conv_instances(std::vector<FpropInstance>& v);
 void register_conv_stream_instances(std::vector<FpropInstance>& v);
 void register_conv_halo_instances(std::vector<FpropInstance>& v);
 void register_conv_align2_instances(std::vector<FpropInstance>& v);
+void register_conv_smallc_instances(std::vector<FpropInstance>& v);
 void register_b2b_gemm_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_instances(std::vector<B2bInstance>& v);
 void register_b2b_gemm_stream_instances(std::vector<B2bInstance>& v);

@@ -894,6 +894,98 @@ def test_b2b_residual_integer_bit_exact(bolt):
 
 
 # ---------------------------------------------------------------------------------------------
+# first layers: at most 4 input channels, unpadded NHWC or NCHW input (Section 3.2.3 folded into the loader)
+# ---------------------------------------------------------------------------------------------
+FIRST_LAYERS = [
+    # N H W C K R S stride pad
+    (2, 40, 300, 3, 64, 7, 7, 2, 3),          # the stem's filter; Q = 150: two column tiles, the second ragged
+    (1, 23, 23, 3, 72, 7, 7, 2, 3),           # two channel tiles, the second 8 wide
+    (2, 17, 19, 3, 64, 3, 3, 1, 1),           # stride 1 (2-byte fragment reads), 9 planes
+    (1, 16, 140, 3, 32, 3, 3, 1, 1),          # stride 1, Q = 140: two column tiles
+    (2, 15, 33, 1, 8, 5, 5, 2, 2),            # one channel
+    (1, 12, 20, 2, 16, 3, 5, (1, 2), (1, 2)),  # even C (also legal for the alignment-2 kernels), S != R
+    (1, 9, 30, 4, 24, 5, 8, (2, 1), (2, 3)),   # C = 4, S = 8 (no masked tap), R * C = 20
+    (3, 8, 8, 3, 16, 1, 1, 1, 0),             # 1x1
+    (1, 20, 21, 3, 64, 7, 2, (3, 2), (0, 0)),  # stride_h = 3, no padding
+]
+
+
+@pytest.mark.parametrize("shape", FIRST_LAYERS)
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+def test_first_layer_conv_every_instance(bolt, shape, layout):
+    """The input is read where it lies: no channel padding, no transformation pass.  NCHW parity is against the
+    oracle's convolution of the oracle's transformed tensor; integers (bit-exact) and fractions on every instance."""
+    N, H, W, Cc, K, R, S, stride, pad = shape
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad, alpha=0.5, beta=-1.0, act="relu", x_layout=layout)
+    P, Q = bolt.conv_out_hw(d)
+    ids = [k for k in range(bolt.bolt_num_instances(bolt.OP_CONV2D)) if bolt.bolt_instance_supports(bolt.OP_CONV2D, k, d)]
+    smallc = [k for k in ids if bolt.bolt_instance_config(bolt.OP_CONV2D, k).tile_k == 32 and bolt.bolt_instance_config(bolt.OP_CONV2D, k).mfma_shape == 16]
+    assert smallc, "no first-layer instance for %s" % (shape,)
+    if layout == "nchw" or Cc % 2:
+        assert smallc == ids
+    x = wl.uniform_fp16(501, 0, (N, H, W, Cc), -1, 1)
+    w = wl.normal_fp16(501, 1, (K, R, S, Cc), (2.0 / (R * S * Cc)) ** 0.5)
+    b = wl.uniform_fp16(501, 2, (K,), -1, 1)
+    xi = wl.integer_fp16(502, 0, (N, H, W, Cc), -3, 3)
+    wi = wl.integer_fp16(502, 1, (K, R, S, Cc), -2, 2)
+    bi = wl.integer_fp16(502, 2, (K,), -4, 4)
+    want = ref.conv2d_nhwc(x, w, b, stride=stride, pad=pad, alpha=0.5, beta=-1.0, act="relu")
+    want_i = ref.conv2d_nhwc(xi, wi, bi, stride=stride, pad=pad, alpha=0.5, beta=-1.0, act="relu")
+    assert np.abs(want_i.astype(np.float64)).max() < 1024  # alpha = 0.5: halves of integers below 2048 are exact
+    as_given = (lambda a: a) if layout == "nhwc" else ref.nhwc_to_nchw
+    if layout == "nchw":  # the oracle's own transformation, both ways: what the kernel is handed is really NCHW
+        assert np.array_equal(ref.nchw_to_nhwc(as_given(x)), x)
+    xd, xid = dev(as_given(x)), dev(as_given(xi))
+    for kid in smallc:
+        _say("first layer %s %s instance %d" % (shape, layout, kid))
+        y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_conv2d_fprop_nhwc(d, xd, dev(w), dev(b), y, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(y), want, "first layer %s %s instance %d" % (shape, layout, kid))
+        y.fill_(float("nan"))
+        bolt.bolt_conv2d_fprop_nhwc(d, xid, dev(wi), dev(bi), y, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_bit_equal(host(y), want_i, "integer first layer %s %s instance %d" % (shape, layout, kid))
+    # no config: the built-in pick rule; no bias; another activation
+    d2 = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad, act="hardswish", x_layout=layout)
+    y = torch.full((N, P, Q, K), float("nan"), dtype=torch.float16, device="cuda")
+    bolt.bolt_conv2d_fprop_nhwc(d2, xd, dev(w), None, y)
+    torch.cuda.synchronize()
+    assert_close(host(y), ref.conv2d_nhwc(x, w, None, stride=stride, pad=pad, act="hardswish"), "first layer %s %s heuristic" % (shape, layout))
+
+
+def test_first_layer_conv_equals_the_padded_path_and_ignores_infinite_neighbours(bolt):
+    """Channel padding is a pure re-scheduling (Section 3.2.3): the unpadded first-layer kernel and the padded C = 8
+    convolution agree bit for bit on integers.  A tap past the filter's width reads the neighbouring pixel's data
+    under a zero weight: an infinity there must not leak (0 * inf) into pixels whose window does not contain it."""
+    N, H, W, Cc, K, R, S, stride, pad = 2, 30, 34, 3, 64, 7, 7, 2, 3
+    xi = wl.integer_fp16(503, 0, (N, H, W, Cc), -3, 3)
+    wi = wl.integer_fp16(503, 1, (K, R, S, Cc), -2, 2)
+    bi = wl.integer_fp16(503, 2, (K,), -4, 4)
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad)
+    P, Q = bolt.conv_out_hw(d)
+    y = torch.empty((N, P, Q, K), dtype=torch.float16, device="cuda")
+    bolt.bolt_conv2d_fprop_nhwc(d, dev(xi), dev(wi), dev(bi), y)
+    x8, w8 = torch.empty((N, H, W, 8), dtype=torch.float16, device="cuda"), torch.empty((K, R, S, 8), dtype=torch.float16, device="cuda")
+    bolt.bolt_pad_channels_nhwc(dev(xi), x8, 8)
+    bolt.bolt_pad_channels_nhwc(dev(wi), w8, 8)
+    y8, _ = torch.empty_like(y), None
+    bolt.bolt_conv2d_fprop_nhwc(bolt.conv_desc(N, H, W, 8, K, R, S, stride, pad), x8, w8, dev(bi), y8)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(y), host(y8), "unpadded first layer vs padded path")
+    assert_bit_equal(host(y), ref.conv2d_nhwc(xi, wi, bi, stride=stride, pad=pad), "unpadded first layer vs oracle")
+    xinf = xi.copy()
+    xinf[0, 10, 20, 1] = np.inf
+    want = ref.conv2d_nhwc(xinf, np.abs(wi) + 1, bi, stride=stride, pad=pad, act="none")
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad, act="none")
+    bolt.bolt_conv2d_fprop_nhwc(d, dev(xinf), dev(np.abs(wi) + 1), dev(bi), y)
+    torch.cuda.synchronize()
+    got = host(y)
+    assert np.isinf(want).any() and not np.isnan(want).any()
+    assert_bit_equal(got, want, "infinite input element")
+
+
+# ---------------------------------------------------------------------------------------------
 # three-op chains
 # ---------------------------------------------------------------------------------------------
 GEMM_CHAINS = [  # (M, K0, N0, N1, N2): ragged M, widths at and below the compiled bounds

@@ -41,7 +41,7 @@ def test_binding_lists_the_same_symbols(bolt):
 def test_struct_layouts_match_header(bolt):
     assert ctypes.sizeof(bolt.BoltConfig) == 44
     assert ctypes.sizeof(bolt.GemmDesc) == 40
-    assert ctypes.sizeof(bolt.ConvDesc) == 56
+    assert ctypes.sizeof(bolt.ConvDesc) == 60
 
 
 def test_instance_tables(bolt):
@@ -87,7 +87,24 @@ def test_gemm_validation(bolt):
 def test_conv_validation(bolt):
     Cd, chk = bolt.conv_desc, bolt.bolt_check
     assert chk(bolt.OP_CONV2D, Cd(32, 56, 56, 64, 64, 3, 3, 1, 1)) == OK
-    assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 3, 64, 7, 7, 2, 3)) == ALIGNMENT   # C = 3 must be padded to 8
+    # first layers: C <= 4 of either parity runs unpadded, from NHWC or NCHW, on the first-layer instances only
+    stem = Cd(32, 224, 224, 3, 64, 7, 7, 2, 3)
+    stem_nchw = Cd(32, 224, 224, 3, 64, 7, 7, 2, 3, x_layout="nchw")
+    n = bolt.bolt_num_instances(bolt.OP_CONV2D)
+    for d in (stem, stem_nchw):
+        assert chk(bolt.OP_CONV2D, d) == OK
+        ids = [i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_CONV2D, i, d)]
+        assert ids and all(bolt.bolt_instance_config(bolt.OP_CONV2D, i).tile_k == 32 for i in ids)
+        assert all(not bolt.bolt_instance_supports(bolt.OP_CONV2D, i, Cd(32, 224, 224, 8, 64, 7, 7, 2, 3)) for i in ids)
+    assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 5, 64, 7, 7, 2, 3)) == ALIGNMENT   # an odd C > 4 must be padded
+    assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 8, 64, 7, 7, 2, 3, x_layout="nchw")) == UNSUPPORTED  # NCHW: C <= 4 only
+    assert chk(bolt.OP_CONV2D, Cd(2, 64, 64, 3, 64, 9, 9, 2, 4)) == UNSUPPORTED    # R * C > 24: no first-layer instance
+    assert chk(bolt.OP_CONV2D, Cd(2, 64, 64, 3, 64, 3, 3, 3, 1)) == UNSUPPORTED    # stride_w > 2
+    assert chk(bolt.OP_CONV2D, Cd(2, 64, 64, 4, 64, 3, 3, 2, 1)) == OK             # C = 4: these or the alignment-2 ones
+    bad = Cd(2, 64, 64, 3, 64, 3, 3, 1, 1)
+    bad.x_layout = 7
+    assert chk(bolt.OP_CONV2D, bad) == INVALID
+    assert chk(bolt.OP_B2B_CONV, Cd(2, 64, 64, 3, 64, 3, 3, 1, 1), Cd(2, 64, 64, 64, 64, 1, 1, 1, 0)) == ALIGNMENT
     assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 8, 64, 7, 7, 2, 3)) == OK
     # an even C that is not a multiple of 8: legal, and only the alignment-2 instances take it
     d46 = Cd(32, 20, 26, 46, 32, 3, 3, 1, 1)
