@@ -769,6 +769,38 @@ def main():
         yh2, yn2 = rnd(32, 56, 56, 256), empty(32, 256, 56, 56)
         t_b2 = timed(lambda: bolt.bolt_nhwc_to_nchw(yh2, yn2), args.reps)
         lay.append(dict(name="NHWC 32x56x56x256 -> NCHW", ms=round(t_b2, 5), gbs=round(4.0 * yh2.numel() / t_b2 / 1e6, 1)))
+        # folded into the kernels: the stem straight from NCHW (no transform, no padding pass) against transform + pad
+        # pass followed by the aligned kernel; the last 1x1 of the ResNet stack (7x7, 512 -> 2048) storing NCHW itself
+        # against the NHWC kernel followed by the transform pass
+        ws3, b3 = rnd(64, 7, 7, 3, scale=0.1), rnd(64)
+        w8 = empty(64, 7, 7, 8)
+        bolt.bolt_pad_channels_nhwc(ws3, w8, 8)
+        ys = empty(32, 112, 112, 64)
+        d_in = bolt.conv_desc(32, 224, 224, 3, 64, 7, 7, 2, 3, x_layout="nchw")
+        d_8 = bolt.conv_desc(32, 224, 224, 8, 64, 7, 7, 2, 3)
+        c_in = tuned("stem from NCHW", bolt.OP_CONV2D, d_in, None, [xn, ws3, b3, ys], ws)
+        c_8 = tuned("stem padded to 8 channels (layout table)", bolt.OP_CONV2D, d_8, None, [xp8, w8, b3, ys], ws)
+        t_fold = timed(lambda: bolt.bolt_conv2d_fprop_nhwc(d_in, xn, ws3, b3, ys, c_in, ws), args.reps)
+
+        def stem_passes():
+            bolt.bolt_nchw_to_nhwc(xn, xp8)
+            bolt.bolt_conv2d_fprop_nhwc(d_8, xp8, w8, b3, ys, c_8, ws)
+        t_pass = timed(stem_passes, args.reps)
+        lay.append(dict(name="stem 7x7/2 3->64 at batch 32 from an NCHW image: first-layer kernel vs transform+pad pass + aligned kernel",
+                        folded_ms=round(t_fold, 5), passes_ms=round(t_pass, 5), speedup=round(t_pass / t_fold, 3)))
+        xl_, wl_, bl_ = rnd(32, 7, 7, 512), rnd(2048, 1, 1, 512, scale=0.05), rnd(2048)
+        d_o = bolt.conv_desc(32, 7, 7, 512, 2048, 1, 1, 1, 0, y_layout="nchw")
+        d_h = bolt.conv_desc(32, 7, 7, 512, 2048, 1, 1, 1, 0)
+        c_o = tuned("last 1x1 to NCHW", bolt.OP_CONV2D, d_o, None, [xl_, wl_, bl_, yn], ws)
+        c_h = tuned("last 1x1 NHWC (layout table)", bolt.OP_CONV2D, d_h, None, [xl_, wl_, bl_, yh], ws)
+        t_fo = timed(lambda: bolt.bolt_conv2d_fprop_nhwc(d_o, xl_, wl_, bl_, yn, c_o, ws), args.reps)
+
+        def last_passes():
+            bolt.bolt_conv2d_fprop_nhwc(d_h, xl_, wl_, bl_, yh, c_h, ws)
+            bolt.bolt_nhwc_to_nchw(yh, yn)
+        t_po = timed(last_passes, args.reps)
+        lay.append(dict(name="last 1x1 7x7 512->2048 at batch 32 to an NCHW tensor: NCHW store in the kernel vs NHWC kernel + transform pass",
+                        folded_ms=round(t_fo, 5), passes_ms=round(t_po, 5), speedup=round(t_po / t_fo, 3)))
     except Exception as e:  # context only
         lay.append({"error": str(e)})
     out["layout_transformation"] = lay

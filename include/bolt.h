@@ -103,17 +103,22 @@ typedef struct {
   int32_t b_layout;      /* bolt_layout                                                           */
 } bolt_gemm_desc;
 
-/* Layout of a convolution's input tensor in memory (Section 3.2.3, Layout transformation). */
+/* Layout of a convolution's input or output tensor in memory (Section 3.2.3, Layout transformation:
+ * done inside the first and the last layer's kernel instead of as passes of their own). */
 typedef enum {
   BOLT_TENSOR_NHWC = 0, /* [N][H][W][C], channels contiguous: what every kernel computes in          */
-  BOLT_TENSOR_NCHW = 1  /* [N][C][H][W]: accepted for the input of a first layer (C <= 4), whose    */
-                        /* loader reads it in place - no bolt_nchw_to_nhwc pass, no padded copy      */
+  BOLT_TENSOR_NCHW = 1  /* [N][C][H][W].  As x_layout: the input of a first layer (C <= 4), whose   */
+                        /* loader reads it in place - no bolt_nchw_to_nhwc pass, no padded copy.     */
+                        /* As y_layout: the output [N][K][P][Q] of a last layer, written by the     */
+                        /* kernel's own store - no bolt_nhwc_to_nchw pass.                           */
 } bolt_tensor_layout;
 
 /* y[N,P,Q,K] = act(alpha * conv(x[N,H,W,C], w[K,R,S,C]) + beta * bias[K]); cross-correlation,
  * zero padding, P = (H + 2 pad_h - R) / stride_h + 1 (floor), Q likewise; dilation 1, groups 1.
- * x_layout: bolt_tensor_layout of x (0 = NHWC; a zero-initialised descriptor keeps the default).
- * The weights are always [K][R][S][C], the output always NHWC. */
+ * x_layout, y_layout: bolt_tensor_layout of x and y (0 = NHWC; a zero-initialised descriptor keeps the
+ * defaults).  The weights are always [K][R][S][C].  y_layout = NCHW runs on a few general instances
+ * (and on the first-layer kernels); it has no residual form, no split-K, and fused pairs / chains do
+ * not take it (BOLT_ERR_UNSUPPORTED). */
 typedef struct {
   int32_t N, H, W, C;
   int32_t K, R, S;
@@ -121,6 +126,7 @@ typedef struct {
   float alpha, beta;
   int32_t act;      /* bolt_act */
   int32_t x_layout; /* bolt_tensor_layout */
+  int32_t y_layout; /* bolt_tensor_layout */
 } bolt_conv_desc;
 
 /* GEMM + fused epilogue (Section 2.2 tiling; Section 3.1 epilogue fusion patterns (i)-(iii)).

@@ -47,7 +47,7 @@ class ConvDesc(C.Structure):
     _fields_ = [("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("C", C.c_int32), ("K", C.c_int32),
                 ("R", C.c_int32), ("S", C.c_int32), ("stride_h", C.c_int32), ("stride_w", C.c_int32),
                 ("pad_h", C.c_int32), ("pad_w", C.c_int32), ("alpha", C.c_float), ("beta", C.c_float),
-                ("act", C.c_int32), ("x_layout", C.c_int32)]
+                ("act", C.c_int32), ("x_layout", C.c_int32), ("y_layout", C.c_int32)]
 
 
 TENSOR_NHWC, TENSOR_NCHW = 0, 1
@@ -201,12 +201,14 @@ def gemm_desc(M, N, K, lda=None, ldb=None, ldd=None, alpha=1.0, beta=1.0, act="r
     return GemmDesc(M, N, K, K if lda is None else lda, ldb, N if ldd is None else ldd, alpha, beta, ACT[act], b_layout)
 
 
-def conv_desc(N, H, W, Cin, K, R, S, stride=1, pad=0, alpha=1.0, beta=1.0, act="relu", x_layout="nhwc") -> ConvDesc:
-    """x_layout: "nhwc" or "nchw" (the latter for first layers with at most 4 channels)."""
+def conv_desc(N, H, W, Cin, K, R, S, stride=1, pad=0, alpha=1.0, beta=1.0, act="relu", x_layout="nhwc",
+              y_layout="nhwc") -> ConvDesc:
+    """x_layout: "nhwc" or "nchw" (the latter for first layers with at most 4 channels); y_layout: "nhwc" or "nchw"
+    (the latter for last layers: the output tensor is then [N][K][P][Q])."""
     sh, sw = (stride, stride) if isinstance(stride, int) else stride
     ph, pw = (pad, pad) if isinstance(pad, int) else pad
     return ConvDesc(N, H, W, Cin, K, R, S, sh, sw, ph, pw, alpha, beta, ACT[act],
-                    {"nhwc": TENSOR_NHWC, "nchw": TENSOR_NCHW}[x_layout])
+                    {"nhwc": TENSOR_NHWC, "nchw": TENSOR_NCHW}[x_layout], {"nhwc": TENSOR_NHWC, "nchw": TENSOR_NCHW}[y_layout])
 
 
 def conv_out_hw(d: ConvDesc) -> Tuple[int, int]:

@@ -241,6 +241,7 @@ struct Tables {
     register_gemm_nk_instances(conv);  // for 1x1 / stride 1 / pad 0 filters
     register_conv_align2_instances(conv);  // even channel counts that are not multiples of 8
     register_conv_smallc_instances(conv);  // first layers: at most 4 channels, unpadded NHWC or NCHW
+    register_conv_nchw_out_instances(conv);  // last layers: the output written as NCHW
     register_b2b_gemm_instances(b2b_gemm);
     register_b2b_gemm_stream_instances(b2b_gemm);
     register_b2b_gemm_dma_instances(b2b_gemm);
@@ -286,6 +287,7 @@ static bolt_status check_conv_desc(const bolt_conv_desc* d, ConvDims* out) {
   if (!valid_act(d->act)) return BOLT_ERR_INVALID_ARG;
   if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return BOLT_ERR_INVALID_ARG;
   if (d->x_layout != BOLT_TENSOR_NHWC && d->x_layout != BOLT_TENSOR_NCHW) return BOLT_ERR_INVALID_ARG;
+  if (d->y_layout != BOLT_TENSOR_NHWC && d->y_layout != BOLT_TENSOR_NCHW) return BOLT_ERR_INVALID_ARG;
   // C % 8 == 0 is the fast path (128-bit accesses); an even C runs on the alignment-2 instances; C <= 4 (any
   // parity, either input layout) on the first-layer instances
   if ((d->K & 7) || ((d->C & 1) && d->C > 4)) return BOLT_ERR_ALIGNMENT;
@@ -332,6 +334,9 @@ static bolt_status check_b2b_conv(const bolt_conv_desc* c0, const bolt_conv_desc
   s = check_conv_desc(c1, &d1);
   if (s != BOLT_OK) return s;
   if (c0->C & 7) return BOLT_ERR_ALIGNMENT;  // the fused kernels have no alignment-2 form
+  if (c0->x_layout != BOLT_TENSOR_NHWC || c0->y_layout != BOLT_TENSOR_NHWC || c1->x_layout != BOLT_TENSOR_NHWC ||
+      c1->y_layout != BOLT_TENSOR_NHWC)
+    return BOLT_ERR_UNSUPPORTED;  // fused pairs and chains compute and store NHWC only
   if (c1->R != 1 || c1->S != 1 || c1->stride_h != 1 || c1->stride_w != 1 || c1->pad_h != 0 || c1->pad_w != 0)
     return BOLT_ERR_ILLEGAL_FUSION;
   if (c1->C != c0->K || c1->N != c0->N || c1->H != d0.P || c1->W != d0.Q) return BOLT_ERR_ILLEGAL_FUSION;
@@ -353,8 +358,11 @@ static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
     // first-layer kernels: at most 4 channels of any parity, NHWC or NCHW input, weights [K][R][S][C] as they are; no
     // residual epilogue.  The geometry test is the instance's own.
     const bool small_nhwc = pr.xmode == 2 && pr.p.cg.C <= 4;
-    return (pr.xmode == 4 || small_nhwc) && !pr.residual && in.dyn_supports(pr.p);
+    return (pr.xmode == 4 || small_nhwc) && !pr.residual && in.dyn_supports(pr.p);  // either output layout
   }
+  // an NCHW output: only the instances with that store, and they have no other; no residual form
+  if ((pr.p.y_nchw != 0) != in.nchw_out) return false;
+  if (in.nchw_out && pr.residual) return false;
   if (in.wmode != pr.wmode) return false;
   if (in.xmode == 3) {
     // filter-row gather: a whole filter row of one output pixel (S*C halves) fits one k-tile
@@ -501,6 +509,7 @@ static bolt_status make_conv_problem(const bolt_conv_desc* d, FpropProblem* pr) 
   // odd channel counts and NCHW inputs: only the first-layer instances (which also take C = 2 and 4 from NHWC)
   if ((d->C & 1) || d->x_layout == BOLT_TENSOR_NCHW) pr->xmode = 4;
   p.x_nchw = d->x_layout == BOLT_TENSOR_NCHW ? 1 : 0;
+  p.y_nchw = d->y_layout == BOLT_TENSOR_NCHW ? 1 : 0;
   return BOLT_OK;
 }
 

@@ -297,7 +297,17 @@ __global__ __launch_bounds__(256, 3) void conv_smallc_kernel(const FpropParams p
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[4 * b2 + e] = (half_t)u[e];
           }
-          if (n < p.N) __builtin_nontemporal_store(o, (half8*)(yrow + n));
+          if (n < p.N) {
+            if (!p.y_nchw) {
+              __builtin_nontemporal_store(o, (half8*)(yrow + n));
+            } else {
+              // [N][K][P][Q]: 8 channel planes; the 16 lanes of a pixel block write 16 consecutive pixels of each
+              const int img = orow / cg.P, op = orow - img * cg.P;
+              half_t* y = p.Y + (((int64_t)img * p.N + n) * cg.P + op) * cg.Q + q;
+#pragma unroll
+              for (int k = 0; k < 8; ++k) y[(int64_t)k * cg.P * cg.Q] = o[k];
+            }
+          }
         }
       }
     };

@@ -228,7 +228,7 @@ __device__ __forceinline__ int ctile_swizzle(int row) {
 // `writer`: this wave holds the final accumulators (k-group 0).  Called by every thread of the workgroup.
 // `to_lds(slow, ep)` writes this wave's accumulators as FP16 quads into the staged tile (the layout of the quads
 // depends on the matrix-core instruction the main loop used).
-template <bool RES, int BM, int BN, int STORE_THREADS, int ROWS_PER_PASS, typename ToLds>
+template <bool RES, int BM, int BN, int STORE_THREADS, int ROWS_PER_PASS, bool NCHW = false, typename ToLds>
 __device__ __forceinline__ void fprop_tile_out_with(half_t* lds, const FpropParams& p, int m0, int n0, bool writer, int tid,
                                                     ToLds&& to_lds) {
   constexpr int CPR = BN / 8;
@@ -258,6 +258,25 @@ __device__ __forceinline__ void fprop_tile_out_with(half_t* lds, const FpropPara
     else to_lds(std::false_type{}, ep);
   }
   barrier_after_lds_writes();
+  if constexpr (NCHW) {
+    // The mirror image of the first layer's loader (Section 3.2.3: the transformation lives in the last layer's
+    // kernel): the output is [N][K][P][Q].  A thread takes one 8-channel chunk of one tile row (= output pixel) out of
+    // LDS and writes its 8 halves into 8 channel planes; consecutive lanes take consecutive pixels, so that for every
+    // channel a wave writes one contiguous run of its plane.
+    const int PQ = p.cg.P * p.cg.Q;
+    for (int e = tid; e < BM * CPR; e += (int)blockDim.x) {
+      const int row = e % BM, chunk = e / BM;
+      const int m = m0 + row, n = n0 + chunk * 8;
+      if (m < p.M && n < p.N) {
+        const half8 v = *(const half8*)(lds + row * BN + ((chunk ^ ctile_swizzle<CPR>(row)) << 3));
+        const int img = m / PQ, pq = m - img * PQ;
+        half_t* y = p.Y + ((int64_t)img * p.N + n) * PQ + pq;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) y[(int64_t)k * PQ] = v[k];
+      }
+    }
+    return;
+  }
   // LDS -> global: each thread moves 16 bytes, consecutive threads cover consecutive row bytes
   if (tid < STORE_THREADS) {
     const int chunk = tid % CPR, r0 = tid / CPR;
@@ -277,12 +296,12 @@ __device__ __forceinline__ void fprop_tile_out_with(half_t* lds, const FpropPara
 
 // The 32 x 32 accumulator layout: lane l of a fragment holds, in registers 4q .. 4q+3, columns 8q + 4(l / 32) .. +3
 // of row l % 32.
-template <bool RES, int BM, int BN, int WTM, int WTN, int STORE_THREADS, int ROWS_PER_PASS, int FN, int FM>
+template <bool RES, int BM, int BN, int WTM, int WTN, int STORE_THREADS, int ROWS_PER_PASS, bool NCHW = false, int FN, int FM>
 __device__ __forceinline__ void fprop_tile_out(half_t* lds, const floatx16 (&acc)[FN][FM], const FpropParams& p, int m0,
                                                int n0, int wm, int wn, bool writer, int tid) {
   constexpr int CPR = BN / 8;
   const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
-  fprop_tile_out_with<RES, BM, BN, STORE_THREADS, ROWS_PER_PASS>(lds, p, m0, n0, writer, tid, [&](auto slow, const EpilogueArgs& ep) {
+  fprop_tile_out_with<RES, BM, BN, STORE_THREADS, ROWS_PER_PASS, NCHW>(lds, p, m0, n0, writer, tid, [&](auto slow, const EpilogueArgs& ep) {
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
@@ -326,7 +345,8 @@ struct FpropDmaTraits {
   static_assert(STORE_THREADS % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
 };
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1, bool RES = false>
+// NCHW: the output tensor is [N][K][P][Q] (convolutions only; see fprop_tile_out_with)
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1, bool RES = false, bool NCHW = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(const FpropParams p) {
   using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
   constexpr int WPG = T::WPG, WTM = T::WTM, WTN = T::WTN, FM = T::FM, FN = T::FN;
@@ -597,7 +617,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
     return;
   }
 
-  fprop_tile_out<RES, BM, BN, WTM, WTN, T::STORE_THREADS, T::ROWS_PER_PASS>(lds, acc, p, m0, n0, wm, wn, kg == 0, tid);
+  fprop_tile_out<RES, BM, BN, WTM, WTN, T::STORE_THREADS, T::ROWS_PER_PASS, NCHW>(lds, acc, p, m0, n0, wm, wn, kg == 0, tid);
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1>
@@ -612,6 +632,25 @@ hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
   hipLaunchKernelGGL(kern, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
   return hipGetLastError();
 }
+
+// The instances whose output is NCHW: no residual form, no split-K (the reduction kernel writes NHWC).
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS>
+hipError_t launch_fprop_dma_nchw(const FpropParams& p, hipStream_t stream) {
+  using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, 1>;
+  auto kern = fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, 1, false, true>;
+  static LdsOptIn opt_in;
+  if (hipError_t e = opt_in.ensure((const void*)kern, T::LDS_BYTES); e != hipSuccess) return e;
+  dim3 grid(p.tiles_m * p.tiles_n, 1, 1);
+  hipLaunchKernelGGL(kern, grid, dim3(T::NT), T::LDS_BYTES, stream, p);
+  return hipGetLastError();
+}
+#define BOLT_FPROP_DMA_NCHW_INSTANCE(BM, BN, BK, WM, WN, NS, XMODE)                                     \
+  {                                                                                                     \
+    "dma_nchw_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK, WM, WN, XMODE, 0, NS,          \
+        bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS>::LDS_BYTES,                                  \
+        &bolt::launch_fprop_dma_nchw<BM, BN, BK, WM, WN, XMODE, NS>, 0, nullptr, nullptr, nullptr,       \
+        nullptr, 0, 0, true, true                                                                       \
+  }
 
 #define BOLT_FPROP_DMA_INSTANCE(BM, BN, BK, WM, WN, NS, XMODE)                                          \
   {                                                                                                     \

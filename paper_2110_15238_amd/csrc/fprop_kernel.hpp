@@ -41,6 +41,7 @@ struct FpropParams {
   int split_k, ktiles_per_split;
   ConvGeom cg;  // convolutions only
   int x_nchw;   // x mode 4 only: the input is [N][C][H][W]
+  int y_nchw;   // the output is [N][K][P][Q] (first-layer kernels take it as a run-time switch)
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>
@@ -195,6 +196,7 @@ struct FpropInstance {
   int kgroups;  // k-groups of waves per workgroup (0 or 1: none); threads = 64 * waves_m * waves_n * kgroups
   int mi;       // matrix-core instruction: 0 or 32 = 32 x 32 x 16, 16 = 16 x 16 x 32
   bool no_split_k;  // the kernel has no partial-sum output
+  bool nchw_out;    // writes its output as [N][K][P][Q] (and only that)
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>

@@ -133,6 +133,7 @@ void register_conv_stream_instances(std::vector<FpropInstance>& v);
 void register_conv_halo_instances(std::vector<FpropInstance>& v);
 void register_conv_align2_instances(std::vector<FpropInstance>& v);
 void register_conv_smallc_instances(std::vector<FpropInstance>& v);
+void register_conv_nchw_out_instances(std::vector<FpropInstance>& v);
 void register_b2b_gemm_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_instances(std::vector<B2bInstance>& v);
 void register_b2b_gemm_stream_instances(std::vector<B2bInstance>& v);

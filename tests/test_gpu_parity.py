@@ -985,6 +985,76 @@ def test_first_layer_conv_equals_the_padded_path_and_ignores_infinite_neighbours
     assert_bit_equal(got, want, "infinite input element")
 
 
+LAST_LAYERS = [
+    # N H W C K R S stride pad: P * Q odd and even, ragged M and N tiles, several images inside one tile
+    (3, 7, 7, 64, 72, 1, 1, 1, 0),      # 1x1 / stride 1: GEMM addressing; P * Q = 49
+    (2, 14, 14, 64, 128, 3, 3, 1, 1),   # gather
+    (5, 5, 9, 16, 40, 3, 3, 2, 1),      # stride 2, P * Q = 15: up to 9 images in a 128-row tile
+    (1, 20, 20, 8, 8, 5, 5, 1, 2),      # one image, N tile mostly empty
+]
+
+
+@pytest.mark.parametrize("shape", LAST_LAYERS)
+def test_last_layer_conv_writes_nchw_every_instance(bolt, shape):
+    """Section 3.2.3, layout transformation in the last layer: y_layout = NCHW stores [N][K][P][Q] from the kernel
+    itself.  Against the oracle's transformation of the oracle's convolution; bit-exact on integers."""
+    N, H, W, Cc, K, R, S, stride, pad = shape
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad, act="relu", y_layout="nchw")
+    P, Q = bolt.conv_out_hw(d)
+    ids = [k for k in range(bolt.bolt_num_instances(bolt.OP_CONV2D)) if bolt.bolt_instance_supports(bolt.OP_CONV2D, k, d)]
+    assert ids
+    x = wl.uniform_fp16(601, 0, (N, H, W, Cc), -1, 1)
+    w = wl.normal_fp16(601, 1, (K, R, S, Cc), (2.0 / (R * S * Cc)) ** 0.5)
+    b = wl.uniform_fp16(601, 2, (K,), -1, 1)
+    xi, wi, bi = wl.integer_fp16(602, 0, (N, H, W, Cc), -2, 2), wl.integer_fp16(602, 1, (K, R, S, Cc), -1, 1), wl.integer_fp16(602, 2, (K,), -4, 4)
+    want = ref.nhwc_to_nchw(ref.conv2d_nhwc(x, w, b, stride=stride, pad=pad))
+    want_i = ref.nhwc_to_nchw(ref.conv2d_nhwc(xi, wi, bi, stride=stride, pad=pad))
+    assert want.shape == (N, K, P, Q) and np.abs(want_i.astype(np.float64)).max() < 2048
+    for kid in ids:
+        _say("last layer %s instance %d" % (shape, kid))
+        y = torch.full((N, K, P, Q), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_conv2d_fprop_nhwc(d, dev(x), dev(w), dev(b), y, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(y), want, "last layer %s instance %d" % (shape, kid))
+        y.fill_(float("nan"))
+        bolt.bolt_conv2d_fprop_nhwc(d, dev(xi), dev(wi), dev(bi), y, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_bit_equal(host(y), want_i, "integer last layer %s instance %d" % (shape, kid))
+    y = torch.full((N, K, P, Q), float("nan"), dtype=torch.float16, device="cuda")
+    r = bolt.bolt_tune(bolt.OP_CONV2D, d, None, [dev(x), dev(w), dev(b), y])
+    assert r.config.kernel_id in ids
+    y.fill_(float("nan"))
+    bolt.bolt_conv2d_fprop_nhwc(d, dev(x), dev(w), dev(b), y, r.config)
+    torch.cuda.synchronize()
+    assert_close(host(y), want, "last layer %s tuned" % (shape,))
+
+
+@pytest.mark.parametrize("shape", [FIRST_LAYERS[0], FIRST_LAYERS[1], FIRST_LAYERS[2], FIRST_LAYERS[6]])
+def test_single_layer_network_nchw_in_nchw_out(bolt, shape):
+    """A first layer that is also the last: NCHW in, NCHW out, no transformation or padding pass anywhere."""
+    N, H, W, Cc, K, R, S, stride, pad = shape
+    d = bolt.conv_desc(N, H, W, Cc, K, R, S, stride, pad, x_layout="nchw", y_layout="nchw")
+    P, Q = bolt.conv_out_hw(d)
+    xi = wl.integer_fp16(603, 0, (N, Cc, H, W), -3, 3)  # NCHW as given
+    wi, bi = wl.integer_fp16(603, 1, (K, R, S, Cc), -2, 2), wl.integer_fp16(603, 2, (K,), -4, 4)
+    x = wl.uniform_fp16(604, 0, (N, Cc, H, W), -1, 1)
+    w = wl.normal_fp16(604, 1, (K, R, S, Cc), (2.0 / (R * S * Cc)) ** 0.5)
+    want_i = ref.nhwc_to_nchw(ref.conv2d_nhwc(ref.nchw_to_nhwc(xi), wi, bi, stride=stride, pad=pad))
+    want = ref.nhwc_to_nchw(ref.conv2d_nhwc(ref.nchw_to_nhwc(x), w, bi, stride=stride, pad=pad))
+    ids = [k for k in range(bolt.bolt_num_instances(bolt.OP_CONV2D)) if bolt.bolt_instance_supports(bolt.OP_CONV2D, k, d)]
+    assert ids
+    for kid in ids:
+        _say("single layer nchw->nchw %s instance %d" % (shape, kid))
+        y = torch.full((N, K, P, Q), float("nan"), dtype=torch.float16, device="cuda")
+        bolt.bolt_conv2d_fprop_nhwc(d, dev(xi), dev(wi), dev(bi), y, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_bit_equal(host(y), want_i, "integer nchw->nchw %s instance %d" % (shape, kid))
+        y.fill_(float("nan"))
+        bolt.bolt_conv2d_fprop_nhwc(d, dev(x), dev(w), dev(bi), y, {"kernel_id": kid})
+        torch.cuda.synchronize()
+        assert_close(host(y), want, "nchw->nchw %s instance %d" % (shape, kid))
+
+
 # ---------------------------------------------------------------------------------------------
 # three-op chains
 # ---------------------------------------------------------------------------------------------

@@ -41,7 +41,7 @@ def test_binding_lists_the_same_symbols(bolt):
 def test_struct_layouts_match_header(bolt):
     assert ctypes.sizeof(bolt.BoltConfig) == 44
     assert ctypes.sizeof(bolt.GemmDesc) == 40
-    assert ctypes.sizeof(bolt.ConvDesc) == 60
+    assert ctypes.sizeof(bolt.ConvDesc) == 64
 
 
 def test_instance_tables(bolt):
@@ -104,6 +104,19 @@ def test_conv_validation(bolt):
     bad = Cd(2, 64, 64, 3, 64, 3, 3, 1, 1)
     bad.x_layout = 7
     assert chk(bolt.OP_CONV2D, bad) == INVALID
+    bad = Cd(2, 64, 64, 8, 64, 3, 3, 1, 1)
+    bad.y_layout = 2
+    assert chk(bolt.OP_CONV2D, bad) == INVALID
+    # last layers: an NCHW output runs on the instances that have that store (and the first-layer kernels), and only there
+    last = Cd(32, 7, 7, 512, 2048, 1, 1, 1, 0, y_layout="nchw")
+    plain = Cd(32, 7, 7, 512, 2048, 1, 1, 1, 0)
+    a = {i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_CONV2D, i, last)}
+    b = {i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_CONV2D, i, plain)}
+    assert a and b and not (a & b) and chk(bolt.OP_CONV2D, last) == OK
+    assert chk(bolt.OP_CONV2D, last, None, {"kernel_id": min(b)}) == UNSUPPORTED
+    assert chk(bolt.OP_CONV2D, last, None, {"kernel_id": min(a), "split_k": 2}) == UNSUPPORTED   # the reduction kernel writes NHWC
+    assert chk(bolt.OP_CONV2D, Cd(2, 64, 64, 3, 64, 7, 7, 2, 3, x_layout="nchw", y_layout="nchw")) == OK
+    assert chk(bolt.OP_B2B_CONV, Cd(2, 16, 16, 64, 64, 3, 3, 1, 1), Cd(2, 16, 16, 64, 64, 1, 1, 1, 0, y_layout="nchw")) == UNSUPPORTED
     assert chk(bolt.OP_B2B_CONV, Cd(2, 64, 64, 3, 64, 3, 3, 1, 1), Cd(2, 64, 64, 64, 64, 1, 1, 1, 0)) == ALIGNMENT
     assert chk(bolt.OP_CONV2D, Cd(32, 224, 224, 8, 64, 7, 7, 2, 3)) == OK
     # an even C that is not a multiple of 8: legal, and only the alignment-2 instances take it
