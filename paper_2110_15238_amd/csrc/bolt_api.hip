@@ -236,7 +236,6 @@ struct Tables {
     register_gemm_kn_instances(gemm);
     register_gemm_nk_instances(gemm);
     register_conv_instances(conv);
-    register_conv_stream_instances(conv);
     register_conv_halo_instances(conv);
     register_gemm_nk_instances(conv);  // for 1x1 / stride 1 / pad 0 filters
     register_conv_align2_instances(conv);  // even channel counts that are not multiples of 8
@@ -246,7 +245,6 @@ struct Tables {
     register_b2b_gemm_stream_instances(b2b_gemm);
     register_b2b_gemm_dma_instances(b2b_gemm);
     register_b2b_conv_instances(b2b_conv);
-    register_b2b_conv_stream_instances(b2b_conv);
     register_b2b_conv_dma_instances(b2b_conv);
     register_b2b_conv_halo_instances(b2b_conv);
   }
@@ -364,19 +362,7 @@ static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
   if ((pr.p.y_nchw != 0) != in.nchw_out) return false;
   if (in.nchw_out && pr.residual) return false;
   if (in.wmode != pr.wmode) return false;
-  if (in.xmode == 3) {
-    // filter-row gather: a whole filter row of one output pixel (S*C halves) fits one k-tile
-    if (pr.xmode != 1 || pr.p.cg.S * pr.p.cg.C > in.bk) return false;
-  } else if (in.xmode != pr.xmode) {
-    return false;
-  }
-  if (in.stream_launch && pr.residual) return false;  // the persistent kernels have no residual epilogue
-  if (in.stream_launch) {
-    // persistent weights-resident kernel: the tile spans all of N and the whole weight matrix
-    // must fit in LDS next to the activation stages
-    if (pr.p.N > in.n0t || (in.n0t > 32 && in.n0t / 2 >= pr.p.N)) return false;
-    return in.stream_lds_bytes(pr.p.K) <= kLdsPerCU;
-  }
+  if (in.xmode != pr.xmode) return false;
   if (in.dyn_supports && (!in.dyn_supports(pr.p) || in.dyn_lds_bytes(pr.p) > kLdsPerCU)) return false;
   if (in.lds_bytes > kLdsPerCU) return false;
   // single-stage instances hold exactly one k-tile per k-group
@@ -395,9 +381,9 @@ static void fprop_fill_config(const FpropInstance& in, int id, bolt_config* c) {
 
 // Built-in pick rule: smallest estimated time under a crude model -- rounds of workgroups over
 // the compute units times the work of one tile, de-rated for small tiles (low FLOP per LDS byte).
-// The weights-resident, halo, single-stage and ping-pong kernels have no partial-sum output.
+// The halo, single-stage and ping-pong kernels have no partial-sum output.
 static bool fprop_can_split_k(const FpropInstance& in) {
-  return !in.stream_launch && !in.dyn_supports && in.stages != 1 && !in.no_split_k;
+  return !in.dyn_supports && in.stages != 1 && !in.no_split_k;
 }
 
 // need_split_k: only instances that can write partial sums qualify (the caller asked for split-K).
@@ -409,7 +395,7 @@ static int fprop_heuristic(const std::vector<FpropInstance>& tab, const FpropPro
     if (!fprop_supports(in, pr)) continue;
     if (need_split_k && !fprop_can_split_k(in)) continue;
     const double tiles = (double)ceil_div(pr.p.M, in.bm) * ceil_div(pr.p.N, in.bn);
-    const int lds = in.stream_launch ? in.stream_lds_bytes(pr.p.K) : (in.dyn_lds_bytes ? in.dyn_lds_bytes(pr.p) : in.lds_bytes);
+    const int lds = in.dyn_lds_bytes ? in.dyn_lds_bytes(pr.p) : in.lds_bytes;
     const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n * std::max(1, in.kgroups)) / 2));
     const double rounds = std::ceil(tiles / (kNumCU * per_cu)) * per_cu;
     const double wtm = (double)in.bm / in.waves_m, wtn = (double)in.bn / in.waves_n;
@@ -431,27 +417,11 @@ static bolt_status fprop_launch(const FpropInstance& in, FpropProblem pr, int sw
   p.bias_on = p.bias ? 1 : 0;
   if (!p.bias) p.bias = zero_bias();
   if (!p.bias) return BOLT_ERR_LAUNCH;
-  if (in.stream_launch) {
-    if (split_k > 1) return BOLT_ERR_UNSUPPORTED;
-    B2bParams q;
-    std::memset(&q, 0, sizeof(q));
-    q.X = p.X; q.W0 = p.W; q.b0 = p.bias; q.b0_on = p.bias_on; q.b1 = p.bias; q.b1_on = 0; q.Y = p.Y;
-    q.M = p.M; q.N0 = p.N; q.K0 = p.K; q.N1 = 0;
-    q.ldx = p.ldx; q.ldw0 = p.ldw; q.ldy = p.ldy;
-    q.alpha0 = p.alpha; q.beta0 = p.beta; q.act0 = p.act;
-    q.cg = p.cg;
-    q.tiles_m = ceil_div(p.M, in.bm);
-    const int lds = in.stream_lds_bytes(p.K);
-    if (lds > kLdsPerCU) return BOLT_ERR_UNSUPPORTED;
-    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n * std::max(1, in.kgroups))));
-    const int grid = std::min(q.tiles_m, kNumCU * per_cu);
-    return in.stream_launch(q, grid, lds, stream) == hipSuccess ? BOLT_OK : BOLT_ERR_LAUNCH;
-  }
   p.tiles_m = ceil_div(p.M, in.bm);
   p.tiles_n = ceil_div(p.N, in.bn);
   p.swizzle = swizzle < 0 ? 0 : swizzle;
-  if (split_k > 1 && !fprop_can_split_k(in) && !in.stream_launch) return BOLT_ERR_UNSUPPORTED;
-  const int nk = in.xmode == 3 ? p.cg.R : ceil_div(p.K, in.bk);  // x mode 3: one k-tile per filter row
+  if (split_k > 1 && !fprop_can_split_k(in)) return BOLT_ERR_UNSUPPORTED;
+  const int nk = ceil_div(p.K, in.bk);
   split_k = std::max(1, std::min(std::min(split_k, kMaxSplitK), nk));
   p.ktiles_per_split = ceil_div(nk, split_k);
   split_k = ceil_div(nk, p.ktiles_per_split);  // no empty splits
@@ -816,8 +786,8 @@ static std::vector<Candidate> fprop_candidates(const std::vector<FpropInstance>&
     if (!fprop_supports(in, pr)) continue;
     const int tiles_m = ceil_div(pr.p.M, in.bm), tiles_n = ceil_div(pr.p.N, in.bn);
     const int64_t tiles = (int64_t)tiles_m * tiles_n;
-    const int nk = in.xmode == 3 ? pr.p.cg.R : ceil_div(pr.p.K, in.bk);
-    if (in.stream_launch || in.dyn_supports) {  // no split-K / swizzle variants for these
+    const int nk = ceil_div(pr.p.K, in.bk);
+    if (in.dyn_supports) {  // no split-K / swizzle variants for these
       out.push_back({i, 0, 1, 0.f});
       continue;
     }
@@ -1185,6 +1155,8 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
     const bool have_ws = workspace && is_aligned16(workspace);
     std::vector<Candidate> cands = fprop_candidates(tab, fp, workspace_bytes, have_ws);
     if (cands.empty()) return BOLT_ERR_UNSUPPORTED;
+    if (tune_log_enabled())
+      std::fprintf(stderr, "[bolt_tune] problem op %d M %d N %d K %d: %zu candidates\n", (int)op, fp.p.M, fp.p.N, fp.p.K, cands.size());
     s = tune_candidates(cands, [&](const Candidate& c) {
       return fprop_launch(tab[c.id], fp, c.swizzle, c.split_k, workspace, workspace_bytes, stream);
     }, stream, &win, &tried);
@@ -1205,6 +1177,8 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
     for (int i = 0; i < (int)tab.size(); ++i)
       if (b2b_supports(tab[i], bp)) cands.push_back({i, 0, 1, 0.f});
     if (cands.empty()) return BOLT_ERR_UNSUPPORTED;
+    if (tune_log_enabled())
+      std::fprintf(stderr, "[bolt_tune] problem op %d M %d N0 %d K0 %d N1 %d: %zu candidates\n", (int)op, p.M, p.N0, p.K0, p.N1, cands.size());
     s = tune_candidates(cands, [&](const Candidate& c) { return b2b_launch(tab[c.id], bp, stream); }, stream, &win,
                         &tried);
     if (s != BOLT_OK) return s;
@@ -1315,6 +1289,9 @@ bolt_status bolt_tune_chain(bolt_op op, int32_t n_ops, const void* const* descs,
   if (cands.empty()) return BOLT_ERR_UNSUPPORTED;
   Candidate win{};
   int tried = 0;
+  if (tune_log_enabled())
+    std::fprintf(stderr, "[bolt_tune] problem op %d M %d N0 %d K0 %d N1 %d N2 %d: %zu candidates\n", (int)op, pr.p.M, pr.p.N0,
+                 pr.p.K0, pr.p.N1, pr.p.N2, cands.size());
   s = tune_candidates(cands, [&](const Candidate& c) { return chain_launch(tab[c.id], pr, stream); }, stream, &win, &tried);
   if (s != BOLT_OK) return s;
   std::memset(best, 0, sizeof(*best));

@@ -362,7 +362,7 @@ hipError_t launch_conv_halo(const FpropParams& p, hipStream_t stream) {
 #define BOLT_CONV_HALO_INSTANCE(BM, BN, WM, WN, NS, XI)                                                 \
   {                                                                                                     \
     "halo_" #BM "x" #BN "_w" #WM "x" #WN "_s" #NS "_x" #XI, BM, BN, 64, WM, WN, 1, 0, NS, 0,              \
-        &bolt::launch_conv_halo<BM, BN, WM, WN, NS, XI>, 0, nullptr, nullptr,                            \
+        &bolt::launch_conv_halo<BM, BN, WM, WN, NS, XI>,                                                 \
         &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI>::supports,                                         \
         &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI>::lds_bytes                                         \
   }
@@ -370,7 +370,7 @@ hipError_t launch_conv_halo(const FpropParams& p, hipStream_t stream) {
 #define BOLT_CONV_HALO_KG_INSTANCE(BM, BN, WM, WN, NS, XI, KG)                                          \
   {                                                                                                     \
     "halo_" #BM "x" #BN "_w" #WM "x" #WN "_s" #NS "_x" #XI "_kg" #KG, BM, BN, 64, WM, WN, 1, 0, NS, 0,    \
-        &bolt::launch_conv_halo<BM, BN, WM, WN, NS, XI, KG>, 0, nullptr, nullptr,                        \
+        &bolt::launch_conv_halo<BM, BN, WM, WN, NS, XI, KG>,                                             \
         &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI, KG>::supports,                                     \
         &bolt::ConvHaloTraits<BM, BN, WM, WN, NS, XI, KG>::lds_bytes, KG                                 \
   }

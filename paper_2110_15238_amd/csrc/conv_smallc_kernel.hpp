@@ -335,7 +335,7 @@ hipError_t launch_conv_smallc(const FpropParams& p, hipStream_t stream) {
 #define BOLT_CONV_SMALLC_INSTANCE(T, SW)                                                                  \
   {                                                                                                       \
     "smallc_t" #T "_sw" #SW, 128, 64, 32, 4, 1, 4, 0, 1, bolt::ConvSmallCTraits<T, SW>::LDS_BYTES,         \
-        &bolt::launch_conv_smallc<T, SW>, 0, nullptr, nullptr, &bolt::ConvSmallCTraits<T, SW>::supports,  \
+        &bolt::launch_conv_smallc<T, SW>, &bolt::ConvSmallCTraits<T, SW>::supports,                        \
         &bolt::ConvSmallCTraits<T, SW>::lds_bytes, 0, 16, true                                            \
   }
 

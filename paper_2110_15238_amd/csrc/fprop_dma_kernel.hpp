@@ -91,14 +91,9 @@ struct DmaTileLoader {
   int xhw[XMODE >= 1 ? NI : 1];
   int cr, cs, cc;
   int ld, rows_valid, K, wave, lrow, lc;
-  int kt_elems;  // XMODE 0: elements from one k-tile to the next (BK unless the caller overrides it)
 
   // GEMM-like source (XMODE 0): `base` points at row 0 of this tile, `bytes` is what remains of the
-  // tensor from there.  Conv source (XMODE 1, 3): base/bytes describe the whole NHWC tensor.
-  // XMODE 3 is the gather for thin inputs (S*C <= BK, e.g. the channel-padded 7x7 stem): k-tile r is
-  // filter row r, whose S*C halves are contiguous in memory for one output pixel, so the 8 lanes
-  // of a tile row fetch one contiguous run instead of 8 scattered pixels; the BK - S*C slack halves
-  // are zero-filled on this side, which makes whatever the weight tile holds there irrelevant.
+  // tensor from there.  Conv source (XMODE 1): base/bytes describe the whole NHWC tensor.
   __device__ __forceinline__ void init(const half_t* base, unsigned bytes, int ld_, int rows_valid_, int K_,
                                        const ConvGeom& cg, int m0, int kt_begin, int wave_, int lane) {
     rsrc = make_rsrc(base, bytes);
@@ -106,31 +101,9 @@ struct DmaTileLoader {
     rows_valid = rows_valid_;
     K = K_;
     wave = wave_;
-    kt_elems = BK;
     lrow = lane / CH;
     lc = (lane % CH) ^ dma_swizzle<BK>(wave * RPI + lrow);  // same for every j because NW is even
     cr = cs = cc = 0;
-    if constexpr (XMODE == 3) {
-      const int PQ = cg.P * cg.Q;
-#pragma unroll
-      for (int j = 0; j < NI; ++j) {
-        const int row = (j * NW + wave) * RPI + lrow;
-        xbase[j] = 0;
-        xhw[j] = (int)0x80000000u;  // window row origin far outside: never valid
-        if (row < rows_valid && lc * 8 < cg.S * cg.C) {
-          const int m = m0 + row;
-          const int img = m / PQ, rem = m - img * PQ;
-          const int op = rem / cg.Q, oq = rem - op * cg.Q;
-          const int ih0 = op * cg.stride_h - cg.pad_h, iw0 = oq * cg.stride_w - cg.pad_w;
-          const int iw = iw0 + (lc * 8) / cg.C;  // the pixel this lane's chunk belongs to
-          if ((unsigned)iw < (unsigned)cg.Wi) {
-            xbase[j] = ((img * cg.H + ih0) * cg.Wi + iw0) * cg.C + lc * 8;
-            xhw[j] = ih0;
-          }
-        }
-      }
-      cr = kt_begin;  // filter row of the next k-tile
-    }
     if constexpr (XMODE == 1) {
       const int PQ = cg.P * cg.Q;
 #pragma unroll
@@ -165,17 +138,8 @@ struct DmaTileLoader {
   // once all parts of a tile have been issued.
   template <int J0, int J1>
   __device__ __forceinline__ void issue_part(int kt, half_t* dst, const ConvGeom& cg) {
-    const int k = (XMODE == 0 ? kt * kt_elems : kt * BK) + lc * 8;
-    if constexpr (XMODE == 3) {
-      const int delta = cr * cg.Wi * cg.C;
-#pragma unroll
-      for (int j = J0; j < J1; ++j) {
-        const int rb = (j * NW + wave) * RPI;
-        const bool ok = cr < K && (unsigned)(xhw[j] + cr) < (unsigned)cg.H;  // K holds the filter-row limit here
-        const unsigned off = ok ? (unsigned)(xbase[j] + delta) * 2u : kInvalidOffset;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, BOLT_LDS_PTR(dst + rb * BK), 16, off, 0, 0, 0);
-      }
-    } else if constexpr (XMODE == 0) {
+    const int k = kt * BK + lc * 8;
+    if constexpr (XMODE == 0) {
 #pragma unroll
       for (int j = J0; j < J1; ++j) {
         const int rb = (j * NW + wave) * RPI;
@@ -196,7 +160,6 @@ struct DmaTileLoader {
     }
   }
   __device__ __forceinline__ void advance(const ConvGeom& cg) {
-    if constexpr (XMODE == 3) cr += KSTRIDE;
     if constexpr (XMODE == 1) {
       cc += BK * KSTRIDE;
       while (cc >= cg.C) {
@@ -367,13 +330,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
   tile_of_workgroup(blockIdx.x, p.tiles_m, p.tiles_n, p.swizzle, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int z = blockIdx.y;
-  const int nk_total = XMODE == 3 ? p.cg.R : (p.K + BK - 1) / BK;  // XMODE 3: one k-tile per filter row
+  const int nk_total = (p.K + BK - 1) / BK;
   const int kt_first = z * p.ktiles_per_split;
   const int kt_end = (kt_first + p.ktiles_per_split) < nk_total ? (kt_first + p.ktiles_per_split) : nk_total;
   // This group's k-tiles are kt_begin, kt_begin + KG, ...; every group runs the same number of
   // pipeline steps (the barriers are shared), tiles at or past kt_end load zeros.
   const int kt_begin = kt_first + kg;
-  const int k_limit = XMODE == 3 ? p.K : (kt_end * BK < p.K ? kt_end * BK : p.K);
+  const int k_limit = kt_end * BK < p.K ? kt_end * BK : p.K;
 
   XL xl;
   WL wl;
@@ -383,13 +346,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
             m0, kt_begin, wave, lane);
   } else {
     const int64_t bytes = (int64_t)p.cg.H * p.cg.Wi * p.cg.C * 2 * (int64_t)(p.M / (p.cg.P * p.cg.Q));
-    xl.init(p.X, (unsigned)bytes, 0, p.M - m0, XMODE == 3 ? kt_end : k_limit, p.cg, m0, kt_begin, wave, lane);
+    xl.init(p.X, (unsigned)bytes, 0, p.M - m0, k_limit, p.cg, m0, kt_begin, wave, lane);
   }
   {
     const int64_t rem = ((int64_t)(p.N - n0 - 1) * p.ldw + p.K) * 2;
     wl.init(p.W + (int64_t)n0 * p.ldw, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldw, p.N - n0, k_limit, p.cg,
             n0, kt_begin, wave, lane);
-    if constexpr (XMODE == 3) wl.kt_elems = p.cg.S * p.cg.C;  // weights of filter row r start at r * S * C
   }
 
   floatx16 acc[FN][FM];
@@ -648,15 +610,14 @@ hipError_t launch_fprop_dma_nchw(const FpropParams& p, hipStream_t stream) {
   {                                                                                                     \
     "dma_nchw_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK, WM, WN, XMODE, 0, NS,          \
         bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS>::LDS_BYTES,                                  \
-        &bolt::launch_fprop_dma_nchw<BM, BN, BK, WM, WN, XMODE, NS>, 0, nullptr, nullptr, nullptr,       \
-        nullptr, 0, 0, true, true                                                                       \
+        &bolt::launch_fprop_dma_nchw<BM, BN, BK, WM, WN, XMODE, NS>, nullptr, nullptr, 0, 0, true, true  \
   }
 
 #define BOLT_FPROP_DMA_INSTANCE(BM, BN, BK, WM, WN, NS, XMODE)                                          \
   {                                                                                                     \
     "dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK, WM, WN, XMODE, 0, NS,               \
         bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS>::LDS_BYTES,                                  \
-        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>, 0, nullptr, nullptr, nullptr, nullptr    \
+        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>, nullptr, nullptr                        \
   }
 
 // The same kernel with KG k-groups (64 * WM * WN * KG threads).
@@ -664,8 +625,7 @@ hipError_t launch_fprop_dma_nchw(const FpropParams& p, hipStream_t stream) {
   {                                                                                                     \
     "dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_kg" #KG, BM, BN, BK, WM, WN, XMODE, 0, NS,     \
         bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS, KG>::LDS_BYTES,                              \
-        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS, KG>, 0, nullptr, nullptr, nullptr,        \
-        nullptr, KG                                                                                     \
+        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS, KG>, nullptr, nullptr, KG                 \
   }
 
 }  // namespace bolt

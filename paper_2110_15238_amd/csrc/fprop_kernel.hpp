@@ -185,11 +185,6 @@ struct FpropInstance {
   int stages;  // LDS operand buffers in flight
   int lds_bytes;
   hipError_t (*launch)(const FpropParams&, hipStream_t);
-  // persistent weights-resident instances (stream_kernel.hpp): compiled width n0t, LDS need as a
-  // function of K, and their own launcher; null for the tiled kernels
-  int n0t;
-  int (*stream_lds_bytes)(int K);
-  hipError_t (*stream_launch)(const struct B2bParams&, int grid, int lds_bytes, hipStream_t);
   // instances whose legality / LDS need depends on the problem (conv_halo_kernel.hpp); null otherwise
   bool (*dyn_supports)(const FpropParams&);
   int (*dyn_lds_bytes)(const FpropParams&);
@@ -214,7 +209,7 @@ hipError_t launch_fprop(const FpropParams& p, hipStream_t stream) {
   {                                                                                                    \
     #BM "x" #BN "x" #BK "_w" #WM "x" #WN, BM, BN, BK, WM, WN, XMODE, WMODE, 2,                           \
         bolt::FpropTraits<BM, BN, BK, WM, WN, XMODE, WMODE>::LDS_BYTES,                                 \
-        &bolt::launch_fprop<BM, BN, BK, WM, WN, XMODE, WMODE>, 0, nullptr, nullptr, nullptr, nullptr    \
+        &bolt::launch_fprop<BM, BN, BK, WM, WN, XMODE, WMODE>, nullptr, nullptr                        \
   }
 
 }  // namespace bolt

@@ -500,7 +500,7 @@ inline int fprop_pp_lds_bytes(const FpropParams&) { return FpropPpTraits::LDS_BY
 #define BOLT_FPROP_PP_INSTANCE(XMODE, MI, PK, BM)                                                           \
   {                                                                                                         \
     "pp_" #BM "x256x64_w2x4_mi" #MI "_pk" #PK, BM, 256, 64, 2, 4, XMODE, 0, 2, bolt::FpropPpTraits::LDS_BYTES, \
-        &bolt::launch_fprop_pp<XMODE, MI, PK, BM>, 0, nullptr, nullptr,                                     \
+        &bolt::launch_fprop_pp<XMODE, MI, PK, BM>,                                                          \
         XMODE == 1 ? &bolt::fprop_pp_conv_supports : nullptr, XMODE == 1 ? &bolt::fprop_pp_lds_bytes : nullptr, 0, MI, true \
   }
 

@@ -6,15 +6,10 @@ namespace bolt {
 #define HK(BM, BN, WM, WN, NS, XI, KG) BOLT_CONV_HALO_KG_INSTANCE(BM, BN, WM, WN, NS, XI, KG)
 void register_conv_halo_instances(std::vector<FpropInstance>& v) {
   static const FpropInstance table[] = {
-      H(128, 64, 2, 2, 3, 2), H(128, 64, 4, 1, 3, 2), H(256, 64, 4, 1, 3, 2), H(256, 64, 4, 2, 3, 1),
-      H(64, 64, 2, 2, 3, 1),  H(64, 128, 2, 2, 3, 1), H(128, 128, 2, 2, 3, 1), H(64, 256, 1, 4, 3, 1),
-      H(128, 256, 2, 4, 3, 1), H(64, 64, 2, 2, 4, 1), H(128, 128, 2, 2, 2, 1),
+      H(128, 64, 4, 1, 3, 2), H(256, 64, 4, 1, 3, 2), H(256, 64, 4, 2, 3, 1), H(64, 64, 2, 2, 3, 1), H(128, 128, 2, 2, 3, 1),
       // k-groups over the 64-channel chunks: HK(..., STAGES, XI, KG)
-      HK(64, 64, 2, 2, 2, 1, 2), HK(64, 64, 2, 2, 3, 1, 2), HK(64, 64, 2, 2, 2, 1, 4), HK(64, 128, 2, 2, 2, 1, 2),
-      HK(128, 64, 2, 2, 2, 2, 2), HK(128, 128, 2, 2, 2, 1, 2),
+      HK(64, 64, 2, 2, 2, 1, 2), HK(64, 64, 2, 2, 2, 1, 4), HK(64, 128, 2, 2, 2, 1, 2), HK(128, 128, 2, 2, 2, 1, 2),
   };
   for (const auto& t : table) v.push_back(t);
-  static const FpropInstance rowgather[] = {BOLT_FPROP_DMA_ROWGATHER_TILE_LIST(BOLT_FPROP_DMA_INSTANCE)};
-  for (const auto& t : rowgather) v.push_back(t);
 }
 }  // namespace bolt

@@ -1,10 +1,10 @@
-// Persistent, weights-resident streaming kernel: the engine of the back-to-back fusion of
-// Section 3.1.1 and of single GEMM / conv problems whose weights fit in LDS.
+// Persistent, weights-resident streaming kernel for the back-to-back GEMM fusion of Section 3.1.1
+// with row-major weights ([K][N], transposed on their way into LDS).
 //
-//   D0 = act0(alpha0 * X . W0 + beta0 * b0)                      (Eq. 1)
-//   D1 = act1(alpha1 * fp16(D0) . W1 + beta1 * b1)   [optional]   (Eq. 2)
+//   D0 = act0(alpha0 * X . W0 + beta0 * b0)          (Eq. 1)
+//   D1 = act1(alpha1 * fp16(D0) . W1 + beta1 * b1)   (Eq. 2)
 //
-// A workgroup keeps W0 (and W1) in LDS for its whole life and walks over BM-row tiles of X,
+// A workgroup keeps W0 and W1 in LDS for its whole life and walks over BM-row tiles of X,
 // persistently (grid = number of compute units x residency).  Threadblock residence: the tile
 // spans all N0 (and N1) columns; RF-resident fusion: waves split the tile along M only, the
 // FP16-rounded D0 accumulators are re-used in registers as the operand of the second MFMA chain.
@@ -39,27 +39,17 @@ __device__ __forceinline__ void wait_vmcnt_upto(int n) {
 #undef BOLT_VM_CASE
 }
 
-// Offset of (row, 16-byte chunk) inside a resident weight tile: tiles written by direct-to-LDS
-// loads (WMODE 0) use the DMA swizzle, tiles written by the transposing register path (WMODE 1)
-// the general one.
-template <int BK, int WMODE>
-__device__ __forceinline__ int weight_chunk_offset(int row, int chunk) {
-  if constexpr (WMODE == 0) return dma_chunk_offset<BK>(row, chunk);
-  else return lds_chunk_offset<BK>(row, chunk);
-}
-
-template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int WMODE, int NS>
+template <int BM, int BK, int NW, int N0T, int N1T, int NS>
 struct StreamTraits {
   static constexpr int NT = 64 * NW;
   static constexpr int WTM = BM / NW, FM = WTM / 32;
   static constexpr int FN0 = N0T / 32, FN1 = N1T / 32;
-  static constexpr bool FUSED = N1T > 0;
-  static constexpr int NC1 = FN1 < 4 ? (FN1 < 1 ? 1 : FN1) : 4;
+  static constexpr int NC1 = FN1 < 4 ? FN1 : 4;
   static constexpr int KB1 = N0T < 64 ? N0T : 64;
   static constexpr int NKT1 = N0T / KB1;
-  static constexpr int STORES = FM * (FUSED ? FN1 : FN0) * 4;  // store instructions per wave per row tile
-  static_assert(WTM % 32 == 0 && N0T % 32 == 0 && N1T % 32 == 0, "tile shape");
-  static_assert(!FUSED || FN1 % NC1 == 0, "op1 column chunks");
+  static constexpr int STORES = FM * FN1 * 4;  // store instructions per wave per row tile
+  static_assert(WTM % 32 == 0 && N0T % 32 == 0 && N1T % 32 == 0 && N1T > 0, "tile shape");
+  static_assert(FN1 % NC1 == 0, "op1 column chunks");
   static_assert(NS >= 2 && NS <= 8, "stages");
   static int lds_bytes(int K0) {
     const int nk0 = (K0 + BK - 1) / BK;
@@ -67,13 +57,12 @@ struct StreamTraits {
   }
 };
 
-template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int WMODE, int NS>
+template <int BM, int BK, int NW, int N0T, int N1T, int NS>
 __global__ __launch_bounds__(64 * NW) void stream_kernel(const B2bParams p) {
-  using T = StreamTraits<BM, BK, NW, N0T, N1T, XMODE, WMODE, NS>;
+  using T = StreamTraits<BM, BK, NW, N0T, N1T, NS>;
   constexpr int NT = T::NT, WTM = T::WTM, FM = T::FM, FN0 = T::FN0, FN1 = T::FN1, NC1 = T::NC1;
   constexpr int KB1 = T::KB1, NKT1 = T::NKT1, KS = BK / 16;
-  constexpr bool FUSED = T::FUSED;
-  using XL = DmaTileLoader<BM, BK, NW, XMODE>;
+  using XL = DmaTileLoader<BM, BK, NW, 0>;
   constexpr int L = XL::NI;
   static_assert(KS % 2 == 0, "fragment double buffering");
 
@@ -92,55 +81,32 @@ __global__ __launch_bounds__(64 * NW) void stream_kernel(const B2bParams p) {
   const int S = n_mine * nk0;  // length of this workgroup's stream of k-tiles
 
   // ---- weights -> LDS, once ----------------------------------------------------------------
-  if constexpr (WMODE == 0) {
-    {
-      DmaTileLoader<N0T, BK, NW, 0> wl;
-      const int64_t bytes = ((int64_t)(p.N0 - 1) * p.ldw0 + p.K0) * 2;
-      wl.init(p.W0, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), p.ldw0, p.N0, p.K0, p.cg, 0, 0, wave, lane);
-      for (int kt = 0; kt < nk0; ++kt) wl.issue(kt, W0s + kt * N0T * BK, p.cg);
+  {
+    WTileLoader<N0T, BK, NT, 1> wl;
+    wl.init(p.W0, p.ldw0, p.N0, p.K0, 0, tid);
+    for (int kt = 0; kt < nk0; ++kt) {
+      wl.load(kt);
+      wl.store(W0s + kt * N0T * BK);
     }
-    if constexpr (FUSED) {
-      DmaTileLoader<N1T, KB1, NW, 0> wl;
-      const int64_t bytes = ((int64_t)(p.N1 - 1) * p.ldw1 + p.N0) * 2;
-      wl.init(p.W1, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), p.ldw1, p.N1, p.N0, p.cg, 0, 0, wave, lane);
+  }
+  {
+    WTileLoader<N1T, KB1, NT, 1> wl;
+    wl.init(p.W1, p.ldw1, p.N1, p.N0, 0, tid);
 #pragma unroll
-      for (int kt = 0; kt < NKT1; ++kt) wl.issue(kt, W1s + kt * N1T * KB1, p.cg);
-    }
-  } else {
-    {
-      WTileLoader<N0T, BK, NT, 1> wl;
-      wl.init(p.W0, p.ldw0, p.N0, p.K0, 0, tid);
-      for (int kt = 0; kt < nk0; ++kt) {
-        wl.load(kt);
-        wl.store(W0s + kt * N0T * BK);
-      }
-    }
-    if constexpr (FUSED) {
-      WTileLoader<N1T, KB1, NT, 1> wl;
-      wl.init(p.W1, p.ldw1, p.N1, p.N0, 0, tid);
-#pragma unroll
-      for (int kt = 0; kt < NKT1; ++kt) {
-        wl.load(kt);
-        wl.store(W1s + kt * N1T * KB1);
-      }
+    for (int kt = 0; kt < NKT1; ++kt) {
+      wl.load(kt);
+      wl.store(W1s + kt * N1T * KB1);
     }
   }
 
   // ---- the load side of the stream ---------------------------------------------------------------
   XL xl;
   int l_tile = blockIdx.x, l_k = 0, fill = 0, issued = 0;
-  unsigned x_bytes = 0;
-  if constexpr (XMODE == 1)
-    x_bytes = (unsigned)((int64_t)p.cg.H * p.cg.Wi * p.cg.C * 2 * (int64_t)(p.M / (p.cg.P * p.cg.Q)));
   auto init_loader = [&](int tile) {
     const int m0 = tile * BM;
-    if constexpr (XMODE == 0) {
-      const int64_t rem = ((int64_t)(p.M - m0 - 1) * p.ldx + p.K0) * 2;
-      xl.init(p.X + (int64_t)m0 * p.ldx, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldx, p.M - m0, p.K0, p.cg, m0,
-              0, wave, lane);
-    } else {
-      xl.init(p.X, x_bytes, 0, p.M - m0, p.K0, p.cg, m0, 0, wave, lane);
-    }
+    const int64_t rem = ((int64_t)(p.M - m0 - 1) * p.ldx + p.K0) * 2;
+    xl.init(p.X + (int64_t)m0 * p.ldx, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldx, p.M - m0, p.K0, p.cg, m0, 0,
+            wave, lane);
   };
   auto issue_next = [&]() {  // issue stream item `issued` into stage `fill`
     xl.issue(l_k, Xs + fill * BM * BK, p.cg);
@@ -168,7 +134,7 @@ __global__ __launch_bounds__(64 * NW) void stream_kernel(const B2bParams p) {
 #pragma unroll
     for (int b = 0; b < FM; ++b) x[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wave * WTM + b * 32 + l32, chunk));
 #pragma unroll
-    for (int a = 0; a < FN0; ++a) w[a] = *(const half8*)(ws + weight_chunk_offset<BK, WMODE>(a * 32 + l32, chunk));
+    for (int a = 0; a < FN0; ++a) w[a] = *(const half8*)(ws + lds_chunk_offset<BK>(a * 32 + l32, chunk));
   };
   read_frags(0, 0, 0, xf[0], wf[0]);
 
@@ -178,7 +144,7 @@ __global__ __launch_bounds__(64 * NW) void stream_kernel(const B2bParams p) {
   // every row of the wave's slice and every column of the compiled width is valid.  Otherwise the
   // stores are not counted, which only makes the wait below longer.
   unsigned hist = 0;
-  const bool all_cols = (FUSED ? p.N1 == N1T : p.N0 == N0T);
+  const bool all_cols = p.N1 == N1T;
   for (int j = 0; j < n_mine; ++j) {
     const int m0 = ((int)blockIdx.x + j * G) * BM;
     floatx16 acc0[FN0][FM];
@@ -219,82 +185,52 @@ __global__ __launch_bounds__(64 * NW) void stream_kernel(const B2bParams p) {
     }
 
     const int mrow = m0 + wave * WTM + l32;
-    if constexpr (!FUSED) {
-      // ---- single op: epilogue on the accumulators, 8-byte stores -----------------------------
-      const EpilogueArgs ep{p.b0, p.b0_on, p.N0, p.alpha0, p.beta0, p.act0};
-      auto store_tile = [&](auto slow) {
+    // ---- epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 ------------
+    half8 d0[FN0 * 2][FM];
+    b2b_make_d0<FN0, FM>(p, acc0, d0, g);
+    // ---- op1: W1 fragments from LDS with the matching reduction-index permutation ----------
 #pragma unroll
-        for (int a = 0; a < FN0; ++a)
+    for (int c1 = 0; c1 < FN1 / NC1; ++c1) {
+      floatx16 acc1[NC1][FM];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int n = a * 32 + q * 8 + g * 4;
+      for (int a = 0; a < NC1; ++a)
 #pragma unroll
-            for (int b = 0; b < FM; ++b) {
-              const int m = mrow + b * 32;
-              const half4 o = epilogue_quad<decltype(slow)::value>(acc0[a][b], q, n, ep);
-              if (n < p.N0 && m < p.M) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
-            }
-          }
-      };
-      if (p.act0 > ACT_RELU) store_tile(std::true_type{});
-      else store_tile(std::false_type{});
-    } else {
-      // ---- epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 ------------
-      half8 d0[FN0 * 2][FM];
-      b2b_make_d0<FN0, FM>(p, acc0, d0, g);
-      // ---- op1: W1 fragments from LDS with the matching reduction-index permutation ----------
+        for (int b = 0; b < FM; ++b)
 #pragma unroll
-      for (int c1 = 0; c1 < (FUSED ? FN1 / NC1 : 0); ++c1) {
-        floatx16 acc1[NC1][FM];
+          for (int r = 0; r < 16; ++r) acc1[a][b][r] = 0.f;
 #pragma unroll
-        for (int a = 0; a < NC1; ++a)
+      for (int t = 0; t < FN0 * 2; ++t) {
+        const int kbase = t * 16;
+        const int kt1 = kbase / KB1;
+        const int chunk = (kbase % KB1) / 8;
+        const half_t* ws = W1s + kt1 * N1T * KB1;
 #pragma unroll
-          for (int b = 0; b < FM; ++b)
+        for (int a = 0; a < NC1; ++a) {
+          const int row = (c1 * NC1 + a) * 32 + l32;
+          const half4 lo = *(const half4*)(ws + lds_chunk_offset<KB1>(row, chunk) + g * 4);
+          const half4 hi = *(const half4*)(ws + lds_chunk_offset<KB1>(row, chunk + 1) + g * 4);
+          const half8 w1 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc1[a][b][r] = 0.f;
-#pragma unroll
-        for (int t = 0; t < FN0 * 2; ++t) {
-          const int kbase = t * 16;
-          const int kt1 = kbase / KB1;
-          const int chunk = (kbase % KB1) / 8;
-          const half_t* ws = W1s + kt1 * N1T * KB1;
-#pragma unroll
-          for (int a = 0; a < NC1; ++a) {
-            const int row = (c1 * NC1 + a) * 32 + l32;
-            const half4 lo = *(const half4*)(ws + weight_chunk_offset<KB1, WMODE>(row, chunk) + g * 4);
-            const half4 hi = *(const half4*)(ws + weight_chunk_offset<KB1, WMODE>(row, chunk + 1) + g * 4);
-            const half8 w1 = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-#pragma unroll
-            for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(w1, d0[t][b], acc1[a][b]);
-          }
+          for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(w1, d0[t][b], acc1[a][b]);
         }
-        b2b_store_tile<NC1, FM>(p, acc1, mrow, c1 * NC1 * 32 + g * 4);
       }
+      b2b_store_tile<NC1, FM>(p, acc1, mrow, c1 * NC1 * 32 + g * 4);
     }
   }
 }
 
-template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int WMODE, int NS>
+template <int BM, int BK, int NW, int N0T, int N1T, int NS>
 hipError_t launch_stream(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
   static LdsOptIn opt_in;
-  return b2b_launch_common(stream_kernel<BM, BK, NW, N0T, N1T, XMODE, WMODE, NS>, opt_in, p, grid, 64 * NW, lds_bytes,
-                           stream);
+  return b2b_launch_common(stream_kernel<BM, BK, NW, N0T, N1T, NS>, opt_in, p, grid, 64 * NW, lds_bytes, stream);
 }
 
-// mode 0 = RF-resident fusion (or single op when N1T == 0)
-#define BOLT_STREAM_INSTANCE(BM, BK, NW, N0T, N1T, NS, XMODE, WMODE)                                      \
-  {                                                                                                       \
-    "stream_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_s" #NS, 0, BM, BK, NW, 1, N0T, N1T, XMODE, WMODE,   \
-        64 * NW, NS, &bolt::StreamTraits<BM, BK, NW, N0T, N1T, XMODE, WMODE, NS>::lds_bytes,                \
-        &bolt::launch_stream<BM, BK, NW, N0T, N1T, XMODE, WMODE, NS>                                       \
-  }
-
-// The same kernel (N1T = 0) as an entry of the single-op tables: tile_n = the compiled width.
-#define BOLT_STREAM_FPROP_INSTANCE(BM, BK, NW, N0T, NS, XMODE, WMODE)                                         \
-  {                                                                                                           \
-    "stream_" #BM "x" #BK "_w" #NW "_n" #N0T "_s" #NS, BM, N0T, BK, NW, 1, XMODE, WMODE, NS, 0, nullptr, N0T,   \
-        &bolt::StreamTraits<BM, BK, NW, N0T, 0, XMODE, WMODE, NS>::lds_bytes,                                  \
-        &bolt::launch_stream<BM, BK, NW, N0T, 0, XMODE, WMODE, NS>, nullptr, nullptr                           \
+// mode 0 = RF-resident fusion; GEMM rows (x mode 0), row-major weights (w mode 1)
+#define BOLT_STREAM_INSTANCE(BM, BK, NW, N0T, N1T, NS)                                                  \
+  {                                                                                                     \
+    "stream_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_s" #NS, 0, BM, BK, NW, 1, N0T, N1T, 0, 1, 64 * NW, \
+        NS, &bolt::StreamTraits<BM, BK, NW, N0T, N1T, NS>::lds_bytes,                                   \
+        &bolt::launch_stream<BM, BK, NW, N0T, N1T, NS>                                                  \
   }
 
 }  // namespace bolt

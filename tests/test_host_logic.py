@@ -168,12 +168,17 @@ def test_fused_pair_residual_instance_sets(bolt):
         b = {i for i in range(n) if bolt.bolt_instance_supports(res, i, d0, d1)}
         assert b and b <= a
         assert bolt.bolt_check(res, d0, d1) == OK
-        if plain == bolt.OP_B2B_CONV:  # the streaming weights-resident conv instances lack it
-            assert b < a and bolt.bolt_check(res, d0, d1, {"kernel_id": min(a - b)}) == UNSUPPORTED
         assert bolt.bolt_check(res, d0, d1, {"kernel_id": min(b)}) == OK
         assert bolt.bolt_instance_config(res, min(b)).as_dict() == bolt.bolt_instance_config(plain, min(b)).as_dict()
-    # row-major weights: only the weights-resident kernels take them, and those have the residual epilogue too
-    assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, G(16384, 64, 256), G(16384, 128, 64)) == OK
+    # row-major weights: only the weights-resident kernels take them; the register / LDS residence ones have the
+    # residual epilogue, the persistent streaming one does not
+    k0, k1 = G(16384, 64, 256), G(16384, 128, 64)
+    n = bolt.bolt_num_instances(bolt.OP_B2B_GEMM)
+    a = {i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM, i, k0, k1)}
+    b = {i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM_RES, i, k0, k1)}
+    assert b and b < a
+    assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, k0, k1) == OK
+    assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, k0, k1, {"kernel_id": min(a - b)}) == UNSUPPORTED
     assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, g0, G(16000, 128, 64, b_layout=nk)) == ILLEGAL
 
 
