@@ -610,6 +610,7 @@ static bool chain_supports(const ChainInstance& in, const B2bProblem& pr) {
   // threadblock residence with the tightest compiled bounds: no more than 2x padding per op
   if ((in.n0t > 64 && in.n0t / 2 >= p.N0) || (in.n1t > 64 && in.n1t / 2 >= p.N1) || (in.n2t > 64 && in.n2t / 2 >= p.N2))
     return false;
+  if (in.dyn_supports) return in.dyn_supports(p) && in.dyn_lds_bytes(p) <= kLdsPerCU;
   return in.lds_bytes <= kLdsPerCU;
 }
 

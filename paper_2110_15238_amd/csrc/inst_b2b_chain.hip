@@ -13,8 +13,15 @@ void register_gemm_chain_instances(std::vector<ChainInstance>& v) {
   static const ChainInstance table[] = {BOLT_CHAIN_WIDTHS(CH, 0)};
   for (const auto& t : table) v.push_back(t);
 }
+// CHH(BM, WAVES, N0T, N1T, N2T, STAGES, XI): first op on the halo main loop (stride-1 "same" filters, C % 64 == 0)
+#define CHH(BM, NW, N0T, N1T, N2T, NS, XI) BOLT_B2B_CHAIN_HALO_INSTANCE(BM, NW, N0T, N1T, N2T, NS, XI)
 void register_conv_chain_instances(std::vector<ChainInstance>& v) {
-  static const ChainInstance table[] = {BOLT_CHAIN_WIDTHS(CH, 1)};
+  static const ChainInstance table[] = {
+      BOLT_CHAIN_WIDTHS(CH, 1),
+      CHH(128, 4, 64, 64, 64, 2, 2),  CHH(128, 4, 64, 64, 64, 3, 2),  CHH(256, 4, 64, 64, 64, 2, 2),
+      CHH(128, 4, 64, 64, 128, 2, 2), CHH(128, 4, 64, 128, 64, 2, 2), CHH(128, 4, 64, 64, 256, 2, 2),
+      CHH(128, 4, 64, 128, 128, 2, 2), CHH(128, 4, 128, 64, 64, 2, 2), CHH(128, 4, 128, 128, 128, 2, 2),
+  };
   for (const auto& t : table) v.push_back(t);
 }
 }  // namespace bolt

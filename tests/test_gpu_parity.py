@@ -1096,7 +1096,10 @@ def test_gemm_chain3_every_instance(bolt, shape):
 
 CONV_CHAINS = [  # (N, H, W, C, K0, R, S, stride, pad, K1, K2)
     (2, 12, 12, 64, 64, 3, 3, 1, 1, 64, 64), (1, 17, 13, 24, 48, 3, 3, 2, 1, 48, 48), (2, 23, 23, 8, 64, 7, 7, 2, 3, 64, 256),
-    (3, 9, 11, 64, 64, 1, 1, 1, 0, 256, 64), (1, 10, 9, 16, 128, 5, 3, (1, 2), (2, 0), 64, 128)]
+    (3, 9, 11, 64, 64, 1, 1, 1, 0, 256, 64), (1, 10, 9, 16, 128, 5, 3, (1, 2), (2, 0), 64, 128),
+    # stride-1 "same" first filters over whole 64-channel chunks: also the chains whose first op re-uses the halo
+    (2, 9, 10, 128, 64, 3, 3, 1, 1, 64, 256), (1, 11, 9, 192, 128, 5, 3, 1, (2, 1), 120, 128), (2, 12, 12, 64, 64, 3, 3, 1, 1, 128, 40),
+    (3, 30, 30, 64, 64, 3, 3, 1, 1, 64, 128), (2, 10, 10, 64, 64, 3, 3, 1, 1, 128, 128), (1, 9, 12, 128, 128, 3, 3, 1, 1, 64, 64)]
 
 
 @pytest.mark.parametrize("shape", CONV_CHAINS)
@@ -1192,7 +1195,7 @@ def test_gemm_chain3_residual_every_instance(bolt, shape):
             bolt.bolt_b2b_gemm_chain_residual(descs, dev(A), Wd, bd, C_arg, D2, gamma=1.0, **kwargs)
 
 
-@pytest.mark.parametrize("shape", [CONV_CHAINS[0], CONV_CHAINS[1], CONV_CHAINS[3]])
+@pytest.mark.parametrize("shape", [CONV_CHAINS[0], CONV_CHAINS[1], CONV_CHAINS[3], CONV_CHAINS[5], CONV_CHAINS[6]])
 def test_conv_chain3_residual_every_instance(bolt, shape):
     N, H, W, Cc, K0, R, S, stride, pad, K1, K2 = shape
     x = wl.uniform_fp16(312, 0, (N, H, W, Cc), -1, 1)

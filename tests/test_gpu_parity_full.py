@@ -160,7 +160,10 @@ def test_b2b_conv_integer_bit_exact_every_instance(bolt, shape):
 
 
 @pytest.mark.parametrize("shape", [(2, 12, 12, 64, 64, 3, 3, 1, 1, 64, 64), (1, 17, 13, 24, 48, 3, 3, 2, 1, 48, 48),
-                                   (2, 23, 23, 8, 64, 7, 7, 2, 3, 64, 256), (3, 9, 11, 64, 64, 1, 1, 1, 0, 256, 64)])
+                                   (2, 23, 23, 8, 64, 7, 7, 2, 3, 64, 256), (3, 9, 11, 64, 64, 1, 1, 1, 0, 256, 64),
+                                   (2, 9, 10, 128, 64, 3, 3, 1, 1, 64, 256), (1, 11, 9, 192, 128, 5, 3, 1, (2, 1), 120, 128),
+                                   (3, 30, 30, 64, 64, 3, 3, 1, 1, 64, 128), (2, 10, 10, 64, 64, 3, 3, 1, 1, 128, 128),
+                                   (1, 9, 12, 128, 128, 3, 3, 1, 1, 64, 64)])
 def test_conv_chain3_integer_bit_exact_every_instance(bolt, shape):
     N, H, W, Cc, K0, R, S, stride, pad, K1, K2 = shape
     x = wl.integer_fp16(602, 0, (N, H, W, Cc), -1, 1)
