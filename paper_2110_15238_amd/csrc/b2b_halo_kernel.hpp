@@ -86,6 +86,92 @@ hipError_t launch_b2b_halo(const B2bParams& p, int /*grid*/, int lds_bytes, hipS
                            stream);
 }
 
+// The same pair with op1 taken in chunks of 64 output columns, for wide second ops (N1 = 256: the bottleneck pair
+// 64 -> 256 of Section 4.1.2).  A resident W1 of 64 x 256 costs 32 KB and its accumulators 128 registers per 32 rows,
+// which limits the kernel above to 128-row tiles with 32 x 64 wave tiles (every wave re-reads all of W0 per filter
+// tap: LDS-bound) and two rounds of workgroups.  Here only two chunks of W1 have LDS of their own; the others land in
+// the W0 stages once the main loop has retired them, each chunk's 64 accumulator columns leave through a [BM][64]
+// staging tile over the dead halo buffer before the next chunk is computed, so 256-row tiles with 64 x 64 wave
+// tiles fit twice on a compute unit and config 4's 392 tiles run in one round.
+template <int BM, int NW, int N0T, int N1T, int NS, int XI>
+struct B2bHaloChunkedTraits {
+  using Halo = ConvHaloTraits<BM, N0T, NW, 1, NS, XI, 1>;
+  static constexpr int NC = 64;                 // columns of op1 per chunk
+  static constexpr int NCHUNK = N1T / NC;
+  static constexpr int OWN = NCHUNK < 2 ? NCHUNK : 2;  // chunks with LDS of their own (fetched before the main loop)
+  static constexpr int SLOT = NC * N0T;         // halves of one chunk of W1 = one W0 stage
+  static constexpr int WTM = BM / NW, FM = WTM / 32, FN0 = N0T / 32;
+  static_assert(N1T % NC == 0 && NCHUNK - OWN <= NS, "the late chunks of W1 re-use the W0 stages");
+  static_assert(WTM % 32 == 0 && N0T % 32 == 0, "tile shape");
+  static bool supports(const B2bParams& p) { return Halo::supports(B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::as_fprop(p)); }
+  static int lds_bytes(const B2bParams& p) { return (Halo::group_halves(p.cg) + OWN * SLOT) * 2; }  // >= the [BM][64] staging tile
+};
+
+template <int BM, int NW, int N0T, int N1T, int NS, int XI, bool RES = false>
+__global__ __launch_bounds__(64 * NW, 2) void b2b_halo_chunked_kernel(const B2bParams p) {
+  using T = B2bHaloChunkedTraits<BM, NW, N0T, N1T, NS, XI>;
+  constexpr int FM = T::FM, FN0 = T::FN0, NC = T::NC, NCHUNK = T::NCHUNK, OWN = T::OWN, SLOT = T::SLOT;
+
+  extern __shared__ __attribute__((aligned(16))) half_t lds[];
+  half_t* own = lds + T::Halo::group_halves(p.cg);            // chunks 0 .. OWN-1 of W1
+  half_t* stages = own - NS * N0T * 64;                        // the W0 stages of the main loop: chunks OWN .. of W1
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, l32 = lane & 31;
+  const int m0 = blockIdx.x * BM;
+  auto issue_chunk = [&](int c, half_t* dst) {  // rows [c * NC, ...) of W1; rows past N1 are zero-filled
+    const int left = p.N1 - c * NC;
+    b2b_issue_weights<NC, N0T, NW>(p.W1 + (int64_t)c * NC * p.ldw1, p.ldw1, left > 0 ? (left < NC ? left : NC) : 1, left > 0 ? p.N0 : 0,
+                                   dst, p.cg, wave, lane);
+  };
+
+  // the first chunks of W1: the oldest loads, the main loop's first wait covers them
+#pragma unroll
+  for (int c = 0; c < OWN; ++c) issue_chunk(c, own + c * SLOT);
+
+  floatx16 acc0[FN0][FM];
+  {
+    const HaloArgs h{p.X, p.W0, p.N0, p.M, p.K0, p.ldw0, p.cg, m0};
+    conv_halo_mainloop<BM, N0T, NW, 1, NS, XI, 1>(h, lds, acc0);
+  }
+  // every wave has passed the main loop's last barrier, which follows the last read of a W0 stage that is used
+#pragma unroll
+  for (int c = OWN; c < NCHUNK; ++c) issue_chunk(c, stages + (c - OWN) * SLOT);
+
+  half8 d0[FN0 * 2][FM];
+  b2b_make_d0<FN0, FM>(p, acc0, d0, g);
+
+#pragma unroll
+  for (int c = 0; c < NCHUNK; ++c) {
+    if (c * NC >= p.N1) break;  // uniform over the workgroup
+    floatx16 acc1[NC / 32][FM];
+    b2b_rf_gemm<N0T, NC, FM>(c < OWN ? own + c * SLOT : stages + (c - OWN) * SLOT, d0, acc1, l32, g);
+    // this wave's share of the late chunks has landed; the barrier that opens b2b_tile_out publishes it
+    if (c == 0 && NCHUNK > OWN) __builtin_amdgcn_s_waitcnt(0x0F70);
+    const EpilogueArgs ep{p.b1 + c * NC, p.b1_on, p.N1 - c * NC, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
+    b2b_tile_out<BM, NW, NC, RES>(lds, acc1, ep, p.Y + c * NC, p.ldy, p.M, m0, wave, tid, RES ? p.res + c * NC : nullptr, p.ldr);
+  }
+}
+
+template <int BM, int NW, int N0T, int N1T, int NS, int XI>
+hipError_t launch_b2b_halo_chunked(const B2bParams& p, int /*grid*/, int lds_bytes, hipStream_t stream) {
+  static LdsOptIn opt_in[2];
+  if (p.res)
+    return b2b_launch_common(b2b_halo_chunked_kernel<BM, NW, N0T, N1T, NS, XI, true>, opt_in[1], p, p.tiles_m, 64 * NW,
+                             lds_bytes, stream);
+  return b2b_launch_common(b2b_halo_chunked_kernel<BM, NW, N0T, N1T, NS, XI, false>, opt_in[0], p, p.tiles_m, 64 * NW,
+                           lds_bytes, stream);
+}
+
+#define BOLT_B2B_HALO_CHUNKED_INSTANCE(BM, NW, N0T, N1T, NS, XI)                                               \
+  {                                                                                                            \
+    "b2bhalo_c64_" #BM "_w" #NW "_n" #N0T "_" #N1T "_s" #NS "_x" #XI, 0, BM, 64, NW, 1, N0T, N1T, 1, 0, 64 * NW,  \
+        NS, nullptr, &bolt::launch_b2b_halo_chunked<BM, NW, N0T, N1T, NS, XI>,                                   \
+        &bolt::B2bHaloChunkedTraits<BM, NW, N0T, N1T, NS, XI>::supports,                                         \
+        &bolt::B2bHaloChunkedTraits<BM, NW, N0T, N1T, NS, XI>::lds_bytes, true                                   \
+  }
+
 // mode 0 = RF-resident fusion; legality and LDS need depend on the geometry (dyn hooks)
 #define BOLT_B2B_HALO_INSTANCE(BM, NW, N0T, N1T, NS, XI)                                                  \
   {                                                                                                       \

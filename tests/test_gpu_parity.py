@@ -567,6 +567,9 @@ def test_config4_b2b_conv_full_size_tuned_sampled_rows(bolt):
 B2B_CONV_SHAPES = [  # N H W C K0 stride K1
     (2, 20, 20, 8, 48, 2, 48), (1, 15, 17, 48, 48, 1, 48), (2, 12, 12, 64, 64, 2, 64), (1, 9, 9, 16, 32, 1, 32),
     (1, 11, 11, 24, 128, 1, 128),
+    # stride-1 "same" first op over whole 64-channel chunks with a wide second op: the instances that take op1 in
+    # chunks of 64 columns (a partial last chunk, a chunk that is skipped, two halo buffers)
+    (1, 10, 12, 64, 64, 1, 200), (2, 9, 10, 64, 40, 1, 136), (1, 12, 9, 128, 64, 1, 256),
 ]
 
 

@@ -126,7 +126,7 @@ def _sparse(w):
 
 B2B_CONV_INT = [  # N H W C K0 stride K1: stride-1 "same" shapes (halo family), stride 2, thin and ragged widths
     (2, 12, 12, 64, 64, 1, 256), (2, 12, 12, 64, 64, 2, 64), (1, 15, 17, 48, 48, 1, 48), (2, 20, 20, 8, 48, 2, 48),
-    (3, 9, 11, 128, 64, 1, 128), (1, 11, 11, 24, 128, 1, 128),
+    (3, 9, 11, 128, 64, 1, 128), (1, 11, 11, 24, 128, 1, 128), (1, 10, 12, 64, 64, 1, 200), (2, 9, 10, 64, 40, 1, 136),
 ]
 
 
