@@ -274,7 +274,7 @@ hipError_t launch_b2b_dma(const B2bParams& p, int /*grid*/, int lds_bytes, hipSt
   {                                                                                                       \
     "b2bdma_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_s" #NS, 0, BM, BK, NW, 1, N0T, N1T, XMODE, 0, 64 * NW, \
         NS, &bolt::B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::lds_bytes,                                \
-        &bolt::launch_b2b_dma<BM, BK, NW, N0T, N1T, XMODE, NS>, nullptr, nullptr, true                     \
+        &bolt::launch_b2b_dma<BM, BK, NW, N0T, N1T, XMODE, NS>, nullptr, nullptr, true, 0.5f               \
   }
 
 }  // namespace bolt

@@ -169,7 +169,7 @@ hipError_t launch_b2b_halo_chunked(const B2bParams& p, int /*grid*/, int lds_byt
     "b2bhalo_c64_" #BM "_w" #NW "_n" #N0T "_" #N1T "_s" #NS "_x" #XI, 0, BM, 64, NW, 1, N0T, N1T, 1, 0, 64 * NW,  \
         NS, nullptr, &bolt::launch_b2b_halo_chunked<BM, NW, N0T, N1T, NS, XI>,                                   \
         &bolt::B2bHaloChunkedTraits<BM, NW, N0T, N1T, NS, XI>::supports,                                         \
-        &bolt::B2bHaloChunkedTraits<BM, NW, N0T, N1T, NS, XI>::lds_bytes, true                                   \
+        &bolt::B2bHaloChunkedTraits<BM, NW, N0T, N1T, NS, XI>::lds_bytes, true, 0.3f                             \
   }
 
 // mode 0 = RF-resident fusion; legality and LDS need depend on the geometry (dyn hooks)
@@ -178,7 +178,7 @@ hipError_t launch_b2b_halo_chunked(const B2bParams& p, int /*grid*/, int lds_byt
     "b2bhalo_" #BM "_w" #NW "_n" #N0T "_" #N1T "_s" #NS "_x" #XI, 0, BM, 64, NW, 1, N0T, N1T, 1, 0, 64 * NW, \
         NS, nullptr, &bolt::launch_b2b_halo<BM, NW, N0T, N1T, NS, XI>,                                     \
         &bolt::B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::supports,                                          \
-        &bolt::B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::lds_bytes, true                                    \
+        &bolt::B2bHaloTraits<BM, NW, N0T, N1T, NS, XI>::lds_bytes, true, 0.4f                              \
   }
 
 }  // namespace bolt

@@ -391,6 +391,9 @@ struct B2bInstance {
   bool (*dyn_supports)(const B2bParams&);
   int (*dyn_lds_bytes)(const B2bParams&);
   bool residual;  // has the variant whose last epilogue adds a full matrix C (B2bParams::res)
+  // Relative time per unit of tile work of this kernel family on the convolution pairs of Section 4.1.2, as measured
+  // (0 = 1.0: the weights-resident kernels); read by the built-in pick rule only, bolt_tune measures.
+  float prior;
 };
 
 template <typename KernT>

@@ -534,8 +534,12 @@ static int b2b_heuristic(const std::vector<B2bInstance>& tab, const B2bProblem& 
     if (!b2b_supports(tab[i], pr)) continue;
     const B2bInstance& in = tab[i];
     const double tiles = ceil_div(pr.p.M, in.bm);
-    const double rounds = std::ceil(tiles / kNumCU);
-    double cost = rounds * in.bm * (in.mode == 0 ? 1.0 : 1.1) * (double)in.n0t * in.n1t;
+    const int lds = in.dyn_lds_bytes ? in.dyn_lds_bytes(pr.p) : in.lds_bytes(pr.p.K0);
+    const int per_cu = std::max(1, std::min(kLdsPerCU / std::max(lds, 1), 2048 / in.nthreads));  // co-resident workgroups
+    const double rounds = std::ceil(tiles / (kNumCU * per_cu)) * per_cu;
+    const double kpad = (double)ceil_div(pr.p.K0, in.bk) * in.bk;  // a short reduction pays for the whole last k-tile
+    double cost = rounds * in.bm * (in.mode == 0 ? 1.0 : 1.1) * (kpad * in.n0t + (double)in.n0t * in.n1t) *
+                  (in.prior > 0.f ? in.prior : 1.0);
     if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
   }
   return best;
