@@ -167,8 +167,18 @@ __global__ __launch_bounds__(256, 3) void conv_smallc_kernel(const FpropParams p
       }
     }
   };
-  TileAt cur = locate((int)blockIdx.x < total ? blockIdx.x : 0);
-  if ((int)blockIdx.x < total) fetch(cur);
+  // This workgroup's tiles: first, first + step, ... below end.  Consecutive workgroup ids land on consecutive XCDs
+  // (8, each with an L2 of its own), and neighbouring output rows share R - stride input rows: every XCD takes one
+  // contiguous eighth of the tiles, so that the rows its workgroups have in flight are neighbours in one L2.
+  int first = blockIdx.x, step = gridDim.x, end = total;
+  if ((gridDim.x & 7) == 0 && total >= (int)gridDim.x) {
+    const int band = (total + 7) >> 3, xcd = blockIdx.x & 7;
+    first = xcd * band + (int)(blockIdx.x >> 3);
+    step = gridDim.x >> 3;
+    end = (xcd + 1) * band < total ? (xcd + 1) * band : total;
+  }
+  TileAt cur = locate(first < end ? first : 0);
+  if (first < end) fetch(cur);
 
   // ---- weights and masks: global [K][R][S][C] -> LDS in fragment order ---------------------------------------------
   // Four threads per output channel, each every fourth fragment (r, fr) of it: the 8 halves w[ch][r][8 * fr ..] are
@@ -225,12 +235,12 @@ __global__ __launch_bounds__(256, 3) void conv_smallc_kernel(const FpropParams p
     bias_h[hb] = (n < p.N && p.bias_on) ? got : half8{0, 0, 0, 0, 0, 0, 0, 0};
   }
 
-  for (int tile = blockIdx.x; tile < total; tile += gridDim.x) {
+  for (int tile = first; tile < end; tile += step) {
     scatter(cur);
     __syncthreads();
     const int orow = cur.orow, q0 = cur.q0;
-    if (tile + (int)gridDim.x < total) {
-      cur = locate(tile + gridDim.x);
+    if (tile + step < end) {
+      cur = locate(tile + step);
       fetch(cur);
     }
 
