@@ -766,7 +766,9 @@ static bolt_status tune_candidates(std::vector<Candidate>& cands, RunF&& run, hi
   if (status == BOLT_OK) {
     std::vector<Candidate*> order;
     for (auto& c : cands) if (c.ms >= 0.f) order.push_back(&c);
-    std::sort(order.begin(), order.end(), [](Candidate* a, Candidate* b) { return a->ms < b->ms; });
+    // Near-ties go to the XCD-aware tile order: the same time with fewer operand bytes crossing the fabric.
+    auto score = [](const Candidate* c) { return c->ms * (c->swizzle > 0 ? 0.985f : 1.f); };
+    std::sort(order.begin(), order.end(), [&](Candidate* a, Candidate* b) { return score(a) < score(b); });
     // pass 2: the few fastest again, longer
     const int finalists = std::min<int>(6, (int)order.size());
     Candidate* win = nullptr;
@@ -774,7 +776,7 @@ static bolt_status tune_candidates(std::vector<Candidate>& cands, RunF&& run, hi
       Candidate* c = order[i];
       bolt_status s = time_launches([&] { return run(*c); }, 3, 60, stream, e0, e1, &c->ms);
       if (s != BOLT_OK) { status = s; break; }
-      if (!win || c->ms < win->ms) win = c;
+      if (!win || score(c) < score(win)) win = c;
     }
     if (status == BOLT_OK) { *best = *win; *tried = n_ok; }
   }
