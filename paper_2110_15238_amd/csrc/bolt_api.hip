@@ -509,14 +509,27 @@ struct B2bProblem {
   bool residual;  // the call carries a residual matrix for the last op: kernels without that epilogue are excluded
 };
 
-static bool b2b_supports(const B2bInstance& in, const B2bProblem& pr) {
+// Can this instance run the problem at all (threadblock residence within its compiled widths, LDS)?
+static bool b2b_can_run(const B2bInstance& in, const B2bProblem& pr) {
   if (in.xmode != pr.xmode || in.wmode != pr.wmode) return false;
   if (pr.residual && !in.residual) return false;
   if (pr.p.N0 > in.n0t || pr.p.N1 > in.n1t) return false;
-  // threadblock residence with the tightest compiled bound: do not carry more than 2x padding
-  if ((in.n0t > 32 && in.n0t / 2 >= pr.p.N0) || (in.n1t > 32 && in.n1t / 2 >= pr.p.N1)) return false;
   if (in.dyn_supports) return in.dyn_supports(pr.p) && in.dyn_lds_bytes(pr.p) <= kLdsPerCU;
   if (in.lds_bytes(pr.p.K0) > kLdsPerCU) return false;
+  return true;
+}
+// Threadblock residence with the tightest compiled bound: an instance that would carry more than 2x padding in a
+// width is left out ...
+static bool b2b_is_tight(const B2bInstance& in, const B2bProblem& pr) {
+  return !((in.n0t > 32 && in.n0t / 2 >= pr.p.N0) || (in.n1t > 32 && in.n1t / 2 >= pr.p.N1));
+}
+// ... unless that leaves the problem without a kernel (e.g. N0 = 128 with N1 = 16: no compiled pair of widths is tight
+// in both).
+static bool b2b_supports(const std::vector<B2bInstance>& tab, int id, const B2bProblem& pr) {
+  if (!b2b_can_run(tab[id], pr)) return false;
+  if (b2b_is_tight(tab[id], pr)) return true;
+  for (const B2bInstance& other : tab)
+    if (b2b_can_run(other, pr) && b2b_is_tight(other, pr)) return false;
   return true;
 }
 
@@ -531,7 +544,7 @@ static int b2b_heuristic(const std::vector<B2bInstance>& tab, const B2bProblem& 
   int best = -1;
   double best_cost = 0;
   for (int i = 0; i < (int)tab.size(); ++i) {
-    if (!b2b_supports(tab[i], pr)) continue;
+    if (!b2b_supports(tab, i, pr)) continue;
     const B2bInstance& in = tab[i];
     const double tiles = ceil_div(pr.p.M, in.bm);
     const int lds = in.dyn_lds_bytes ? in.dyn_lds_bytes(pr.p) : in.lds_bytes(pr.p.K0);
@@ -595,7 +608,7 @@ static bolt_status resolve_b2b(const std::vector<B2bInstance>& tab, const B2bPro
                                int* id) {
   if (cfg && cfg->kernel_id >= 0) {
     if (cfg->kernel_id >= (int)tab.size()) return BOLT_ERR_INVALID_ARG;
-    if (!b2b_supports(tab[cfg->kernel_id], pr)) return BOLT_ERR_UNSUPPORTED;
+    if (!b2b_supports(tab, cfg->kernel_id, pr)) return BOLT_ERR_UNSUPPORTED;
     *id = cfg->kernel_id;
     return BOLT_OK;
   }
@@ -607,15 +620,25 @@ static bolt_status resolve_b2b(const std::vector<B2bInstance>& tab, const B2bPro
 // ------------------------------------------------------------------------------------------
 // three-op chains
 // ------------------------------------------------------------------------------------------
-static bool chain_supports(const ChainInstance& in, const B2bProblem& pr) {
+static bool chain_can_run(const ChainInstance& in, const B2bProblem& pr) {
   if (in.xmode != pr.xmode || pr.wmode != 0) return false;
   const B2bParams& p = pr.p;
   if (p.N0 > in.n0t || p.N1 > in.n1t || p.N2 > in.n2t) return false;
-  // threadblock residence with the tightest compiled bounds: no more than 2x padding per op
-  if ((in.n0t > 64 && in.n0t / 2 >= p.N0) || (in.n1t > 64 && in.n1t / 2 >= p.N1) || (in.n2t > 64 && in.n2t / 2 >= p.N2))
-    return false;
   if (in.dyn_supports) return in.dyn_supports(p) && in.dyn_lds_bytes(p) <= kLdsPerCU;
   return in.lds_bytes <= kLdsPerCU;
+}
+// threadblock residence with the tightest compiled bounds: no more than 2x padding per op ...
+static bool chain_is_tight(const ChainInstance& in, const B2bProblem& pr) {
+  const B2bParams& p = pr.p;
+  return !((in.n0t > 64 && in.n0t / 2 >= p.N0) || (in.n1t > 64 && in.n1t / 2 >= p.N1) || (in.n2t > 64 && in.n2t / 2 >= p.N2));
+}
+// ... unless no instance that can run the problem is tight in all three widths
+static bool chain_supports(const std::vector<ChainInstance>& tab, int id, const B2bProblem& pr) {
+  if (!chain_can_run(tab[id], pr)) return false;
+  if (chain_is_tight(tab[id], pr)) return true;
+  for (const ChainInstance& other : tab)
+    if (chain_can_run(other, pr) && chain_is_tight(other, pr)) return false;
+  return true;
 }
 
 static void chain_fill_config(const ChainInstance& in, int id, bolt_config* c) {
@@ -672,7 +695,7 @@ static int chain_heuristic(const std::vector<ChainInstance>& tab, const B2bProbl
   int best = -1;
   double best_cost = 0;
   for (int i = 0; i < (int)tab.size(); ++i) {
-    if (!chain_supports(tab[i], pr)) continue;
+    if (!chain_supports(tab, i, pr)) continue;
     const double cost = (double)tab[i].n0t * tab[i].n1t + (double)tab[i].n1t * tab[i].n2t + 1e-3 * tab[i].lds_bytes;
     if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
   }
@@ -683,7 +706,7 @@ static bolt_status resolve_chain(const std::vector<ChainInstance>& tab, const B2
                                  int* id) {
   if (cfg && cfg->kernel_id >= 0) {
     if (cfg->kernel_id >= (int)tab.size()) return BOLT_ERR_INVALID_ARG;
-    if (!chain_supports(tab[cfg->kernel_id], pr)) return BOLT_ERR_UNSUPPORTED;
+    if (!chain_supports(tab, cfg->kernel_id, pr)) return BOLT_ERR_UNSUPPORTED;
     *id = cfg->kernel_id;
     return BOLT_OK;
   }
@@ -875,11 +898,11 @@ int32_t bolt_instance_supports(bolt_op op, int32_t id, const void* desc0, const 
     case BOLT_OP_B2B_GEMM: case BOLT_OP_B2B_GEMM_RES:
       if (make_b2b_gemm_problem((const bolt_gemm_desc*)desc0, (const bolt_gemm_desc*)desc1, &bp) != BOLT_OK) return 0;
       bp.residual = op == BOLT_OP_B2B_GEMM_RES;
-      return b2b_supports(tables().b2b_gemm[id], bp);
+      return b2b_supports(tables().b2b_gemm, id, bp);
     case BOLT_OP_B2B_CONV: case BOLT_OP_B2B_CONV_RES:
       if (make_b2b_conv_problem((const bolt_conv_desc*)desc0, (const bolt_conv_desc*)desc1, &bp) != BOLT_OK) return 0;
       bp.residual = op == BOLT_OP_B2B_CONV_RES;
-      return b2b_supports(tables().b2b_conv[id], bp);
+      return b2b_supports(tables().b2b_conv, id, bp);
     default: return 0;
   }
 }
@@ -1182,7 +1205,7 @@ bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const vo
     }
     std::vector<Candidate> cands;
     for (int i = 0; i < (int)tab.size(); ++i)
-      if (b2b_supports(tab[i], bp)) cands.push_back({i, 0, 1, 0.f});
+      if (b2b_supports(tab, i, bp)) cands.push_back({i, 0, 1, 0.f});
     if (cands.empty()) return BOLT_ERR_UNSUPPORTED;
     if (tune_log_enabled())
       std::fprintf(stderr, "[bolt_tune] problem op %d M %d N0 %d K0 %d N1 %d: %zu candidates\n", (int)op, p.M, p.N0, p.K0, p.N1, cands.size());
@@ -1211,7 +1234,7 @@ int32_t bolt_chain_instance_supports(bolt_op op, int32_t kernel_id, int32_t n_op
   B2bProblem pr;
   if (make_chain_problem(op, n_ops, descs, &pr) != BOLT_OK) return 0;
   const auto& tab = op == BOLT_OP_GEMM_CHAIN3 ? tables().gemm_chain : tables().conv_chain;
-  return kernel_id >= 0 && kernel_id < (int)tab.size() && chain_supports(tab[kernel_id], pr);
+  return kernel_id >= 0 && kernel_id < (int)tab.size() && chain_supports(tab, kernel_id, pr);
 }
 
 // ptrs: {x, w0, b0, w1, b1, w2, b2, y}
@@ -1292,7 +1315,7 @@ bolt_status bolt_tune_chain(bolt_op op, int32_t n_ops, const void* const* descs,
   const auto& tab = op == BOLT_OP_GEMM_CHAIN3 ? tables().gemm_chain : tables().conv_chain;
   std::vector<Candidate> cands;
   for (int i = 0; i < (int)tab.size(); ++i)
-    if (chain_supports(tab[i], pr)) cands.push_back({i, 0, 1, 0.f});
+    if (chain_supports(tab, i, pr)) cands.push_back({i, 0, 1, 0.f});
   if (cands.empty()) return BOLT_ERR_UNSUPPORTED;
   Candidate win{};
   int tried = 0;

@@ -153,6 +153,9 @@ def test_b2b_fusion_legality(bolt):
     assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 28, 28, 64, 256, 1, 1, 1, 0)) == ILLEGAL   # extent must match
     c0s = Cd(32, 56, 56, 64, 64, 3, 3, 2, 1)
     assert chk(bolt.OP_B2B_CONV, c0s, Cd(32, 28, 28, 64, 64, 1, 1, 1, 0)) == OK
+    # no compiled pair of widths is within 2x of (128, 16): the padding rule gives way rather than refuse the pair
+    assert chk(bolt.OP_B2B_CONV, Cd(2, 12, 12, 64, 128, 3, 3, 1, 1), Cd(2, 12, 12, 128, 16, 1, 1, 1, 0)) == OK
+    assert chk(bolt.OP_B2B_CONV, Cd(2, 12, 12, 64, 128, 3, 3, 1, 1), Cd(2, 12, 12, 128, 256, 1, 1, 1, 0)) == UNSUPPORTED  # no tile spans it
 
 
 def test_fused_pair_residual_instance_sets(bolt):
