@@ -73,8 +73,8 @@ def main():
 
     def timed(fn, reps):
         """GPU ms per call of fn: the median of REPS_MEDIAN repetitions, each `reps` calls enqueued back to back on
-        the launch stream between two events (Section 4's protocol of averaged repeated runs; the survey's
-        timing protocol asks for the median of at least five repetitions).
+        the launch stream between two events (Section 4's protocol of averaged repeated runs; the median of
+        five repetitions rejects the occasional slow one).
 
         The calls are captured into a HIP graph once and every repetition is one replay: issuing a call from
         Python costs ~5 us of host time, as much as the shortest kernels run, so an eager loop would time the
