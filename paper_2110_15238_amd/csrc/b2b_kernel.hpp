@@ -57,9 +57,66 @@ struct B2bK1 {
   static constexpr int NKT1 = N0T / KB1;
 };
 
+// Row-major weights ([K][N]): both matrices as one flat list of 8 x 8 blocks (a thread fetches 8 rows of 16 bytes,
+// transposes them in registers and writes 8 reduction-contiguous chunks), dealt over ALL threads two blocks at a
+// time with every load of a batch in flight before the first transpose - one memory round trip for the pair of
+// matrices of Table 1's shapes, where a k-tile at a time costs one per k-tile with a single wave at work.
+template <int BK, int NT, int N0T, int N1T>
+__device__ __forceinline__ void b2b_preload_weights_kn(const B2bParams& p, half_t* W0s, half_t* W1s, int tid) {
+  constexpr int KB1 = B2bK1<N0T>::KB1, NKT1 = B2bK1<N0T>::NKT1;
+  constexpr int NB0 = (BK / 8) * (N0T / 8);   // blocks per k-tile of W0
+  constexpr int NB1 = (KB1 / 8) * (N1T / 8);  // ... of W1
+  constexpr int U = 2;
+  const int nk0 = (p.K0 + BK - 1) / BK;
+  const int total0 = nk0 * NB0, total = total0 + NKT1 * NB1;
+  const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int base = 0; base < total; base += U * NT) {
+    half8 r[U][8];
+    half_t* dst[U];
+    int kb[U], row0[U];
+    bool first[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int blk = base + u * NT + tid;
+      first[u] = blk < total0;
+      const int w = first[u] ? blk % NB0 : (blk - total0) % NB1;
+      const int kt = first[u] ? blk / NB0 : (blk - total0) / NB1;
+      const int nblocks = first[u] ? N0T / 8 : N1T / 8;
+      const int nb = w % nblocks;
+      kb[u] = w / nblocks;
+      row0[u] = nb * 8;
+      const half_t* src = first[u] ? p.W0 : p.W1;
+      const int ld = first[u] ? p.ldw0 : p.ldw1;
+      const int kmax = first[u] ? p.K0 : p.N0, nmax = first[u] ? p.N0 : p.N1;
+      const int k0 = kt * (first[u] ? BK : KB1) + kb[u] * 8;
+      dst[u] = first[u] ? W0s + kt * N0T * BK : W1s + kt * N1T * KB1;
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj)
+        r[u][jj] = (blk < total && k0 + jj < kmax && row0[u] < nmax) ? *(const half8*)(src + (int64_t)(k0 + jj) * ld + row0[u]) : zero8;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (base + u * NT + tid >= total) continue;
+#pragma unroll
+      for (int nn = 0; nn < 8; ++nn) {
+        half8 t;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) t[jj] = r[u][jj][nn];
+        const int off = first[u] ? lds_chunk_offset<BK>(row0[u] + nn, kb[u]) : lds_chunk_offset<KB1>(row0[u] + nn, kb[u]);
+        *(half8*)(dst[u] + off) = t;
+      }
+    }
+  }
+  __syncthreads();
+}
+
 // Loads W0 as [nk0][N0T][BK] and W1 as [N0T/KB1][N1T][KB1] into LDS (all threads, then barrier).
 template <int BK, int NT, int N0T, int N1T, int WMODE>
 __device__ __forceinline__ void b2b_preload_weights(const B2bParams& p, half_t* W0s, half_t* W1s, int tid) {
+  if constexpr (WMODE == 1) {
+    b2b_preload_weights_kn<BK, NT, N0T, N1T>(p, W0s, W1s, tid);
+    return;
+  }
   constexpr int KB1 = B2bK1<N0T>::KB1;
   const int nk0 = (p.K0 + BK - 1) / BK;
   {
@@ -253,6 +310,57 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
   }
 }
 
+// Epilogue of op1 for a 2-D wave tiling, through LDS: accumulators -> FP16 tile [BM][NOUT_T] in `stage` (16-byte
+// chunks XOR-swizzled by row, see ctile_swizzle) -> 16-byte non-temporal row stores, every instruction whole
+// 128-byte row segments (the direct form above issues one 8-byte store per accumulator quad, four times the
+// instructions at a quarter of the bytes each).  `stage` may overlay whatever op1 has finished reading: the first
+// barrier orders that, the last one lets the next tile re-use the memory.  RES as in b2b_store_tile.
+template <int BM, int NOUT_T, int WTM, int WTN, int NT, bool RES>
+__device__ __forceinline__ void b2b_tile_out_2d(half_t* stage, const floatx16 (&acc)[WTN / 32][WTM / 32], const B2bParams& p,
+                                                int m0, int wm, int wn, int tid) {
+  constexpr int CPR = NOUT_T / 8, ROWS_PER_PASS = NT / CPR;
+  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
+  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
+  __syncthreads();
+  auto to_lds = [&](auto slow) {
+#pragma unroll
+    for (int a = 0; a < WTN / 32; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;
+#pragma unroll
+        for (int b = 0; b < WTM / 32; ++b) {
+          const int row = wm * WTM + b * 32 + l32;
+          half4 o;
+          if constexpr (RES) {
+            half4 c = {0, 0, 0, 0};
+            if (nl < p.N1 && m0 + row < p.M) c = *(const half4*)(p.res + (int64_t)(m0 + row) * p.ldr + nl);
+            o = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, nl, ep, c);
+          } else {
+            o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, nl, ep);
+          }
+          *(half4*)(stage + row * NOUT_T + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4)) = o;
+        }
+      }
+  };
+  if (p.act1 > ACT_RELU) to_lds(std::true_type{});
+  else to_lds(std::false_type{});
+  __syncthreads();
+  const int chunk = tid % CPR, r0 = tid / CPR;
+  if (chunk * 8 < p.N1) {
+#pragma unroll
+    for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
+      const int row = r0 + i * ROWS_PER_PASS;
+      if (m0 + row < p.M) {
+        const half8 v = *(const half8*)(stage + row * NOUT_T + ((chunk ^ ctile_swizzle<CPR>(row)) << 3));
+        __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + chunk * 8));
+      }
+    }
+  }
+  __syncthreads();
+}
+
 template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE>
 struct B2bLdsTraits {
   static constexpr int NT = 64 * WM0 * WN0;
@@ -262,7 +370,8 @@ struct B2bLdsTraits {
   static_assert(WTM0 % 32 == 0 && WTN0 % 32 == 0 && WTM1 % 32 == 0 && WTN1 % 32 == 0, "tile shape");
   static int lds_bytes(int K0) {
     const int nk0 = (K0 + BK - 1) / BK;
-    return (nk0 * N0T * BK + N0T * N1T + 2 * BM * BK + BM * N0T) * 2;
+    constexpr int loop_halves = 2 * BM * BK + BM * N0T, out_halves = BM * N1T;  // the output tile overlays X and D0
+    return (nk0 * N0T * BK + N0T * N1T + (loop_halves > out_halves ? loop_halves : out_halves)) * 2;
   }
 };
 
@@ -376,7 +485,7 @@ __global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams
           for (int b = 0; b < FM1; ++b) acc1[a][b] = mfma_32x32x16(wf[a], xf[b], acc1[a][b]);
       }
     }
-    b2b_store_tile<FN1, FM1, RES>(p, acc1, m0 + wm1 * WTM1 + l32, wn1 * WTN1 + g * 4);
+    b2b_tile_out_2d<BM, N1T, WTM1, WTN1, NT, RES>(Xs, acc1, p, m0, wm1, wn1, tid);
   }
 }
 

@@ -176,6 +176,16 @@ __device__ __forceinline__ half4 epilogue_quad_res(const floatx16& acc, int q, i
   return epilogue_quad_impl<SLOW, true>(acc, q, n, ep, res);
 }
 
+// XOR term of the FP16 C tile staged in LDS ([rows][BN], 16-byte chunks): physical chunk = chunk ^ term(row).
+// The term walks through all 16 bank groups (256 bytes) over 16 consecutive rows whatever the row length,
+// so the 8-byte accumulator-quad writes of 32 rows conflict two ways (rows r and r + 16) instead of four, and
+// the 16-byte reads of the store phase (16 lanes: consecutive chunks of one or two rows) not at all.
+template <int CPR>
+__device__ __forceinline__ int ctile_swizzle(int row) {
+  static_assert(CPR == 4 || CPR == 8 || CPR == 16 || CPR == 32, "chunks per C-tile row");
+  return CPR >= 16 ? (row & 15) : CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+
 // Host side: a kernel that wants more than 64 KiB of dynamic LDS has to opt in once per process.  Every launcher
 // owns one of these per kernel; call_once makes the first launch safe from several host threads, and the
 // attribute is set before (never as part of) the first launch, so it does not matter whether that launch is

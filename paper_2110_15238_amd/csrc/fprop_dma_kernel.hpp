@@ -173,16 +173,6 @@ struct DmaTileLoader {
   }
 };
 
-// XOR term of the FP16 C tile staged in LDS ([rows][BN], 16-byte chunks): physical chunk = chunk ^ term(row).
-// The term walks through all 16 bank groups (256 bytes) over 16 consecutive rows whatever the row length,
-// so the 8-byte accumulator-quad writes of 32 rows conflict two ways (rows r and r + 16) instead of four, and
-// the 16-byte reads of the store phase (16 lanes: consecutive chunks of one or two rows) not at all.
-template <int CPR>
-__device__ __forceinline__ int ctile_swizzle(int row) {
-  static_assert(CPR == 4 || CPR == 8 || CPR == 16 || CPR == 32, "chunks per C-tile row");
-  return CPR >= 16 ? (row & 15) : CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3);
-}
-
 // Last step of the tiled single-op kernels: accumulators -> FP16 C tile in LDS ([BM][BN], 16-byte chunks
 // XOR-swizzled by row, over whatever the main loop left there) -> 16-byte coalesced non-temporal row stores.
 // RES (Eq. 1's C as a full matrix, p.res): the residual tile is first brought into the same LDS locations
