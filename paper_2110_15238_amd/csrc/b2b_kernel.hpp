@@ -205,6 +205,59 @@ __device__ __forceinline__ void b2b_make_d0(const B2bParams& p, const floatx16 (
   b2b_make_d<FN0, FM>(EpilogueArgs{p.b0, p.b0_on, p.N0, p.alpha0, p.beta0, p.act0}, acc0, d0, g);
 }
 
+// Epilogue of op1 for a 2-D wave tiling, through LDS: accumulators -> FP16 tile [BM][NOUT_T] in `stage` (16-byte
+// chunks XOR-swizzled by row, see ctile_swizzle) -> 16-byte non-temporal row stores, every instruction whole
+// 128-byte row segments (the direct form above issues one 8-byte store per accumulator quad, four times the
+// instructions at a quarter of the bytes each).  `stage` may overlay whatever op1 has finished reading: the first
+// barrier orders that, the last one lets the next tile re-use the memory.  RES as in b2b_store_tile.
+template <int BM, int NOUT_T, int WTM, int WTN, int NT, bool RES>
+__device__ __forceinline__ void b2b_tile_out_2d(half_t* stage, const floatx16 (&acc)[WTN / 32][WTM / 32], const B2bParams& p,
+                                                int m0, int wm, int wn, int tid, int n_off = 0) {
+  // n_off: the staged tile is columns [n_off, n_off + NOUT_T) of D1 (kernels that take op1 a column chunk at a time)
+  constexpr int CPR = NOUT_T / 8, ROWS_PER_PASS = NT / CPR;
+  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
+  const int n_valid = p.N1 - n_off;
+  const EpilogueArgs ep{p.b1 + n_off, p.b1_on, n_valid, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
+  __syncthreads();
+  auto to_lds = [&](auto slow) {
+#pragma unroll
+    for (int a = 0; a < WTN / 32; ++a)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;
+#pragma unroll
+        for (int b = 0; b < WTM / 32; ++b) {
+          const int row = wm * WTM + b * 32 + l32;
+          half4 o;
+          if constexpr (RES) {
+            half4 c = {0, 0, 0, 0};
+            if (nl < n_valid && m0 + row < p.M) c = *(const half4*)(p.res + (int64_t)(m0 + row) * p.ldr + n_off + nl);
+            o = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, nl, ep, c);
+          } else {
+            o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, nl, ep);
+          }
+          *(half4*)(stage + row * NOUT_T + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4)) = o;
+        }
+      }
+  };
+  if (p.act1 > ACT_RELU) to_lds(std::true_type{});
+  else to_lds(std::false_type{});
+  __syncthreads();
+  const int chunk = tid % CPR, r0 = tid / CPR;
+  if (chunk * 8 < n_valid) {
+#pragma unroll
+    for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
+      const int row = r0 + i * ROWS_PER_PASS;
+      if (m0 + row < p.M) {
+        const half8 v = *(const half8*)(stage + row * NOUT_T + ((chunk ^ ctile_swizzle<CPR>(row)) << 3));
+        __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n_off + chunk * 8));
+      }
+    }
+  }
+  __syncthreads();
+}
+
 template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
 struct B2bRfTraits {
   static constexpr int NT = 64 * NWAVES;
@@ -279,7 +332,6 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
     b2b_make_d0<FN0, FM>(p, acc0, d0, g);
 
     // ---- op1: W1 fragments from LDS with the matching reduction-index permutation ------------
-    const int mrow = m0 + wave * WTM + l32;
 #pragma unroll
     for (int c1 = 0; c1 < FN1 / NC1; ++c1) {
       floatx16 acc1[NC1][FM];
@@ -305,60 +357,10 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
           for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(wf, d0[t][b], acc1[a][b]);
         }
       }
-      b2b_store_tile<NC1, FM, RES>(p, acc1, mrow, c1 * NC1 * 32 + g * 4);
+      // this chunk's [BM][NC1 * 32] columns through a staged tile over the activation buffers
+      if (c1 * NC1 * 32 < p.N1) b2b_tile_out_2d<BM, NC1 * 32, WTM, NC1 * 32, NT, RES>(Xs, acc1, p, m0, wave, 0, tid, c1 * NC1 * 32);
     }
   }
-}
-
-// Epilogue of op1 for a 2-D wave tiling, through LDS: accumulators -> FP16 tile [BM][NOUT_T] in `stage` (16-byte
-// chunks XOR-swizzled by row, see ctile_swizzle) -> 16-byte non-temporal row stores, every instruction whole
-// 128-byte row segments (the direct form above issues one 8-byte store per accumulator quad, four times the
-// instructions at a quarter of the bytes each).  `stage` may overlay whatever op1 has finished reading: the first
-// barrier orders that, the last one lets the next tile re-use the memory.  RES as in b2b_store_tile.
-template <int BM, int NOUT_T, int WTM, int WTN, int NT, bool RES>
-__device__ __forceinline__ void b2b_tile_out_2d(half_t* stage, const floatx16 (&acc)[WTN / 32][WTM / 32], const B2bParams& p,
-                                                int m0, int wm, int wn, int tid) {
-  constexpr int CPR = NOUT_T / 8, ROWS_PER_PASS = NT / CPR;
-  static_assert(NT % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
-  const int lane = tid & 63, g = lane >> 5, l32 = lane & 31;
-  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
-  __syncthreads();
-  auto to_lds = [&](auto slow) {
-#pragma unroll
-    for (int a = 0; a < WTN / 32; ++a)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;
-#pragma unroll
-        for (int b = 0; b < WTM / 32; ++b) {
-          const int row = wm * WTM + b * 32 + l32;
-          half4 o;
-          if constexpr (RES) {
-            half4 c = {0, 0, 0, 0};
-            if (nl < p.N1 && m0 + row < p.M) c = *(const half4*)(p.res + (int64_t)(m0 + row) * p.ldr + nl);
-            o = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, nl, ep, c);
-          } else {
-            o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, nl, ep);
-          }
-          *(half4*)(stage + row * NOUT_T + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4)) = o;
-        }
-      }
-  };
-  if (p.act1 > ACT_RELU) to_lds(std::true_type{});
-  else to_lds(std::false_type{});
-  __syncthreads();
-  const int chunk = tid % CPR, r0 = tid / CPR;
-  if (chunk * 8 < p.N1) {
-#pragma unroll
-    for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
-      const int row = r0 + i * ROWS_PER_PASS;
-      if (m0 + row < p.M) {
-        const half8 v = *(const half8*)(stage + row * NOUT_T + ((chunk ^ ctile_swizzle<CPR>(row)) << 3));
-        __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + chunk * 8));
-      }
-    }
-  }
-  __syncthreads();
 }
 
 template <int BM, int BK, int WM0, int WN0, int WM1, int WN1, int N0T, int N1T, int XMODE, int WMODE>
