@@ -6,7 +6,7 @@
 //   op1: W1 (all of it, [N1][N0] K-contiguous) is fetched to LDS once, at kernel start, so the
 //        second GEMM runs entirely out of registers and LDS;
 //   epilogue: D1 tile -> FP16 -> LDS -> 16-byte coalesced row stores.
-// Unlike stream_kernel.hpp this kernel is not persistent: 2 workgroups fit on a compute unit and
+// Unlike the weights-resident kernels of b2b_kernel.hpp this kernel is not persistent: 2 workgroups fit on a compute unit and
 // cover each other's prologue / epilogue.  K-contiguous weights only (conv KRSC, GEMM B as [N][K]).
 #pragma once
 #include "b2b_kernel.hpp"

@@ -139,38 +139,6 @@ __device__ __forceinline__ void b2b_preload_weights(const B2bParams& p, half_t* 
   __syncthreads();
 }
 
-// Epilogue of op1 for accumulators in the transposed MFMA layout, direct 8-byte stores.
-// RES: Eq. 1 with a full matrix C - each lane first reads the quad of C it is about to overwrite in D (8-byte loads of
-// the same shape as the stores; C may be the output buffer), p.gamma scales it.
-template <int FN, int FM, bool RES = false>
-__device__ __forceinline__ void b2b_store_tile(const B2bParams& p, floatx16 (&acc)[FN][FM], int mrow, int ncol) {
-  const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
-  auto store_tile = [&](auto slow) {
-#pragma unroll
-    for (int a = 0; a < FN; ++a)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = ncol + a * 32 + q * 8;
-#pragma unroll
-        for (int b = 0; b < FM; ++b) {
-          const int m = mrow + b * 32;
-          const bool ok = n < p.N1 && m < p.M;
-          half4 o;
-          if constexpr (RES) {
-            half4 c = {0, 0, 0, 0};
-            if (ok) c = *(const half4*)(p.res + (int64_t)m * p.ldr + n);
-            o = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n, ep, c);
-          } else {
-            o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n, ep);
-          }
-          if (ok) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
-        }
-      }
-  };
-  if (p.act1 > ACT_RELU) store_tile(std::true_type{});
-  else store_tile(std::false_type{});
-}
-
 // Epilogue of op0 in registers (RF-resident fusion): accumulators -> FP16 B-operand fragments of
 // op1.  Step t = 2a + h of op1 reduces over D0 columns [32a + 16h, 32a + 16h + 16): lane group g
 // holds columns 32a+16h+4g+{0..3} (accumulator quad 2h) and 32a+16h+8+4g+{0..3} (quad 2h+1), and the
@@ -207,9 +175,11 @@ __device__ __forceinline__ void b2b_make_d0(const B2bParams& p, const floatx16 (
 
 // Epilogue of op1 for a 2-D wave tiling, through LDS: accumulators -> FP16 tile [BM][NOUT_T] in `stage` (16-byte
 // chunks XOR-swizzled by row, see ctile_swizzle) -> 16-byte non-temporal row stores, every instruction whole
-// 128-byte row segments (the direct form above issues one 8-byte store per accumulator quad, four times the
-// instructions at a quarter of the bytes each).  `stage` may overlay whatever op1 has finished reading: the first
-// barrier orders that, the last one lets the next tile re-use the memory.  RES as in b2b_store_tile.
+// 128-byte row segments (one 8-byte store per accumulator quad straight from the MFMA layout is four times the
+// instructions at a quarter of the bytes each: measured 1 us more on a 64 x 128 tile).  `stage` may overlay whatever op1 has finished reading: the first
+// barrier orders that, the last one lets the next tile re-use the memory.  RES: Eq. 1 with a full matrix C - each
+// lane first reads the quad of C that its quad of D will replace (8-byte loads; C may be the output buffer), p.gamma
+// scales it.
 template <int BM, int NOUT_T, int WTM, int WTN, int NT, bool RES>
 __device__ __forceinline__ void b2b_tile_out_2d(half_t* stage, const floatx16 (&acc)[WTN / 32][WTM / 32], const B2bParams& p,
                                                 int m0, int wm, int wn, int tid, int n_off = 0) {
@@ -518,7 +488,7 @@ hipError_t b2b_launch_common(KernT kern, LdsOptIn& opt_in, const B2bParams& p, i
 template <int BM, int BK, int NWAVES, int N0T, int N1T, int XMODE, int WMODE>
 hipError_t launch_b2b_rf(const B2bParams& p, int grid, int lds_bytes, hipStream_t stream) {
   static LdsOptIn opt_in[2];
-  if (p.res)  // the residual epilogue is a kernel of its own (see b2b_store_tile)
+  if (p.res)  // the residual epilogue is a kernel of its own (see b2b_tile_out_2d)
     return b2b_launch_common(b2b_rf_kernel<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE, true>, opt_in[1], p, grid, 64 * NWAVES,
                              lds_bytes, stream);
   return b2b_launch_common(b2b_rf_kernel<BM, BK, NWAVES, N0T, N1T, XMODE, WMODE, false>, opt_in[0], p, grid, 64 * NWAVES,

@@ -242,7 +242,6 @@ struct Tables {
     register_conv_smallc_instances(conv);  // first layers: at most 4 channels, unpadded NHWC or NCHW
     register_conv_nchw_out_instances(conv);  // last layers: the output written as NCHW
     register_b2b_gemm_instances(b2b_gemm);
-    register_b2b_gemm_stream_instances(b2b_gemm);
     register_b2b_gemm_dma_instances(b2b_gemm);
     register_b2b_conv_instances(b2b_conv);
     register_b2b_conv_dma_instances(b2b_conv);

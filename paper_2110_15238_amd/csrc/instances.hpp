@@ -18,7 +18,6 @@
 #include "fprop_dma_kernel.hpp"
 #include "fprop_kernel.hpp"
 #include "fprop_pp_kernel.hpp"
-#include "stream_kernel.hpp"
 
 // The lists below are what survived a measurement: every tile shape tried during development was
 // timed by bolt_tune on the workloads of Section 4 (the ResNet-50 layers at batch 32, the GEMM and
@@ -98,7 +97,6 @@ void register_conv_smallc_instances(std::vector<FpropInstance>& v);
 void register_conv_nchw_out_instances(std::vector<FpropInstance>& v);
 void register_b2b_gemm_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_instances(std::vector<B2bInstance>& v);
-void register_b2b_gemm_stream_instances(std::vector<B2bInstance>& v);
 void register_b2b_gemm_dma_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_dma_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_halo_instances(std::vector<B2bInstance>& v);

@@ -173,15 +173,13 @@ def test_fused_pair_residual_instance_sets(bolt):
         assert bolt.bolt_check(res, d0, d1) == OK
         assert bolt.bolt_check(res, d0, d1, {"kernel_id": min(b)}) == OK
         assert bolt.bolt_instance_config(res, min(b)).as_dict() == bolt.bolt_instance_config(plain, min(b)).as_dict()
-    # row-major weights: only the weights-resident kernels take them; the register / LDS residence ones have the
-    # residual epilogue, the persistent streaming one does not
+    # row-major weights: only the weights-resident kernels take them, and every one of them has the residual epilogue
     k0, k1 = G(16384, 64, 256), G(16384, 128, 64)
     n = bolt.bolt_num_instances(bolt.OP_B2B_GEMM)
     a = {i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM, i, k0, k1)}
     b = {i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM_RES, i, k0, k1)}
-    assert b and b < a
+    assert b and b == a
     assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, k0, k1) == OK
-    assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, k0, k1, {"kernel_id": min(a - b)}) == UNSUPPORTED
     assert bolt.bolt_check(bolt.OP_B2B_GEMM_RES, g0, G(16000, 128, 64, b_layout=nk)) == ILLEGAL
 
 
