@@ -13,8 +13,8 @@
 //   WMODE 1: weights stored [K][N] (row-major GEMM B); 8x8 blocks are transposed in registers on
 //   the way to LDS so that both operands sit K-contiguous in LDS.
 // The MFMA computes the transposed product (weights as the A operand, activations as the B
-// operand), so a lane ends up with 4 consecutive output channels of one output row: an 8-byte
-// store, and the layout the back-to-back kernels need to reuse accumulators as operands.
+// operand), so a lane ends up with 4 consecutive output channels of one output row: a quad for the
+// epilogue, and the layout the back-to-back kernels need to reuse accumulators as operands.
 #pragma once
 #include <type_traits>
 
@@ -147,35 +147,57 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fprop_kernel(const Fpr
         }
     return;
   }
+  // FP16 tile through LDS (over the operand buffers, which the loop's last barrier has retired; 16-byte chunks
+  // XOR-swizzled by row, see ctile_swizzle) so that every store instruction writes whole 128-byte row segments
+  // instead of one 8-byte quad per lane.  With a residual each lane first reads the quad of C its quad replaces.
+  constexpr int CPR = BN / 8, STORE_THREADS = NT / CPR <= BM ? NT : BM * CPR, ROWS_PER_PASS = STORE_THREADS / CPR;
+  static_assert(STORE_THREADS % CPR == 0 && BM % ROWS_PER_PASS == 0, "C tile store mapping");
+  static_assert(BM * BN * 2 <= T::LDS_BYTES, "the C tile fits over the operand buffers");
   const EpilogueArgs ep{p.bias, p.bias_on, p.N, p.alpha, p.beta, p.act, p.gamma};
-  auto store_tile = [&](auto slow, auto with_res) {
+  const int g = lane >> 5, l32 = lane & 31;
+  auto tile_to_lds = [&](auto slow, auto with_res) {
 #pragma unroll
     for (int a = 0; a < FN; ++a)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = ncol + a * 32 + q * 8;
+        const int nl = wn * WTN + a * 32 + q * 8 + g * 4;  // column inside the tile
 #pragma unroll
         for (int b = 0; b < FM; ++b) {
-          const int m = mrow + b * 32;
-          const bool ok = n < p.N && m < p.M;
+          const int row = wm * WTM + b * 32 + l32;
           half4 o;
           if constexpr (decltype(with_res)::value) {
             const half4 zero = {0, 0, 0, 0};
-            const half4 r = ok ? *(const half4*)(p.res + (int64_t)m * p.ldr + n) : zero;
-            o = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n, ep, r);
+            const bool ok = n0 + nl < p.N && m0 + row < p.M;
+            const half4 r = ok ? *(const half4*)(p.res + (int64_t)(m0 + row) * p.ldr + n0 + nl) : zero;
+            o = epilogue_quad_res<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep, r);
           } else {
-            o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n, ep);
+            o = epilogue_quad<decltype(slow)::value>(acc[a][b], q, n0 + nl, ep);
           }
-          if (ok) *(half4*)(p.Y + (int64_t)m * p.ldy + n) = o;
+          *(half4*)(lds + row * BN + (((nl >> 3) ^ ctile_swizzle<CPR>(row)) << 3) + (nl & 4)) = o;
         }
       }
   };
   if (p.res) {
-    if (p.act > ACT_RELU) store_tile(std::true_type{}, std::true_type{});
-    else store_tile(std::false_type{}, std::true_type{});
+    if (p.act > ACT_RELU) tile_to_lds(std::true_type{}, std::true_type{});
+    else tile_to_lds(std::false_type{}, std::true_type{});
   } else {
-    if (p.act > ACT_RELU) store_tile(std::true_type{}, std::false_type{});
-    else store_tile(std::false_type{}, std::false_type{});
+    if (p.act > ACT_RELU) tile_to_lds(std::true_type{}, std::false_type{});
+    else tile_to_lds(std::false_type{}, std::false_type{});
+  }
+  __syncthreads();
+  if (tid < STORE_THREADS) {
+    const int chunk = tid % CPR, r0 = tid / CPR;
+    const int n = n0 + chunk * 8;
+    if (n < p.N) {
+#pragma unroll
+      for (int i = 0; i < BM / ROWS_PER_PASS; ++i) {
+        const int row = r0 + i * ROWS_PER_PASS;
+        if (m0 + row < p.M) {
+          const half8 v = *(const half8*)(lds + row * BN + ((chunk ^ ctile_swizzle<CPR>(row)) << 3));
+          __builtin_nontemporal_store(v, (half8*)(p.Y + (int64_t)(m0 + row) * p.ldy + n));
+        }
+      }
+    }
   }
 }
 
