@@ -235,6 +235,7 @@ struct Tables {
     register_conv_chain_instances(conv_chain);
     register_gemm_kn_instances(gemm);
     register_gemm_nk_instances(gemm);
+    register_gemm_kn_dma_instances(gemm);  // (after the older families: their kernel ids stay what they were)
     register_conv_instances(conv);
     register_conv_halo_instances(conv);
     register_gemm_nk_instances(conv);  // for 1x1 / stride 1 / pad 0 filters
@@ -362,6 +363,7 @@ static bool fprop_supports(const FpropInstance& in, const FpropProblem& pr) {
   if (in.nchw_out && pr.residual) return false;
   if (in.wmode != pr.wmode) return false;
   if (in.xmode != pr.xmode) return false;
+  if (in.kn_dma && (int64_t)pr.p.K * pr.p.ldw * 2 >= (1ll << 31)) return false;
   if (in.dyn_supports && (!in.dyn_supports(pr.p) || in.dyn_lds_bytes(pr.p) > kLdsPerCU)) return false;
   if (in.lds_bytes > kLdsPerCU) return false;
   // single-stage instances hold exactly one k-tile per k-group

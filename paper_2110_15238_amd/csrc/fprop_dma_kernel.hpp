@@ -173,6 +173,79 @@ struct DmaTileLoader {
   }
 };
 
+// Row-major weights (GEMM, B stored [K][N]): the k-tile is BK rows of BN contiguous halves and goes to LDS as it
+// lies in memory, 16 bytes per lane; nothing is transposed on the way.  The matrix core wants, per lane, 8
+// consecutive k of ONE column n, which in this tile is a column walk; the LDS transpose read of this chip
+// (ds_read_b64_tr_b16) does that walk in hardware: within each group of 16 lanes, lanes 4r .. 4r+3 address the
+// four 8-byte quarters of a 16-half row segment r (r = 0..3), and lane i of the group receives element i of each of
+// the four segments, that is 4 consecutive k of column i when the segments are 4 consecutive rows of the tile.
+// Two such reads make one 8-half operand.
+// A half-wave (32 lanes, one pass of an 8-byte read) touches 4 consecutive rows x 64 bytes; the 16-byte chunk of a
+// row is XOR-ed with row bits so that those 16 chunks fall into 16 different bank groups whatever the row length.
+template <int BN>
+__device__ __forceinline__ int kn_swizzle(int k) {
+  static_assert(BN == 32 || BN == 64 || BN == 128 || BN == 256, "row-major weight tile width");
+  if constexpr (BN == 32) return 0;             // 64-byte rows: 4 consecutive rows already cover 256 bytes
+  else if constexpr (BN == 64) return ((k >> 1) & 1) << 2;  // rows k and k+2 share a bank half: flip chunk bit 2
+  else return (k & 3) << 2;                     // rows are multiples of 256 bytes: 4 rows take 4 chunk quartets
+}
+template <int BK, int BN, int NW>
+struct DmaKnTileLoader {
+  static constexpr int CH = BN / 8;            // 16-byte chunks per tile row
+  static constexpr int RPI = 64 / CH;          // tile rows (k) per load instruction
+  static constexpr int NI = BK / RPI / NW;     // instructions per wave per tile
+  static_assert(CH <= 64 && 64 % CH == 0, "a load instruction fills whole tile rows");
+  static_assert(BK % (RPI * NW) == 0 && NI >= 1, "tile rows must split evenly over the waves");
+
+  __amdgpu_buffer_rsrc_t rsrc;
+  int ld, cols_valid, K, wave, lrow, lc;
+
+  // `base` points at column n0 of row 0 of the weight matrix, `bytes` is what remains of the matrix from there;
+  // cols_valid = N - n0, K = the first k this workgroup must not read.
+  __device__ __forceinline__ void init(const half_t* base, unsigned bytes, int ld_, int cols_valid_, int K_, int wave_, int lane) {
+    rsrc = make_rsrc(base, bytes);
+    ld = ld_;
+    cols_valid = cols_valid_;
+    K = K_;
+    wave = wave_;
+    lrow = lane / CH;
+    lc = lane % CH;
+  }
+  template <int J0, int J1>
+  __device__ __forceinline__ void issue_part(int kt, half_t* dst, const ConvGeom&) {
+#pragma unroll
+    for (int j = J0; j < J1; ++j) {
+      const int rb = (j * NW + wave) * RPI;
+      const int row = rb + lrow, k = kt * BK + row;
+      const int c = lc ^ kn_swizzle<BN>(row);  // the chunk of the row this lane's fixed LDS slot holds
+      const unsigned off = (k < K && c * 8 < cols_valid) ? (unsigned)(k * ld + c * 8) * 2u : kInvalidOffset;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, BOLT_LDS_PTR(dst + rb * BN), 16, off, 0, 0, 0);
+    }
+  }
+  __device__ __forceinline__ void issue(int kt, half_t* dst, const ConvGeom& cg) { issue_part<0, NI>(kt, dst, cg); }
+  __device__ __forceinline__ void advance(const ConvGeom&) {}
+};
+// This lane's part of the operand for the 32 columns that start at tile column col0, k-step ks (16 rows) of the
+// row-major tile at ws: k = 16 ks + 8 (lane / 32) .. +7 of column col0 + lane % 32.
+template <int BN>
+__device__ __forceinline__ int kn_frag_offset(int col0, int lane) {
+  const int r = (lane & 15) >> 2, col = col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  return ((lane >> 5) * 8 + r) * BN + (((col >> 3) ^ kn_swizzle<BN>(r)) << 3) + (col & 7);
+}
+// `ws` is __restrict__ for the sake of the compiler's wait-count pass: an LDS access that carries no alias
+// information is given a wait for EVERY direct-to-LDS load in flight (the pass cannot tell the stage being read from
+// the stages being filled), which would serialise the pipeline; ordinary loads carry type-based alias information
+// and escape that, the transpose-read builtin carries none unless the inlined restrict scope gives it some.  The
+// explicit waits in front of the workgroup barriers are what orders these reads after the loads they depend on.
+template <int BN>
+__device__ __forceinline__ half8 kn_frag_read(const half_t* __restrict__ ws, int lane_off, int ks) {
+  typedef short short4v __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) short4v lds_short4;
+  const half4 lo = __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(ws + lane_off + ks * 16 * BN)));
+  const half4 hi = __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(ws + lane_off + (ks * 16 + 4) * BN)));
+  return half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
+
 // Last step of the tiled single-op kernels: accumulators -> FP16 C tile in LDS ([BM][BN], 16-byte chunks
 // XOR-swizzled by row, over whatever the main loop left there) -> 16-byte coalesced non-temporal row stores.
 // RES (Eq. 1's C as a full matrix, p.res): the residual tile is first brought into the same LDS locations
@@ -299,13 +372,16 @@ struct FpropDmaTraits {
 };
 
 // NCHW: the output tensor is [N][K][P][Q] (convolutions only; see fprop_tile_out_with)
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1, bool RES = false, bool NCHW = false>
+// WKN: the weights are row-major [K][N] (GEMM only), see DmaKnTileLoader.
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1, bool RES = false, bool NCHW = false,
+          bool WKN = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(const FpropParams p) {
   using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
   constexpr int WPG = T::WPG, WTM = T::WTM, WTN = T::WTN, FM = T::FM, FN = T::FN;
   constexpr int STAGE = T::STAGE_HALVES;
   using XL = DmaTileLoader<BM, BK, WPG, XMODE, KG>;
-  using WL = DmaTileLoader<BN, BK, WPG, 0, KG>;
+  using WL = std::conditional_t<WKN, DmaKnTileLoader<BK, BN, WPG>, DmaTileLoader<BN, BK, WPG, 0, KG>>;
+  static_assert(!WKN || XMODE == 0, "row-major weights: GEMM only");
   constexpr int L = XL::NI + WL::NI;  // load instructions per wave per k-tile
   static_assert((NS - 1) * L < 64, "vmcnt range");
 
@@ -338,7 +414,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
     const int64_t bytes = (int64_t)p.cg.H * p.cg.Wi * p.cg.C * 2 * (int64_t)(p.M / (p.cg.P * p.cg.Q));
     xl.init(p.X, (unsigned)bytes, 0, p.M - m0, k_limit, p.cg, m0, kt_begin, wave, lane);
   }
-  {
+  int wfo[WKN ? FN : 1];  // row-major weights: this lane's offset inside the tile, per fragment column
+  if constexpr (WKN) {
+    const int64_t rem = ((int64_t)(p.K - 1) * p.ldw + (p.N - n0)) * 2;  // (the host keeps the matrix under 2 GiB)
+    wl.init(p.W + n0, (unsigned)rem, p.ldw, p.N - n0, k_limit, wave, lane);
+#pragma unroll
+    for (int a = 0; a < FN; ++a) wfo[a] = kn_frag_offset<BN>(wn * WTN + a * 32, lane);
+  } else {
     const int64_t rem = ((int64_t)(p.N - n0 - 1) * p.ldw + p.K) * 2;
     wl.init(p.W + (int64_t)n0 * p.ldw, (unsigned)(rem < 0x7fffffff ? rem : 0x7fffffff), p.ldw, p.N - n0, k_limit, p.cg,
             n0, kt_begin, wave, lane);
@@ -378,8 +460,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
       for (int b = 0; b < FM; ++b)
         x[k][b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
 #pragma unroll
-      for (int a = 0; a < FN; ++a)
-        w[k][a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+      for (int a = 0; a < FN; ++a) {
+        if constexpr (WKN) w[k][a] = kn_frag_read<BN>(ws, wfo[a], grp * G + k);
+        else w[k][a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+      }
     }
   };
   auto mfma_group = [&](const half8 (&x)[G][FM], const half8 (&w)[G][FN]) {
@@ -427,7 +511,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
 #pragma unroll
       for (int b = 0; b < FM; ++b) x[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
 #pragma unroll
-      for (int a = 0; a < FN; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+      for (int a = 0; a < FN; ++a) {
+        if constexpr (WKN) w[a] = kn_frag_read<BN>(ws, wfo[a], ks);
+        else w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
+      }
     };
     int fill_stage = 0;  // stage that the tile in flight of issue (tile it-1+NS) goes to
     // One k-tile; `par` = register set that holds its first fragment group.
@@ -572,12 +659,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
   fprop_tile_out<RES, BM, BN, WTM, WTN, T::STORE_THREADS, T::ROWS_PER_PASS, NCHW>(lds, acc, p, m0, n0, wm, wn, kg == 0, tid);
 }
 
-template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int NS, int KG = 1, bool WKN = false>
 hipError_t launch_fprop_dma(const FpropParams& p, hipStream_t stream) {
   using T = FpropDmaTraits<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG>;
   // the residual epilogue is a kernel of its own (see fprop_tile_out)
-  auto kern = p.res ? fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG, true>
-                    : fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG, false>;
+  auto kern = p.res ? fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG, true, false, WKN>
+                    : fprop_dma_kernel<BM, BN, BK, WAVES_M, WAVES_N, XMODE, NS, KG, false, false, WKN>;
   static LdsOptIn opt_in[2];
   if (hipError_t e = opt_in[p.res ? 1 : 0].ensure((const void*)kern, T::LDS_BYTES); e != hipSuccess) return e;
   dim3 grid(p.tiles_m * p.tiles_n, p.split_k, 1);
@@ -608,6 +695,15 @@ hipError_t launch_fprop_dma_nchw(const FpropParams& p, hipStream_t stream) {
     "dma_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS, BM, BN, BK, WM, WN, XMODE, 0, NS,               \
         bolt::FpropDmaTraits<BM, BN, BK, WM, WN, XMODE, NS>::LDS_BYTES,                                  \
         &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, XMODE, NS>, nullptr, nullptr                        \
+  }
+
+// GEMM with row-major weights [K][N] (wmode 1): X(BM, BN, BK, WM, WN, NS, KG).
+#define BOLT_FPROP_DMA_KN_INSTANCE(BM, BN, BK, WM, WN, NS, KG)                                          \
+  {                                                                                                     \
+    "dmakn_" #BM "x" #BN "x" #BK "_w" #WM "x" #WN "_s" #NS "_kg" #KG, BM, BN, BK, WM, WN, 0, 1, NS,       \
+        bolt::FpropDmaTraits<BM, BN, BK, WM, WN, 0, NS, KG>::LDS_BYTES,                                  \
+        &bolt::launch_fprop_dma<BM, BN, BK, WM, WN, 0, NS, KG, true>, nullptr, nullptr, KG, 0, false,  \
+        false, true                                                                                     \
   }
 
 // The same kernel with KG k-groups (64 * WM * WN * KG threads).

@@ -214,6 +214,7 @@ struct FpropInstance {
   int mi;       // matrix-core instruction: 0 or 32 = 32 x 32 x 16, 16 = 16 x 16 x 32
   bool no_split_k;  // the kernel has no partial-sum output
   bool nchw_out;    // writes its output as [N][K][P][Q] (and only that)
+  bool kn_dma;      // row-major weights fetched through one 32-bit-offset buffer descriptor over the whole matrix
 };
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N, int XMODE, int WMODE>

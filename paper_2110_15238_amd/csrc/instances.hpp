@@ -86,10 +86,37 @@
   X(128, 64, 64, 2, 2, 3, XMODE, 2),          \
   X(64, 128, 64, 2, 2, 3, XMODE, 2)
 
+// Row-major weights through the direct-to-LDS pipeline (transposing LDS reads): tile M, N, K, waves M, N, stages, k-groups.
+#define BOLT_FPROP_DMA_KN_TILE_LIST(X) \
+  X(256, 256, 64, 2, 4, 2, 1),         \
+  X(256, 128, 64, 4, 2, 3, 1),         \
+  X(128, 256, 64, 2, 4, 3, 1),         \
+  X(128, 128, 64, 2, 2, 3, 1),         \
+  X(128, 128, 64, 2, 4, 3, 1),         \
+  X(256, 64, 64, 4, 2, 3, 1),          \
+  X(128, 64, 64, 2, 2, 3, 1),          \
+  X(64, 128, 64, 2, 2, 3, 1),          \
+  X(64, 64, 64, 2, 2, 3, 1),           \
+  X(64, 64, 64, 2, 2, 2, 1),           \
+  X(32, 64, 64, 1, 2, 4, 1),           \
+  X(64, 32, 64, 2, 1, 4, 1),           \
+  X(64, 64, 64, 2, 2, 2, 2),           \
+  X(64, 64, 64, 2, 2, 3, 2),           \
+  X(64, 128, 64, 2, 2, 2, 2),          \
+  X(128, 64, 64, 2, 2, 2, 2),          \
+  X(128, 128, 64, 2, 2, 1, 1),         \
+  X(128, 64, 64, 2, 2, 1, 1),          \
+  X(64, 128, 64, 2, 2, 1, 1),          \
+  X(64, 64, 64, 2, 2, 1, 1),           \
+  X(128, 64, 32, 2, 2, 3, 1),          \
+  X(128, 128, 32, 2, 2, 3, 1),         \
+  X(256, 128, 32, 2, 4, 3, 1)
+
 namespace bolt {
 // Each function appends its instances in a fixed order; kernel_id is the index in the op's table.
 void register_gemm_kn_instances(std::vector<FpropInstance>& v);
 void register_gemm_nk_instances(std::vector<FpropInstance>& v);
+void register_gemm_kn_dma_instances(std::vector<FpropInstance>& v);
 void register_conv_instances(std::vector<FpropInstance>& v);
 void register_conv_halo_instances(std::vector<FpropInstance>& v);
 void register_conv_align2_instances(std::vector<FpropInstance>& v);

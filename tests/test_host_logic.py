@@ -82,6 +82,13 @@ def test_gemm_validation(bolt):
     nk = [i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_GEMM, i, G(512, 512, 512, b_layout=bolt.LAYOUT_NK))]
     assert kn and nk and not set(kn) & set(nk)
     assert chk(bolt.OP_GEMM, G(512, 512, 512), None, {"kernel_id": nk[0]}) == UNSUPPORTED
+    # the direct-to-LDS instances for row-major weights address the whole weight matrix with 32-bit byte offsets:
+    # from 2 GiB on only the register-staged instances remain
+    sup = lambda K: {i for i in range(n) if bolt.bolt_instance_supports(bolt.OP_GEMM, i, G(512, 2048, K))}
+    below, at = sup((1 << 19) - 8), sup(1 << 19)
+    assert at and at < below
+    assert all(bolt.bolt_instance_config(bolt.OP_GEMM, i).stages == 2 for i in at)
+    assert chk(bolt.OP_GEMM, G(512, 2048, 1 << 19), None, {"kernel_id": max(below)}) == UNSUPPORTED
 
 
 def test_conv_validation(bolt):
