@@ -164,8 +164,8 @@ bolt_status bolt_gemm_epilogue_noalloc(const bolt_gemm_desc* desc, const void* A
 /* Persistent back-to-back GEMM (Eq. 1-2, Section 3.1.1): D0 = act0(alpha0 A0.W0 + beta0 b0) is
  * rounded to FP16 and stays on chip; D1 = act1(alpha1 D0.W1 + beta1 b1) is the only output.
  * Legal only if g1->M == g0->M and g1->K == g0->N (else BOLT_ERR_ILLEGAL_FUSION).  Threadblock
- * residence: the workgroup tile spans all of N0 and N1, so N0 <= 128, N1 <= 256 and both weight
- * matrices must fit in LDS next to the streaming tiles (else BOLT_ERR_UNSUPPORTED).
+ * residence: the workgroup tile spans all of N0 and N1, so N0 <= 128, N1 <= 256 and W1 must fit
+ * in LDS next to the streaming tiles (else BOLT_ERR_UNSUPPORTED); W0 may be of any depth K0.
  * g0->ldd and g1->lda are ignored (D0 is never stored). */
 bolt_status bolt_b2b_gemm(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1, const void* A0, const void* W0,
                           const void* b0, const void* W1, const void* b1, void* D1, const bolt_config* config,
@@ -220,7 +220,7 @@ bolt_status bolt_b2b_conv_residual(const bolt_conv_desc* c0, const bolt_conv_des
  * descs: host array of n_ops descriptor pointers.  Legality is that of bolt_b2b_gemm / bolt_b2b_conv
  * applied to each consecutive pair (else BOLT_ERR_ILLEGAL_FUSION): same M, K_i = N_{i-1}; for
  * convolutions every op after the first is 1x1, stride 1, no padding, on the previous op's output
- * extent.  GEMM chains need every weight matrix stored [N][K] (BOLT_LAYOUT_NK).  Each N_i must fit a
+ * extent.  The weight matrices of a GEMM chain share one layout (either one).  Each N_i must fit a
  * compiled bound (N_0, N_1 <= 128, N_2 <= 256), else BOLT_ERR_UNSUPPORTED.
  * weights, biases: host arrays of n_ops device pointers (biases, or single entries of it, may be NULL).
  * config->kernel_id indexes the instances of BOLT_OP_GEMM_CHAIN3 / BOLT_OP_CONV_CHAIN3. */

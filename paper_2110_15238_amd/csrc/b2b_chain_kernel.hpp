@@ -25,7 +25,8 @@ struct B2bChainTraits {
 
 // RES: the last epilogue adds gamma * C, C a full M x N2 matrix (Eq. 1 with C0 a matrix, taken by the op whose output
 // is stored); its tile comes through LDS as in b2b_tile_out.
-template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS, bool RES = false>
+// WKN: GEMM chain whose three weight matrices are row-major [K][N] (see DmaKnTileLoader / kn_matrix_to_lds).
+template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS, bool RES = false, bool WKN = false>
 __global__ __launch_bounds__(64 * NW) void b2b_chain_kernel(const B2bParams p) {
   using T = B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>;
   constexpr int FM = T::FM;
@@ -40,21 +41,21 @@ __global__ __launch_bounds__(64 * NW) void b2b_chain_kernel(const B2bParams p) {
   const int m0 = blockIdx.x * BM;
 
   // resident weights first: the oldest loads, covered by the main loop's final wait
-  b2b_issue_weights<N1T, N0T, NW>(p.W1, p.ldw1, p.N1, p.N0, W1s, p.cg, wave, lane);
-  b2b_issue_weights<N2T, N1T, NW>(p.W2, p.ldw2, p.N2, p.N1, W2s, p.cg, wave, lane);
+  b2b_issue_weights<N1T, N0T, NW, WKN>(p.W1, p.ldw1, p.N1, p.N0, W1s, p.cg, wave, lane);
+  b2b_issue_weights<N2T, N1T, NW, WKN>(p.W2, p.ldw2, p.N2, p.N1, W2s, p.cg, wave, lane);
 
   floatx16 acc0[N0T / 32][FM];
-  b2b_dma_op0<BM, BK, NW, N0T, XMODE, NS>(p, lds, m0, wave, lane, acc0);
+  b2b_dma_op0<BM, BK, NW, N0T, XMODE, NS, WKN>(p, lds, m0, wave, lane, acc0);
 
   half8 d0[N0T / 16][FM];
   b2b_make_d<N0T / 32, FM>(EpilogueArgs{p.b0, p.b0_on, p.N0, p.alpha0, p.beta0, p.act0}, acc0, d0, g);
   floatx16 acc1[N1T / 32][FM];
-  b2b_rf_gemm<N0T, N1T, FM>(W1s, d0, acc1, l32, g);
+  b2b_rf_gemm<N0T, N1T, FM, WKN>(W1s, d0, acc1, l32, g);
 
   half8 d1[N1T / 16][FM];
   b2b_make_d<N1T / 32, FM>(EpilogueArgs{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1}, acc1, d1, g);
   floatx16 acc2[N2T / 32][FM];
-  b2b_rf_gemm<N1T, N2T, FM>(W2s, d1, acc2, l32, g);
+  b2b_rf_gemm<N1T, N2T, FM, WKN>(W2s, d1, acc2, l32, g);
 
   const EpilogueArgs ep{p.b2, p.b2_on, p.N2, p.alpha2, p.beta2, p.act2, RES ? p.gamma : 0.f};
   b2b_tile_out<BM, NW, N2T, RES>(lds, acc2, ep, p.Y, p.ldy, p.M, m0, wave, tid, p.res, p.ldr);
@@ -121,16 +122,17 @@ struct ChainInstance {
   // instances whose legality / LDS need depends on the geometry (the halo chains); null otherwise
   bool (*dyn_supports)(const B2bParams&);
   int (*dyn_lds_bytes)(const B2bParams&);
+  int wmode;  // 0: weights stored [N][K] (reduction index contiguous), 1: row-major [K][N] (GEMM chains)
 };
 
-template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS>
+template <int BM, int BK, int NW, int N0T, int N1T, int N2T, int XMODE, int NS, bool WKN = false>
 hipError_t launch_b2b_chain(const B2bParams& p, hipStream_t stream) {
   static LdsOptIn opt_in[2];
   constexpr int kLds = B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>::LDS_BYTES;
   if (p.res)  // the residual epilogue is a kernel of its own (see b2b_tile_out)
-    return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS, true>, opt_in[1], p, p.tiles_m,
+    return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS, true, WKN>, opt_in[1], p, p.tiles_m,
                              64 * NW, kLds, stream);
-  return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS, false>, opt_in[0], p, p.tiles_m,
+  return b2b_launch_common(b2b_chain_kernel<BM, BK, NW, N0T, N1T, N2T, XMODE, NS, false, WKN>, opt_in[0], p, p.tiles_m,
                            64 * NW, kLds, stream);
 }
 
@@ -158,6 +160,14 @@ hipError_t launch_b2b_chain_halo(const B2bParams& p, hipStream_t stream) {
     "chain_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_" #N2T "_s" #NS, BM, BK, NW, N0T, N1T, N2T, XMODE, NS,     \
         bolt::B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>::LDS_BYTES,                                   \
         &bolt::launch_b2b_chain<BM, BK, NW, N0T, N1T, N2T, XMODE, NS>, nullptr, nullptr                          \
+  }
+
+// The GEMM chain with row-major weights.
+#define BOLT_B2B_CHAIN_KN_INSTANCE(BM, BK, NW, N0T, N1T, N2T, NS)                                              \
+  {                                                                                                            \
+    "chainkn_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_" #N2T "_s" #NS, BM, BK, NW, N0T, N1T, N2T, 0, NS,       \
+        bolt::B2bChainTraits<BM, BK, NW, N0T, N1T, N2T, 0, NS>::LDS_BYTES,                                       \
+        &bolt::launch_b2b_chain<BM, BK, NW, N0T, N1T, N2T, 0, NS, true>, nullptr, nullptr, 1                     \
   }
 
 }  // namespace bolt

@@ -38,9 +38,14 @@ struct B2bDmaTraits {
 
 // Weights of a later op, W [n_valid][k_valid] with leading dimension ld, K-contiguous: all of it goes to LDS
 // once as [NKT][NOUT_T][KB] k-tiles of width KB = min(NIN_T, 64); missing rows and columns are zero-filled.
-template <int NOUT_T, int NIN_T, int NW>
+// WKN: W is row-major [k_valid][n_valid] instead and stays so in LDS, as [NIN_T][NOUT_T] (kn_matrix_to_lds).
+template <int NOUT_T, int NIN_T, int NW, bool WKN = false>
 __device__ __forceinline__ void b2b_issue_weights(const half_t* W, int ld, int n_valid, int k_valid, half_t* Ws,
                                                   const ConvGeom& cg, int wave, int lane) {
+  if constexpr (WKN) {
+    kn_matrix_to_lds<64 * NW, NOUT_T>(W, ld, k_valid, n_valid, NIN_T, Ws, wave * 64 + lane);
+    return;
+  }
   constexpr int KB = NIN_T < 64 ? NIN_T : 64, NKT = NIN_T / KB;
   DmaTileLoader<NOUT_T, KB, NW, 0> wl;
   const int64_t bytes = ((int64_t)(n_valid - 1) * ld + k_valid) * 2;
@@ -52,12 +57,14 @@ __device__ __forceinline__ void b2b_issue_weights(const half_t* W, int ld, int n
 // op0: acc0 = X tile (GEMM rows or implicit im2col) x W0^T over K0, NS-deep direct-to-LDS pipeline with the
 // fragments double-buffered across the k-tile barrier.  On return every load this wave has issued, the
 // resident weights of the later ops included, has landed (the loop's final wait is vmcnt 0).
-template <int BM, int BK, int NW, int N0T, int XMODE, int NS>
+// WKN: W0 is row-major [K0][N0]; its k-tiles go to LDS as they lie in memory and are read with the LDS
+// transpose read (DmaKnTileLoader).
+template <int BM, int BK, int NW, int N0T, int XMODE, int NS, bool WKN = false>
 __device__ __forceinline__ void b2b_dma_op0(const B2bParams& p, half_t* lds, int m0, int wave, int lane,
                                             floatx16 (&acc0)[N0T / 32][BM / NW / 32]) {
   constexpr int WTM = BM / NW, FM = WTM / 32, FN0 = N0T / 32, STAGE = (BM + N0T) * BK, KS = BK / 16;
   using XL = DmaTileLoader<BM, BK, NW, XMODE>;
-  using WL = DmaTileLoader<N0T, BK, NW, 0>;
+  using WL = std::conditional_t<WKN, DmaKnTileLoader<BK, N0T, NW>, DmaTileLoader<N0T, BK, NW, 0>>;
   constexpr int L = XL::NI + WL::NI;
   static_assert((NS - 1) * L < 64, "vmcnt range");
   static_assert(KS % 2 == 0, "fragment double buffering");
@@ -73,7 +80,12 @@ __device__ __forceinline__ void b2b_dma_op0(const B2bParams& p, half_t* lds, int
     const int64_t bytes = (int64_t)p.cg.H * p.cg.Wi * p.cg.C * 2 * (int64_t)(p.M / (p.cg.P * p.cg.Q));
     xl.init(p.X, (unsigned)bytes, 0, p.M - m0, p.K0, p.cg, m0, 0, wave, lane);
   }
-  {
+  int w0off[WKN ? FN0 : 1];
+  if constexpr (WKN) {
+    wl.init(p.W0, (unsigned)(((p.K0 - 1) * p.ldw0 + p.N0) * 2), p.ldw0, p.N0, p.K0, wave, lane);  // (under 2 GiB: host check)
+#pragma unroll
+    for (int a = 0; a < FN0; ++a) w0off[a] = kn_frag_offset<N0T>(a * 32, lane);
+  } else {
     const int64_t bytes = ((int64_t)(p.N0 - 1) * p.ldw0 + p.K0) * 2;
     wl.init(p.W0, (unsigned)(bytes < 0x7fffffff ? bytes : 0x7fffffff), p.ldw0, p.N0, p.K0, p.cg, 0, 0, wave, lane);
   }
@@ -97,7 +109,10 @@ __device__ __forceinline__ void b2b_dma_op0(const B2bParams& p, half_t* lds, int
 #pragma unroll
     for (int b = 0; b < FM; ++b) x[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wave * WTM + b * 32 + l32, chunk));
 #pragma unroll
-    for (int a = 0; a < FN0; ++a) w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(a * 32 + l32, chunk));
+    for (int a = 0; a < FN0; ++a) {
+      if constexpr (WKN) w[a] = kn_frag_read<N0T>(ws, w0off[a], ks * 16);
+      else w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(a * 32 + l32, chunk));
+    }
   };
 #pragma unroll
   for (int s = 0; s < NS; ++s)
@@ -131,10 +146,16 @@ __device__ __forceinline__ void b2b_dma_op0(const B2bParams& p, half_t* lds, int
 // A later op entirely out of registers and LDS: acc[NOUT_T columns] = d (FP16 fragments of the previous
 // op's output, NIN_T columns) x Ws^T, Ws as b2b_issue_weights leaves it.  Step t reduces over input columns
 // [16t, 16t + 16); the fragment reads apply the permutation of the reduction index that b2b_make_d documents.
-template <int NIN_T, int NOUT_T, int FM>
+// WKN: Ws holds the row-major matrix as [NIN_T][NOUT_T]; the transpose read gathers the same permuted rows.
+template <int NIN_T, int NOUT_T, int FM, bool WKN = false>
 __device__ __forceinline__ void b2b_rf_gemm(const half_t* Ws, const half8 (&d)[NIN_T / 16][FM],
                                             floatx16 (&acc)[NOUT_T / 32][FM], int l32, int g) {
   constexpr int KB = NIN_T < 64 ? NIN_T : 64, FNO = NOUT_T / 32;
+  int woff[WKN ? FNO : 1];
+  if constexpr (WKN) {
+#pragma unroll
+    for (int a = 0; a < FNO; ++a) woff[a] = kn_frag_offset<NOUT_T>(a * 32, g * 32 + l32, 4);
+  }
 #pragma unroll
   for (int a = 0; a < FNO; ++a)
 #pragma unroll
@@ -149,9 +170,14 @@ __device__ __forceinline__ void b2b_rf_gemm(const half_t* Ws, const half8 (&d)[N
 #pragma unroll
     for (int a = 0; a < FNO; ++a) {
       const int row = a * 32 + l32;
-      const half4 lo = *(const half4*)(ws + dma_chunk_offset<KB>(row, chunk) + g * 4);
-      const half4 hi = *(const half4*)(ws + dma_chunk_offset<KB>(row, chunk + 1) + g * 4);
-      const half8 w = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      half8 w;
+      if constexpr (WKN) {
+        w = kn_frag_read<NOUT_T>(Ws, woff[a], kbase, 8);
+      } else {
+        const half4 lo = *(const half4*)(ws + dma_chunk_offset<KB>(row, chunk) + g * 4);
+        const half4 hi = *(const half4*)(ws + dma_chunk_offset<KB>(row, chunk + 1) + g * 4);
+        w = half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      }
 #pragma unroll
       for (int b = 0; b < FM; ++b) acc[a][b] = mfma_32x32x16(w, d[t][b], acc[a][b]);
     }
@@ -225,7 +251,7 @@ __device__ __forceinline__ void b2b_tile_out(half_t* lds, const floatx16 (&acc)[
   }
 }
 
-template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS, bool RES = false>
+template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS, bool RES = false, bool WKN = false>
 __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::MIN_WAVES)) void b2b_dma_kernel(
     const B2bParams p) {
   using T = B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>;
@@ -240,10 +266,10 @@ __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE,
   const int m0 = blockIdx.x * BM;
 
   // W1 first: these are the oldest loads, any later wait for an operand tile covers them
-  b2b_issue_weights<N1T, N0T, NW>(p.W1, p.ldw1, p.N1, p.N0, W1s, p.cg, wave, lane);
+  b2b_issue_weights<N1T, N0T, NW, WKN>(p.W1, p.ldw1, p.N1, p.N0, W1s, p.cg, wave, lane);
 
   floatx16 acc0[FN0][FM];
-  b2b_dma_op0<BM, BK, NW, N0T, XMODE, NS>(p, lds, m0, wave, lane, acc0);
+  b2b_dma_op0<BM, BK, NW, N0T, XMODE, NS, WKN>(p, lds, m0, wave, lane, acc0);
 
   // epilogue0 in registers: accumulators -> FP16 B-operand fragments of op1 (b2b_make_d0)
   half8 d0[FN0 * 2][FM];
@@ -251,21 +277,21 @@ __global__ __launch_bounds__(64 * NW, (B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE,
 
   // op1: all N1 columns accumulate in registers
   floatx16 acc1[FN1][FM];
-  b2b_rf_gemm<N0T, N1T, FM>(W1s, d0, acc1, l32, g);
+  b2b_rf_gemm<N0T, N1T, FM, WKN>(W1s, d0, acc1, l32, g);
 
   // epilogue1 through LDS (over the dead stages and W1)
   const EpilogueArgs ep{p.b1, p.b1_on, p.N1, p.alpha1, p.beta1, p.act1, RES ? p.gamma : 0.f};
   b2b_tile_out<BM, NW, N1T, RES>(lds, acc1, ep, p.Y, p.ldy, p.M, m0, wave, tid, p.res, p.ldr);
 }
 
-template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS>
+template <int BM, int BK, int NW, int N0T, int N1T, int XMODE, int NS, bool WKN = false>
 hipError_t launch_b2b_dma(const B2bParams& p, int /*grid*/, int lds_bytes, hipStream_t stream) {
   static LdsOptIn opt_in[2];
   // the residual epilogue is a kernel of its own (see b2b_tile_out)
   if (p.res)
-    return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, true>, opt_in[1], p, p.tiles_m, 64 * NW,
+    return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, true, WKN>, opt_in[1], p, p.tiles_m, 64 * NW,
                              lds_bytes, stream);
-  return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, false>, opt_in[0], p, p.tiles_m, 64 * NW,
+  return b2b_launch_common(b2b_dma_kernel<BM, BK, NW, N0T, N1T, XMODE, NS, false, WKN>, opt_in[0], p, p.tiles_m, 64 * NW,
                            lds_bytes, stream);
 }
 
@@ -275,6 +301,14 @@ hipError_t launch_b2b_dma(const B2bParams& p, int /*grid*/, int lds_bytes, hipSt
     "b2bdma_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_s" #NS, 0, BM, BK, NW, 1, N0T, N1T, XMODE, 0, 64 * NW, \
         NS, &bolt::B2bDmaTraits<BM, BK, NW, N0T, N1T, XMODE, NS>::lds_bytes,                                \
         &bolt::launch_b2b_dma<BM, BK, NW, N0T, N1T, XMODE, NS>, nullptr, nullptr, true, 0.5f               \
+  }
+
+// The GEMM pair with row-major weights (wmode 1) on the same kernel.
+#define BOLT_B2B_DMA_KN_INSTANCE(BM, BK, NW, N0T, N1T, NS)                                                \
+  {                                                                                                       \
+    "b2bdmakn_" #BM "x" #BK "_w" #NW "_n" #N0T "_" #N1T "_s" #NS, 0, BM, BK, NW, 1, N0T, N1T, 0, 1, 64 * NW,  \
+        NS, &bolt::B2bDmaTraits<BM, BK, NW, N0T, N1T, 0, NS>::lds_bytes,                                    \
+        &bolt::launch_b2b_dma<BM, BK, NW, N0T, N1T, 0, NS, true>, nullptr, nullptr, true, 0.5f             \
   }
 
 }  // namespace bolt

@@ -21,6 +21,7 @@
 #include <type_traits>
 
 #include "bolt_device.hpp"
+#include "fprop_dma_kernel.hpp"
 #include "tile_loaders.hpp"
 
 namespace bolt {
@@ -57,57 +58,15 @@ struct B2bK1 {
   static constexpr int NKT1 = N0T / KB1;
 };
 
-// Row-major weights ([K][N]): both matrices as one flat list of 8 x 8 blocks (a thread fetches 8 rows of 16 bytes,
-// transposes them in registers and writes 8 reduction-contiguous chunks), dealt over ALL threads two blocks at a
-// time with every load of a batch in flight before the first transpose - one memory round trip for the pair of
-// matrices of Table 1's shapes, where a k-tile at a time costs one per k-tile with a single wave at work.
+// Row-major weights ([K][N]) stay row-major in LDS: W0 as [nk0 * BK][N0T], W1 as [N0T][N1T], fetched with
+// direct-to-LDS loads (no registers, no transposes; one memory round trip that the first activation tile shares) and
+// read as matrix-core operands with the LDS transpose read (kn_frag_read).  Issues the loads only: the kernels wait
+// for them in front of the first workgroup barrier of their tile loop.
 template <int BK, int NT, int N0T, int N1T>
 __device__ __forceinline__ void b2b_preload_weights_kn(const B2bParams& p, half_t* W0s, half_t* W1s, int tid) {
-  constexpr int KB1 = B2bK1<N0T>::KB1, NKT1 = B2bK1<N0T>::NKT1;
-  constexpr int NB0 = (BK / 8) * (N0T / 8);   // blocks per k-tile of W0
-  constexpr int NB1 = (KB1 / 8) * (N1T / 8);  // ... of W1
-  constexpr int U = 2;
   const int nk0 = (p.K0 + BK - 1) / BK;
-  const int total0 = nk0 * NB0, total = total0 + NKT1 * NB1;
-  const half8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int base = 0; base < total; base += U * NT) {
-    half8 r[U][8];
-    half_t* dst[U];
-    int kb[U], row0[U];
-    bool first[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int blk = base + u * NT + tid;
-      first[u] = blk < total0;
-      const int w = first[u] ? blk % NB0 : (blk - total0) % NB1;
-      const int kt = first[u] ? blk / NB0 : (blk - total0) / NB1;
-      const int nblocks = first[u] ? N0T / 8 : N1T / 8;
-      const int nb = w % nblocks;
-      kb[u] = w / nblocks;
-      row0[u] = nb * 8;
-      const half_t* src = first[u] ? p.W0 : p.W1;
-      const int ld = first[u] ? p.ldw0 : p.ldw1;
-      const int kmax = first[u] ? p.K0 : p.N0, nmax = first[u] ? p.N0 : p.N1;
-      const int k0 = kt * (first[u] ? BK : KB1) + kb[u] * 8;
-      dst[u] = first[u] ? W0s + kt * N0T * BK : W1s + kt * N1T * KB1;
-#pragma unroll
-      for (int jj = 0; jj < 8; ++jj)
-        r[u][jj] = (blk < total && k0 + jj < kmax && row0[u] < nmax) ? *(const half8*)(src + (int64_t)(k0 + jj) * ld + row0[u]) : zero8;
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (base + u * NT + tid >= total) continue;
-#pragma unroll
-      for (int nn = 0; nn < 8; ++nn) {
-        half8 t;
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj) t[jj] = r[u][jj][nn];
-        const int off = first[u] ? lds_chunk_offset<BK>(row0[u] + nn, kb[u]) : lds_chunk_offset<KB1>(row0[u] + nn, kb[u]);
-        *(half8*)(dst[u] + off) = t;
-      }
-    }
-  }
-  __syncthreads();
+  kn_matrix_to_lds<NT, N0T>(p.W0, p.ldw0, p.K0, p.N0, nk0 * BK, W0s, tid);
+  kn_matrix_to_lds<NT, N1T>(p.W1, p.ldw1, p.N0, p.N1, N0T, W1s, tid);
 }
 
 // Loads W0 as [nk0][N0T][BK] and W1 as [N0T/KB1][N1T][KB1] into LDS (all threads, then barrier).
@@ -256,6 +215,13 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, l32 = lane & 31;
   b2b_preload_weights<BK, NT, N0T, N1T, WMODE>(p, W0s, W1s, tid);
+  int w0off[WMODE == 1 ? FN0 : 1], w1off[WMODE == 1 ? FN1 : 1];  // row-major weights: lane offsets of the transpose reads
+  if constexpr (WMODE == 1) {
+#pragma unroll
+    for (int a = 0; a < FN0; ++a) w0off[a] = kn_frag_offset<N0T>(a * 32, lane);
+#pragma unroll
+    for (int a = 0; a < FN1; ++a) w1off[a] = kn_frag_offset<N1T>(a * 32, lane, 4);
+  }
 
   for (int tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
     const int m0 = tile * BM;
@@ -273,6 +239,7 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
     // ---- op0 main loop: X streamed through a double-buffered LDS tile, W0 resident ----------
     xl.load(0, p.cg);
     xl.store(Xs);
+    if constexpr (WMODE == 1) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's weight loads have landed
     __syncthreads();
     for (int kt = 0; kt < nk0; ++kt) {
       const int buf = kt & 1;
@@ -287,7 +254,10 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
 #pragma unroll
         for (int b = 0; b < FM; ++b) xf[b] = *(const half8*)(xs + lds_chunk_offset<BK>(wave * WTM + b * 32 + l32, chunk));
 #pragma unroll
-        for (int a = 0; a < FN0; ++a) wf[a] = *(const half8*)(ws + lds_chunk_offset<BK>(a * 32 + l32, chunk));
+        for (int a = 0; a < FN0; ++a) {
+          if constexpr (WMODE == 1) wf[a] = kn_frag_read<N0T>(W0s, w0off[a], kt * BK + ks * 16);
+          else wf[a] = *(const half8*)(ws + lds_chunk_offset<BK>(a * 32 + l32, chunk));
+        }
 #pragma unroll
         for (int a = 0; a < FN0; ++a)
 #pragma unroll
@@ -320,9 +290,14 @@ __global__ __launch_bounds__(64 * NWAVES) void b2b_rf_kernel(const B2bParams p) 
 #pragma unroll
         for (int a = 0; a < NC1; ++a) {
           const int row = (c1 * NC1 + a) * 32 + l32;
-          const half4 lo = *(const half4*)(ws + lds_chunk_offset<KB1>(row, chunk) + g * 4);
-          const half4 hi = *(const half4*)(ws + lds_chunk_offset<KB1>(row, chunk + 1) + g * 4);
-          const half8 wf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          half8 wf;
+          if constexpr (WMODE == 1) {
+            wf = kn_frag_read<N1T>(W1s, w1off[c1 * NC1 + a], kbase, 8);
+          } else {
+            const half4 lo = *(const half4*)(ws + lds_chunk_offset<KB1>(row, chunk) + g * 4);
+            const half4 hi = *(const half4*)(ws + lds_chunk_offset<KB1>(row, chunk + 1) + g * 4);
+            wf = half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          }
 #pragma unroll
           for (int b = 0; b < FM; ++b) acc1[a][b] = mfma_32x32x16(wf, d0[t][b], acc1[a][b]);
         }
@@ -366,6 +341,13 @@ __global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams
   const int wm0 = wave % WM0, wn0 = wave / WM0;
   const int wm1 = wave % WM1, wn1 = wave / WM1;
   b2b_preload_weights<BK, NT, N0T, N1T, WMODE>(p, W0s, W1s, tid);
+  int w0off[WMODE == 1 ? FN0 : 1], w1off[WMODE == 1 ? FN1 : 1];  // row-major weights: lane offsets of the transpose reads
+  if constexpr (WMODE == 1) {
+#pragma unroll
+    for (int a = 0; a < FN0; ++a) w0off[a] = kn_frag_offset<N0T>(wn0 * WTN0 + a * 32, lane);
+#pragma unroll
+    for (int a = 0; a < FN1; ++a) w1off[a] = kn_frag_offset<N1T>(wn1 * WTN1 + a * 32, lane);
+  }
 
   for (int tile = blockIdx.x; tile < p.tiles_m; tile += gridDim.x) {
     const int m0 = tile * BM;
@@ -382,6 +364,7 @@ __global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams
 
     xl.load(0, p.cg);
     xl.store(Xs);
+    if constexpr (WMODE == 1) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's weight loads have landed
     __syncthreads();
     for (int kt = 0; kt < nk0; ++kt) {
       const int buf = kt & 1;
@@ -396,7 +379,10 @@ __global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams
 #pragma unroll
         for (int b = 0; b < FM0; ++b) xf[b] = *(const half8*)(xs + lds_chunk_offset<BK>(wm0 * WTM0 + b * 32 + l32, chunk));
 #pragma unroll
-        for (int a = 0; a < FN0; ++a) wf[a] = *(const half8*)(ws + lds_chunk_offset<BK>(wn0 * WTN0 + a * 32 + l32, chunk));
+        for (int a = 0; a < FN0; ++a) {
+          if constexpr (WMODE == 1) wf[a] = kn_frag_read<N0T>(W0s, w0off[a], kt * BK + ks * 16);
+          else wf[a] = *(const half8*)(ws + lds_chunk_offset<BK>(wn0 * WTN0 + a * 32 + l32, chunk));
+        }
 #pragma unroll
         for (int a = 0; a < FN0; ++a)
 #pragma unroll
@@ -450,7 +436,10 @@ __global__ __launch_bounds__(64 * WM0 * WN0) void b2b_lds_kernel(const B2bParams
 #pragma unroll
         for (int b = 0; b < FM1; ++b) xf[b] = *(const half8*)(xs + lds_chunk_offset<KB1>(wm1 * WTM1 + b * 32 + l32, chunk));
 #pragma unroll
-        for (int a = 0; a < FN1; ++a) wf[a] = *(const half8*)(ws + lds_chunk_offset<KB1>(wn1 * WTN1 + a * 32 + l32, chunk));
+        for (int a = 0; a < FN1; ++a) {
+          if constexpr (WMODE == 1) wf[a] = kn_frag_read<N1T>(W1s, w1off[a], kt1 * KB1 + ks * 16);
+          else wf[a] = *(const half8*)(ws + lds_chunk_offset<KB1>(wn1 * WTN1 + a * 32 + l32, chunk));
+        }
 #pragma unroll
         for (int a = 0; a < FN1; ++a)
 #pragma unroll

@@ -244,6 +244,7 @@ struct Tables {
     register_conv_nchw_out_instances(conv);  // last layers: the output written as NCHW
     register_b2b_gemm_instances(b2b_gemm);
     register_b2b_gemm_dma_instances(b2b_gemm);
+    register_b2b_gemm_dma_kn_instances(b2b_gemm);
     register_b2b_conv_instances(b2b_conv);
     register_b2b_conv_dma_instances(b2b_conv);
     register_b2b_conv_halo_instances(b2b_conv);
@@ -515,6 +516,8 @@ static bool b2b_can_run(const B2bInstance& in, const B2bProblem& pr) {
   if (in.xmode != pr.xmode || in.wmode != pr.wmode) return false;
   if (pr.residual && !in.residual) return false;
   if (pr.p.N0 > in.n0t || pr.p.N1 > in.n1t) return false;
+  // row-major weights are fetched through one buffer descriptor per matrix with 32-bit byte offsets
+  if (in.wmode == 1 && ((int64_t)pr.p.K0 * pr.p.ldw0 * 2 >= (1ll << 31) || (int64_t)pr.p.N0 * pr.p.ldw1 * 2 >= (1ll << 31))) return false;
   if (in.dyn_supports) return in.dyn_supports(pr.p) && in.dyn_lds_bytes(pr.p) <= kLdsPerCU;
   if (in.lds_bytes(pr.p.K0) > kLdsPerCU) return false;
   return true;
@@ -622,9 +625,12 @@ static bolt_status resolve_b2b(const std::vector<B2bInstance>& tab, const B2bPro
 // three-op chains
 // ------------------------------------------------------------------------------------------
 static bool chain_can_run(const ChainInstance& in, const B2bProblem& pr) {
-  if (in.xmode != pr.xmode || pr.wmode != 0) return false;
+  if (in.xmode != pr.xmode || in.wmode != pr.wmode) return false;
   const B2bParams& p = pr.p;
   if (p.N0 > in.n0t || p.N1 > in.n1t || p.N2 > in.n2t) return false;
+  // row-major weights are fetched through one buffer descriptor per matrix with 32-bit byte offsets
+  const int64_t lim = 1ll << 31;
+  if (in.wmode == 1 && ((int64_t)p.K0 * p.ldw0 * 2 >= lim || (int64_t)p.N0 * p.ldw1 * 2 >= lim || (int64_t)p.N1 * p.ldw2 * 2 >= lim)) return false;
   if (in.dyn_supports) return in.dyn_supports(p) && in.dyn_lds_bytes(p) <= kLdsPerCU;
   return in.lds_bytes <= kLdsPerCU;
 }
@@ -675,7 +681,6 @@ static bolt_status make_chain_problem(bolt_op op, int32_t n_ops, const void* con
     const bolt_gemm_desc* g2 = (const bolt_gemm_desc*)descs[2];
     if ((s = make_b2b_gemm_problem(g0, g1, pr)) != BOLT_OK) return s;
     if ((s = check_b2b_gemm(g1, g2)) != BOLT_OK) return s;
-    if (g0->b_layout != BOLT_LAYOUT_NK) return BOLT_ERR_UNSUPPORTED;  // the chain kernels stream K-contiguous weights
     B2bParams& p = pr->p;
     p.N2 = g2->N; p.ldw2 = g2->ldb; p.ldy = g2->ldd;
     p.alpha2 = g2->alpha; p.beta2 = g2->beta; p.act2 = g2->act;

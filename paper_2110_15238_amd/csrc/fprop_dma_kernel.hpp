@@ -225,12 +225,15 @@ struct DmaKnTileLoader {
   __device__ __forceinline__ void issue(int kt, half_t* dst, const ConvGeom& cg) { issue_part<0, NI>(kt, dst, cg); }
   __device__ __forceinline__ void advance(const ConvGeom&) {}
 };
-// This lane's part of the operand for the 32 columns that start at tile column col0, k-step ks (16 rows) of the
-// row-major tile at ws: k = 16 ks + 8 (lane / 32) .. +7 of column col0 + lane % 32.
+// This lane's part of the operand for the 32 columns that start at tile column col0, reduction rows row0 .. row0+15 of
+// the row-major tile at ws (row0 a multiple of 4): kn_frag_offset is the lane's constant part.  With the defaults the
+// lane receives k = row0 + 8 (lane / 32) .. +7 of column col0 + lane % 32, the operand order of the matrix core;
+// group_rows = 4 with second = 8 gives rows row0 + 4 (lane / 32) + {0..3, 8..11} (the RF-resident fused kernel's
+// permutation of op1's reduction index).
 template <int BN>
-__device__ __forceinline__ int kn_frag_offset(int col0, int lane) {
+__device__ __forceinline__ int kn_frag_offset(int col0, int lane, int group_rows = 8) {
   const int r = (lane & 15) >> 2, col = col0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  return ((lane >> 5) * 8 + r) * BN + (((col >> 3) ^ kn_swizzle<BN>(r)) << 3) + (col & 7);
+  return ((lane >> 5) * group_rows + r) * BN + (((col >> 3) ^ kn_swizzle<BN>(r)) << 3) + (col & 7);
 }
 // `ws` is __restrict__ for the sake of the compiler's wait-count pass: an LDS access that carries no alias
 // information is given a wait for EVERY direct-to-LDS load in flight (the pass cannot tell the stage being read from
@@ -238,12 +241,27 @@ __device__ __forceinline__ int kn_frag_offset(int col0, int lane) {
 // and escape that, the transpose-read builtin carries none unless the inlined restrict scope gives it some.  The
 // explicit waits in front of the workgroup barriers are what orders these reads after the loads they depend on.
 template <int BN>
-__device__ __forceinline__ half8 kn_frag_read(const half_t* __restrict__ ws, int lane_off, int ks) {
+__device__ __forceinline__ half8 kn_frag_read(const half_t* __restrict__ ws, int lane_off, int row0, int second = 4) {
   typedef short short4v __attribute__((ext_vector_type(4)));
   typedef __attribute__((address_space(3))) short4v lds_short4;
-  const half4 lo = __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(ws + lane_off + ks * 16 * BN)));
-  const half4 hi = __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(ws + lane_off + (ks * 16 + 4) * BN)));
+  const half4 lo = __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(ws + lane_off + row0 * BN)));
+  const half4 hi = __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(ws + lane_off + (row0 + second) * BN)));
   return half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
+// A whole row-major matrix [rows][cols] (leading dimension ld) into LDS as [rows_padded][BN] with the row swizzle
+// above, zero beyond rows / cols: the flat list of 16-byte chunks dealt over the waves, 64 per instruction.  Issues
+// the loads only; the caller waits (vmcnt) and synchronises.  The matrix must end below 2 GiB from W (host check).
+template <int NT, int BN>
+__device__ __forceinline__ void kn_matrix_to_lds(const half_t* W, int ld, int rows, int cols, int rows_padded, half_t* dst, int tid) {
+  constexpr int CH = BN / 8;
+  const __amdgpu_buffer_rsrc_t rsrc = make_rsrc(W, (unsigned)(((rows - 1) * ld + cols) * 2));
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int ninst = rows_padded * CH / 64;  // (rows_padded and CH are multiples of 32 and 4)
+  for (int i = wave; i < ninst; i += NT / 64) {
+    const int f = i * 64 + lane, row = f / CH, c = (f - row * CH) ^ kn_swizzle<BN>(row);
+    const unsigned off = (row < rows && c * 8 < cols) ? (unsigned)(row * ld + c * 8) * 2u : kInvalidOffset;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, BOLT_LDS_PTR(dst + i * 512), 16, off, 0, 0, 0);
+  }
 }
 
 // Last step of the tiled single-op kernels: accumulators -> FP16 C tile in LDS ([BM][BN], 16-byte chunks
@@ -461,7 +479,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
         x[k][b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
 #pragma unroll
       for (int a = 0; a < FN; ++a) {
-        if constexpr (WKN) w[k][a] = kn_frag_read<BN>(ws, wfo[a], grp * G + k);
+        if constexpr (WKN) w[k][a] = kn_frag_read<BN>(ws, wfo[a], (grp * G + k) * 16);
         else w[k][a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
       }
     }
@@ -512,7 +530,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N * KG) void fprop_dma_kernel(
       for (int b = 0; b < FM; ++b) x[b] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + b * 32 + l32, chunk));
 #pragma unroll
       for (int a = 0; a < FN; ++a) {
-        if constexpr (WKN) w[a] = kn_frag_read<BN>(ws, wfo[a], ks);
+        if constexpr (WKN) w[a] = kn_frag_read<BN>(ws, wfo[a], ks * 16);
         else w[a] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + a * 32 + l32, chunk));
       }
     };

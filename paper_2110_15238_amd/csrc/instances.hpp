@@ -125,6 +125,7 @@ void register_conv_nchw_out_instances(std::vector<FpropInstance>& v);
 void register_b2b_gemm_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_instances(std::vector<B2bInstance>& v);
 void register_b2b_gemm_dma_instances(std::vector<B2bInstance>& v);
+void register_b2b_gemm_dma_kn_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_dma_instances(std::vector<B2bInstance>& v);
 void register_b2b_conv_halo_instances(std::vector<B2bInstance>& v);
 void register_gemm_chain_instances(std::vector<ChainInstance>& v);

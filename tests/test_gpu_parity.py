@@ -458,6 +458,7 @@ def test_config3_b2b_gemm_every_instance(bolt):
 B2B_GEMM_SHAPES = [  # M, K0, N0, N1 (ragged M, every compiled (N0T, N1T) family, K0 tails)
     (1000, 72, 64, 128), (333, 256, 64, 16), (515, 256, 128, 64), (700, 96, 32, 96), (129, 8, 8, 8),
     (260, 200, 64, 256), (100, 64, 24, 72), (64, 128, 128, 128),
+    (515, 576, 128, 64),  # a row-major W0 beyond LDS: only the multi-stage kernel streams it
 ]
 
 
@@ -1066,25 +1067,26 @@ GEMM_CHAINS = [  # (M, K0, N0, N1, N2): ragged M, widths at and below the compil
     (333, 64, 64, 256, 64), (129, 136, 128, 128, 128), (1, 8, 8, 8, 8)]
 
 
+@pytest.mark.parametrize("layout", ["nk", "kn"])
 @pytest.mark.parametrize("shape", GEMM_CHAINS)
-def test_gemm_chain3_every_instance(bolt, shape):
+def test_gemm_chain3_every_instance(bolt, shape, layout):
     M, K0, N0, N1, N2 = shape
+    L = bolt.LAYOUT_NK if layout == "nk" else bolt.LAYOUT_KN
     A = wl.uniform_fp16(301, 0, (M, K0), -0.5, 0.5)
     Ws = [wl.uniform_fp16(301, 1, (K0, N0), -0.5, 0.5), wl.uniform_fp16(301, 2, (N0, N1), -0.5, 0.5),
           wl.uniform_fp16(301, 3, (N1, N2), -0.5, 0.5)]
     bs = [wl.uniform_fp16(301, 4, (N0,), -1, 1), None, wl.uniform_fp16(301, 6, (N2,), -1, 1)]
     acts = ["relu", "gelu", "none"]
     want = ref.gemm_chain(A, Ws, bs, acts)
-    descs = [bolt.gemm_desc(M, N0, K0, act=acts[0], b_layout=bolt.LAYOUT_NK),
-             bolt.gemm_desc(M, N1, N0, act=acts[1], b_layout=bolt.LAYOUT_NK),
-             bolt.gemm_desc(M, N2, N1, act=acts[2], b_layout=bolt.LAYOUT_NK)]
-    Wd = [dev(np.ascontiguousarray(W.T)) for W in Ws]
+    descs = [bolt.gemm_desc(M, N0, K0, act=acts[0], b_layout=L), bolt.gemm_desc(M, N1, N0, act=acts[1], b_layout=L),
+             bolt.gemm_desc(M, N2, N1, act=acts[2], b_layout=L)]
+    Wd = [dev(np.ascontiguousarray(W.T)) if layout == "nk" else dev(W) for W in Ws]
     bd = [dev(b) for b in bs]
     ran = 0
     for kid in range(bolt.bolt_num_instances(bolt.OP_GEMM_CHAIN3)):
         if not bolt.bolt_chain_instance_supports(bolt.OP_GEMM_CHAIN3, kid, descs):
             continue
-        _say("gemm chain %s instance %d" % (shape, kid))
+        _say("gemm chain %s weights %s instance %d" % (shape, layout, kid))
         D = torch.full((M, N2), float("nan"), dtype=torch.float16, device="cuda")
         bolt.bolt_b2b_gemm_chain(descs, dev(A), Wd, bd, D, {"kernel_id": kid})
         torch.cuda.synchronize()
@@ -1156,10 +1158,12 @@ def test_gemm_chain3_integer_bit_exact(bolt):
     assert_bit_equal(host(D), want, "integer gemm chain")
 
 
+@pytest.mark.parametrize("layout", ["nk", "kn"])
 @pytest.mark.parametrize("shape", [GEMM_CHAINS[0], GEMM_CHAINS[2], GEMM_CHAINS[3], GEMM_CHAINS[6]])
-def test_gemm_chain3_residual_every_instance(bolt, shape):
+def test_gemm_chain3_residual_every_instance(bolt, shape, layout):
     """Eq. 1 with a full matrix C in the last epilogue of a chain: strided C (ldc > N2), gamma != 1, every instance."""
     M, K0, N0, N1, N2 = shape
+    L = bolt.LAYOUT_NK if layout == "nk" else bolt.LAYOUT_KN
     A = wl.uniform_fp16(311, 0, (M, K0), -0.5, 0.5)
     Ws = [wl.uniform_fp16(311, 1, (K0, N0), -0.5, 0.5), wl.uniform_fp16(311, 2, (N0, N1), -0.5, 0.5),
           wl.uniform_fp16(311, 3, (N1, N2), -0.5, 0.5)]
@@ -1169,10 +1173,9 @@ def test_gemm_chain3_residual_every_instance(bolt, shape):
     acts = ["relu", "gelu", "relu"]
     want = ref.gemm_chain_residual(A, Ws, bs, acts, np.ascontiguousarray(Cfull[:, :N2]), gamma=-0.75)
     assert not np.array_equal(want, ref.gemm_chain(A, Ws, bs, acts))
-    descs = [bolt.gemm_desc(M, N0, K0, act=acts[0], b_layout=bolt.LAYOUT_NK),
-             bolt.gemm_desc(M, N1, N0, act=acts[1], b_layout=bolt.LAYOUT_NK),
-             bolt.gemm_desc(M, N2, N1, act=acts[2], b_layout=bolt.LAYOUT_NK)]
-    Wd = [dev(np.ascontiguousarray(W.T)) for W in Ws]
+    descs = [bolt.gemm_desc(M, N0, K0, act=acts[0], b_layout=L), bolt.gemm_desc(M, N1, N0, act=acts[1], b_layout=L),
+             bolt.gemm_desc(M, N2, N1, act=acts[2], b_layout=L)]
+    Wd = [dev(np.ascontiguousarray(W.T)) if layout == "nk" else dev(W) for W in Ws]
     bd = [dev(b) for b in bs]
     Cd = dev(Cfull)
     ran = 0

@@ -150,7 +150,7 @@ def test_b2b_fusion_legality(bolt):
     assert chk(bolt.OP_B2B_GEMM, G(16384, 64, 256), G(16384, 128, 72)) == ILLEGAL    # K1 must equal N0
     assert chk(bolt.OP_B2B_GEMM, G(16384, 64, 256), None) == INVALID
     assert chk(bolt.OP_B2B_GEMM, G(16384, 512, 256), G(16384, 128, 512)) == UNSUPPORTED  # no tile spans N0 = 512
-    assert chk(bolt.OP_B2B_GEMM, G(16384, 128, 8192), G(16384, 64, 128)) == UNSUPPORTED  # W0 does not fit in LDS
+    assert chk(bolt.OP_B2B_GEMM, G(16384, 128, 8192), G(16384, 64, 128)) == OK  # a W0 beyond LDS streams (multi-stage kernel)
     c0 = Cd(32, 56, 56, 64, 64, 3, 3, 1, 1)
     assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 64, 256, 1, 1, 1, 0)) == OK
     assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 64, 256, 3, 3, 1, 1)) == ILLEGAL   # 2nd conv must be 1x1
@@ -198,7 +198,12 @@ def test_chain_legality(bolt):
     assert chk(bolt.OP_GEMM_CHAIN3, g[:2]) == UNSUPPORTED                                  # only three-op chains are compiled
     assert chk(bolt.OP_GEMM_CHAIN3, [g[0], g[1], G(4096, 64, 120, b_layout=nk)]) == ILLEGAL  # K2 must equal N1
     assert chk(bolt.OP_GEMM_CHAIN3, [g[0], g[1], G(4000, 64, 128, b_layout=nk)]) == ILLEGAL  # same M
-    assert chk(bolt.OP_GEMM_CHAIN3, [G(4096, 64, 256), G(4096, 128, 64), G(4096, 64, 128)]) == UNSUPPORTED  # row-major weights
+    kn = [G(4096, 64, 256), G(4096, 128, 64), G(4096, 64, 128)]
+    assert chk(bolt.OP_GEMM_CHAIN3, kn) == OK                                              # row-major weights: instances of their own
+    assert chk(bolt.OP_GEMM_CHAIN3, [kn[0], kn[1], g[2]]) == UNSUPPORTED                   # ... but one layout per chain
+    n3 = bolt.bolt_num_instances(bolt.OP_GEMM_CHAIN3)
+    sup = lambda d: {i for i in range(n3) if bolt.bolt_chain_instance_supports(bolt.OP_GEMM_CHAIN3, i, d)}
+    assert sup(kn) and sup(g) and not sup(kn) & sup(g)
     assert chk(bolt.OP_GEMM_CHAIN3, [g[0], g[1], G(4096, 512, 128, b_layout=nk)]) == UNSUPPORTED  # N2 beyond every bound
     assert chk(bolt.OP_GEMM, g) == INVALID
     assert chk(bolt.OP_GEMM_CHAIN3, g, {"kernel_id": 9999}) == INVALID
