@@ -153,16 +153,18 @@ def main():
         try:
             # 8192^3 and 4096^3 are ours (long enough for steady state); 1280 x 3072 x 768 is the FFN GEMM of
             # the paper's epilogue-fusion experiment (Section 4.1.1)
-            for (M, N, K) in ((8192, 8192, 8192), (4096, 4096, 4096), (wl.EPILOGUE_GEMM.M, wl.EPILOGUE_GEMM.N, wl.EPILOGUE_GEMM.K)):
+            # each with B stored [N][K] (reduction index contiguous) and row-major [K][N]
+            gemms = ((8192, 8192, 8192), (4096, 4096, 4096), (wl.EPILOGUE_GEMM.M, wl.EPILOGUE_GEMM.N, wl.EPILOGUE_GEMM.K))
+            for (M, N, K, lay) in [g + (l,) for g in gemms for l in ("NK", "KN")]:
                 Ag = torch.randn((M, K), device="cuda", dtype=torch.float16) * 0.5
-                Bg = torch.randn((N, K), device="cuda", dtype=torch.float16) * 0.5
+                Bg = torch.randn((N, K) if lay == "NK" else (K, N), device="cuda", dtype=torch.float16) * 0.5
                 biasg = torch.randn((N,), device="cuda", dtype=torch.float16)
                 Dg = empty(M, N)
-                gd = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK, act="relu")
-                cfg = tuned("large gemm %dx%dx%d NK" % (M, N, K), bolt.OP_GEMM, gd, None, [Ag, Bg, biasg, Dg], ws)
+                gd = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK if lay == "NK" else bolt.LAYOUT_KN, act="relu")
+                cfg = tuned("large gemm %dx%dx%d %s" % (M, N, K, lay), bolt.OP_GEMM, gd, None, [Ag, Bg, biasg, Dg], ws)
                 ms = timed(lambda: bolt.bolt_gemm_epilogue(gd, Ag, Bg, biasg, Dg, cfg, ws), 10 if M >= 8192 else 30)
-                large.append(dict(name="GEMM %dx%dx%d + bias + ReLU (B as [N][K])" % (M, N, K), ms=round(ms, 4),
-                                  tflops=round(2.0 * M * N * K / ms / 1e9, 1),
+                large.append(dict(name="GEMM %dx%dx%d + bias + ReLU (B as %s)" % (M, N, K, "[N][K]" if lay == "NK" else "[K][N]"),
+                                  ms=round(ms, 4), tflops=round(2.0 * M * N * K / ms / 1e9, 1),
                                   pct_mfma_peak=round(100 * 2.0 * M * N * K / ms / 1e9 / MFMA_PEAK_TFLOPS, 2),
                                   config={k: cfg.as_dict()[k] for k in cfg_keys}))
                 del Ag, Bg, Dg
