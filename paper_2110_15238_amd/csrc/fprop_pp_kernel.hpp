@@ -69,9 +69,17 @@ __device__ __forceinline__ void pp_static_for(F&& f, std::integer_sequence<int, 
 // BM: rows of the output tile, 256 or 224 (two wave groups of 128 or 112 rows).  The narrower tile exists for the
 //     tuner: 256 compute units each take whole tiles, and a problem of 6.1 rounds of 256-row tiles is 7.0 rounds of
 //     224-row tiles that are 12.5 % shorter.
-template <int XMODE, int MI = 16, int PK = 64, bool RES = false, int BM = 256>
+// The transpose-read swizzle of a row-major [64][256] weight tile for the 16 x 16 x 32 operand layout: a half-wave reads
+// rows {0..3} and {8..11} (+16 for the other half) x 32 bytes, so chunk bits 2-3 take row bits 0-1 and chunk bit 1 takes row
+// bit 3; the 8 rows x 2 chunks then fall into 16 different bank groups (rows are multiples of 256 bytes).
+__device__ __forceinline__ int pp_kn_swizzle(int k) { return ((k & 3) << 2) | (((k >> 3) & 1) << 1); }
+
+// WKN (GEMM only): the weights are row-major [K][N]; their k-tiles go to LDS as they lie in memory and the operand is
+// gathered by the LDS transpose read (see DmaKnTileLoader in fprop_dma_kernel.hpp for the instruction's semantics).
+template <int XMODE, int MI = 16, int PK = 64, bool RES = false, int BM = 256, bool WKN = false>
 __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
   using T = FpropPpTraits;
+  static_assert(!WKN || (XMODE == 0 && MI == 16), "row-major weights: GEMM rows, 16 x 16 x 32 instruction");
   static_assert(MI == 16 || MI == 32, "matrix-core instruction");
   static_assert(PK == 32 || PK == 64, "phase depth");
   static_assert(XMODE == 0 || XMODE == 1, "row-major matrix or implicit im2col");
@@ -126,7 +134,19 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
     m0 = tm * BM;
     n0 = tn * BN;
     cur_r = cur_s = cur_c = 0;
-    if (grp == 0 || XMODE == 0) {
+    if (WKN && grp == 0) {
+      // instruction j of this wave fills tile rows (k) 2 (4 j + wq) and the next: lane / 32 picks the row, lane % 32 the
+      // 16-byte slot, which holds the row's chunk slot ^ swizzle(row).  st[j] = byte offset of that chunk from (row 0,
+      // column n0), or the invalid offset for columns beyond N.
+      const int64_t rem = ((int64_t)(p.K - 1) * p.ldw + (p.N - n0)) * 2;  // (the host keeps the matrix under 2 GiB)
+      rsrc = make_rsrc(p.W + n0, (unsigned)rem);
+#pragma unroll
+      for (int j = 0; j < L; ++j) {
+        const int krow = (j * 4 + wq) * 2 + (lane >> 5);
+        const int c = (lane & 31) ^ pp_kn_swizzle(krow);
+        st[j] = n0 + c * 8 < p.N ? krow * p.ldw * 2 + c * 16 : (int)kInvalidOffset;
+      }
+    } else if (grp == 0 || XMODE == 0) {
       const half_t* base = grp == 0 ? p.W + (int64_t)n0 * p.ldw : p.X + (int64_t)m0 * p.ldx;
       const int ld = grp == 0 ? p.ldw : p.ldx, rows_valid = grp == 0 ? p.N - n0 : p.M - m0;
       const int64_t rem = ((int64_t)(rows_valid - 1) * ld + p.K) * 2;
@@ -196,9 +216,13 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
     // fields, st[j] + lc16: more than one register per row would not fit)
     int sj = st[j];
     asm volatile("" : "+v"(sj));
-    if constexpr (decltype(gather)::value) {
+    if constexpr (decltype(gather)::value == 1) {
       const unsigned inv = __builtin_amdgcn_ubfe((unsigned)sj, (unsigned)tap_bit, 1u);
       off = (unsigned)(__mul24(sj >> 10, p.cg.C * 2) + tap_off) | (inv << 31);
+    } else if constexpr (decltype(gather)::value == 2) {
+      // row-major weights: k-tile kt starts 64 rows further down; rows at or beyond K are out of range
+      const int krow = kt * BK + (j * 4 + wq) * 2 + (lane >> 5);
+      off = ((unsigned)sj + (unsigned)(kt * BK * p.ldw * 2)) | (krow < p.K ? 0u : kInvalidOffset);
     } else {
       const int kb = (XMODE == 1 ? w_kb : kt * (BK * 2)) + lc16;
       off = ((unsigned)sj + (unsigned)kb) | (kb < k_limit_bytes ? 0u : kInvalidOffset);
@@ -221,12 +245,13 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
     pp_static_for([&](auto jc) { issue_one(jc, kt, dst, gather); }, std::make_integer_sequence<int, L>{});
     advance_tile();
   };
-  using Gather = std::integral_constant<bool, XMODE == 1>;  // group 1 of a convolution
-  using Rows = std::false_type;                            // matrix rows
+  using Gather = std::integral_constant<int, XMODE == 1 ? 1 : 0>;  // group 1 of a convolution
+  using Rows = std::integral_constant<int, 0>;                    // matrix rows
+  using WRows = std::integral_constant<int, WKN ? 2 : 0>;         // the weight tile: [N][K] rows, or row-major [K][N]
   // the first k-tiles of an output tile: W(0) by group 0, X(0) and X(1) by group 1
   auto issue_first_tiles = [&]() {
     if (grp == 0) {
-      issue_tile(0, wring, Rows{});
+      issue_tile(0, wring, WRows{});
     } else {
       issue_tile(0, xring, Gather{});
       issue_tile(1, xring + T::X_HALVES, Gather{});
@@ -236,11 +261,30 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
   acc_t acc[FN][FM];
   half8 xf[KS][FM], wf[KS][FN];
   constexpr int NREAD = KS * (FM + FN);  // fragment reads per phase
+  // row-major weights: this lane's offset (halves) inside the [64][256] tile for fragment column 0 of its wave and k-step
+  // 0: row 8 g + (lr / 4), columns wn * 64 + 4 (lr % 4) .. +3.  Fragment column i flips chunk bits 1-2 (i * 16 halves),
+  // k-step k adds 32 rows, the second transpose read 4 rows.
+  int kn_off = 0;
+  if constexpr (WKN) {
+    const int r4 = lr >> 2, q4 = lr & 3;
+    kn_off = (g * 8 + r4) * BN + (((wn * 8 + (q4 >> 1)) ^ pp_kn_swizzle(g * 8 + r4)) << 3) + (q4 & 1) * 4;
+  }
   auto read_one = [&](const half_t* xs, const half_t* ws, int h, auto rc) {
     constexpr int r = decltype(rc)::value, k = r / (FM + FN), i = r % (FM + FN);
     const int chunk = (h * KS + k) * KL + g;
     if constexpr (i < FM) xf[k][i] = *(const half8*)(xs + dma_chunk_offset<BK>(wm * WTM + i * MI + lr, chunk));
+    else if constexpr (WKN) {
+      int ko = kn_off;  // (the empty asm keeps the per-fragment addresses from being hoisted out of the k loop: one register, not eight)
+      asm volatile("" : "+v"(ko));
+      wf[k][i - FM] = kn_frag_read<BN>(ws, ko ^ ((i - FM) * 16), (h * KS + k) * MK);
+    }
     else wf[k][i - FM] = *(const half8*)(ws + dma_chunk_offset<BK>(wn * WTN + (i - FM) * MI + lr, chunk));
+  };
+  // LDS read instructions of fragment reads [r0, r1) of a phase (a row-major weight fragment takes two)
+  constexpr auto ds_reads = [](int r0, int r1) constexpr {
+    int n = 0;
+    for (int r = r0; r < r1; ++r) n += (WKN && r % (FM + FN) >= FM) ? 2 : 1;
+    return n;
   };
   // An M phase that also loads: the L load instructions of k-tile kt (into dst) interleaved with the phase's fragment
   // reads, so that the address path and the LDS pipe work side by side.
@@ -256,7 +300,7 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
     pp_static_for([&](auto jc) {
       constexpr int j = decltype(jc)::value;
       __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                        // one load
-      __builtin_amdgcn_sched_group_barrier(0x100, (j + 1) * NREAD / L - j * NREAD / L, 0);      // its share of reads
+      __builtin_amdgcn_sched_group_barrier(0x100, ds_reads(j * NREAD / L, (j + 1) * NREAD / L), 0);  // its share of reads
     }, std::make_integer_sequence<int, L>{});
   };
   auto m_phase_reads = [&](const half_t* xs, const half_t* ws, int h) {
@@ -428,9 +472,12 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
         // ---- M phase --------------------------------------------------------------------------------------
         fence();
         if (h == 0) {
-          if constexpr (XMODE == 0) {
+          if constexpr (XMODE == 0 && !WKN) {
             // both groups run the same code on their own rows, offsets and stage
             m_phase_loads(grp == 0 ? wring + ws_next * T::W_HALVES : xring + xs_fill * T::X_HALVES, t + 1 + grp, xs, ws, Rows{});
+          } else if constexpr (XMODE == 0) {
+            if (grp == 0) m_phase_loads(wring + ws_next * T::W_HALVES, t + 1, xs, ws, WRows{});
+            else m_phase_loads(xring + xs_fill * T::X_HALVES, t + 2, xs, ws, Rows{});
           } else {
             if (grp == 0) m_phase_loads(wring + ws_next * T::W_HALVES, t + 1, xs, ws, Rows{});
             else m_phase_loads(xring + xs_fill * T::X_HALVES, t + 2, xs, ws, Gather{});
@@ -472,10 +519,10 @@ __global__ __launch_bounds__(512) void fprop_pp_kernel(const FpropParams p) {
   }
 }
 
-template <int XMODE, int MI = 16, int PK = 64, int BM = 256>
+template <int XMODE, int MI = 16, int PK = 64, int BM = 256, bool WKN = false>
 hipError_t launch_fprop_pp(const FpropParams& p, hipStream_t stream) {
   using T = FpropPpTraits;
-  auto kern = p.res ? fprop_pp_kernel<XMODE, MI, PK, true, BM> : fprop_pp_kernel<XMODE, MI, PK, false, BM>;
+  auto kern = p.res ? fprop_pp_kernel<XMODE, MI, PK, true, BM, WKN> : fprop_pp_kernel<XMODE, MI, PK, false, BM, WKN>;
   static LdsOptIn opt_in[2];
   if (hipError_t e = opt_in[p.res ? 1 : 0].ensure((const void*)kern, T::LDS_BYTES); e != hipSuccess) return e;
   // one workgroup per compute unit; 256 is a multiple of the 8 XCDs, so the tiles w, w + 256, ... of a workgroup
@@ -502,6 +549,13 @@ inline int fprop_pp_lds_bytes(const FpropParams&) { return FpropPpTraits::LDS_BY
     "pp_" #BM "x256x64_w2x4_mi" #MI "_pk" #PK, BM, 256, 64, 2, 4, XMODE, 0, 2, bolt::FpropPpTraits::LDS_BYTES, \
         &bolt::launch_fprop_pp<XMODE, MI, PK, BM>,                                                          \
         XMODE == 1 ? &bolt::fprop_pp_conv_supports : nullptr, XMODE == 1 ? &bolt::fprop_pp_lds_bytes : nullptr, 0, MI, true \
+  }
+
+// The GEMM form for row-major weights (wmode 1).
+#define BOLT_FPROP_PP_KN_INSTANCE(MI, PK, BM)                                                                \
+  {                                                                                                         \
+    "ppkn_" #BM "x256x64_w2x4_mi" #MI "_pk" #PK, BM, 256, 64, 2, 4, 0, 1, 2, bolt::FpropPpTraits::LDS_BYTES,    \
+        &bolt::launch_fprop_pp<0, MI, PK, BM, true>, nullptr, nullptr, 0, MI, true, false, true               \
   }
 
 }  // namespace bolt

@@ -237,7 +237,8 @@ def test_conv_pingpong_instance_integer_bit_exact(bolt, case):
         assert_close(got, want, "ping-pong conv %s act %s" % (case, act))
 
 
-def test_gemm_pingpong_instance_integer_bit_exact_k_tails_and_split_k_refusal(bolt):
+@pytest.mark.parametrize("layout", ["nk", "kn"])
+def test_gemm_pingpong_instance_integer_bit_exact_k_tails_and_split_k_refusal(bolt, layout):
     ids = _pingpong_ids(bolt, bolt.OP_GEMM)
     assert ids
     for (M, N, K) in ((700, 264, 200), (257, 520, 64), (1, 136, 8), (513, 256, 1096)):
@@ -245,15 +246,17 @@ def test_gemm_pingpong_instance_integer_bit_exact_k_tails_and_split_k_refusal(bo
         B = wl.integer_fp16(233, 1, (K, N), -1, 1)
         bias = wl.integer_fp16(233, 2, (N,), -3, 3)
         want = ref.gemm(A, B, bias)
-        d = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK)
-        for kid in [k for k in ids if bolt.bolt_instance_supports(bolt.OP_GEMM, k, d)]:
-            _say("ping-pong gemm %s instance %d" % ((M, N, K), kid))
-            got, _ = _run_gemm(bolt, A, B, bias, layout="nk", config={"kernel_id": kid, "swizzle": 4})
-            assert_bit_equal(got, want, "ping-pong gemm %s instance %d" % ((M, N, K), kid))
+        d = bolt.gemm_desc(M, N, K, b_layout=bolt.LAYOUT_NK if layout == "nk" else bolt.LAYOUT_KN)
+        mine = [k for k in ids if bolt.bolt_instance_supports(bolt.OP_GEMM, k, d)]
+        assert mine, "no ping-pong instance for weights stored %s" % layout
+        for kid in mine:
+            _say("ping-pong gemm %s weights %s instance %d" % ((M, N, K), layout, kid))
+            got, _ = _run_gemm(bolt, A, B, bias, layout=layout, config={"kernel_id": kid, "swizzle": 4})
+            assert_bit_equal(got, want, "ping-pong gemm %s weights %s instance %d" % ((M, N, K), layout, kid))
             # the kernel has no partial-sum output: asking for split-K is an error, not a silent full-K run
             ws = torch.empty(8 * M * N, dtype=torch.float32, device="cuda")
             with pytest.raises(bolt.BoltError) as e:
-                _run_gemm(bolt, A, B, bias, layout="nk", config={"kernel_id": kid, "split_k": 2}, workspace=ws)
+                _run_gemm(bolt, A, B, bias, layout=layout, config={"kernel_id": kid, "split_k": 2}, workspace=ws)
             assert e.value.status == 2
 
 
