@@ -7,7 +7,7 @@ namespace bolt {
 #define BOLT_CHAIN_WIDTHS(X, XMODE)                                                                          \
   X(64, 64, 64, 2, XMODE), X(64, 64, 64, 3, XMODE), X(64, 64, 128, 3, XMODE), X(64, 128, 64, 3, XMODE),       \
   X(64, 64, 256, 2, XMODE), X(64, 256, 64, 2, XMODE), X(128, 64, 64, 2, XMODE), X(128, 64, 128, 2, XMODE),     \
-  X(64, 128, 128, 2, XMODE), X(128, 128, 64, 2, XMODE), X(128, 128, 128, 2, XMODE)
+  X(64, 128, 128, 2, XMODE), X(128, 128, 64, 2, XMODE), X(128, 128, 128, 2, XMODE), X(32, 128, 32, 2, XMODE)
 #define CH(N0T, N1T, N2T, NS, XMODE) BOLT_B2B_CHAIN_INSTANCE(128, 64, 4, N0T, N1T, N2T, NS, XMODE)
 #define CHK(N0T, N1T, N2T, NS, XMODE) BOLT_B2B_CHAIN_KN_INSTANCE(128, 64, 4, N0T, N1T, N2T, NS)
 void register_gemm_chain_instances(std::vector<ChainInstance>& v) {

@@ -1067,7 +1067,7 @@ def test_single_layer_network_nchw_in_nchw_out(bolt, shape):
 # ---------------------------------------------------------------------------------------------
 GEMM_CHAINS = [  # (M, K0, N0, N1, N2): ragged M, widths at and below the compiled bounds
     (1000, 72, 64, 64, 64), (515, 256, 64, 128, 64), (700, 96, 40, 64, 256), (260, 200, 128, 64, 120),
-    (333, 64, 64, 256, 64), (129, 136, 128, 128, 128), (1, 8, 8, 8, 8)]
+    (333, 64, 64, 256, 64), (129, 136, 128, 128, 128), (1, 8, 8, 8, 8), (700, 96, 32, 96, 32)]
 
 
 @pytest.mark.parametrize("layout", ["nk", "kn"])
