@@ -128,19 +128,33 @@ def test_gemm_split_k_and_swizzle(bolt):
     assert e.value.status == 4
 
 
-def test_gemm_leading_dimensions(bolt):
-    M, N, K, lda, ldb, ldd = 70, 40, 48, 64, 56, 72
+@pytest.mark.parametrize("layout", ["kn", "nk"])
+def test_gemm_leading_dimensions_every_instance(bolt, layout):
+    """Row strides beyond the extents on all three matrices (the bytes between are poison for B: NaN), N and K ragged
+    against every tile, through the built-in pick and every instance of the layout."""
+    M, N, K, lda, ldd = 300, 104, 136, 152, 120
+    ldb = 112 if layout == "kn" else 144
     A = wl.uniform_fp16(105, 0, (M, lda), -1, 1)
-    B = wl.uniform_fp16(105, 1, (K, ldb), -1, 1)
+    Bm = wl.uniform_fp16(105, 1, (K, N), -1, 1)
     bias = wl.uniform_fp16(105, 2, (N,), -1, 1)
-    want = ref.gemm(A[:, :K], B[:, :N], bias)
-    d = bolt.gemm_desc(M, N, K, lda=lda, ldb=ldb, ldd=ldd)
-    D = torch.zeros((M, ldd), dtype=torch.float16, device="cuda")
-    bolt.bolt_gemm_epilogue(d, dev(A), dev(B), dev(bias), D)
-    torch.cuda.synchronize()
-    got = host(D)
-    assert_close(got[:, :N], want, "gemm with leading dimensions")
-    assert not got[:, N:].any(), "columns beyond N were written"
+    want = ref.gemm(np.ascontiguousarray(A[:, :K]), Bm, bias)
+    Bs = np.full((K, ldb) if layout == "kn" else (N, ldb), np.nan, dtype=np.float16)
+    if layout == "kn":
+        Bs[:, :N] = Bm
+    else:
+        Bs[:, :K] = Bm.T
+    d = bolt.gemm_desc(M, N, K, lda=lda, ldb=ldb, ldd=ldd, b_layout=bolt.LAYOUT_KN if layout == "kn" else bolt.LAYOUT_NK)
+    Ad, Bd, bd = dev(A), dev(Bs), dev(bias)
+    ids = [k for k in range(bolt.bolt_num_instances(bolt.OP_GEMM)) if bolt.bolt_instance_supports(bolt.OP_GEMM, k, d)]
+    assert len(ids) >= 8
+    for cfg in [None] + [{"kernel_id": k} for k in ids]:
+        _say("gemm leading dimensions, weights %s, config %s" % (layout, cfg))
+        D = torch.zeros((M, ldd), dtype=torch.float16, device="cuda")
+        bolt.bolt_gemm_epilogue(d, Ad, Bd, bd, D, cfg)
+        torch.cuda.synchronize()
+        got = host(D)
+        assert_close(got[:, :N], want, "gemm with leading dimensions, weights %s, config %s" % (layout, cfg))
+        assert not got[:, N:].any(), "columns beyond N were written (config %s)" % (cfg,)
 
 
 # ---------------------------------------------------------------------------------------------
@@ -439,6 +453,40 @@ def _run_b2b_gemm(bolt, t, config=None, act0="relu", act1="relu", layout="kn"):
     bolt.bolt_b2b_gemm(g0, g1, dev(t["A"]), dev(W0), dev(t["b0"]), dev(W1), dev(t["b1"]), D1, config)
     torch.cuda.synchronize()
     return host(D1), g0, g1
+
+
+@pytest.mark.parametrize("layout", ["kn", "nk"])
+@pytest.mark.parametrize("shape", [(300, 136, 56, 104), (260, 72, 32, 24), (130, 600, 128, 64)])
+def test_b2b_gemm_leading_dimensions_every_instance(bolt, shape, layout):
+    """Row strides beyond the extents on A, both weight matrices and D1; what lies between the rows of the weights is NaN,
+    so a kernel that reads a chunk beyond N or K (instead of taking zeros for it) fails.  Every instance of the layout."""
+    M, K0, N0, N1 = shape
+    lda, ldd = K0 + 16, N1 + 8
+    A = wl.uniform_fp16(421, 0, (M, lda), -0.5, 0.5)
+    W0, W1 = wl.uniform_fp16(421, 1, (K0, N0), -0.5, 0.5), wl.uniform_fp16(421, 3, (N0, N1), -0.5, 0.5)
+    b0, b1 = wl.uniform_fp16(421, 2, (N0,), -0.5, 0.5), wl.uniform_fp16(421, 4, (N1,), -0.5, 0.5)
+    want = ref.b2b_gemm(np.ascontiguousarray(A[:, :K0]), W0, b0, W1, b1)
+
+    def padded(Wm):  # the matrix as stored, 24 poisoned halves behind every row
+        src = Wm if layout == "kn" else np.ascontiguousarray(Wm.T)
+        out = np.full((src.shape[0], src.shape[1] + 24), np.nan, dtype=np.float16)
+        out[:, :src.shape[1]] = src
+        return out
+    W0s, W1s = padded(W0), padded(W1)
+    lay = bolt.LAYOUT_KN if layout == "kn" else bolt.LAYOUT_NK
+    g0 = bolt.gemm_desc(M, N0, K0, lda=lda, ldb=W0s.shape[1], b_layout=lay)
+    g1 = bolt.gemm_desc(M, N1, N0, ldb=W1s.shape[1], ldd=ldd, b_layout=lay)
+    Ad, W0d, W1d, b0d, b1d = dev(A), dev(W0s), dev(W1s), dev(b0), dev(b1)
+    ids = [k for k in range(bolt.bolt_num_instances(bolt.OP_B2B_GEMM)) if bolt.bolt_instance_supports(bolt.OP_B2B_GEMM, k, g0, g1)]
+    assert ids, "no instance for %s weights %s" % (shape, layout)
+    for cfg in [None] + [{"kernel_id": k} for k in ids]:
+        _say("b2b gemm leading dimensions %s weights %s config %s" % (shape, layout, cfg))
+        D1 = torch.zeros((M, ldd), dtype=torch.float16, device="cuda")
+        bolt.bolt_b2b_gemm(g0, g1, Ad, W0d, b0d, W1d, b1d, D1, cfg)
+        torch.cuda.synchronize()
+        got = host(D1)
+        assert_close(got[:, :N1], want, "b2b gemm leading dimensions %s weights %s config %s" % (shape, layout, cfg))
+        assert not got[:, N1:].any(), "columns beyond N1 were written (config %s)" % (cfg,)
 
 
 def test_config3_b2b_gemm_every_instance(bolt):
