@@ -166,6 +166,9 @@ bolt_status bolt_gemm_epilogue_noalloc(const bolt_gemm_desc* desc, const void* A
  * Legal only if g1->M == g0->M and g1->K == g0->N (else BOLT_ERR_ILLEGAL_FUSION).  Threadblock
  * residence: the workgroup tile spans all of N0 and N1, so N0 <= 128, N1 <= 256 and W1 must fit
  * in LDS next to the streaming tiles (else BOLT_ERR_UNSUPPORTED); W0 may be of any depth K0.
+ * Row-major weights (BOLT_LAYOUT_KN) are addressed with 32-bit byte offsets from their first element: a matrix with
+ * rows * ldb * 2 >= 2^31 bytes is BOLT_ERR_UNSUPPORTED here and in the chain calls (bolt_gemm_epilogue has a slower
+ * kernel for it).
  * g0->ldd and g1->lda are ignored (D0 is never stored). */
 bolt_status bolt_b2b_gemm(const bolt_gemm_desc* g0, const bolt_gemm_desc* g1, const void* A0, const void* W0,
                           const void* b0, const void* W1, const void* b1, void* D1, const bolt_config* config,
