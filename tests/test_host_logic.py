@@ -151,6 +151,9 @@ def test_b2b_fusion_legality(bolt):
     assert chk(bolt.OP_B2B_GEMM, G(16384, 64, 256), None) == INVALID
     assert chk(bolt.OP_B2B_GEMM, G(16384, 512, 256), G(16384, 128, 512)) == UNSUPPORTED  # no tile spans N0 = 512
     assert chk(bolt.OP_B2B_GEMM, G(16384, 128, 8192), G(16384, 64, 128)) == OK  # a W0 beyond LDS streams (multi-stage kernel)
+    # row-major weights are addressed with 32-bit byte offsets: K0 * ldb * 2 must stay below 2 GiB
+    assert chk(bolt.OP_B2B_GEMM, G(4096, 32, 1024, ldb=(1 << 20) - 8), G(4096, 32, 32)) == OK
+    assert chk(bolt.OP_B2B_GEMM, G(4096, 32, 1024, ldb=1 << 20), G(4096, 32, 32)) == UNSUPPORTED
     c0 = Cd(32, 56, 56, 64, 64, 3, 3, 1, 1)
     assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 64, 256, 1, 1, 1, 0)) == OK
     assert chk(bolt.OP_B2B_CONV, c0, Cd(32, 56, 56, 64, 256, 3, 3, 1, 1)) == ILLEGAL   # 2nd conv must be 1x1
