@@ -9,6 +9,7 @@ void register_b2b_gemm_dma_instances(std::vector<B2bInstance>& v) {
       BDG(128, 64, 4, 64, 128, 3), BDG(128, 64, 4, 64, 128, 2), BDG(128, 64, 4, 128, 64, 2), BDG(128, 64, 4, 128, 64, 3),
       BDG(128, 64, 4, 64, 64, 3),  BDG(128, 64, 4, 32, 128, 3), BDG(128, 64, 4, 64, 32, 3),  BDG(128, 64, 4, 128, 128, 2),
       BDG(128, 64, 4, 64, 256, 2), BDG(64, 64, 2, 64, 128, 3),  BDG(128, 64, 4, 32, 128, 2),
+      BDG(64, 64, 2, 64, 32, 3),
   };
   for (const auto& t : table) v.push_back(t);
 }
@@ -19,6 +20,7 @@ void register_b2b_gemm_dma_kn_instances(std::vector<B2bInstance>& v) {
       BDK(128, 64, 4, 64, 128, 3), BDK(128, 64, 4, 64, 128, 2), BDK(128, 64, 4, 128, 64, 2), BDK(128, 64, 4, 128, 64, 3),
       BDK(128, 64, 4, 64, 64, 3),  BDK(128, 64, 4, 32, 128, 3), BDK(128, 64, 4, 64, 32, 3),  BDK(128, 64, 4, 128, 128, 2),
       BDK(128, 64, 4, 64, 256, 2), BDK(64, 64, 2, 64, 128, 3),  BDK(128, 64, 4, 32, 128, 2),
+      BDK(64, 64, 2, 64, 32, 3),
   };
   for (const auto& t : table) v.push_back(t);
 }
