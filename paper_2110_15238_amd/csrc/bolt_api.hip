@@ -381,11 +381,27 @@ static void fprop_fill_config(const FpropInstance& in, int id, bolt_config* c) {
   c->mfma_shape = in.mi ? in.mi : 32; c->stages = in.stages; c->b2b_mode = 0;
 }
 
-// Built-in pick rule: smallest estimated time under a crude model -- rounds of workgroups over
-// the compute units times the work of one tile, de-rated for small tiles (low FLOP per LDS byte).
+// Built-in pick rule (a caller that passes no config and does not tune): the smallest estimated time, in
+// microseconds, under a model of three overlapping parts plus a launch floor,
+//   matrix work   tiles a compute unit runs one after the other x MACs of a tile (whole k-tiles) / (rate x eff), where
+//                 eff = 1 / (1 + 71 (1 / wave_tile_m + 1 / wave_tile_n)) stands for the FLOP per LDS byte of the wave tile;
+//   tile traffic  the same tiles' operands through the L2;
+//   latency chain of one workgroup, prologue + k-tile steps (+ the k-groups' reduction), repeated once per round of
+//                 co-resident workgroups;
+//   memory        every tensor once at the bandwidth the kernels sustain.
+// The constants are a fit to the per-instance timings of 53 problems - the ResNet-50 layers at batch 32 and a few
+// other batches, the GEMM shapes of Section 4 in both weight layouts, 1671 measurements: least squares on log time,
+// then perturbed for the smallest mean time of the pick over the fastest instance.  bolt_tune measures instead.
 // The halo, single-stage and ping-pong kernels have no partial-sum output.
 static bool fprop_can_split_k(const FpropInstance& in) {
   return !in.dyn_supports && in.stages != 1 && !in.no_split_k;
+}
+
+// BOLT_TUNE_LOG=1 in the environment prints every candidate's time (bolt_tune) or estimated cost (the built-in pick
+// rule) to stderr.
+static bool tune_log_enabled() {
+  static const bool on = [] { const char* e = std::getenv("BOLT_TUNE_LOG"); return e && e[0] && e[0] != '0'; }();
+  return on;
 }
 
 // need_split_k: only instances that can write partial sums qualify (the caller asked for split-K).
@@ -396,15 +412,34 @@ static int fprop_heuristic(const std::vector<FpropInstance>& tab, const FpropPro
     const FpropInstance& in = tab[i];
     if (!fprop_supports(in, pr)) continue;
     if (need_split_k && !fprop_can_split_k(in)) continue;
-    const double tiles = (double)ceil_div(pr.p.M, in.bm) * ceil_div(pr.p.N, in.bn);
-    const int lds = in.dyn_lds_bytes ? in.dyn_lds_bytes(pr.p) : in.lds_bytes;
-    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n * std::max(1, in.kgroups)) / 2));
-    const double rounds = std::ceil(tiles / (kNumCU * per_cu)) * per_cu;
+    const FpropParams& p = pr.p;
+    const double tiles = (double)ceil_div(p.M, in.bm) * ceil_div(p.N, in.bn);
+    const int kg = std::max(1, in.kgroups);
+    const int lds = in.dyn_lds_bytes ? in.dyn_lds_bytes(p) : in.lds_bytes;
+    const int per_cu = std::max(1, std::min(kLdsPerCU / lds, 2048 / (64 * in.waves_m * in.waves_n * kg) / 2));
+    const bool pingpong = in.mi == 16 && in.bn == 256, halo = !pingpong && in.dyn_supports && in.xmode == 1;
+    const bool reg_staged = in.wmode == 1 && !in.kn_dma;  // the slow cover of the direct-to-LDS row-major kernels
+    const double nk = ceil_div(p.K, in.bk), kpad = nk * in.bk;
     const double wtm = (double)in.bm / in.waves_m, wtn = (double)in.bn / in.waves_n;
-    const double eff = 1.0 / (1.0 + 48.0 * (1.0 / wtm + 1.0 / wtn) / 2.0);
-    const double cost = rounds * (double)in.bm * in.bn / eff;
+    const double eff = 1.0 / (1.0 + 71.0 * (1.0 / wtm + 1.0 / wtn));
+    const double family = reg_staged ? 1.95 : pingpong ? 0.88 : halo ? 0.84 : 1.0;
+    const double seq = std::ceil(tiles / kNumCU);  // tiles a compute unit runs one after the other
+    const double t_mfma = seq * in.bm * in.bn * kpad / eff / 7.99e6 * family;
+    // one workgroup's chain: prologue, k-tile steps (a deeper pipeline hides more of each), the k-groups' reduction
+    const double step = 0.526 * std::pow(2.0 / std::max(2, in.stages), 0.85);
+    const double t_lat = std::ceil(tiles / (kNumCU * per_cu)) * (1.66 + nk / kg * step + (kg - 1) * 0.32);
+    // operand tiles through the L2: (bm + bn) x bk halves per k-tile of every tile
+    const double t_l2 = seq * nk * (in.bm + in.bn) * in.bk * 2.0 / 1.95e5;
+    // activations: a 1x1 / stride 1 filter or a GEMM reads M x K, a filter window re-reads its pixels out of cache
+    double in_halves = (double)p.M * p.K;
+    if (pr.xmode != 0 && p.cg.C > 0) in_halves = (double)p.M * std::min<double>(p.K, (double)p.cg.C * p.cg.stride_h * p.cg.stride_w);
+    const double t_mem = 2.0 * (in_halves + (double)p.N * p.K + (double)p.M * p.N) / 6.43e6;
+    const double cost = 2.85 + (std::max(std::max(t_mfma, t_l2), std::max(t_lat, t_mem)) + 0.3 * std::min(t_mfma, t_lat)) *
+                                   std::pow((double)in.bm / in.bn, 0.01);
+    if (tune_log_enabled()) std::fprintf(stderr, "[bolt_pick] candidate %d %s cost %.4g\n", i, in.name, cost);
     if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
   }
+  if (tune_log_enabled() && best >= 0) std::fprintf(stderr, "[bolt_pick] -> %d %s\n", best, tab[best].name);
   return best;
 }
 
@@ -769,11 +804,6 @@ static bolt_status time_launches(F&& fn, int warm, int reps, hipStream_t stream,
   return BOLT_OK;
 }
 
-// BOLT_TUNE_LOG=1 in the environment prints every candidate's time to stderr.
-static bool tune_log_enabled() {
-  static const bool on = [] { const char* e = std::getenv("BOLT_TUNE_LOG"); return e && e[0] && e[0] != '0'; }();
-  return on;
-}
 
 template <typename RunF>
 static bolt_status tune_candidates(std::vector<Candidate>& cands, RunF&& run, hipStream_t stream, Candidate* best,
