@@ -588,12 +588,19 @@ static int b2b_heuristic(const std::vector<B2bInstance>& tab, const B2bProblem& 
     const double tiles = ceil_div(pr.p.M, in.bm);
     const int lds = in.dyn_lds_bytes ? in.dyn_lds_bytes(pr.p) : in.lds_bytes(pr.p.K0);
     const int per_cu = std::max(1, std::min(kLdsPerCU / std::max(lds, 1), 2048 / in.nthreads));  // co-resident workgroups
-    const double rounds = std::ceil(tiles / (kNumCU * per_cu)) * per_cu;
+    const double rounds = std::ceil(tiles / kNumCU);  // tiles a compute unit works through, co-resident or in turn
     const double kpad = (double)ceil_div(pr.p.K0, in.bk) * in.bk;  // a short reduction pays for the whole last k-tile
     double cost = rounds * in.bm * (in.mode == 0 ? 1.0 : 1.1) * (kpad * in.n0t + (double)in.n0t * in.n1t) *
                   (in.prior > 0.f ? in.prior : 1.0);
+    // 64-row wave tiles read half the weight fragments per MFMA of 32-row ones, and a second co-resident workgroup
+    // covers the load and store phases of the first (measured on the pairs of Table 2: 256-row tiles of 4 waves win
+    // wherever two of them fit a compute unit)
+    cost *= 1.0 + 32.0 / ((double)in.bm / in.waves_m);
+    cost *= 1.0 + 0.5 / std::min<double>(per_cu, std::max(1.0, std::ceil(tiles / kNumCU)));
+    if (tune_log_enabled()) std::fprintf(stderr, "[bolt_pick] candidate %d %s cost %.4g\n", i, in.name, cost);
     if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
   }
+  if (tune_log_enabled() && best >= 0) std::fprintf(stderr, "[bolt_pick] -> %d %s\n", best, tab[best].name);
   return best;
 }
 
@@ -737,9 +744,13 @@ static int chain_heuristic(const std::vector<ChainInstance>& tab, const B2bProbl
   double best_cost = 0;
   for (int i = 0; i < (int)tab.size(); ++i) {
     if (!chain_supports(tab, i, pr)) continue;
-    const double cost = (double)tab[i].n0t * tab[i].n1t + (double)tab[i].n1t * tab[i].n2t + 1e-3 * tab[i].lds_bytes;
+    // the tightest widths; the halo main loop where it applies; 64-row wave tiles (as for the fused pairs)
+    double cost = (double)tab[i].n0t * tab[i].n1t + (double)tab[i].n1t * tab[i].n2t + 1e-3 * tab[i].lds_bytes;
+    cost *= (tab[i].dyn_supports ? 0.75 : 1.0) * (1.0 + 32.0 / ((double)tab[i].bm / tab[i].waves));
+    if (tune_log_enabled()) std::fprintf(stderr, "[bolt_pick] candidate %d %s cost %.4g\n", i, tab[i].name, cost);
     if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
   }
+  if (tune_log_enabled() && best >= 0) std::fprintf(stderr, "[bolt_pick] -> %d %s\n", best, tab[best].name);
   return best;
 }
 
