@@ -80,8 +80,9 @@ typedef enum {
  * swizzling functor, stages, ...).  kernel_id selects a compiled instance of the op's table
  * (0 <= kernel_id < bolt_num_instances(op)); kernel_id = -1 (or a NULL config) lets the library
  * choose by a built-in rule.  swizzle and split_k are run-time knobs and are honoured as given
- * (0 is read as "off"); the remaining fields describe the instance and are filled in by
- * bolt_tune / bolt_instance_config, ignored on input.
+ * (0 is read as "off"; with a NULL config the rule also chooses the tile order, never split-K);
+ * the remaining fields describe the instance and are filled in by bolt_tune /
+ * bolt_instance_config, ignored on input.
  */
 typedef struct {
   int32_t kernel_id;
