@@ -301,3 +301,35 @@ def test_pingpong_kernels_keep_their_working_set_in_registers():
                 seen += 1
                 assert int(line.rsplit(":", 1)[1]) <= 128, (name, line)
     assert seen >= 4  # GEMM and convolution instance, each with and without the residual epilogue
+
+
+def test_built_in_pick_rule_families():
+    """What a call without a config runs (no GPU needed: bolt_check resolves the pick, BOLT_TUNE_LOG=1 names it): the
+    halo kernel for a 3x3 stride-1 layer, the ping-pong kernels for a GEMM that fills the chip in either weight layout,
+    the direct-to-LDS kernel (never its register-staged cover) for row-major weights, 32-deep k-tiles for K = 32."""
+    import os
+    import re
+    import subprocess
+    import sys
+    root = os.path.join(os.path.dirname(__file__), "..")
+    code = """
+import sys
+sys.path.insert(0, %r)
+import paper_2110_15238_amd as b
+cases = [(b.OP_CONV2D, b.conv_desc(32, 56, 56, 64, 64, 3, 3, 1, 1)),
+         (b.OP_GEMM, b.gemm_desc(4096, 4096, 4096, b_layout=b.LAYOUT_NK)),
+         (b.OP_GEMM, b.gemm_desc(4096, 4096, 4096)),
+         (b.OP_GEMM, b.gemm_desc(1280, 768, 3072)),
+         (b.OP_GEMM, b.gemm_desc(128320, 96, 32))]
+for op, d in cases:
+    assert b.bolt_check(op, d) == 0
+""" % os.path.abspath(root)
+    r = subprocess.run([sys.executable, "-c", code], env=dict(os.environ, BOLT_TUNE_LOG="1"), capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-2000:]
+    picks = re.findall(r"\[bolt_pick\] -> \d+ (\S+)", r.stderr)
+    assert len(picks) == 5, picks
+    assert picks[0].startswith("halo_")
+    assert picks[1].startswith("pp_") and picks[2].startswith("ppkn_")
+    assert picks[3].startswith("dmakn_")
+    assert picks[4].startswith("dmakn_") and re.match(r"dmakn_\d+x\d+x32_", picks[4])
+
