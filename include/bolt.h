@@ -262,7 +262,9 @@ int32_t bolt_chain_instance_supports(bolt_op op, int32_t kernel_id, int32_t n_op
  *   B2B_GEMM {A0, W0, b0, W1, b1, D1}  B2B_CONV {x, w0, b0, w1, b1, y}
  * desc1 is NULL for single ops.  The output buffer is overwritten.  Synchronises the stream.
  * best_ms (may be NULL) receives the mean time per launch of the winner, n_tried (may be NULL) the
- * number of candidates timed.  Results are cached per (op, shape) for the life of the process. */
+ * number of candidates timed.  Results are cached per (op, shape) for the life of the process.
+ * With BOLT_TUNE_LOG=1 in the environment every candidate's time goes to stderr (and, for calls that
+ * pass no config, every candidate's estimate under the built-in rule with the instance it picks). */
 bolt_status bolt_tune(bolt_op op, const void* desc0, const void* desc1, const void* const* ptrs, void* workspace,
                       size_t workspace_bytes, void* stream, bolt_config* best, float* best_ms, int32_t* n_tried);
 
