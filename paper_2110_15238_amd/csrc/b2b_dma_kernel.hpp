@@ -7,7 +7,7 @@
 //        second GEMM runs entirely out of registers and LDS;
 //   epilogue: D1 tile -> FP16 -> LDS -> 16-byte coalesced row stores.
 // Unlike the weights-resident kernels of b2b_kernel.hpp this kernel is not persistent: 2 workgroups fit on a compute unit and
-// cover each other's prologue / epilogue.  K-contiguous weights only (conv KRSC, GEMM B as [N][K]).
+// cover each other's prologue / epilogue.  Weights K-contiguous (conv KRSC, GEMM B as [N][K]) or, for GEMM pairs, row-major (WKN).
 #pragma once
 #include "b2b_kernel.hpp"
 #include "fprop_dma_kernel.hpp"

@@ -2,8 +2,9 @@
 // (buffer_load ... lds, 16 bytes per lane, no staging registers), NS tiles deep, so that the
 // latency of the loads for tile k+NS-1 is hidden behind the MFMA work on tiles k .. k+NS-2.
 // "Stages" is one of the searched template parameters of Section 3.2.2; everything else follows
-// the tiling of Section 2.2 as in fprop_kernel.hpp.  Both operands must be K-contiguous in memory
-// (conv: NHWC activations, KRSC weights; GEMM: A row-major, B stored [N][K]).
+// the tiling of Section 2.2 as in fprop_kernel.hpp.  The activations are K-contiguous in memory (NHWC, or a
+// row-major A); the weights are K-contiguous too (KRSC, or B stored [N][K]) or, for GEMMs, row-major [K][N]: those
+// tiles go to LDS as they lie in memory and are read with the LDS transpose read (WKN, DmaKnTileLoader below).
 //
 // Out-of-range rows, the K tail and zero-padding taps are not branched on: their lanes are given a
 // byte offset beyond the buffer descriptor's range, for which the hardware writes zeros to LDS.
